@@ -1,0 +1,354 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test names the mistake it would catch.  None of these compares the oracle with
+a retyped copy of its own formula: the references are textbook attention written
+five lines long on the raw inputs, torch's CPU scaled_dot_product_attention, an
+exact-rational scalar brute force, closed forms and invariants.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import brute
+from oracle import cocktail_oracle as O
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _seqs(w, layer=0):
+    ks, vs = [], []
+    for b in range(w.batch):
+        kh, vh = zip(*[workloads.kv_head(w, layer, b, h) for h in range(w.num_kv_heads)])
+        ks.append(np.stack(kh))
+        vs.append(np.stack(vh))
+    return ks, vs
+
+
+def _textbook(q, k, v, sm_scale):
+    s = (k.astype(np.float64) @ q.astype(np.float64)) * sm_scale
+    p = np.exp(s - s.max())
+    p /= p.sum()
+    return p @ v.astype(np.float64), np.log(np.exp(s - s.max()).sum()) + s.max()
+
+
+# -- 1. all-FP16 is exact attention (Alg. 1 with only the mm branch) ------------------------
+def test_all_fp16_equals_textbook_attention():
+    w = workloads.small("allfp16", 2, 4, 2, [96, 77], 16, 32, mix=(1.0, 0.0, 0.0))
+    ks, vs = _seqs(w)
+    bits = workloads.chunk_bits(w)
+    assert all((b == 16).all() for b in bits)
+    cache = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    q = workloads.query(w, 0)
+    out, lse = O.decode_attention(q, cache)
+    for b in range(w.batch):
+        for h in range(w.num_q_heads):
+            ref, rl = _textbook(q[b, h], ks[b][h // 2], vs[b][h // 2], 1 / np.sqrt(128))
+            np.testing.assert_allclose(out[b, h], ref, rtol=0, atol=1e-12)
+            assert abs(lse[b, h] - rl) < 1e-12
+
+
+def test_all_fp16_equals_torch_sdpa():
+    w = workloads.small("sdpa", 1, 4, 4, [200], 8, 32, mix=(1.0, 0.0, 0.0))
+    ks, vs = _seqs(w)
+    cache = O.reorder_quantize(ks, vs, workloads.chunk_bits(w), w.chunk_size, w.group_size)
+    q = workloads.query(w, 0)
+    out, _ = O.decode_attention(q, cache)
+    tq = torch.from_numpy(q.astype(np.float32))[0][:, None, :]            # [H, 1, D]
+    tk = torch.from_numpy(ks[0].astype(np.float32))
+    tv = torch.from_numpy(vs[0].astype(np.float32))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[:, 0].numpy()
+    np.testing.assert_allclose(out[0], ref, rtol=0, atol=1e-5)
+
+
+# -- 2. permutation invariance (Sec. III-C, Eq. 4-5) ---------------------------------------
+def test_reordering_does_not_change_output():
+    w = workloads.small("perm", 1, 2, 2, [16 * 12 + 5], 16, 32, mix=(0.3, 0.3, 0.4))
+    ks, vs = _seqs(w)
+    bits = workloads.chunk_bits(w)
+    assert len(set(bits[0].tolist())) == 3
+    cache = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    q = workloads.query(w, 0)
+    out, lse = O.decode_attention(q, cache)
+    # same quantiser applied chunk by chunk with the cache left in ORIGINAL token order
+    t, c = w.seq_lens[0], w.chunk_size
+    for h in range(2):
+        kh = np.empty((t, 128))
+        vh = np.empty((t, 128))
+        for i, b in enumerate(bits[0]):
+            sl = slice(i * c, (i + 1) * c)
+            if b == 16:
+                kh[sl], vh[sl] = ks[0][h, sl], vs[0][h, sl]
+            else:
+                kh[sl] = O.dequantize(*O.quantize_rows(ks[0][h, sl], int(b), 32), 32)
+                vh[sl] = O.dequantize(*O.quantize_rows(vs[0][h, sl], int(b), 32), 32)
+        kh[(t // c) * c:], vh[(t // c) * c:] = ks[0][h, (t // c) * c:], vs[0][h, (t // c) * c:]
+        ref, rl = _textbook(q[0, h], kh, vh, 1 / np.sqrt(128))
+        np.testing.assert_allclose(out[0, h], ref, rtol=0, atol=1e-12)
+        assert abs(lse[0, h] - rl) < 1e-12
+
+
+def test_plan_is_stable_partition_and_tail_is_fp16():
+    bits = np.array([4, 2, 16, 2, 4, 4, 16, 2], dtype=np.uint8)
+    sp = O.plan_sequence(8 * 8 + 3, 8, bits)
+    assert sp.perm.tolist() == [1, 3, 7, 0, 4, 5, 2, 6]          # INT2 | INT4 | FP16, each ascending
+    assert sp.class_tokens == (24, 24, 16 + 3) and sp.tail == 3
+    idx = O.class_token_index(67, 8, sp)
+    assert idx[2].tolist()[-3:] == [64, 65, 66]                    # tail follows the FP16 chunks
+    assert sorted(np.concatenate(idx).tolist()) == list(range(67))
+
+
+# -- 3. quantisation bound and extremes ----------------------------------------------------
+@pytest.mark.parametrize("bits,group", [(2, 32), (4, 32), (2, 64), (4, 64), (2, 128), (4, 128)])
+def test_quantisation_error_at_most_half_a_step(bits, group):
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal((512, 128)).astype(np.float32)
+    x[:, [3, 40, 77, 100]] *= 10
+    x = x.astype(np.float16)
+    codes, scale, zero = O.quantize_rows(x, bits, group)
+    qmax = (1 << bits) - 1
+    assert codes.min() >= 0 and codes.max() <= qmax
+    xh = O.dequantize(codes, scale, zero, group)
+    sc = np.repeat(scale.astype(np.float64), group, axis=-1)
+    assert (np.abs(x.astype(np.float64) - xh) <= 0.5 * sc * (1 + 1e-4) + 1e-30).all()
+    cg = codes.reshape(512, 128 // group, group)
+    assert (cg.min(-1) == 0).all() and (cg.max(-1) == qmax).all()   # min -> 0, max -> qmax
+    xg = x.reshape(512, 128 // group, group)
+    assert (zero == xg.min(-1)).all()
+
+
+def test_closed_form_groups():
+    row = np.tile(np.arange(4, dtype=np.float16), 32)[None]                   # {0,1,2,3}: scale 1, zero 0
+    c, s, z = O.quantize_rows(row, 2, 32)
+    assert (c == row).all() and (s == 1).all() and (z == 0).all()
+    row = np.tile(np.arange(16, dtype=np.float16), 8)[None]
+    c, s, z = O.quantize_rows(row, 4, 64)
+    assert (c == row).all() and (s == 1).all() and (z == 0).all()
+    const = np.full((1, 128), -2.5, dtype=np.float16)                          # constant: scale 0, exact
+    c, s, z = O.quantize_rows(const, 4, 32)
+    assert (c == 0).all() and (s == 0).all() and (z == np.float16(-2.5)).all()
+    assert (O.dequantize(c, s, z, 32) == -2.5).all()
+    # affine ramp a + k*h with qmax steps is reproduced exactly
+    ramp = (np.float16(-3.0) + np.float16(0.5) * np.arange(16)).astype(np.float16)
+    c, s, z = O.quantize_rows(np.tile(ramp, 8)[None], 4, 32)
+    assert (c == np.tile(np.arange(16), 8)).all() and (s == 0.5).all() and (z == -3).all()
+    # ties go to even: x - mn = 0.5, 1.5, 2.5 steps
+    x = np.array([0, 3, 0.5, 1.5, 2.5] + [0] * 27, dtype=np.float16)
+    c, _, _ = O.quantize_rows(x[None], 2, 32)
+    assert c[0, :5].tolist() == [0, 3, 0, 2, 2]
+
+
+def test_two_equal_logits_and_dominant_token():
+    d = 128
+    k = np.zeros((1, 2, d), dtype=np.float16)
+    v = np.stack([np.full(d, 1.0), np.full(d, 3.0)]).astype(np.float16)[None]
+    cache = O.reorder_quantize([k], [v], [np.zeros(0, np.uint8)], 8, 32)       # both tokens are tail
+    q = np.ones((1, 1, d), dtype=np.float16)
+    out, lse = O.decode_attention(q, cache)
+    np.testing.assert_allclose(out[0, 0], 2.0, atol=1e-15)
+    assert abs(lse[0, 0] - np.log(2)) < 1e-15
+    k[0, 1, 0] = 60 * np.sqrt(d)                                                # logit +60
+    cache = O.reorder_quantize([k], [v], [np.zeros(0, np.uint8)], 8, 32)
+    out, _ = O.decode_attention(q, cache)
+    np.testing.assert_allclose(out[0, 0], 3.0, atol=1e-20 + 3 * np.exp(-59.0))
+
+
+# -- 4. exact-rational brute force on tiny inputs ------------------------------------------
+def test_rounding_helper_matches_ieee():
+    from fractions import Fraction
+    rng = np.random.default_rng(0)
+    for v in rng.standard_normal(200) * 10.0 ** rng.integers(-9, 5, 200):
+        fr = Fraction(float(v))
+        assert float(brute.rn32(fr)) == float(np.float32(v))
+        if abs(v) < 6e4:
+            assert float(brute.rn16(fr)) == float(np.float16(v))
+    assert brute.rn16(Fraction(2049)) == 2048 and brute.rn16(Fraction(2051)) == 2052   # ties to even
+    assert brute.rn16(Fraction(1, 2 ** 25)) == 0 and brute.rn16(Fraction(3, 2 ** 25)) == Fraction(1, 2 ** 23)
+
+
+@pytest.mark.parametrize("bits", [2, 4])
+def test_quantiser_matches_exact_rational_brute_force(bits):
+    rng = np.random.default_rng(11 + bits)
+    x = rng.standard_normal((40, 64)).astype(np.float32)
+    x[:, 5] *= 10
+    x[7] *= 1e-4                       # small magnitudes: fp16 subnormal scales
+    x[8] = 0.125                       # constant
+    x[9, :3] = [0.0, -0.0, 1e-7]
+    x = x.astype(np.float16)
+    for group in (32, 64):
+        codes, scale, zero = O.quantize_rows(x, bits, group)
+        for t in range(x.shape[0]):
+            for g in range(64 // group):
+                bc, bs, bz = brute.quantize_group([float(v) for v in x[t, g * group:(g + 1) * group]], bits)
+                assert bc == codes[t, g * group:(g + 1) * group].tolist(), (t, g)
+                assert bs == float(scale[t, g]) and bz == float(zero[t, g])
+                assert not np.signbit(zero[t, g]) or zero[t, g] != 0
+
+
+def _tiny_case(bsz, hkv, rep, d, t_list, chunk, group, assign, seed):
+    rng = np.random.default_rng(seed)
+    ks = [rng.standard_normal((hkv, t, d)).astype(np.float16) for t in t_list]
+    vs = [rng.standard_normal((hkv, t, d)).astype(np.float16) for t in t_list]
+    q = rng.standard_normal((bsz, hkv * rep, d)).astype(np.float16)
+    return ks, vs, q, [np.array(a, dtype=np.uint8) for a in assign]
+
+
+@pytest.mark.parametrize("d,chunk,t", [(64, 4, 14), (64, 8, 27)])
+def test_full_path_matches_brute_force_all_assignments(d, chunk, t):
+    n = t // chunk
+    group = 32
+    for assign in itertools.product((2, 4, 16), repeat=n):
+        ks, vs, q, bits = _tiny_case(1, 2, 2, d, [t], chunk, group, [assign], seed=hash(assign) % 1000)
+        cache = O.reorder_quantize(ks, vs, bits, chunk, group)
+        order, tok = brute.plan(t, chunk, list(assign))
+        assert cache.plans[0].perm.tolist() == order
+        assert list(cache.plans[0].class_tokens) == [len(x) for x in tok]
+        kl = [[[float(x) for x in row] for row in ks[0][h]] for h in range(2)]
+        vl = [[[float(x) for x in row] for row in vs[0][h]] for h in range(2)]
+        for cls, b in enumerate((2, 4, 16)):
+            assert O.pack_class_buffer(cache, cls, "k").tobytes() == brute.build_class_bytes(kl, tok[cls], b, group)
+            assert O.pack_class_buffer(cache, cls, "v").tobytes() == brute.build_class_bytes(vl, tok[cls], b, group)
+        out, lse = O.decode_attention(q, cache, sm_scale=0.3)
+        for hq in range(4):
+            h = hq // 2
+            krows = [brute.dequant_token(kl[h][tt], b, group) for b, ts in zip((2, 4, 16), tok) for tt in ts]
+            vrows = [brute.dequant_token(vl[h][tt], b, group) for b, ts in zip((2, 4, 16), tok) for tt in ts]
+            bo, bl = brute.attention([float(x) for x in q[0, hq]], krows, vrows, 0.3)
+            np.testing.assert_allclose(out[0, hq], bo, rtol=0, atol=1e-12)
+            assert abs(lse[0, hq] - bl) < 1e-12
+
+
+def test_ragged_batch_brute_force_block_tail():
+    # 70 INT2 tokens -> two 64-token blocks, the second with 6 valid tokens; sequences of different length
+    ks, vs, q, bits = _tiny_case(2, 1, 1, 64, [70, 9], 70, 32, [[2], []], seed=3)
+    bits[1] = np.zeros(0, dtype=np.uint8)
+    cache = O.reorder_quantize(ks, vs, bits, 70, 32)
+    kl = [[[float(x) for x in row] for row in ks[0][0]]]
+    _, tok = brute.plan(70, 70, [2])
+    buf = O.pack_class_buffer(cache, 0, "k")
+    assert buf.size == 2 * O.block_bytes(0, 64, 32)
+    assert buf.tobytes() == brute.build_class_bytes(kl, tok[0], 2, 32)
+    # second sequence: 9 tail tokens only, FP16 class
+    assert cache.plans[1].class_tokens == (0, 0, 9)
+    fp = O.pack_class_buffer(cache, 2, "k")
+    kl1 = [[[float(x) for x in row] for row in ks[1][0]]]
+    assert fp.tobytes() == brute.build_class_bytes(kl1, list(range(9)), 16, 32)
+
+
+# -- 5. pack / unpack round trip and byte count ---------------------------------------------
+def test_pack_round_trip_and_sizes():
+    w = workloads.small("rt", 2, 2, 2, [64 * 3 + 40, 200], 8, 32, mix=(0.2, 0.3, 0.5))
+    ks, vs = _seqs(w)
+    cache = O.reorder_quantize(ks, vs, workloads.chunk_bits(w), 8, 32)
+    for cls in range(3):
+        for which in "kv":
+            buf = O.pack_class_buffer(cache, cls, which)
+            nblk = sum(((s[cls].n_tokens + 63) // 64) * 2 for s in cache.seqs)
+            assert buf.size == nblk * O.block_bytes(cls, 128, 32)
+            back = O.unpack_class_buffer(buf, cache, cls)
+            for b in range(2):
+                cc = cache.seqs[b][cls]
+                if cc.n_tokens == 0:
+                    continue
+                for h in range(2):
+                    if cls == 2:
+                        ref = (cc.k_raw if which == "k" else cc.v_raw)[h]
+                        assert (back[b][h][0] == ref).all()
+                    else:
+                        assert (back[b][h][0] == (cc.k_codes if which == "k" else cc.v_codes)[h]).all()
+                        assert (back[b][h][1] == (cc.k_scale if which == "k" else cc.v_scale)[h]).all()
+                        assert (back[b][h][2] == (cc.k_zero if which == "k" else cc.v_zero)[h]).all()
+    # algorithmic bytes: 48 / 80 / 256 per (token, head) at G=32
+    assert O.packed_bytes((1, 0, 0), 1, 128, 32) == 2 * 48
+    assert O.packed_bytes((0, 1, 0), 1, 128, 32) == 2 * 80
+    assert O.packed_bytes((0, 0, 1), 1, 128, 64) == 2 * 256
+    assert O.packed_bytes((1, 1, 0), 1, 128, 64) == 2 * (40 + 72)
+
+
+def test_row_word_layout_by_hand():
+    codes = np.zeros(128, dtype=np.uint8)
+    codes[0], codes[1], codes[2], codes[15], codes[16] = 1, 2, 3, 3, 2
+    w = O.pack_row_words(codes, 2)
+    assert w.shape == (8,)
+    # ch0 -> bit 0, ch1 -> bit 16, ch2 -> bit 2, ch15 -> bits 30..31, ch16 -> word 1 bit 0
+    assert int(w[0]) == (1 << 0) | (2 << 16) | (3 << 2) | (3 << 30) and int(w[1]) == 2
+    codes = np.zeros(128, dtype=np.uint8)
+    codes[0], codes[1], codes[6], codes[7], codes[8] = 15, 1, 9, 5, 7
+    w = O.pack_row_words(codes, 4)
+    assert int(w[0]) == 15 | (1 << 16) | (9 << 12) | (5 << 28) and int(w[1]) == 7
+    assert (O.unpack_row_words(w, 4) == codes).all()
+
+
+# -- 6. partial-softmax merge identity -------------------------------------------------------
+def test_merging_partials_equals_global_softmax():
+    rng = np.random.default_rng(5)
+    s = rng.standard_normal(300) * 3
+    v = rng.standard_normal((300, 16))
+    p = np.exp(s - s.max())
+    ref = (p / p.sum()) @ v
+    cuts = [0, 0, 17, 17, 120, 300]                                    # includes empty splits
+    ms, ls, os_ = [], [], []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        if a == b:
+            ms.append(-np.inf), ls.append(0.0), os_.append(np.zeros(16))
+            continue
+        m = s[a:b].max()
+        e = np.exp(s[a:b] - m)
+        ms.append(m), ls.append(e.sum()), os_.append(e @ v[a:b])
+    out, lse = O.merge_partials(ms, ls, os_)
+    np.testing.assert_allclose(out, ref, rtol=0, atol=1e-13)
+    assert abs(lse - (np.log(p.sum()) + s.max())) < 1e-12
+    assert O.merge_partials([], [], [])[0] is None
+
+
+# -- 7. reorder and quantise commute; GQA = replicated MHA; ragged = separate calls ----------
+def test_quantise_then_reorder_equals_reorder_then_quantise():
+    w = workloads.small("comm", 1, 1, 1, [8 * 9], 8, 32, mix=(0.0, 0.5, 0.5))
+    ks, vs = _seqs(w)
+    bits = workloads.chunk_bits(w)
+    cache = O.reorder_quantize(ks, vs, bits, 8, 32)
+    idx = O.class_token_index(72, 8, cache.plans[0])
+    for cls, b in ((0, 2), (1, 4)):
+        c_all, s_all, z_all = O.quantize_rows(ks[0][0], b, 32)          # quantise in original order first
+        assert (c_all[idx[cls]] == cache.seqs[0][cls].k_codes[0]).all()
+        assert (s_all[idx[cls]] == cache.seqs[0][cls].k_scale[0]).all()
+        assert (z_all[idx[cls]] == cache.seqs[0][cls].k_zero[0]).all()
+
+
+def test_gqa_equals_replicated_mha_and_ragged_equals_single_calls():
+    w = workloads.small("gqa", 2, 4, 2, [40, 88], 8, 32)
+    ks, vs = _seqs(w)
+    bits = workloads.chunk_bits(w)
+    q = workloads.query(w, 0)
+    out, lse = O.decode_attention(q, O.reorder_quantize(ks, vs, bits, 8, 32))
+    for b in range(2):
+        krep = [np.repeat(ks[b], 2, axis=0)]
+        vrep = [np.repeat(vs[b], 2, axis=0)]
+        o1, l1 = O.decode_attention(q[b:b + 1], O.reorder_quantize(krep, vrep, [bits[b]], 8, 32))
+        np.testing.assert_array_equal(o1[0], out[b])
+        np.testing.assert_array_equal(l1[0], lse[b])
+
+
+def test_subset_of_heads_matches_full():
+    w = workloads.small("subset", 1, 4, 2, [64], 8, 32)
+    ks, vs = _seqs(w)
+    cache = O.reorder_quantize(ks, vs, workloads.chunk_bits(w), 8, 32)
+    q = workloads.query(w, 0)
+    full, _ = O.decode_attention(q, cache)
+    part, _ = O.decode_attention(q, cache, heads=[(0, 3)])
+    np.testing.assert_array_equal(part[0, 3], full[0, 3])
+    assert np.isnan(part[0, 0]).all()
+
+
+# -- 8. the paper's KV-size figure (Sec. I) ---------------------------------------------------
+def test_kv_size_figure_from_paper():
+    with open(os.path.join(GOLDEN, "kv_cache_size_llama2_13b_128k.txt")) as f:
+        rows = [ln.split() for ln in f if ln.strip() and not ln.startswith("#")]
+    layers, heads, hd, tokens, gb, tol = rows[0]
+    got = O.kv_bytes_fp16(int(layers), int(heads), int(hd), int(tokens)) / 1e9
+    assert abs(got - float(gb)) / float(gb) <= float(tol)
+    # the same count from the packed-bytes formula with every token in the FP16 class
+    assert O.packed_bytes((0, 0, int(tokens)), int(heads), int(hd), 64) * int(layers) / 1e9 == got
