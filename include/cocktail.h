@@ -1,0 +1,194 @@
+/*
+ * cocktail.h - C ABI of the chunk-level KV cache computation of Cocktail
+ * (arXiv 2503.23294, Sec. III-C, Algorithm 1) for AMD MI355X (gfx950).
+ *
+ * The library covers the data-parallel hot path of the paper's second module.
+ * Given the bitwidth (FP16 / INT4 / INT2) that the chunk-level quantization
+ * search (Sec. III-B) chose for every context chunk, it
+ *   1. reorders the KV chunks so that every bitwidth class is contiguous in
+ *      memory (Alg. 1, prefill loop; Fig. 3),
+ *   2. quantizes and packs the INT2 and INT4 classes (Alg. 1, `quant`),
+ *   3. runs single-query decode attention over the three classes: logits of the
+ *      INT2, INT4 and FP16 blocks, one softmax over their concatenation, three
+ *      att x V products summed (Alg. 1, decode phase).  The concatenation is
+ *      never materialised: each worker keeps a partial softmax state
+ *      (max, sum, weighted V sum) and the states are merged exactly, which
+ *      gives the same result because the softmax-weighted sum does not depend
+ *      on the order or grouping of the tokens (Sec. III-C, Eq. 4-5).
+ *
+ * Conventions
+ *   - Every pointer is marked HOST or DEVICE.  The library never allocates,
+ *     frees or copies device memory and never synchronises the device; the two
+ *     GPU entry points only enqueue kernels on the caller's stream.
+ *   - All functions return a cocktail_status; on failure a message is kept in
+ *     thread-local storage (cocktail_last_error).  Arguments are validated on
+ *     the host before anything is launched.
+ *   - class index 0 = INT2, 1 = INT4, 2 = FP16 (the concatenation order of Alg. 1).
+ *
+ * Packed cache layout (an encoding defined by this library; the paper does not
+ * fix one).  For each class c the K data and the V data live in one device
+ * buffer each.  A buffer is a sequence of 64-token blocks ordered by
+ * (sequence b, kv head h, block j); sequence b owns ceil(n_{b,c}/64) blocks per
+ * head, n_{b,c} being its token count in class c.  Inside a block:
+ *   codes   the row of token i (i = 0..63) is cut into 16-byte pieces; piece p
+ *           of token i is at byte (p*64 + i)*16.  Row size: D*bits/8 bytes for
+ *           INT2/INT4, 2*D bytes (raw fp16, channel order) for FP16.
+ *           A quantized row is a sequence of little-endian 32-bit words; word k
+ *           covers the n = 32/bits channels k*n .. k*n+n-1, channel k*n+2f in
+ *           bits [f*bits, f*bits+bits) and channel k*n+2f+1 in bits
+ *           [16+f*bits, 16+f*bits+bits).
+ *   meta    (INT2/INT4 only) after the codes, at byte 64*rowbytes: for token i
+ *           and group g of G consecutive channels, 4 bytes at (i*(D/G)+g)*4 =
+ *           fp16 scale, then fp16 zero.  Value of a code: zero + code*scale.
+ *   Tokens past n_{b,c} in the last block of a head are zero bytes.
+ *
+ * Quantizer (the paper names `quant` without defining it; this is the reading
+ * used): per token, per group of G channels along head_dim, asymmetric min/max.
+ * Every step is one IEEE binary32 operation, round-to-nearest-even, unfused:
+ *   mn, mx = min, max of the group (a zero minimum is stored as +0)
+ *   scale  = fp16((f32(mx) - f32(mn)) / (2^bits - 1)),  zero = mn
+ *   code   = 0 if scale == 0, else
+ *            clamp(rint((f32(x) - f32(mn)) * (1.0f / f32(scale))), 0, 2^bits - 1)
+ */
+#ifndef COCKTAIL_H
+#define COCKTAIL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COCKTAIL_NUM_CLASSES 3
+#define COCKTAIL_TOKENS_PER_BLOCK 64
+#define COCKTAIL_MAX_Q_PER_KV 8
+
+typedef enum cocktail_status {
+  COCKTAIL_OK = 0,
+  COCKTAIL_EINVAL = -1,       /* NULL pointer, non-positive size, bad chunk bit value, ...    */
+  COCKTAIL_EUNSUPPORTED = -2, /* valid request this build has no kernel for                    */
+  COCKTAIL_EALIGN = -3,       /* a device pointer is not 16-byte aligned                       */
+  COCKTAIL_ENOSPACE = -4,     /* plan or workspace buffer smaller than required                */
+  COCKTAIL_EHIP = -5          /* the HIP runtime reported an error at launch                   */
+} cocktail_status;
+
+/* Geometry of one attention layer call.  group_size divides head_dim. */
+typedef struct cocktail_shape {
+  int32_t batch;        /* B  sequences                                        */
+  int32_t num_q_heads;  /* Hq query heads, a multiple of num_kv_heads          */
+  int32_t num_kv_heads; /* Hkv                                                 */
+  int32_t head_dim;     /* D, a multiple of 64 (kernels: 128)                  */
+  int32_t chunk_size;   /* C tokens per context chunk (Sec. III-A)             */
+  int32_t group_size;   /* G in {32, 64, 128}: channels per scale/zero pair    */
+} cocktail_shape;
+
+/* Sizes the caller needs to allocate buffers; filled by cocktail_plan. */
+typedef struct cocktail_sizes {
+  int64_t total_chunks;                        /* sum_b floor(T_b / C): entries of perm            */
+  int64_t class_tokens[COCKTAIL_NUM_CLASSES];  /* sum_b n_{b,c}                                    */
+  int64_t class_blocks[COCKTAIL_NUM_CLASSES];  /* 64-token blocks in the K (= V) buffer of class c */
+  int64_t class_bytes[COCKTAIL_NUM_CLASSES];   /* bytes of the K buffer, and of the V buffer       */
+  int64_t plan_bytes;                          /* bytes of the plan blob                           */
+  int64_t workspace_bytes;                     /* bytes of the decode-attention workspace          */
+  int64_t packed_bytes;                        /* K+V bytes of codes + scale/zero, padding excluded */
+  int32_t num_workers;                         /* workgroups the decode kernel is launched with    */
+  int32_t num_partials;                        /* partial softmax states written per call          */
+  int32_t num_segments;
+  int32_t reserved;
+} cocktail_sizes;
+
+/* The packed mixed-precision cache of one layer: the six lists of Alg. 1
+ * (K_q2, K_q4, K_fp16, V_q2, V_q4, V_fp16) plus the plan that describes them. */
+typedef struct cocktail_cache {
+  void* k[COCKTAIL_NUM_CLASSES]; /* DEVICE, class_bytes[c] each, 256-byte aligned; may be NULL iff 0 bytes */
+  void* v[COCKTAIL_NUM_CLASSES]; /* DEVICE, same sizes                                                     */
+  const void* plan_host;         /* HOST   plan blob written by cocktail_plan                              */
+  const void* plan_dev;          /* DEVICE byte-for-byte copy of the plan blob, 16-byte aligned            */
+} cocktail_cache;
+
+/*
+ * Host-only planning step (Alg. 1, prefill loop, lines "for i in range(N): ... append").
+ * Computes the stable partition of every sequence's chunks by bitwidth, the token
+ * count of every class (the FP16 class also receives the T_b mod C tail tokens,
+ * Sec. III-A), the block layout of the packed cache and the static split of the
+ * decode work over `num_workers` workgroups.
+ *
+ *   seq_lens     HOST [B]           context tokens T_b >= 0
+ *   chunk_bits   HOST [sum_b N_b]   N_b = floor(T_b / C) values in {2, 4, 16}, sequence after sequence
+ *   num_workers  workgroups for the decode kernel (> 0), normally
+ *                cocktail_default_workers()
+ *   sizes        HOST out, always written on success
+ *   plan_host    HOST out, plan_capacity bytes, or NULL to query sizes only
+ *   class_tokens HOST out [B][3] n_{b,c}, or NULL
+ *   perm         HOST out [sum_b N_b]: position j of sequence b's reordered chunk
+ *                list holds original chunk perm[off_b + j] (the x_j of Eq. 5), or NULL
+ *
+ * Errors: EINVAL (NULL, bad shape, bad bit value), ENOSPACE (plan_capacity too small).
+ * The plan blob is position independent: copy its plan_bytes bytes to the device
+ * unchanged.  The host arrays may be freed on return.
+ */
+int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
+                  int32_t num_workers, cocktail_sizes* sizes, void* plan_host, size_t plan_capacity,
+                  int32_t* class_tokens, int32_t* perm);
+
+/* Source layouts accepted by cocktail_reorder_quantize (element = one fp16). */
+#define COCKTAIL_SRC_STRIDED 0 /* element (b,h,t,d) at b*stride_b + h*stride_h + t*stride_t + d        */
+#define COCKTAIL_SRC_RAGGED 1  /* sequences concatenated; sequence b is [Hkv][T_b] rows of stride_t
+                                  elements, starting at (sum_{b'<b} T_b') * Hkv * stride_t              */
+
+/*
+ * Prefill side of Alg. 1: gather every chunk into its class (reorder), then
+ * quantize and pack the INT2 and INT4 classes; FP16 chunks and the tail are
+ * copied.  One kernel launch handles K and V of all classes.
+ *
+ *   k_src, v_src  DEVICE fp16, 16-byte aligned, head_dim contiguous; strides in
+ *                 elements, multiples of 8
+ *   cache         k/v buffers are written completely (padding included);
+ *                 plan_host/plan_dev must come from cocktail_plan for this shape
+ *   stream        hipStream_t (NULL = default stream)
+ *
+ * Inputs must be finite.  Errors: EINVAL, EUNSUPPORTED (head_dim != 128),
+ * EALIGN, EHIP.  Nothing is launched when an error is returned.
+ */
+int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, const void* v_src,
+                              int32_t src_layout, int64_t stride_b, int64_t stride_h, int64_t stride_t,
+                              const cocktail_cache* cache, void* stream);
+
+/*
+ * Decode side of Alg. 1: out[b,h] = softmax(sm_scale * q[b,h] . K^_b^T) V^_b over
+ * all tokens of the three classes of sequence b, K^/V^ being the dequantized
+ * (or raw fp16) rows of kv head h / (Hq/Hkv).  Two launches: partial states per
+ * worker, then the exact merge.
+ *
+ *   q          DEVICE fp16 [B][Hq][D], 16-byte aligned
+ *   sm_scale   softmax scale; <= 0 selects 1/sqrt(D)
+ *   out        DEVICE fp16 [B][Hq][D]; a sequence with no tokens yields zeros
+ *   lse        DEVICE fp32 [B][Hq] natural-log-sum-exp of the scaled logits
+ *              (-inf for an empty sequence), or NULL
+ *   workspace  DEVICE, workspace_bytes >= sizes.workspace_bytes, 16-byte aligned;
+ *              contents need not be initialised and are overwritten
+ *
+ * The cache is not modified.  Errors: EINVAL, EUNSUPPORTED (head_dim != 128,
+ * Hq/Hkv > COCKTAIL_MAX_Q_PER_KV), EALIGN, ENOSPACE, EHIP.
+ */
+int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
+                              float sm_scale, void* out, float* lse, void* workspace,
+                              size_t workspace_bytes, void* stream);
+
+/*
+ * Number of decode workgroups that fills the current HIP device for this shape
+ * (compute units x resident waves per unit / (Hq/Hkv)).  Needs a GPU: EHIP otherwise.
+ */
+int cocktail_default_workers(const cocktail_shape* shape, int32_t* num_workers);
+
+/* Message of the last failure on the calling thread ("" if none).  Static storage. */
+const char* cocktail_last_error(void);
+
+/* Library version, (major << 16) | minor. */
+int cocktail_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COCKTAIL_H */

@@ -1,0 +1,80 @@
+"""ctypes loader for libcocktail.so (argument marshalling only).
+
+`import torch` happens first on purpose: torch brings its own HIP runtime and
+the library must bind to that one so that torch's streams and device pointers
+are valid inside it.  There is no fallback: a missing library is an error.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch  # noqa: F401  (must be imported before the library is loaded)
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libcocktail.so")
+
+NUM_CLASSES = 3
+TOKENS_PER_BLOCK = 64
+MAX_Q_PER_KV = 8
+
+OK, EINVAL, EUNSUPPORTED, EALIGN, ENOSPACE, EHIP = 0, -1, -2, -3, -4, -5
+SRC_STRIDED, SRC_RAGGED = 0, 1
+
+
+class Shape(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("chunk_size", C.c_int32), ("group_size", C.c_int32)]
+
+
+class Sizes(C.Structure):
+    _fields_ = [("total_chunks", C.c_int64), ("class_tokens", C.c_int64 * 3), ("class_blocks", C.c_int64 * 3),
+                ("class_bytes", C.c_int64 * 3), ("plan_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
+                ("packed_bytes", C.c_int64), ("num_workers", C.c_int32), ("num_partials", C.c_int32),
+                ("num_segments", C.c_int32), ("reserved", C.c_int32)]
+
+
+class Cache(C.Structure):
+    _fields_ = [("k", C.c_void_p * 3), ("v", C.c_void_p * 3), ("plan_host", C.c_void_p), ("plan_dev", C.c_void_p)]
+
+
+EXPORTS = {
+    "cocktail_plan": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.c_int32,
+                                C.POINTER(Sizes), C.c_void_p, C.c_size_t, C.POINTER(C.c_int32),
+                                C.POINTER(C.c_int32)]),
+    "cocktail_reorder_quantize": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
+                                            C.c_int64, C.c_int64, C.POINTER(Cache), C.c_void_p]),
+    "cocktail_decode_attention": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float, C.c_void_p,
+                                            C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "cocktail_default_workers": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32)]),
+    "cocktail_last_error": (C.c_char_p, []),
+    "cocktail_version": (C.c_int, []),
+}
+
+_lib = None
+
+
+class CocktailError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"cocktail error {code}: {message}")
+        self.code = code
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2503_23294_amd.build` "
+                "(there is no CPU or PyTorch fallback for the Cocktail kernels)")
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def check(rc: int) -> None:
+    if rc != OK:
+        raise CocktailError(rc, lib().cocktail_last_error().decode())

@@ -1,0 +1,125 @@
+"""Thin Python binding of the C ABI in include/cocktail.h.
+
+Same names as the C entry points; this layer only marshals arguments.  torch is
+used for device memory and for the current HIP stream, nothing else: every step
+of the path (planning, reordering, quantisation, attention, merge) runs inside
+libcocktail.so.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import _lib
+from ._lib import Cache, CocktailError, Shape, Sizes, check, lib  # noqa: F401
+
+
+def make_shape(batch: int, num_q_heads: int, num_kv_heads: int, head_dim: int, chunk_size: int,
+               group_size: int) -> Shape:
+    return Shape(batch, num_q_heads, num_kv_heads, head_dim, chunk_size, group_size)
+
+
+@dataclass
+class Plan:
+    shape: Shape
+    sizes: Sizes
+    blob: np.ndarray            # uint8 [plan_bytes], host
+    class_tokens: np.ndarray    # int32 [B, 3]
+    perm: np.ndarray            # int32 [total_chunks]
+    seq_lens: np.ndarray
+
+
+def cocktail_default_workers(shape: Shape) -> int:
+    n = C.c_int32(0)
+    check(lib().cocktail_default_workers(C.byref(shape), C.byref(n)))
+    return int(n.value)
+
+
+def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[int], num_workers: int) -> Plan:
+    """Host-only: Alg. 1's prefill partition plus cache layout and decode work split."""
+    sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
+    cb = np.ascontiguousarray(np.asarray(chunk_bits, dtype=np.uint8).reshape(-1))
+    if sl.shape != (shape.batch,):
+        raise ValueError("seq_lens must have one entry per sequence")
+    need = int(sum(int(t) // shape.chunk_size for t in sl if t >= 0)) if shape.chunk_size > 0 else 0
+    if cb.size != need:
+        raise ValueError(f"chunk_bits has {cb.size} entries, {need} expected")
+    sizes = Sizes()
+    slp = sl.ctypes.data_as(C.POINTER(C.c_int32))
+    cbp = cb.ctypes.data_as(C.POINTER(C.c_uint8)) if cb.size else None
+    check(lib().cocktail_plan(C.byref(shape), slp, cbp, num_workers, C.byref(sizes), None, 0, None, None))
+    blob = np.zeros(int(sizes.plan_bytes), dtype=np.uint8)
+    ct = np.zeros((shape.batch, 3), dtype=np.int32)
+    perm = np.zeros(max(int(sizes.total_chunks), 1), dtype=np.int32)
+    check(lib().cocktail_plan(C.byref(shape), slp, cbp, num_workers, C.byref(sizes), blob.ctypes.data, blob.size,
+                              ct.ctypes.data_as(C.POINTER(C.c_int32)), perm.ctypes.data_as(C.POINTER(C.c_int32))))
+    return Plan(shape, sizes, blob, ct, perm[:int(sizes.total_chunks)], sl)
+
+
+class PackedCache:
+    """Device buffers of one layer's packed cache plus the ctypes descriptor handed to the library."""
+
+    def __init__(self, plan: Plan, device: torch.device):
+        self.plan = plan
+        self.device = device
+        self.plan_dev = torch.from_numpy(plan.blob).to(device)
+        self.k: List[torch.Tensor] = []
+        self.v: List[torch.Tensor] = []
+        for c in range(3):
+            n = int(plan.sizes.class_bytes[c])
+            self.k.append(torch.empty(n, dtype=torch.uint8, device=device))
+            self.v.append(torch.empty(n, dtype=torch.uint8, device=device))
+        self.desc = Cache()
+        for c in range(3):
+            self.desc.k[c] = self.k[c].data_ptr() if self.k[c].numel() else None
+            self.desc.v[c] = self.v[c].data_ptr() if self.v[c].numel() else None
+        self.desc.plan_host = plan.blob.ctypes.data
+        self.desc.plan_dev = self.plan_dev.data_ptr()
+        self.workspace = torch.empty(int(plan.sizes.workspace_bytes), dtype=torch.uint8, device=device)
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def cocktail_reorder_quantize(cache: PackedCache, k_src: torch.Tensor, v_src: torch.Tensor, *,
+                              ragged: bool = False, stride_b: int = 0, stride_h: int = 0,
+                              stride_t: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Reorder + quantise + pack K and V (device fp16 tensors) into `cache`.
+
+    Strided layout: element (b,h,t,d) at b*stride_b + h*stride_h + t*stride_t + d.  With ragged=True the
+    sequences are concatenated, each stored as [Hkv][T_b] rows of stride_t elements.
+    """
+    if k_src.dtype != torch.float16 or v_src.dtype != torch.float16:
+        raise TypeError("k_src and v_src must be float16")
+    if not (k_src.is_cuda and v_src.is_cuda):
+        raise ValueError("k_src and v_src must be device tensors")
+    sh = cache.plan.shape
+    st = sh.head_dim if stride_t is None else stride_t
+    check(lib().cocktail_reorder_quantize(C.byref(sh), k_src.data_ptr(), v_src.data_ptr(),
+                                          _lib.SRC_RAGGED if ragged else _lib.SRC_STRIDED, stride_b, stride_h, st,
+                                          C.byref(cache.desc), _stream_ptr(stream)))
+
+
+def cocktail_decode_attention(cache: PackedCache, q: torch.Tensor, sm_scale: float = 0.0,
+                              out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None,
+                              stream: Optional[torch.cuda.Stream] = None):
+    """Single-query attention over the packed cache.  q: device fp16 [B, Hq, D].  Returns (out, lse)."""
+    sh = cache.plan.shape
+    if q.dtype != torch.float16 or not q.is_cuda or not q.is_contiguous():
+        raise TypeError("q must be a contiguous float16 device tensor")
+    if tuple(q.shape) != (sh.batch, sh.num_q_heads, sh.head_dim):
+        raise ValueError("q must have shape [B, Hq, D]")
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((sh.batch, sh.num_q_heads), dtype=torch.float32, device=q.device)
+    check(lib().cocktail_decode_attention(C.byref(sh), q.data_ptr(), C.byref(cache.desc), float(sm_scale),
+                                          out.data_ptr(), lse.data_ptr(), cache.workspace.data_ptr(),
+                                          cache.workspace.numel(), _stream_ptr(stream)))
+    return out, lse

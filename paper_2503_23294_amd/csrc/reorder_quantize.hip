@@ -1,0 +1,234 @@
+// Prefill side of Alg. 1 (Sec. III-C): gather every chunk into its bitwidth class
+// (KV cache chunk reordering, Fig. 3), quantize + pack the INT2 / INT4 classes,
+// copy the FP16 class.  One workgroup produces one 64-token block of the packed
+// cache: 16-byte coalesced reads of the source rows, the block is assembled in LDS
+// in its final layout and written out with 16-byte coalesced stores.
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+#include "plan.h"
+
+namespace cocktail {
+
+struct RQParams {
+  const void* plan;
+  const _Float16* src[2];  // K, V
+  char* dst[2][3];         // [K|V][class]
+  int64_t stride_b, stride_h, stride_t;
+  int32_t ragged;
+  int32_t cls_end0, cls_end1, cls_end2;  // prefix sums of class_blocks
+};
+
+// One token-group step of the quantizer.  Every operation is a single IEEE
+// binary32 operation; contraction is disabled so that no multiply-add is fused.
+template <int BITS>
+__device__ __forceinline__ void quantize8(const float (&x)[8], float mn, float mx, uint32_t (&code)[8],
+                                          _Float16& scale_h) {
+#pragma clang fp contract(off)
+  constexpr float qmax = float((1 << BITS) - 1);
+  const float r = mx - mn;
+  const float s32 = r / qmax;
+  scale_h = static_cast<_Float16>(s32);
+  const float sc = static_cast<float>(scale_h);
+  if (sc == 0.0f) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) code[i] = 0;
+    return;
+  }
+  const float inv = 1.0f / sc;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float d = x[i] - mn;
+    float t = __builtin_rintf(d * inv);
+    t = fminf(fmaxf(t, 0.0f), qmax);
+    code[i] = static_cast<uint32_t>(t);
+  }
+}
+
+template <int D, int G>
+__global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
+  static_assert(D == 128, "one 16-lane row of 8 channels per lane");
+  constexpr int LPG = G / 8;   // lanes per group
+  constexpr int NG = D / G;
+  __shared__ __attribute__((aligned(16))) char lds[kTB * 2 * D];
+
+  const PlanHeader* hd = static_cast<const PlanHeader*>(p.plan);
+  const int which = blockIdx.y;  // 0 = K, 1 = V
+  int idx = blockIdx.x;
+  int cls;
+  if (idx < p.cls_end0) {
+    cls = 0;
+  } else if (idx < p.cls_end1) {
+    cls = 1, idx -= p.cls_end0;
+  } else {
+    cls = 2, idx -= p.cls_end1;
+  }
+  const int B = hd->batch, Hkv = hd->num_kv_heads, C = hd->chunk_size;
+  const int32_t* blk_base = plan_array<int32_t>(p.plan, hd->off_blk_base);
+  // sequence b with blk_base[b][cls] <= idx < blk_base[b+1][cls]
+  int lo = 0, hi = B;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (blk_base[3 * mid + cls] <= idx) lo = mid; else hi = mid;
+  }
+  // skip sequences without blocks in this class that share the same base
+  int b = lo;
+  while (blk_base[3 * (b + 1) + cls] <= idx) ++b;
+  const int nblk = plan_array<int32_t>(p.plan, hd->off_nblk)[3 * b + cls];
+  const int local = idx - blk_base[3 * b + cls];
+  const int h = local / nblk;
+  const int j = local - h * nblk;
+  const int ntok = plan_array<int32_t>(p.plan, hd->off_class_tokens)[3 * b + cls];
+  const int T = plan_array<int32_t>(p.plan, hd->off_seq_len)[b];
+  const int32_t* chunk_off = plan_array<int32_t>(p.plan, hd->off_chunk_off);
+  const int N = chunk_off[b + 1] - chunk_off[b];
+  const int32_t* perm = plan_array<int32_t>(p.plan, hd->off_perm) + chunk_off[b];
+  const int cc0 = plan_array<int32_t>(p.plan, hd->off_class_chunk0)[3 * b + cls];
+  const int tail = T - N * C;
+  const int chunk_tokens = (cls == 2) ? ntok - tail : ntok;  // tokens of this class that come from chunks
+
+  int64_t base;
+  int64_t sh;
+  if (p.ragged) {
+    const int64_t cum = plan_array<int64_t>(p.plan, hd->off_cum_tokens)[b];
+    sh = int64_t(T) * p.stride_t;
+    base = cum * Hkv * p.stride_t + h * sh;
+  } else {
+    base = b * p.stride_b + h * p.stride_h;
+  }
+  const _Float16* src = p.src[which] + base;
+
+  const int tid = threadIdx.x;
+  const int seg = tid & 15;        // 8 channels seg*8 .. seg*8+7
+  const int r0 = j * kTB;
+  const int row_bytes = (cls == 0) ? D / 4 : (cls == 1) ? D / 2 : 2 * D;
+
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const int i = pass * 16 + (tid >> 4);
+    const int r = r0 + i;
+    u32x4 raw = {0u, 0u, 0u, 0u};
+    if (r < ntok) {
+      int t;
+      if (r < chunk_tokens) {
+        const int slot = r / C;
+        t = perm[cc0 + slot] * C + (r - slot * C);
+      } else {
+        t = N * C + (r - chunk_tokens);   // Sec. III-A: tail tokens follow the FP16 chunks
+      }
+      raw = *reinterpret_cast<const u32x4*>(src + int64_t(t) * p.stride_t + seg * 8);
+    }
+    if (cls == 2) {
+      *reinterpret_cast<u32x4*>(lds + (seg * kTB + i) * 16) = raw;
+      continue;
+    }
+    float x[8];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const h2 v = __builtin_bit_cast(h2, raw[k]);
+      x[2 * k] = static_cast<float>(v.x);
+      x[2 * k + 1] = static_cast<float>(v.y);
+    }
+    float mn = x[0], mx = x[0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) mn = fminf(mn, x[k]), mx = fmaxf(mx, x[k]);
+#pragma unroll
+    for (int o = 1; o < LPG; o <<= 1) {
+      mn = fminf(mn, __shfl_xor(mn, o));
+      mx = fmaxf(mx, __shfl_xor(mx, o));
+    }
+    if (mn == 0.0f) mn = 0.0f;   // a zero minimum is stored as +0
+    uint32_t c[8];
+    _Float16 scale_h;
+    if (cls == 0) quantize8<2>(x, mn, mx, c, scale_h); else quantize8<4>(x, mn, mx, c, scale_h);
+    if ((seg & (LPG - 1)) == 0) {
+      h2 m;
+      m.x = scale_h;
+      m.y = static_cast<_Float16>(mn);
+      const int g = seg / LPG;
+      *reinterpret_cast<uint32_t*>(lds + kTB * row_bytes + (i * NG + g) * 4) = __builtin_bit_cast(uint32_t, m);
+    }
+    if (cls == 1) {
+      // word = 8 channels: even channels in the low half-word, odd ones in the high half-word
+      const uint32_t w = c[0] | (c[2] << 4) | (c[4] << 8) | (c[6] << 12) | (c[1] << 16) | (c[3] << 20) |
+                         (c[5] << 24) | (c[7] << 28);
+      *reinterpret_cast<uint32_t*>(lds + ((seg >> 2) * kTB + i) * 16 + (seg & 3) * 4) = w;
+    } else {
+      // word = 16 channels = two lanes; this lane holds fields 0..3 (even seg) or 4..7 (odd seg) of both half-words
+      const uint32_t mine = c[0] | (c[2] << 2) | (c[4] << 4) | (c[6] << 6) | (c[1] << 16) | (c[3] << 18) |
+                            (c[5] << 20) | (c[7] << 22);
+      const uint32_t other = __shfl_xor(mine, 1);
+      if ((seg & 1) == 0) {
+        const uint32_t w = mine | (other << 8);
+        const int word = seg >> 1;
+        *reinterpret_cast<uint32_t*>(lds + ((word >> 2) * kTB + i) * 16 + (word & 3) * 4) = w;
+      }
+    }
+  }
+  __syncthreads();
+  const int bb = hd->block_bytes[cls];
+  char* dst = p.dst[which][cls] + int64_t(plan_array<int32_t>(p.plan, hd->off_blk_base)[3 * b + cls] + local) * bb;
+  for (int o = tid * 16; o < bb; o += 256 * 16)
+    *reinterpret_cast<u32x4*>(dst + o) = *reinterpret_cast<const u32x4*>(lds + o);
+}
+
+}  // namespace cocktail
+
+using namespace cocktail;
+
+extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, const void* v_src,
+                                         int32_t src_layout, int64_t stride_b, int64_t stride_h,
+                                         int64_t stride_t, const cocktail_cache* cache, void* stream) {
+  if (int rc = check_shape(shape)) return rc;
+  if (!cache || !cache->plan_host || !cache->plan_dev) return fail(COCKTAIL_EINVAL, "cache or its plan is NULL");
+  const PlanHeader* hd = static_cast<const PlanHeader*>(cache->plan_host);
+  if (hd->magic != kPlanMagic || hd->version != kPlanVersion)
+    return fail(COCKTAIL_EINVAL, "plan_host is not a plan written by this library version");
+  if (hd->batch != shape->batch || hd->num_kv_heads != shape->num_kv_heads || hd->head_dim != shape->head_dim ||
+      hd->chunk_size != shape->chunk_size || hd->group_size != shape->group_size ||
+      hd->num_q_heads != shape->num_q_heads)
+    return fail(COCKTAIL_EINVAL, "plan was made for a different shape");
+  if (shape->head_dim != 128) return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
+  if (src_layout != COCKTAIL_SRC_STRIDED && src_layout != COCKTAIL_SRC_RAGGED)
+    return fail(COCKTAIL_EINVAL, "unknown src_layout %d", src_layout);
+  if (hd->total_tokens > 0 && (!k_src || !v_src)) return fail(COCKTAIL_EINVAL, "k_src or v_src is NULL");
+  if ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src) |
+       reinterpret_cast<uintptr_t>(cache->plan_dev)) & 15)
+    return fail(COCKTAIL_EALIGN, "k_src, v_src and plan_dev must be 16-byte aligned");
+  if (stride_t < shape->head_dim || (stride_t & 7))
+    return fail(COCKTAIL_EINVAL, "stride_t %lld must be >= head_dim and a multiple of 8", (long long)stride_t);
+  if (src_layout == COCKTAIL_SRC_STRIDED && (stride_b < 0 || stride_h < 0 || (stride_b & 7) || (stride_h & 7)))
+    return fail(COCKTAIL_EINVAL, "stride_b and stride_h must be non-negative multiples of 8");
+  RQParams p;
+  p.plan = cache->plan_dev;
+  p.src[0] = static_cast<const _Float16*>(k_src);
+  p.src[1] = static_cast<const _Float16*>(v_src);
+  int64_t tot = 0;
+  for (int c = 0; c < 3; ++c) {
+    if (hd->class_bytes[c] > 0 && (!cache->k[c] || !cache->v[c]))
+      return fail(COCKTAIL_EINVAL, "cache buffer of class %d is NULL but %lld bytes are needed", c,
+                  (long long)hd->class_bytes[c]);
+    if ((reinterpret_cast<uintptr_t>(cache->k[c]) | reinterpret_cast<uintptr_t>(cache->v[c])) & 15)
+      return fail(COCKTAIL_EALIGN, "cache buffers must be 16-byte aligned");
+    p.dst[0][c] = static_cast<char*>(cache->k[c]);
+    p.dst[1][c] = static_cast<char*>(cache->v[c]);
+    tot += hd->class_blocks[c];
+  }
+  if (tot >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "too many blocks for one launch");
+  p.stride_b = stride_b, p.stride_h = stride_h, p.stride_t = stride_t;
+  p.ragged = (src_layout == COCKTAIL_SRC_RAGGED);
+  p.cls_end0 = static_cast<int32_t>(hd->class_blocks[0]);
+  p.cls_end1 = p.cls_end0 + static_cast<int32_t>(hd->class_blocks[1]);
+  p.cls_end2 = static_cast<int32_t>(tot);
+  if (tot == 0) return COCKTAIL_OK;
+  const dim3 grid(static_cast<unsigned>(tot), 2, 1), block(256, 1, 1);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  switch (shape->group_size) {
+    case 32: hipLaunchKernelGGL((reorder_quantize_kernel<128, 32>), grid, block, 0, st, p); break;
+    case 64: hipLaunchKernelGGL((reorder_quantize_kernel<128, 64>), grid, block, 0, st, p); break;
+    default: hipLaunchKernelGGL((reorder_quantize_kernel<128, 128>), grid, block, 0, st, p); break;
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(COCKTAIL_EHIP, "reorder_quantize launch failed: %s", hipGetErrorString(e));
+  return COCKTAIL_OK;
+}

@@ -1,0 +1,251 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Bar: packed codes, scales/zeros and the reorder permutation bit-exact; attention outputs
+within 2e-3 max relative error per (sequence, query head): max_d |gpu - ref| / max_d |ref|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+from oracle import cocktail_oracle as O
+import paper_2503_23294_amd as ck
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-3
+
+
+def _dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    return torch.device("cuda:0")
+
+
+class Case:
+    """Runs plan -> reorder_quantize -> decode_attention on the GPU for one workload layer."""
+
+    def __init__(self, w, layer=0, workers=None, sm_scale=0.0, strided_pad=0):
+        self.w, self.layer = w, layer
+        dev = _dev()
+        self.shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+        self.bits = workloads.chunk_bits(w)
+        flat_bits = np.concatenate(self.bits) if self.bits else np.zeros(0, np.uint8)
+        if workers is None:
+            workers = ck.cocktail_default_workers(self.shape)
+        self.plan = ck.cocktail_plan(self.shape, w.seq_lens, flat_bits, workers)
+        self.cache = ck.PackedCache(self.plan, dev)
+        for t in self.cache.k + self.cache.v:
+            t.fill_(0xAB)                       # the library must overwrite padding too
+        if strided_pad:
+            # padded [B, Hkv, Tmax, D + pad] source
+            tmax = max(w.seq_lens)
+            st = w.head_dim + strided_pad
+            k = np.zeros((w.batch, w.num_kv_heads, tmax, st), dtype=np.float16)
+            v = np.zeros_like(k)
+            for b in range(w.batch):
+                for h in range(w.num_kv_heads):
+                    kh, vh = workloads.kv_head(w, layer, b, h)
+                    k[b, h, :w.seq_lens[b], :w.head_dim] = kh
+                    v[b, h, :w.seq_lens[b], :w.head_dim] = vh
+            self.k_dev, self.v_dev = torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)
+            ck.cocktail_reorder_quantize(self.cache, self.k_dev, self.v_dev, stride_b=w.num_kv_heads * tmax * st,
+                                         stride_h=tmax * st, stride_t=st)
+        else:
+            k, v = workloads.kv_flat(w, layer, threads=16)
+            self.k_dev, self.v_dev = torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)
+            ck.cocktail_reorder_quantize(self.cache, self.k_dev, self.v_dev, ragged=True)
+        self.q = workloads.query(w, layer)
+        self.q_dev = torch.from_numpy(self.q).to(dev)
+        self.sm_scale = sm_scale
+        self.out_dev, self.lse_dev = ck.cocktail_decode_attention(self.cache, self.q_dev, sm_scale)
+        torch.cuda.synchronize()
+        self.out = self.out_dev.cpu().numpy()
+        self.lse = self.lse_dev.cpu().numpy()
+        self.kbuf = [t.cpu().numpy() for t in self.cache.k]
+        self.vbuf = [t.cpu().numpy() for t in self.cache.v]
+        ct = self.plan.class_tokens.astype(np.int64)
+        self.nblk = (ct + 63) // 64
+        self.blk_base = np.zeros((w.batch + 1, 3), dtype=np.int64)
+        self.blk_base[1:] = np.cumsum(self.nblk * w.num_kv_heads, axis=0)
+
+    def check_plan(self):
+        pos = 0
+        for b, t in enumerate(self.w.seq_lens):
+            sp = O.plan_sequence(t, self.w.chunk_size, self.bits[b])
+            n = t // self.w.chunk_size
+            assert self.plan.perm[pos:pos + n].tolist() == sp.perm.tolist()
+            assert tuple(self.plan.class_tokens[b]) == sp.class_tokens
+            pos += n
+
+    def check_head(self, b, h):
+        """Bit-exact cache bytes of kv head (b, h) and attention parity of its query heads."""
+        w = self.w
+        kh, vh = workloads.kv_head(w, self.layer, b, h)
+        oc = O.reorder_quantize([kh[None]], [vh[None]], [self.bits[b]], w.chunk_size, w.group_size)
+        for c in range(3):
+            bb = O.block_bytes(c, w.head_dim, w.group_size)
+            lo = (self.blk_base[b, c] + h * self.nblk[b, c]) * bb
+            hi = lo + self.nblk[b, c] * bb
+            for which, buf in (("k", self.kbuf[c]), ("v", self.vbuf[c])):
+                ref = O.pack_class_buffer(oc, c, which)
+                got = buf[lo:hi]
+                assert ref.size == got.size
+                if not np.array_equal(ref, got):
+                    bad = np.flatnonzero(ref != got)
+                    raise AssertionError(f"cache bytes differ: b={b} h={h} class={c} {which}: {bad.size} bytes, "
+                                         f"first at {bad[0]} (block {bad[0] // bb}, offset {bad[0] % bb})")
+        rep = w.num_q_heads // w.num_kv_heads
+        sm = self.sm_scale if self.sm_scale > 0 else None
+        worst = 0.0
+        for r in range(rep):
+            hq = h * rep + r
+            ref, rl = O.decode_attention(self.q[b:b + 1, hq:hq + 1], oc, sm_scale=sm)
+            ref, rl = ref[0, 0], rl[0, 0]
+            got = self.out[b, hq].astype(np.float64)
+            if w.seq_lens[b] == 0:
+                assert (got == 0).all() and np.isneginf(self.lse[b, hq])
+                continue
+            err = np.abs(got - ref).max() / np.abs(ref).max()
+            worst = max(worst, err)
+            assert err <= TOL, f"attention b={b} hq={hq}: max rel err {err:.3e}"
+            assert abs(self.lse[b, hq] - rl) <= 1e-4 * max(1.0, abs(rl)), (self.lse[b, hq], rl)
+        return worst
+
+    def check_all(self):
+        self.check_plan()
+        worst = 0.0
+        for b in range(self.w.batch):
+            for h in range(self.w.num_kv_heads):
+                worst = max(worst, self.check_head(b, h))
+        return worst
+
+
+def _announce(msg):
+    print(f"[parity] {msg}", flush=True)
+
+
+@pytest.mark.parametrize("workers", [None, 1, 7, 64])
+def test_config1_all_heads(workers):
+    _announce(f"config 1 workers={workers}")
+    c = Case(workloads.config(1), workers=workers)
+    worst = c.check_all()
+    _announce(f"config 1 worst rel err {worst:.2e}")
+
+
+@pytest.mark.parametrize("group", [32, 64, 128])
+@pytest.mark.parametrize("rep", [1, 2, 4, 8])
+def test_group_sizes_and_gqa(group, rep):
+    w = workloads.small(f"g{group}_r{rep}", 2, 2 * rep, 2, [64 * 5 + 32 * 3 + 7, 32 * 9], 32, group,
+                        mix=(0.25, 0.35, 0.4), seed_offset=group + rep)
+    _announce(w.name)
+    Case(w, workers=5).check_all()
+
+
+@pytest.mark.parametrize("mix", [(1, 0, 0), (0, 1, 0), (0, 0, 1), (0.5, 0, 0.5)])
+def test_single_class_and_missing_class(mix):
+    w = workloads.small("mix" + "".join(str(int(10 * m)) for m in mix), 1, 2, 2, [8 * 40 + 3], 8, 32, mix=mix,
+                        seed_offset=11)
+    _announce(w.name)
+    Case(w, workers=3).check_all()
+
+
+def test_ragged_batch_with_empty_and_tail_only_sequences():
+    w = workloads.small("ragged_edge", 5, 4, 2, [0, 5, 96 * 7 + 50, 64, 96], 96, 64, mix=(0.3, 0.3, 0.4),
+                        seed_offset=5)
+    _announce(w.name)
+    c = Case(w, workers=9)
+    c.check_all()
+    assert (c.out[0] == 0).all()
+
+
+def test_chunk_smaller_than_block_and_custom_scale():
+    w = workloads.small("chunk8", 2, 2, 1, [8 * 77 + 1, 8 * 13], 8, 32, mix=(0.2, 0.4, 0.4), seed_offset=3)
+    _announce(w.name)
+    Case(w, workers=16, sm_scale=0.05).check_all()
+
+
+def test_strided_padded_source():
+    w = workloads.small("strided", 2, 2, 2, [300, 128], 32, 32, seed_offset=9)
+    _announce(w.name)
+    Case(w, workers=4, strided_pad=8).check_all()
+
+
+def test_more_workers_than_blocks_and_repeatability():
+    w = workloads.small("tiny", 1, 1, 1, [70], 16, 32, seed_offset=2)
+    _announce(w.name)
+    c = Case(w, workers=64)
+    c.check_all()
+    out2, lse2 = ck.cocktail_decode_attention(c.cache, c.q_dev)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, c.out_dev) and torch.equal(lse2, c.lse_dev)
+
+
+def test_runs_on_a_side_stream():
+    w = workloads.small("stream", 1, 2, 2, [512], 64, 32, seed_offset=4)
+    _announce(w.name)
+    c = Case(w, workers=8)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        out, _ = ck.cocktail_decode_attention(c.cache, c.q_dev)
+    s.synchronize()
+    assert torch.equal(out, c.out_dev)
+
+
+def test_rejects_bad_device_arguments():
+    w = workloads.small("bad", 1, 2, 2, [128], 64, 32)
+    c = Case(w, workers=2)
+    with pytest.raises(TypeError):
+        ck.cocktail_decode_attention(c.cache, c.q_dev.float())
+    small_ws = c.cache.workspace
+    c.cache.workspace = small_ws[:16]
+    with pytest.raises(ck.CocktailError) as e:
+        ck.cocktail_decode_attention(c.cache, c.q_dev)
+    assert e.value.code == -4
+    c.cache.workspace = small_ws
+
+
+# ---- full-size configurations, launch configuration of the bench, sampled heads ----------------
+def _sample_heads(w, n, seed):
+    rng = np.random.default_rng(seed)
+    allh = [(b, h) for b in range(w.batch) for h in range(w.num_kv_heads)]
+    pick = rng.choice(len(allh), size=min(n, len(allh)), replace=False)
+    return sorted(allh[i] for i in pick)
+
+
+@pytest.mark.parametrize("layer", [0, 15, 31])
+def test_config2_layers(layer):
+    w = workloads.config(2)
+    _announce(f"config 2 layer {layer}")
+    c = Case(w, layer=layer)
+    c.check_plan()
+    for b, h in _sample_heads(w, 4, layer):
+        _announce(f"  head {b},{h}: {c.check_head(b, h):.2e}")
+
+
+def test_config3_gqa_batch4():
+    w = workloads.config(3)
+    _announce("config 3")
+    c = Case(w)
+    c.check_plan()
+    for b, h in _sample_heads(w, 6, 3):
+        _announce(f"  head {b},{h}: {c.check_head(b, h):.2e}")
+
+
+def test_config4_128k():
+    w = workloads.config(4)
+    _announce("config 4")
+    c = Case(w)
+    c.check_plan()
+    for b, h in _sample_heads(w, 8, 4):
+        _announce(f"  head {b},{h}: {c.check_head(b, h):.2e}")
+
+
+def test_config5_ragged_dirichlet():
+    w = workloads.config(5)
+    _announce(f"config 5 lens={w.seq_lens}")
+    c = Case(w)
+    c.check_plan()
+    heads = sorted(set(_sample_heads(w, 6, 5) + [(0, 0), (1, 7)]))   # seq 0 all-FP16, seq 1 all-INT2
+    for b, h in heads:
+        _announce(f"  head {b},{h}: {c.check_head(b, h):.2e}")
