@@ -17,4 +17,10 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 
+// Reinterpret a dword as two halves.  Always goes through a by-value scalar:
+// __builtin_bit_cast applied directly to a vector element expression (v[i], v.x)
+// reads element 0 with this compiler.
+__host__ __device__ inline h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__host__ __device__ inline uint32_t as_u32(h2 v) { return __builtin_bit_cast(uint32_t, v); }
+
 }  // namespace cocktail

@@ -57,7 +57,7 @@ __device__ __forceinline__ h2 field(uint32_t w, uint32_t mask, uint32_t magic, f
   h2 b;
   b.x = static_cast<_Float16>(bias);
   b.y = b.x;
-  return __builtin_bit_cast(h2, u) - b;
+  return as_h2(u) - b;
 }
 
 // 16 two-bit codes of one word -> 8 half pairs (channel 2f, 2f+1 of the word)
@@ -83,7 +83,7 @@ __device__ __forceinline__ void unpack4(uint32_t w, h2 (&o)[4]) {
 }
 
 __device__ __forceinline__ float dot2(uint32_t qpair, h2 kv, float acc) {
-  return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, qpair), kv, acc, false);
+  return __builtin_amdgcn_fdot2(as_h2(qpair), kv, acc, false);
 }
 
 template <int G>
@@ -140,7 +140,7 @@ struct QuantClass {
     float s = 0.f;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const h2 mz = __builtin_bit_cast(h2, meta[g]);
+      const h2 mz = as_h2(meta[g]);
       s += static_cast<float>(mz.x) * ga[g] + static_cast<float>(mz.y) * qsum[g];
     }
     return s * scale_log2;
@@ -155,7 +155,7 @@ struct QuantClass {
     float ps[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const h2 mz = __builtin_bit_cast(h2, meta[g]);
+      const h2 mz = as_h2(meta[g]);
       ps[g] = p * static_cast<float>(mz.x);
       st.zacc[g] += p * static_cast<float>(mz.y);
     }
@@ -188,10 +188,10 @@ struct HalfClass {
 #pragma unroll
     for (int p = 0; p < PIECES; ++p) {
       const u32x4 w = load16(blk + (p * kTB + lane) * 16);
-      a0 = dot2(q[p * 4 + 0], __builtin_bit_cast(h2, w.x), a0);
-      a1 = dot2(q[p * 4 + 1], __builtin_bit_cast(h2, w.y), a1);
-      a0 = dot2(q[p * 4 + 2], __builtin_bit_cast(h2, w.z), a0);
-      a1 = dot2(q[p * 4 + 3], __builtin_bit_cast(h2, w.w), a1);
+      a0 = dot2(q[p * 4 + 0], as_h2(w.x), a0);
+      a1 = dot2(q[p * 4 + 1], as_h2(w.y), a1);
+      a0 = dot2(q[p * 4 + 2], as_h2(w.z), a0);
+      a1 = dot2(q[p * 4 + 3], as_h2(w.w), a1);
     }
     return (a0 + a1) * scale_log2;
   }
@@ -202,7 +202,7 @@ struct HalfClass {
       const u32x4 w = load16(blk + (pi * kTB + lane) * 16);
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        const h2 v = __builtin_bit_cast(h2, w[k]);
+        const h2 v = as_h2(w[k]);
         st.acc[pi * 8 + 2 * k] += p * static_cast<float>(v.x);
         st.acc[pi * 8 + 2 * k + 1] += p * static_cast<float>(v.y);
       }

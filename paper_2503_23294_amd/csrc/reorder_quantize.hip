@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
     float x[8];
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      const h2 v = __builtin_bit_cast(h2, raw[k]);
+      const h2 v = as_h2(raw[k]);
       x[2 * k] = static_cast<float>(v.x);
       x[2 * k + 1] = static_cast<float>(v.y);
     }
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
       m.x = scale_h;
       m.y = static_cast<_Float16>(mn);
       const int g = seg / LPG;
-      *reinterpret_cast<uint32_t*>(lds + kTB * row_bytes + (i * NG + g) * 4) = __builtin_bit_cast(uint32_t, m);
+      *reinterpret_cast<uint32_t*>(lds + kTB * row_bytes + (i * NG + g) * 4) = as_u32(m);
     }
     if (cls == 1) {
       // word = 8 channels: even channels in the low half-word, odd ones in the high half-word
