@@ -1,0 +1,176 @@
+"""Benchmark of the chunk-level KV cache computation hot path on one MI355X.
+
+One "step" is one pass of the whole path for one attention layer of the headline
+workload (Llama2-13B-shaped, 128K context, 512-token chunks, G=64): reorder +
+quantize + pack of the layer's fp16 K/V into cache copy A, then single-query
+decode attention over cache copy B (written one step earlier, so nothing it reads
+is still in the last-level cache).  Inputs are resident in HBM before the timed
+region.  `value` is the decode-attention time per layer from HIP events recorded
+on the launch stream inside the timed steps; the reorder+quantize time is
+reported next to it.
+
+Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+METRIC = "decode-attention us/layer and achieved HBM GB/s (% of peak) at 128K ctx"
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(w, bits, q, gpu_out, heads, sm_scale=None):
+    """Times the numpy oracle on `heads` kv heads of the same workload and checks the GPU output on them."""
+    from oracle import cocktail_oracle as O
+    import workloads
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([int(p.get("num_threads", 1)) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    t_rq = t_att = 0.0
+    worst = 0.0
+    rep = w.num_q_heads // w.num_kv_heads
+    for b, h in heads:
+        kh, vh = workloads.kv_head(w, 0, b, h)
+        t0 = time.perf_counter()
+        oc = O.reorder_quantize([kh[None]], [vh[None]], [bits[b]], w.chunk_size, w.group_size)
+        t1 = time.perf_counter()
+        ref, _ = O.decode_attention(q[b:b + 1, h * rep:(h + 1) * rep], oc, sm_scale=sm_scale)
+        t2 = time.perf_counter()
+        t_rq += t1 - t0
+        t_att += t2 - t1
+        for r in range(rep):
+            got = gpu_out[b, h * rep + r].astype(np.float64)
+            worst = max(worst, float(np.abs(got - ref[0, r]).max() / np.abs(ref[0, r]).max()))
+    total_heads = sum(1 for b in range(w.batch) for _ in range(w.num_kv_heads))
+    scale = total_heads / len(heads)
+    return {
+        "value": t_att * scale * 1e6, "unit": "us/layer", "cores": threads, "kind": "oracle",
+        "sample": f"{len(heads)} of {total_heads} (sequence, kv head) units of the same workload, "
+                  f"scaled linearly; reorder+quantize on the same sample: {t_rq * scale * 1e6:.0f} us/layer",
+        "reorder_quantize_us": t_rq * scale * 1e6,
+    }, worst
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload: benchmark configuration 1..5 (headline: 4)")
+    ap.add_argument("--workers", type=int, default=0, help="decode workgroups (0 = library default)")
+    ap.add_argument("--cpu-heads", type=int, default=2, help="kv heads the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--decode-only", action="store_true", help="steps run decode attention only (for profiling)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives or sharding are part of it); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2503_23294_amd as ck
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = torch.device("cuda:0")
+    w = workloads.config(args.config)
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = workloads.chunk_bits(w)
+    workers = args.workers or ck.cocktail_default_workers(shape)
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), workers)
+    t0 = time.perf_counter()
+    k, v = workloads.kv_flat(w, 0, threads=16)
+    log(f"generated {k.nbytes * 2 / 1e9:.2f} GB of fp16 K/V in {time.perf_counter() - t0:.1f} s")
+    k_dev, v_dev = torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)
+    q = workloads.query(w, 0)
+    q_dev = torch.from_numpy(q).to(dev)
+    caches = [ck.PackedCache(plan, dev), ck.PackedCache(plan, dev)]
+    out = torch.empty_like(q_dev)
+    lse = torch.empty((w.batch, w.num_q_heads), dtype=torch.float32, device=dev)
+
+    packed = int(plan.sizes.packed_bytes)
+    qo_bytes = 2 * w.batch * w.num_q_heads * w.head_dim * 2
+    decode_bytes = packed + qo_bytes                        # algorithmic bytes of one decode call
+    rq_bytes = int(k.nbytes + v.nbytes) + packed            # read fp16 K,V once, write the packed cache
+    del k, v
+
+    def rq(i):
+        ck.cocktail_reorder_quantize(caches[i % 2], k_dev, v_dev, ragged=True)
+
+    def dec(i):
+        ck.cocktail_decode_attention(caches[i % 2], q_dev, 0.0, out, lse)
+
+    rq(0), rq(1)
+    torch.cuda.synchronize()
+    for i in range(args.warmup):
+        if not args.decode_only:
+            rq(i)
+        dec(i + 1)
+    torch.cuda.synchronize()
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        if not args.decode_only:
+            rq(i)
+        ev[i][1].record()
+        dec(i + 1)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    rq_us = np.array([e[0].elapsed_time(e[1]) for e in ev]) * 1e3
+    dec_us = np.array([e[1].elapsed_time(e[2]) for e in ev]) * 1e3
+    dec_mean, dec_med, dec_min = float(dec_us.mean()), float(np.median(dec_us)), float(dec_us.min())
+    gbps = decode_bytes / (dec_mean * 1e-6) / 1e9
+    gpu_out = out.cpu().numpy()
+
+    result = {
+        "metric": METRIC, "value": dec_mean, "unit": "us/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall / args.steps * 1e3, "higher_is_better": False,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads,
+                   "head_dim": w.head_dim, "context": list(w.seq_lens), "chunk_size": w.chunk_size,
+                   "group_size": w.group_size,
+                   "class_tokens_int2_int4_fp16": [int(x) for x in plan.class_tokens.sum(axis=0)],
+                   "decode_workgroups": workers, "step": "reorder+quantize (copy A) then decode attention (copy B)"
+                   if not args.decode_only else "decode attention only"},
+        "decode_us_median": dec_med, "decode_us_min": dec_min,
+        "achieved_gbps": gbps, "pct_of_hbm_peak": 100.0 * gbps / HBM_PEAK_GBPS,
+        "decode_algorithmic_bytes": decode_bytes,
+        "reorder_quantize_us": None if args.decode_only else float(rq_us.mean()),
+        "reorder_quantize_gbps": None if args.decode_only else rq_bytes / (float(rq_us.mean()) * 1e-6) / 1e9,
+        "reorder_quantize_bytes": rq_bytes,
+        "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gbps / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "decode_partial_kernel (+ merge, timed together per call)"},
+    }
+    if args.cpu_heads > 0:
+        rng = np.random.default_rng(0)
+        allh = [(b, h) for b in range(w.batch) for h in range(w.num_kv_heads) if w.seq_lens[b] > 0]
+        pick = sorted(allh[i] for i in rng.choice(len(allh), size=min(args.cpu_heads, len(allh)), replace=False))
+        base, worst = cpu_baseline(w, bits, q, gpu_out, pick)
+        result["cpu_baseline"] = base
+        result["parity_max_rel_err_on_cpu_sample"] = worst
+        assert worst <= 2e-3, f"GPU output disagrees with the oracle on the sampled heads: {worst:.3e}"
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
