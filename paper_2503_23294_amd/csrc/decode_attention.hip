@@ -14,10 +14,15 @@
 //    of a token never leaves its lane: the query sits in scalar registers and feeds
 //    v_dot2 as the uniform operand.  No cross-lane traffic exists in the steady
 //    state; lanes are merged only when a partial state is flushed.
-//  * Codes are expanded with the fp16 "magic exponent" trick: (word & mask) | bias
-//    is a pair of halves 2^k + code, the bias is removed exactly by one packed add.
-//    Dequantisation is folded:  q.k^ = sum_g scale_g * (q.code)_g + zero_g * sum(q_g)
-//    and  sum_t p_t v^_t = sum_t (p_t scale_tg) code_t + sum_t p_t zero_tg.
+//  * Codes are expanded without any conversion: a code field masked out of a
+//    half-word IS an fp16 subnormal of value code * 2^(pos-24), which v_dot2_f32_f16
+//    and v_fma_mix_f32 consume exactly; the power of two is folded into per-group
+//    factors.  Dequantisation is folded too:
+//      q.k^      = sum_g scale_g * (q.code)_g + zero_g * sum(q_g)
+//      sum p v^  = sum_t (p_t scale_tg) code_t + sum_t p_t zero_tg
+//  * Loads are software pipelined by hand: the V blocks of a sub-split are in flight
+//    while its logits are computed, and the K blocks of the next sub-split while the
+//    V blocks are accumulated.
 //  * Softmax is online per lane (each lane is its own split): logits of J blocks,
 //    one lazy rescale when the lane's reference maximum grows by more than 2^8,
 //    then the V pass.  (m, l, o[D]) partials go to the workspace and a second small
@@ -37,6 +42,7 @@ namespace cocktail {
 constexpr int D = 128;
 constexpr float kNegBig = -1.0e30f;
 constexpr float kRescaleThreshold = 8.0f;   // log2 units
+constexpr float kTwo24 = 16777216.0f;
 
 typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
 
@@ -49,42 +55,33 @@ struct DecodeParams {
   float scale_log2;         // sm_scale * log2(e)
 };
 
-__device__ __forceinline__ u32x4 load16(const char* p) { return *reinterpret_cast<const u32x4*>(p); }
-
-// (w & mask) | magic  ->  two halves 2^k + code ;  minus 2^k  ->  two halves holding the codes exactly
-__device__ __forceinline__ h2 field(uint32_t w, uint32_t mask, uint32_t magic, float bias) {
-  const uint32_t u = (w & mask) | magic;
-  h2 b;
-  b.x = static_cast<_Float16>(bias);
-  b.y = b.x;
-  return as_h2(u) - b;
+// A run of blocks is addressed through a buffer resource: every load is
+// buffer_load(resource, lane offset in a VGPR, block/piece offset in an SGPR), so a lane needs
+// one address register for the whole kernel, and reads past `bytes` return zero instead of faulting.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const char* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 load16(rsrc_t rs, uint32_t voff, uint32_t soff) {
+  return __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0);
 }
 
-// 16 two-bit codes of one word -> 8 half pairs (channel 2f, 2f+1 of the word)
-__device__ __forceinline__ void unpack2(uint32_t w, h2 (&o)[8]) {
-  const uint32_t t = w >> 10;
-  o[0] = field(w, 0x00030003u, 0x64006400u, 1024.f);
-  o[1] = field(w, 0x000C000Cu, 0x5C005C00u, 256.f);
-  o[2] = field(w, 0x00300030u, 0x54005400u, 64.f);
-  o[3] = field(w, 0x00C000C0u, 0x4C004C00u, 16.f);
-  o[4] = field(w, 0x03000300u, 0x44004400u, 4.f);
-  o[5] = field(t, 0x00030003u, 0x64006400u, 1024.f);
-  o[6] = field(t, 0x000C000Cu, 0x5C005C00u, 256.f);
-  o[7] = field(t, 0x00300030u, 0x54005400u, 64.f);
+__device__ __forceinline__ float dot2(uint32_t qpair, uint32_t kv, float acc) {
+  return __builtin_amdgcn_fdot2(as_h2(qpair), as_h2(kv), acc, false);
 }
 
-// 8 four-bit codes of one word -> 4 half pairs
-__device__ __forceinline__ void unpack4(uint32_t w, h2 (&o)[4]) {
-  const uint32_t t = w >> 8;
-  o[0] = field(w, 0x000F000Fu, 0x64006400u, 1024.f);
-  o[1] = field(w, 0x00F000F0u, 0x54005400u, 64.f);
-  o[2] = field(t, 0x000F000Fu, 0x64006400u, 1024.f);
-  o[3] = field(t, 0x00F000F0u, 0x54005400u, 64.f);
+// acc + f32 * (low | high half of hv as fp16): compiles to v_fma_mix_f32
+__device__ __forceinline__ float fma_lo(float a, uint32_t hv, float acc) {
+  return acc + a * static_cast<float>(as_h2(hv).x);
+}
+__device__ __forceinline__ float fma_hi(float a, uint32_t hv, float acc) {
+  return acc + a * static_cast<float>(as_h2(hv).y);
 }
 
-__device__ __forceinline__ float dot2(uint32_t qpair, h2 kv, float acc) {
-  return __builtin_amdgcn_fdot2(as_h2(qpair), kv, acc, false);
-}
+__device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
+
+// Zero-instruction anchor: the value must exist in a VGPR at this point of the program order.
+__device__ __forceinline__ void pin(float& x) { asm volatile("" : "+v"(x)); }
 
 template <int G>
 struct LaneState {
@@ -94,170 +91,246 @@ struct LaneState {
 };
 
 // ---------------------------------------------------------------- quantised classes
+// A word holds 32/BITS codes; even channels in the low half-word, odd ones in the high
+// half-word.  Masking field k of both half-words of `w` or `w >> 8` leaves two fp16
+// subnormals  code * 2^(BITS*k - 24)  for the channel pair (2f, 2f+1), f = 4*half + k
+// (INT2) or 2*half + k (INT4).
 template <int BITS, int G>
 struct QuantClass {
   static constexpr int PIECES = D * BITS / 128;
   static constexpr int NG = D / G;
   static constexpr int CPW = 32 / BITS;             // channels per word
+  static constexpr int NPOS = 8 / BITS;             // fields per byte: 4 (INT2) or 2 (INT4)
   static constexpr int ROWB = D * BITS / 8;
   static constexpr int BLOCKB = kTB * (ROWB + 4 * NG);
+  static constexpr uint32_t MASK0 = (BITS == 2) ? 0x00030003u : 0x000F000Fu;
 
-  __device__ static __forceinline__ void load_meta(const char* blk, int lane, uint32_t (&meta)[NG]) {
-    const char* mp = blk + kTB * ROWB + lane * (4 * NG);
+  struct Stage {              // one lane's share of one block of K or V
+    u32x4 pc[PIECES];
+    uint32_t meta[NG];
+  };
+
+  // `boff` = byte offset of the block inside the run, `lane16` = lane * 16
+  __device__ static __forceinline__ void load(Stage& s, rsrc_t rs, uint32_t boff, uint32_t lane16) {
+#pragma unroll
+    for (int p = 0; p < PIECES; ++p) s.pc[p] = load16(rs, lane16, boff + p * (kTB * 16));
+    const uint32_t moff = boff + kTB * ROWB;
     if constexpr (NG == 4) {
-      const u32x4 t = *reinterpret_cast<const u32x4*>(mp);
-      meta[0] = t.x, meta[1] = t.y, meta[2] = t.z, meta[3] = t.w;
+      const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rs, lane16, moff, 0);
+      s.meta[0] = t.x, s.meta[1] = t.y, s.meta[2] = t.z, s.meta[3] = t.w;
     } else if constexpr (NG == 2) {
-      const u32x2 t = *reinterpret_cast<const u32x2*>(mp);
-      meta[0] = t.x, meta[1] = t.y;
+      const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, lane16 >> 1, moff, 0);
+      s.meta[0] = t.x, s.meta[1] = t.y;
     } else {
-      meta[0] = *reinterpret_cast<const uint32_t*>(mp);
+      s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, lane16 >> 2, moff, 0);
     }
   }
 
-  // logit (log2 units) of this lane's token in block `blk`
-  __device__ static __forceinline__ float logit(const char* blk, int lane, const uint32_t (&q)[D / 2],
+  // logit (log2 units) of this lane's token
+  __device__ static __forceinline__ float logit(const Stage& s, const uint32_t (&q)[D / 2],
                                                 const float (&qsum)[NG], float scale_log2) {
-    u32x4 pc[PIECES];
+    float ga[NG][NPOS];
 #pragma unroll
-    for (int p = 0; p < PIECES; ++p) pc[p] = load16(blk + (p * kTB + lane) * 16);
-    uint32_t meta[NG];
-    load_meta(blk, lane, meta);
-    float ga[NG];
+    for (int g = 0; g < NG; ++g)
 #pragma unroll
-    for (int g = 0; g < NG; ++g) ga[g] = 0.f;
+      for (int k = 0; k < NPOS; ++k) ga[g][k] = 0.f;
 #pragma unroll
     for (int p = 0; p < PIECES; ++p)
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int word = p * 4 + k;
-        const int cb = word * CPW;
-        h2 c[CPW / 2];
-        if constexpr (BITS == 2) unpack2(pc[p][k], c); else unpack4(pc[p][k], c);
+      for (int wi = 0; wi < 4; ++wi) {
+        const int cb = (p * 4 + wi) * CPW;          // first channel of the word
+        const uint32_t w0 = s.pc[p][wi];
+        const uint32_t w1 = w0 >> 8;
 #pragma unroll
-        for (int f = 0; f < CPW / 2; ++f) ga[cb / G] = dot2(q[cb / 2 + f], c[f], ga[cb / G]);
+        for (int k = 0; k < NPOS; ++k) {
+          const uint32_t mask = MASK0 << (BITS * k);
+          ga[cb / G][k] = dot2(q[cb / 2 + k], w0 & mask, ga[cb / G][k]);
+          ga[cb / G][k] = dot2(q[cb / 2 + NPOS + k], w1 & mask, ga[cb / G][k]);
+        }
+        sched_fence();   // keeps the masked temporaries of one word from piling up across words
       }
-    float s = 0.f;
+    float sum = 0.f;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const h2 mz = as_h2(meta[g]);
-      s += static_cast<float>(mz.x) * ga[g] + static_cast<float>(mz.y) * qsum[g];
+      float t = ga[g][NPOS - 1];
+#pragma unroll
+      for (int k = NPOS - 2; k >= 0; --k) t = t * (1.0f / float(1 << BITS)) + ga[g][k];
+      // t = sum_d q_d code_d * 2^-24
+      const h2 mz = as_h2(s.meta[g]);
+      sum += (static_cast<float>(mz.x) * kTwo24) * t + static_cast<float>(mz.y) * qsum[g];
     }
-    return s * scale_log2;
+    return sum * scale_log2;
   }
 
-  __device__ static __forceinline__ void accumulate(const char* blk, int lane, float p, LaneState<G>& st) {
-    u32x4 pc[PIECES];
-#pragma unroll
-    for (int pi = 0; pi < PIECES; ++pi) pc[pi] = load16(blk + (pi * kTB + lane) * 16);
-    uint32_t meta[NG];
-    load_meta(blk, lane, meta);
-    float ps[NG];
+  __device__ static __forceinline__ void accumulate(const Stage& s, float p, LaneState<G>& st) {
+    float ps[NG][NPOS];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const h2 mz = as_h2(meta[g]);
-      ps[g] = p * static_cast<float>(mz.x);
+      const h2 mz = as_h2(s.meta[g]);
+      float f = p * static_cast<float>(mz.x) * kTwo24;
+#pragma unroll
+      for (int k = 0; k < NPOS; ++k) {
+        ps[g][k] = f;
+        f *= 1.0f / float(1 << BITS);
+      }
       st.zacc[g] += p * static_cast<float>(mz.y);
     }
 #pragma unroll
-    for (int pi = 0; pi < PIECES; ++pi)
+    for (int p_ = 0; p_ < PIECES; ++p_)
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int cb = (pi * 4 + k) * CPW;
-        h2 c[CPW / 2];
-        if constexpr (BITS == 2) unpack2(pc[pi][k], c); else unpack4(pc[pi][k], c);
+      for (int wi = 0; wi < 4; ++wi) {
+        const int cb = (p_ * 4 + wi) * CPW;
+        const uint32_t w0 = s.pc[p_][wi];
+        const uint32_t w1 = w0 >> 8;
 #pragma unroll
-        for (int f = 0; f < CPW / 2; ++f) {
-          st.acc[cb + 2 * f] += ps[cb / G] * static_cast<float>(c[f].x);
-          st.acc[cb + 2 * f + 1] += ps[cb / G] * static_cast<float>(c[f].y);
+        for (int k = 0; k < NPOS; ++k) {
+          const uint32_t mask = MASK0 << (BITS * k);
+          const uint32_t x0 = w0 & mask, x1 = w1 & mask;
+          const float f = ps[cb / G][k];
+          st.acc[cb + 2 * k] = fma_lo(f, x0, st.acc[cb + 2 * k]);
+          st.acc[cb + 2 * k + 1] = fma_hi(f, x0, st.acc[cb + 2 * k + 1]);
+          st.acc[cb + 2 * (NPOS + k)] = fma_lo(f, x1, st.acc[cb + 2 * (NPOS + k)]);
+          st.acc[cb + 2 * (NPOS + k) + 1] = fma_hi(f, x1, st.acc[cb + 2 * (NPOS + k) + 1]);
         }
+        // Pin the word's accumulators here: without it the optimiser sinks all multiply-adds of a
+        // stage below the unpacking of every word and the masked temporaries spill.
+#pragma unroll
+        for (int i = 0; i < CPW; ++i) pin(st.acc[cb + i]);
+        sched_fence();
       }
   }
 };
 
-// ---------------------------------------------------------------------- FP16 class
-template <int G>
-struct HalfClass {
-  static constexpr int PIECES = 16;
-  static constexpr int BLOCKB = kTB * 2 * D;
-  static constexpr int NG = D / G;
-
-  __device__ static __forceinline__ float logit(const char* blk, int lane, const uint32_t (&q)[D / 2],
-                                                const float (&)[NG], float scale_log2) {
-    float a0 = 0.f, a1 = 0.f;
+// One lazy-rescale step of a lane's online softmax followed by p_j = 2^(s_j - m).
+template <int G, int J>
+__device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J], LaneState<G>& st) {
+  float smax = s[0];
 #pragma unroll
-    for (int p = 0; p < PIECES; ++p) {
-      const u32x4 w = load16(blk + (p * kTB + lane) * 16);
-      a0 = dot2(q[p * 4 + 0], as_h2(w.x), a0);
-      a1 = dot2(q[p * 4 + 1], as_h2(w.y), a1);
-      a0 = dot2(q[p * 4 + 2], as_h2(w.z), a0);
-      a1 = dot2(q[p * 4 + 3], as_h2(w.w), a1);
-    }
-    return (a0 + a1) * scale_log2;
+  for (int jj = 1; jj < J; ++jj) smax = fmaxf(smax, s[jj]);
+  // the reference maximum only moves when it is exceeded by more than 2^8
+  const bool grow = smax > st.m + kRescaleThreshold;
+  if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
+    const float mnew = grow ? smax : st.m;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - mnew);
+    st.m = mnew;
+    st.l *= alpha;
+#pragma unroll
+    for (int d = 0; d < D; ++d) st.acc[d] *= alpha;
+#pragma unroll
+    for (int g = 0; g < D / G; ++g) st.zacc[g] *= alpha;
   }
-
-  __device__ static __forceinline__ void accumulate(const char* blk, int lane, float p, LaneState<G>& st) {
 #pragma unroll
-    for (int pi = 0; pi < PIECES; ++pi) {
-      const u32x4 w = load16(blk + (pi * kTB + lane) * 16);
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const h2 v = as_h2(w[k]);
-        st.acc[pi * 8 + 2 * k] += p * static_cast<float>(v.x);
-        st.acc[pi * 8 + 2 * k + 1] += p * static_cast<float>(v.y);
-      }
-    }
+  for (int jj = 0; jj < J; ++jj) {
+    p[jj] = __builtin_amdgcn_exp2f(s[jj] - st.m);
+    st.l += p[jj];
   }
-};
+}
 
-// Process `nb` consecutive blocks of one class starting at `blk` (K) / `vblk` (V);
-// `valid` = number of valid tokens in that range (only the last block can be partial).
+// Process `nb` (>= 1) consecutive blocks of a quantised class; `valid` = valid tokens in
+// that range (only the last block can be partial).  J register stages rotate between K and
+// V: as soon as the logit of a K block has been computed its registers receive the V block
+// of the same tokens, and as soon as that has been accumulated they receive the K block J
+// positions further on.  Blocks past the range are replaced by the last one and masked, so
+// the loop body has no branches around the loads.
 template <class CLS, int G, int J>
-__device__ __forceinline__ void process_range(const char* kblk, const char* vblk, int nb, int valid, int lane,
+__device__ __forceinline__ void process_quant(const char* kblk, const char* vblk, int nb, int valid, int lane,
                                               const uint32_t (&q)[D / 2], const float (&qsum)[D / G],
                                               float scale_log2, LaneState<G>& st) {
+  typename CLS::Stage sg[J];
+  const int last = nb - 1;
+  const uint32_t lane16 = lane * 16u;
+  const rsrc_t krs = make_rsrc(kblk, uint32_t(nb) * CLS::BLOCKB), vrs = make_rsrc(vblk, uint32_t(nb) * CLS::BLOCKB);
+#pragma unroll
+  for (int jj = 0; jj < J; ++jj) CLS::load(sg[jj], krs, uint32_t(min(jj, last)) * CLS::BLOCKB, lane16);
+#pragma unroll 1
   for (int j0 = 0; j0 < nb; j0 += J) {
-    float s[J];
+    float s[J], p[J];
 #pragma unroll
     for (int jj = 0; jj < J; ++jj) {
-      const int j = j0 + jj;
-      s[jj] = -INFINITY;
-      if (j < nb) {
-        const float t = CLS::logit(kblk + int64_t(j) * CLS::BLOCKB, lane, q, qsum, scale_log2);
-        if (j * kTB + lane < valid) s[jj] = t;
-      }
+      const float t = CLS::logit(sg[jj], q, qsum, scale_log2);
+      s[jj] = ((j0 + jj) * kTB + lane < valid) ? t : -INFINITY;
+      sched_fence();
+      CLS::load(sg[jj], vrs, uint32_t(min(j0 + jj, last)) * CLS::BLOCKB, lane16);
+      sched_fence();
     }
-    float smax = s[0];
-#pragma unroll
-    for (int jj = 1; jj < J; ++jj) smax = fmaxf(smax, s[jj]);
-    // lazy rescale: the reference maximum only moves when it is exceeded by more than 2^8
-    const bool grow = smax > st.m + kRescaleThreshold;
-    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-      const float mnew = grow ? smax : st.m;
-      const float alpha = __builtin_amdgcn_exp2f(st.m - mnew);
-      st.m = mnew;
-      st.l *= alpha;
-#pragma unroll
-      for (int d = 0; d < D; ++d) st.acc[d] *= alpha;
-#pragma unroll
-      for (int g = 0; g < D / G; ++g) st.zacc[g] *= alpha;
-    }
-    float p[J];
+    softmax_step<G, J>(s, p, st);
 #pragma unroll
     for (int jj = 0; jj < J; ++jj) {
-      p[jj] = __builtin_amdgcn_exp2f(s[jj] - st.m);
-      st.l += p[jj];
-    }
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      const int j = j0 + jj;
-      if (j < nb) CLS::accumulate(vblk + int64_t(j) * CLS::BLOCKB, lane, p[jj], st);
+      CLS::accumulate(sg[jj], p[jj], st);
+      sched_fence();
+      CLS::load(sg[jj], krs, uint32_t(min(j0 + J + jj, last)) * CLS::BLOCKB, lane16);
+      sched_fence();
     }
   }
 }
 
+// ---------------------------------------------------------------------- FP16 class
+// A block is 16 pieces of K and 16 of V per lane.  Two 8-piece buffers rotate:
+// K.lo K.hi | V.lo V.hi | next K.lo ..., each refilled as soon as it has been consumed.
 template <int G>
-__global__ __launch_bounds__(512) void decode_partial_kernel(DecodeParams prm) {
+__device__ __forceinline__ void process_half(const char* kblk, const char* vblk, int nb, int valid, int lane,
+                                             const uint32_t (&q)[D / 2], float scale_log2, LaneState<G>& st) {
+  constexpr int BLOCKB = kTB * 2 * D;
+  constexpr int HP = 8;   // pieces per buffer
+  u32x4 a[HP], b[HP];
+  const uint32_t lane16 = lane * 16u;
+  const rsrc_t krs = make_rsrc(kblk, uint32_t(nb) * BLOCKB), vrs = make_rsrc(vblk, uint32_t(nb) * BLOCKB);
+  auto fill = [&](u32x4 (&buf)[HP], rsrc_t rs, uint32_t boff, int half) {
+#pragma unroll
+    for (int p = 0; p < HP; ++p) buf[p] = load16(rs, lane16, boff + (half * HP + p) * (kTB * 16));
+  };
+  auto qk = [&](const u32x4 (&buf)[HP], int half, float& a0, float& a1) {
+#pragma unroll
+    for (int p = 0; p < HP; ++p) {
+      const int qb = (half * HP + p) * 4;
+      a0 = dot2(q[qb + 0], buf[p][0], a0);
+      a1 = dot2(q[qb + 1], buf[p][1], a1);
+      a0 = dot2(q[qb + 2], buf[p][2], a0);
+      a1 = dot2(q[qb + 3], buf[p][3], a1);
+    }
+  };
+  auto pv = [&](const u32x4 (&buf)[HP], int half, float p) {
+#pragma unroll
+    for (int pi = 0; pi < HP; ++pi)
+#pragma unroll
+      for (int wi = 0; wi < 4; ++wi) {
+        const int d = ((half * HP + pi) * 4 + wi) * 2;
+        st.acc[d] = fma_lo(p, buf[pi][wi], st.acc[d]);
+        st.acc[d + 1] = fma_hi(p, buf[pi][wi], st.acc[d + 1]);
+      }
+  };
+  const int last = nb - 1;
+  fill(a, krs, 0, 0);
+  fill(b, krs, 0, 1);
+#pragma unroll 1
+  for (int j = 0; j < nb; ++j) {
+    const uint32_t vb = uint32_t(j) * BLOCKB;
+    const uint32_t kn = uint32_t(min(j + 1, last)) * BLOCKB;
+    float a0 = 0.f, a1 = 0.f;
+    qk(a, 0, a0, a1);
+    sched_fence();
+    fill(a, vrs, vb, 0);
+    sched_fence();
+    qk(b, 1, a0, a1);
+    sched_fence();
+    fill(b, vrs, vb, 1);
+    sched_fence();
+    float s[1], p[1];
+    s[0] = (j * kTB + lane < valid) ? (a0 + a1) * scale_log2 : -INFINITY;
+    softmax_step<G, 1>(s, p, st);
+    pv(a, 0, p[0]);
+    sched_fence();
+    fill(a, krs, kn, 0);
+    sched_fence();
+    pv(b, 1, p[0]);
+    sched_fence();
+    fill(b, krs, kn, 1);
+    sched_fence();
+  }
+}
+
+template <int G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_partial_kernel(DecodeParams prm) {
   constexpr int NG = D / G;
   extern __shared__ float red[];   // [rep][64][17]: one 16-channel reduction tile per wave
 
@@ -341,11 +414,8 @@ __global__ __launch_bounds__(512) void decode_partial_kernel(DecodeParams prm) {
 #pragma unroll
       for (int gq = 0; gq < NG; ++gq) {
         float a = 0.f;
-        h2 one;
-        one.x = static_cast<_Float16>(1.0f);
-        one.y = one.x;
 #pragma unroll
-        for (int i = 0; i < G / 2; ++i) a = dot2(q[gq * (G / 2) + i], one, a);
+        for (int i = 0; i < G / 2; ++i) a = dot2(q[gq * (G / 2) + i], 0x3C003C00u, a);   // (1.0, 1.0)
         qsum[gq] = a;
       }
     }
@@ -353,20 +423,20 @@ __global__ __launch_bounds__(512) void decode_partial_kernel(DecodeParams prm) {
     const int je = min(sg.nblk, g1 - sg.gblk0);
     const int nb = je - jb;
     if (nb <= 0) break;   // cannot happen with a plan written by cocktail_plan; guarantees termination
-    const int valid = sg.ntok - jb * kTB;     // tokens from block jb to the end of the segment
+    // valid tokens of this range: up to the end of the segment or of the range, whichever comes first
+    const int valid = min(sg.ntok - jb * kTB, nb * kTB);
     const int64_t first = int64_t(sg.blk0 + jb);
     if (sg.cls == 0) {
       using C = QuantClass<2, G>;
-      process_range<C, G, 4>(prm.k[0] + first * C::BLOCKB, prm.v[0] + first * C::BLOCKB, nb, valid, lane, q, qsum,
-                             prm.scale_log2, st);
+      process_quant<C, G, 4>(prm.k[0] + first * C::BLOCKB, prm.v[0] + first * C::BLOCKB, nb, valid,
+                                             lane, q, qsum, prm.scale_log2, st);
     } else if (sg.cls == 1) {
       using C = QuantClass<4, G>;
-      process_range<C, G, 2>(prm.k[1] + first * C::BLOCKB, prm.v[1] + first * C::BLOCKB, nb, valid, lane, q, qsum,
+      process_quant<C, G, 2>(prm.k[1] + first * C::BLOCKB, prm.v[1] + first * C::BLOCKB, nb, valid, lane, q, qsum,
                              prm.scale_log2, st);
     } else {
-      using C = HalfClass<G>;
-      process_range<C, G, 1>(prm.k[2] + first * C::BLOCKB, prm.v[2] + first * C::BLOCKB, nb, valid, lane, q, qsum,
-                             prm.scale_log2, st);
+      constexpr int BB = kTB * 2 * D;
+      process_half<G>(prm.k[2] + first * BB, prm.v[2] + first * BB, nb, valid, lane, q, prm.scale_log2, st);
     }
     g = sg.gblk0 + je;
     ++s;
@@ -376,8 +446,12 @@ __global__ __launch_bounds__(512) void decode_partial_kernel(DecodeParams prm) {
 
 // Exact merge of the partial states of one (sequence, query head):
 //   M = max m_i,  L = sum l_i 2^(m_i - M),  out = sum o_i 2^(m_i - M) / L.
-__global__ __launch_bounds__(D) void decode_merge_kernel(const void* plan, const float* ws, _Float16* out,
-                                                         float* lse) {
+// 256 threads: 32 channel quads x 8 slices of the partial list.
+__global__ __launch_bounds__(256) void decode_merge_kernel(const void* plan, const float* ws, _Float16* out,
+                                                           float* lse) {
+  __shared__ float sm_max[4];
+  __shared__ float sm_l[8];
+  __shared__ float sm_o[8][D];
   const PlanHeader* hd = static_cast<const PlanHeader*>(plan);
   const int bhq = blockIdx.x;
   const int rep = hd->rep;
@@ -387,19 +461,37 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(const void* plan, const
   const int r = hq % rep;
   const int32_t* bh_pid = plan_array<int32_t>(plan, hd->off_bh_pid);
   const int p0 = bh_pid[bh], p1 = bh_pid[bh + 1];
-  const int d = threadIdx.x;
+  const int tid = threadIdx.x;
+  constexpr int STRIDE = D + kPartialFloats;
   float mx = -INFINITY;
-  for (int p = p0; p < p1; ++p) mx = fmaxf(mx, ws[(int64_t(p) * rep + r) * (D + kPartialFloats)]);
-  float big_l = 0.f, o = 0.f;
-  for (int p = p0; p < p1; ++p) {
-    const float* part = ws + (int64_t(p) * rep + r) * (D + kPartialFloats);
+  for (int p = p0 + tid; p < p1; p += 256) mx = fmaxf(mx, ws[(int64_t(p) * rep + r) * STRIDE]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
+  if ((tid & 63) == 0) sm_max[tid >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(sm_max[0], sm_max[1]), fmaxf(sm_max[2], sm_max[3]));
+  const int quad = tid & 31, slice = tid >> 5;
+  float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f, big_l = 0.f;
+  for (int p = p0 + slice; p < p1; p += 8) {
+    const float* part = ws + (int64_t(p) * rep + r) * STRIDE;
     const float wgt = __builtin_amdgcn_exp2f(part[0] - mx);
     big_l += part[1] * wgt;
-    o += part[kPartialFloats + d] * wgt;
+    const float2 v0 = *reinterpret_cast<const float2*>(part + kPartialFloats + quad * 4);
+    const float2 v1 = *reinterpret_cast<const float2*>(part + kPartialFloats + quad * 4 + 2);
+    o0 += v0.x * wgt, o1 += v0.y * wgt, o2 += v1.x * wgt, o3 += v1.y * wgt;
   }
-  const bool empty = !(big_l > 0.f);
-  out[int64_t(bhq) * D + d] = static_cast<_Float16>(empty ? 0.f : o / big_l);
-  if (lse && d == 0) lse[bhq] = empty ? -INFINITY : (mx + log2f(big_l)) * 0.6931471805599453f;
+  sm_o[slice][quad * 4 + 0] = o0, sm_o[slice][quad * 4 + 1] = o1;
+  sm_o[slice][quad * 4 + 2] = o2, sm_o[slice][quad * 4 + 3] = o3;
+  if (quad == 0) sm_l[slice] = big_l;
+  __syncthreads();
+  if (tid < D) {
+    float l = 0.f, o = 0.f;
+#pragma unroll
+    for (int sidx = 0; sidx < 8; ++sidx) l += sm_l[sidx], o += sm_o[sidx][tid];
+    const bool empty = !(l > 0.f);
+    out[int64_t(bhq) * D + tid] = static_cast<_Float16>(empty ? 0.f : o / l);
+    if (lse && tid == 0) lse[bhq] = empty ? -INFINITY : (mx + log2f(l)) * 0.6931471805599453f;
+  }
 }
 
 }  // namespace cocktail
@@ -416,7 +508,7 @@ extern "C" int cocktail_default_workers(const cocktail_shape* shape, int32_t* nu
     return fail(COCKTAIL_EHIP, "no HIP device available");
   }
   const int rep = shape->num_q_heads / shape->num_kv_heads;
-  const int waves_per_cu = 8;   // two waves per SIMD at <= 256 VGPRs
+  const int waves_per_cu = 4;   // one wave per SIMD, 512 registers each
   int per_cu = waves_per_cu / rep;
   if (per_cu < 1) per_cu = 1;
   *num_workers = prop.multiProcessorCount * per_cu;
@@ -436,7 +528,8 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
       hd->chunk_size != shape->chunk_size || hd->group_size != shape->group_size ||
       hd->num_q_heads != shape->num_q_heads)
     return fail(COCKTAIL_EINVAL, "plan was made for a different shape");
-  if (shape->head_dim != D) return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
+  if (shape->head_dim != D)
+    return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
   if (hd->rep > COCKTAIL_MAX_Q_PER_KV)
     return fail(COCKTAIL_EUNSUPPORTED, "Hq/Hkv = %d exceeds %d", hd->rep, COCKTAIL_MAX_Q_PER_KV);
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(workspace) |
@@ -472,8 +565,8 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_partial launch failed: %s", hipGetErrorString(e));
   }
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(shape->batch * shape->num_q_heads), dim3(D), 0, st, cache->plan_dev,
-                     static_cast<const float*>(workspace), static_cast<_Float16*>(out), lse);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(shape->batch * shape->num_q_heads), dim3(256), 0, st,
+                     cache->plan_dev, static_cast<const float*>(workspace), static_cast<_Float16*>(out), lse);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_merge launch failed: %s", hipGetErrorString(e));
   return COCKTAIL_OK;
