@@ -167,7 +167,8 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  *   lse        DEVICE fp32 [B][Hq] natural-log-sum-exp of the scaled logits
  *              (-inf for an empty sequence), or NULL
  *   workspace  DEVICE, workspace_bytes >= sizes.workspace_bytes, 16-byte aligned;
- *              contents need not be initialised and are overwritten
+ *              contents need not be initialised and are overwritten.  Calls that
+ *              share a workspace must not overlap in time.
  *
  * The cache is not modified.  Errors: EINVAL, EUNSUPPORTED (head_dim != 128,
  * Hq/Hkv > COCKTAIL_MAX_Q_PER_KV), EALIGN, ENOSPACE, EHIP.

@@ -12,7 +12,7 @@ import os
 import torch  # noqa: F401  (must be imported before the library is loaded)
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libcocktail.so")
+LIB_PATH = os.environ.get("COCKTAIL_LIB", os.path.join(HERE, "libcocktail.so"))
 
 NUM_CLASSES = 3
 TOKENS_PER_BLOCK = 64

@@ -26,12 +26,12 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = True, extra: list[str] | None = None) -> str:
-    cmd = [hipcc(), *FLAGS, *(extra or []), *[os.path.join(CSRC, s) for s in SOURCES], "-o", LIB]
+def build(verbose: bool = True, extra: list[str] | None = None, out: str = LIB) -> str:
+    cmd = [hipcc(), *FLAGS, *(extra or []), *[os.path.join(CSRC, s) for s in SOURCES], "-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

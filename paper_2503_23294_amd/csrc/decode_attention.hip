@@ -2,32 +2,31 @@
 // and FP16 classes of the packed cache.
 //
 // Design (gfx950, wave64):
-//  * The packed cache of a layer is one long stream of 64-token blocks ordered by
-//    (sequence, kv head, class, block).  The host planner cuts that stream into
-//    `num_workers` contiguous ranges of equal bytes; workgroup w streams range w.
-//    Every workgroup therefore moves the same number of bytes whatever the class
-//    mix is, and a range that crosses a (sequence, head) boundary simply emits one
-//    partial state per (sequence, head) it touches.
-//  * Inside a wave, lane i owns token i of the current block.  The block layout
-//    stores the j-th 16-byte piece of all 64 tokens contiguously, so every load is
-//    one fully coalesced 1 KiB global_load_dwordx4 per wave and the q.k dot product
-//    of a token never leaves its lane: the query sits in scalar registers and feeds
-//    v_dot2 as the uniform operand.  No cross-lane traffic exists in the steady
-//    state; lanes are merged only when a partial state is flushed.
+//  * The packed cache of a layer is one long stream of 64-token blocks.  The host
+//    planner cuts that stream into `num_workers` contiguous ranges of equal cost;
+//    workgroup w streams range w and emits one partial softmax state per
+//    (sequence, kv head) it touches.
+//  * Inside a wave a token is owned by a PAIR of lanes: lane l works on token
+//    l % 32 of a 32-token unit and on channels [64*(l/32), 64*(l/32)+64).  The block
+//    layout stores the j-th 16-byte piece of all 64 tokens contiguously, so each
+//    half-wave reads one contiguous 512-byte run per load instruction, and the q.k
+//    dot product needs a single cross-lane add per token.  A lane keeps 64 output
+//    accumulators and its half of the query in registers; the whole kernel stays
+//    far below 256 VGPRs so that two waves share every SIMD and one wave's loads
+//    hide behind the other's arithmetic.
 //  * Codes are expanded without any conversion: a code field masked out of a
 //    half-word IS an fp16 subnormal of value code * 2^(pos-24), which v_dot2_f32_f16
 //    and v_fma_mix_f32 consume exactly; the power of two is folded into per-group
 //    factors.  Dequantisation is folded too:
 //      q.k^      = sum_g scale_g * (q.code)_g + zero_g * sum(q_g)
 //      sum p v^  = sum_t (p_t scale_tg) code_t + sum_t p_t zero_tg
-//  * Loads are software pipelined by hand: the V blocks of a sub-split are in flight
-//    while its logits are computed, and the K blocks of the next sub-split while the
-//    V blocks are accumulated.
-//  * Softmax is online per lane (each lane is its own split): logits of J blocks,
-//    one lazy rescale when the lane's reference maximum grows by more than 2^8,
-//    then the V pass.  (m, l, o[D]) partials go to the workspace and a second small
-//    kernel merges them exactly (the softmax-weighted sum does not depend on how
-//    tokens are grouped, Eq. 4-5).
+//  * Loads go through buffer resources (one VGPR of address per lane) and are
+//    software pipelined by hand: J register stages of K units and J of V units are
+//    refilled one loop iteration ahead of the arithmetic.
+//  * Softmax is online per lane pair: logits of J units, one lazy rescale when the
+//    reference maximum grows by more than 2^8, then the V pass.  (m, l, o[D])
+//    partials go to the workspace and a second small kernel merges them exactly
+//    (the softmax-weighted sum does not depend on how tokens are grouped, Eq. 4-5).
 //  * Grouped-query attention: the Hq/Hkv query heads of a kv head run as separate
 //    waves of one workgroup on the same blocks, so the second to last read hits cache.
 #include <hip/hip_runtime.h>
@@ -40,24 +39,44 @@
 namespace cocktail {
 
 constexpr int D = 128;
+constexpr int DH = D / 2;                   // channels per lane
+constexpr int UT = 32;                      // tokens per unit (half a block)
 constexpr float kNegBig = -1.0e30f;
 constexpr float kRescaleThreshold = 8.0f;   // log2 units
 constexpr float kTwo24 = 16777216.0f;
-
-typedef const __attribute__((address_space(4))) uint32_t* const_u32_ptr;
+#ifndef COCKTAIL_J2
+#define COCKTAIL_J2 4
+#endif
+#ifndef COCKTAIL_J4
+#define COCKTAIL_J4 2
+#endif
+#ifndef COCKTAIL_J16
+#define COCKTAIL_J16 1
+#endif
+constexpr int J2 = COCKTAIL_J2;    // INT2 units in flight per wave
+constexpr int J4 = COCKTAIL_J4;    // INT4 units in flight per wave
+constexpr int J16 = COCKTAIL_J16;  // FP16 units in flight per wave
 
 struct DecodeParams {
-  const void* plan;
+  const WorkerRec* recs;    // [num_workers + num_items]: static ranges, then the small items
+  const Segment* segs;      // [num_segments]
+  const int32_t* bh_pid;    // [B*Hkv][3][2][2] partial id ranges per class and part
   const uint32_t* q;        // fp16 [B][Hq][D] viewed as dwords
   const char* k[3];
   const char* v[3];
   float* ws;                // [num_partials][rep][D + 2]
+  _Float16* out;            // [B][Hq][D]
+  float* lse;               // [B][Hq] or NULL
   float scale_log2;         // sm_scale * log2(e)
+  int32_t rep, num_q_heads, num_kv_heads;
+#ifdef COCKTAIL_TRACE
+  uint64_t* trace;          // [num_workers][4]: start, end (100 MHz ticks), hw id, xcc id
+#endif
 };
 
 // A run of blocks is addressed through a buffer resource: every load is
-// buffer_load(resource, lane offset in a VGPR, block/piece offset in an SGPR), so a lane needs
-// one address register for the whole kernel, and reads past `bytes` return zero instead of faulting.
+// buffer_load(resource, lane offset in a VGPR, unit/piece offset in an SGPR), so a lane needs
+// one address register per tensor kind, and reads past `bytes` return zero instead of faulting.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const char* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, bytes, 0x00020000);
@@ -80,13 +99,28 @@ __device__ __forceinline__ float fma_hi(float a, uint32_t hv, float acc) {
 
 __device__ __forceinline__ void sched_fence() { __builtin_amdgcn_sched_barrier(0); }
 
+// Marks a value as wave-uniform (it is: everything derived from the plan is), so that it lives in
+// scalar registers and buffer loads need no per-lane resource handling.
+__device__ __forceinline__ int uni(int x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ const char* uni(const char* p) {
+  const uint64_t v = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(uint32_t(v)), hi = __builtin_amdgcn_readfirstlane(uint32_t(v >> 32));
+  return reinterpret_cast<const char*>((uint64_t(hi) << 32) | lo);
+}
+__device__ __forceinline__ Segment uni(const Segment& x) {
+  Segment y;
+  y.b = uni(x.b), y.h = uni(x.h), y.cls = uni(x.cls), y.ntok = uni(x.ntok);
+  y.blk0 = uni(x.blk0), y.nblk = uni(x.nblk), y.gblk0 = uni(x.gblk0), y.bh = uni(x.bh);
+  return y;
+}
+
 // Zero-instruction anchor: the value must exist in a VGPR at this point of the program order.
 __device__ __forceinline__ void pin(float& x) { asm volatile("" : "+v"(x)); }
 
-template <int G>
+template <int NGH>
 struct LaneState {
-  float acc[D];        // sum_t p_t * (scale * code | value)
-  float zacc[D / G];   // sum_t p_t * zero_tg
+  float acc[DH];       // sum_t p_t * (scale * code | value) for this lane's 64 channels
+  float zacc[NGH];     // sum_t p_t * zero_tg for this lane's groups
   float m, l;
 };
 
@@ -97,75 +131,82 @@ struct LaneState {
 // (INT2) or 2*half + k (INT4).
 template <int BITS, int G>
 struct QuantClass {
-  static constexpr int PIECES = D * BITS / 128;
+  static constexpr int PH = D * BITS / 256;         // 16-byte pieces per lane and unit
   static constexpr int NG = D / G;
+  static constexpr int NGH = NG >= 2 ? NG / 2 : 1;  // groups a lane touches
+  static constexpr int GL = G < DH ? G : DH;        // channels of a lane that share one group
   static constexpr int CPW = 32 / BITS;             // channels per word
   static constexpr int NPOS = 8 / BITS;             // fields per byte: 4 (INT2) or 2 (INT4)
   static constexpr int ROWB = D * BITS / 8;
   static constexpr int BLOCKB = kTB * (ROWB + 4 * NG);
+  static constexpr int J = BITS == 2 ? J2 : J4;
   static constexpr uint32_t MASK0 = (BITS == 2) ? 0x00030003u : 0x000F000Fu;
 
-  struct Stage {              // one lane's share of one block of K or V
-    u32x4 pc[PIECES];
-    uint32_t meta[NG];
+  struct Stage {              // one lane's share of one unit of K or V
+    u32x4 pc[PH];
+    uint32_t meta[NGH];
   };
 
-  // `boff` = byte offset of the block inside the run, `lane16` = lane * 16
-  __device__ static __forceinline__ void load(Stage& s, rsrc_t rs, uint32_t boff, uint32_t lane16) {
+  // per-lane byte offsets of the code pieces and of the scale/zero pairs inside a unit
+  __device__ static __forceinline__ uint32_t code_voff(int t, int h) { return (PH * h * kTB + t) * 16u; }
+  __device__ static __forceinline__ uint32_t meta_voff(int t, int h) {
+    return NG >= 2 ? (t * NG + h * NGH) * 4u : t * 4u;
+  }
+
+  // unit u of the run = tokens [32u, 32u+32): block u/2, first or second half of its token slots
+  __device__ static __forceinline__ void load(Stage& s, rsrc_t rs, int u, uint32_t vc, uint32_t vm) {
+    const uint32_t boff = uint32_t(u >> 1) * BLOCKB;
+    const uint32_t sub = uint32_t(u & 1);
 #pragma unroll
-    for (int p = 0; p < PIECES; ++p) s.pc[p] = load16(rs, lane16, boff + p * (kTB * 16));
-    const uint32_t moff = boff + kTB * ROWB;
-    if constexpr (NG == 4) {
-      const u32x4 t = __builtin_amdgcn_raw_buffer_load_b128(rs, lane16, moff, 0);
-      s.meta[0] = t.x, s.meta[1] = t.y, s.meta[2] = t.z, s.meta[3] = t.w;
-    } else if constexpr (NG == 2) {
-      const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, lane16 >> 1, moff, 0);
+    for (int p = 0; p < PH; ++p) s.pc[p] = load16(rs, vc, boff + sub * (UT * 16) + p * (kTB * 16));
+    const uint32_t moff = boff + kTB * ROWB + sub * (UT * 4 * NG);
+    if constexpr (NGH == 2) {
+      const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, vm, moff, 0);
       s.meta[0] = t.x, s.meta[1] = t.y;
     } else {
-      s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, lane16 >> 2, moff, 0);
+      s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, vm, moff, 0);
     }
   }
 
-  // logit (log2 units) of this lane's token
-  __device__ static __forceinline__ float logit(const Stage& s, const uint32_t (&q)[D / 2],
-                                                const float (&qsum)[NG], float scale_log2) {
-    float ga[NG][NPOS];
+  // this lane's half of q.k^ (natural units, before the softmax scale)
+  __device__ static __forceinline__ float half_logit(const Stage& s, const uint32_t (&q)[DH / 2],
+                                                     const float (&qsum)[NGH]) {
+    float ga[NGH][NPOS];
 #pragma unroll
-    for (int g = 0; g < NG; ++g)
+    for (int g = 0; g < NGH; ++g)
 #pragma unroll
       for (int k = 0; k < NPOS; ++k) ga[g][k] = 0.f;
 #pragma unroll
-    for (int p = 0; p < PIECES; ++p)
+    for (int p = 0; p < PH; ++p)
 #pragma unroll
       for (int wi = 0; wi < 4; ++wi) {
-        const int cb = (p * 4 + wi) * CPW;          // first channel of the word
+        const int cb = (p * 4 + wi) * CPW;          // first local channel of the word
         const uint32_t w0 = s.pc[p][wi];
         const uint32_t w1 = w0 >> 8;
 #pragma unroll
         for (int k = 0; k < NPOS; ++k) {
           const uint32_t mask = MASK0 << (BITS * k);
-          ga[cb / G][k] = dot2(q[cb / 2 + k], w0 & mask, ga[cb / G][k]);
-          ga[cb / G][k] = dot2(q[cb / 2 + NPOS + k], w1 & mask, ga[cb / G][k]);
+          ga[cb / GL][k] = dot2(q[cb / 2 + k], w0 & mask, ga[cb / GL][k]);
+          ga[cb / GL][k] = dot2(q[cb / 2 + NPOS + k], w1 & mask, ga[cb / GL][k]);
         }
-        sched_fence();   // keeps the masked temporaries of one word from piling up across words
       }
     float sum = 0.f;
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
+    for (int g = 0; g < NGH; ++g) {
       float t = ga[g][NPOS - 1];
 #pragma unroll
       for (int k = NPOS - 2; k >= 0; --k) t = t * (1.0f / float(1 << BITS)) + ga[g][k];
-      // t = sum_d q_d code_d * 2^-24
+      // t = sum_d q_d code_d * 2^-24 over the lane's channels of group g
       const h2 mz = as_h2(s.meta[g]);
       sum += (static_cast<float>(mz.x) * kTwo24) * t + static_cast<float>(mz.y) * qsum[g];
     }
-    return sum * scale_log2;
+    return sum;
   }
 
-  __device__ static __forceinline__ void accumulate(const Stage& s, float p, LaneState<G>& st) {
-    float ps[NG][NPOS];
+  __device__ static __forceinline__ void accumulate(const Stage& s, float p, LaneState<NGH>& st) {
+    float ps[NGH][NPOS];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
+    for (int g = 0; g < NGH; ++g) {
       const h2 mz = as_h2(s.meta[g]);
       float f = p * static_cast<float>(mz.x) * kTwo24;
 #pragma unroll
@@ -176,7 +217,7 @@ struct QuantClass {
       st.zacc[g] += p * static_cast<float>(mz.y);
     }
 #pragma unroll
-    for (int p_ = 0; p_ < PIECES; ++p_)
+    for (int p_ = 0; p_ < PH; ++p_)
 #pragma unroll
       for (int wi = 0; wi < 4; ++wi) {
         const int cb = (p_ * 4 + wi) * CPW;
@@ -186,24 +227,72 @@ struct QuantClass {
         for (int k = 0; k < NPOS; ++k) {
           const uint32_t mask = MASK0 << (BITS * k);
           const uint32_t x0 = w0 & mask, x1 = w1 & mask;
-          const float f = ps[cb / G][k];
+          const float f = ps[cb / GL][k];
           st.acc[cb + 2 * k] = fma_lo(f, x0, st.acc[cb + 2 * k]);
           st.acc[cb + 2 * k + 1] = fma_hi(f, x0, st.acc[cb + 2 * k + 1]);
           st.acc[cb + 2 * (NPOS + k)] = fma_lo(f, x1, st.acc[cb + 2 * (NPOS + k)]);
           st.acc[cb + 2 * (NPOS + k) + 1] = fma_hi(f, x1, st.acc[cb + 2 * (NPOS + k) + 1]);
         }
         // Pin the word's accumulators here: without it the optimiser sinks all multiply-adds of a
-        // stage below the unpacking of every word and the masked temporaries spill.
+        // stage below the unpacking of every word and the masked temporaries pile up.
 #pragma unroll
         for (int i = 0; i < CPW; ++i) pin(st.acc[cb + i]);
-        sched_fence();
       }
   }
 };
 
+// ---------------------------------------------------------------------- FP16 class
+template <int G>
+struct HalfClass {
+  static constexpr int PH = 8;
+  static constexpr int NG = D / G;
+  static constexpr int NGH = NG >= 2 ? NG / 2 : 1;
+  static constexpr int BLOCKB = kTB * 2 * D;
+  static constexpr int J = J16;
+
+  struct Stage {
+    u32x4 pc[PH];
+  };
+  __device__ static __forceinline__ uint32_t code_voff(int t, int h) { return (PH * h * kTB + t) * 16u; }
+  __device__ static __forceinline__ uint32_t meta_voff(int, int) { return 0; }
+
+  __device__ static __forceinline__ void load(Stage& s, rsrc_t rs, int u, uint32_t vc, uint32_t) {
+    const uint32_t boff = uint32_t(u >> 1) * BLOCKB + uint32_t(u & 1) * (UT * 16);
+#pragma unroll
+    for (int p = 0; p < PH; ++p) s.pc[p] = load16(rs, vc, boff + p * (kTB * 16));
+  }
+
+  __device__ static __forceinline__ float half_logit(const Stage& s, const uint32_t (&q)[DH / 2],
+                                                     const float (&)[NGH]) {
+    float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+    for (int p = 0; p < PH; ++p) {
+      a0 = dot2(q[p * 4 + 0], s.pc[p][0], a0);
+      a1 = dot2(q[p * 4 + 1], s.pc[p][1], a1);
+      a0 = dot2(q[p * 4 + 2], s.pc[p][2], a0);
+      a1 = dot2(q[p * 4 + 3], s.pc[p][3], a1);
+    }
+    return a0 + a1;
+  }
+
+  __device__ static __forceinline__ void accumulate(const Stage& s, float p, LaneState<NGH>& st) {
+#pragma unroll
+    for (int pi = 0; pi < PH; ++pi) {
+#pragma unroll
+      for (int wi = 0; wi < 4; ++wi) {
+        const int d = (pi * 4 + wi) * 2;
+        st.acc[d] = fma_lo(p, s.pc[pi][wi], st.acc[d]);
+        st.acc[d + 1] = fma_hi(p, s.pc[pi][wi], st.acc[d + 1]);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pin(st.acc[pi * 8 + i]);
+    }
+  }
+};
+
 // One lazy-rescale step of a lane's online softmax followed by p_j = 2^(s_j - m).
-template <int G, int J>
-__device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J], LaneState<G>& st) {
+template <int NGH, int J>
+__device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J], LaneState<NGH>& st) {
   float smax = s[0];
 #pragma unroll
   for (int jj = 1; jj < J; ++jj) smax = fmaxf(smax, s[jj]);
@@ -215,9 +304,9 @@ __device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J],
     st.m = mnew;
     st.l *= alpha;
 #pragma unroll
-    for (int d = 0; d < D; ++d) st.acc[d] *= alpha;
+    for (int d = 0; d < DH; ++d) st.acc[d] *= alpha;
 #pragma unroll
-    for (int g = 0; g < D / G; ++g) st.zacc[g] *= alpha;
+    for (int g = 0; g < NGH; ++g) st.zacc[g] *= alpha;
   }
 #pragma unroll
   for (int jj = 0; jj < J; ++jj) {
@@ -226,245 +315,269 @@ __device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J],
   }
 }
 
-// Process `nb` (>= 1) consecutive blocks of a quantised class; `valid` = valid tokens in
-// that range (only the last block can be partial).  J register stages rotate between K and
-// V: as soon as the logit of a K block has been computed its registers receive the V block
-// of the same tokens, and as soon as that has been accumulated they receive the K block J
-// positions further on.  Blocks past the range are replaced by the last one and masked, so
-// the loop body has no branches around the loads.
-template <class CLS, int G, int J>
-__device__ __forceinline__ void process_quant(const char* kblk, const char* vblk, int nb, int valid, int lane,
-                                              const uint32_t (&q)[D / 2], const float (&qsum)[D / G],
-                                              float scale_log2, LaneState<G>& st) {
-  typename CLS::Stage sg[J];
-  const int last = nb - 1;
-  const uint32_t lane16 = lane * 16u;
+// Process `nb` (>= 1) consecutive blocks of one class; `valid` = valid tokens in that run
+// (only the last block can be partial).  J register stages hold K units and J hold V units,
+// both one loop iteration ahead of the arithmetic: as soon as a stage has been consumed it
+// is refilled with the unit J positions further on.  Units past the run are replaced by the
+// last one and masked, so the loop body has no branches around the loads.
+template <class CLS, int NGH>
+__device__ __forceinline__ void process_run(const char* kblk, const char* vblk, int nb, int valid, int t, int h,
+                                            const uint32_t (&q)[DH / 2], const float (&qsum)[NGH],
+                                            float scale_log2, LaneState<NGH>& st) {
+  constexpr int J = CLS::J;
+  kblk = uni(kblk), vblk = uni(vblk), nb = uni(nb), valid = uni(valid);
+#ifdef COCKTAIL_ROTATE
+  typename CLS::Stage sgs[J];
+  const int nu = 2 * nb;
+  const int last = nu - 1;
+  const uint32_t vc = CLS::code_voff(t, h), vm = CLS::meta_voff(t, h);
   const rsrc_t krs = make_rsrc(kblk, uint32_t(nb) * CLS::BLOCKB), vrs = make_rsrc(vblk, uint32_t(nb) * CLS::BLOCKB);
 #pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::load(sg[jj], krs, uint32_t(min(jj, last)) * CLS::BLOCKB, lane16);
+  for (int jj = 0; jj < J; ++jj) CLS::load(sgs[jj], krs, min(jj, last), vc, vm);
 #pragma unroll 1
-  for (int j0 = 0; j0 < nb; j0 += J) {
+  for (int u0 = 0; u0 < nu; u0 += J) {
     float s[J], p[J];
 #pragma unroll
     for (int jj = 0; jj < J; ++jj) {
-      const float t = CLS::logit(sg[jj], q, qsum, scale_log2);
-      s[jj] = ((j0 + jj) * kTB + lane < valid) ? t : -INFINITY;
+      s[jj] = CLS::half_logit(sgs[jj], q, qsum);
       sched_fence();
-      CLS::load(sg[jj], vrs, uint32_t(min(j0 + jj, last)) * CLS::BLOCKB, lane16);
+      CLS::load(sgs[jj], vrs, min(u0 + jj, last), vc, vm);
       sched_fence();
     }
-    softmax_step<G, J>(s, p, st);
 #pragma unroll
     for (int jj = 0; jj < J; ++jj) {
-      CLS::accumulate(sg[jj], p[jj], st);
+      const float full = (s[jj] + __shfl_xor(s[jj], 32)) * scale_log2;
+      s[jj] = ((u0 + jj) * UT + t < valid) ? full : -INFINITY;
+    }
+    softmax_step<NGH, J>(s, p, st);
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      CLS::accumulate(sgs[jj], p[jj], st);
       sched_fence();
-      CLS::load(sg[jj], krs, uint32_t(min(j0 + J + jj, last)) * CLS::BLOCKB, lane16);
+      CLS::load(sgs[jj], krs, min(u0 + J + jj, last), vc, vm);
       sched_fence();
     }
   }
 }
-
-// ---------------------------------------------------------------------- FP16 class
-// A block is 16 pieces of K and 16 of V per lane.  Two 8-piece buffers rotate:
-// K.lo K.hi | V.lo V.hi | next K.lo ..., each refilled as soon as it has been consumed.
-template <int G>
-__device__ __forceinline__ void process_half(const char* kblk, const char* vblk, int nb, int valid, int lane,
-                                             const uint32_t (&q)[D / 2], float scale_log2, LaneState<G>& st) {
-  constexpr int BLOCKB = kTB * 2 * D;
-  constexpr int HP = 8;   // pieces per buffer
-  u32x4 a[HP], b[HP];
-  const uint32_t lane16 = lane * 16u;
-  const rsrc_t krs = make_rsrc(kblk, uint32_t(nb) * BLOCKB), vrs = make_rsrc(vblk, uint32_t(nb) * BLOCKB);
-  auto fill = [&](u32x4 (&buf)[HP], rsrc_t rs, uint32_t boff, int half) {
+#else
+  typename CLS::Stage ks[J], vs[J];
+  const int nu = 2 * nb;
+  const int last = nu - 1;
+  const uint32_t vc = CLS::code_voff(t, h), vm = CLS::meta_voff(t, h);
+  const rsrc_t krs = make_rsrc(kblk, uint32_t(nb) * CLS::BLOCKB), vrs = make_rsrc(vblk, uint32_t(nb) * CLS::BLOCKB);
 #pragma unroll
-    for (int p = 0; p < HP; ++p) buf[p] = load16(rs, lane16, boff + (half * HP + p) * (kTB * 16));
-  };
-  auto qk = [&](const u32x4 (&buf)[HP], int half, float& a0, float& a1) {
+  for (int jj = 0; jj < J; ++jj) CLS::load(ks[jj], krs, min(jj, last), vc, vm);
 #pragma unroll
-    for (int p = 0; p < HP; ++p) {
-      const int qb = (half * HP + p) * 4;
-      a0 = dot2(q[qb + 0], buf[p][0], a0);
-      a1 = dot2(q[qb + 1], buf[p][1], a1);
-      a0 = dot2(q[qb + 2], buf[p][2], a0);
-      a1 = dot2(q[qb + 3], buf[p][3], a1);
-    }
-  };
-  auto pv = [&](const u32x4 (&buf)[HP], int half, float p) {
-#pragma unroll
-    for (int pi = 0; pi < HP; ++pi)
-#pragma unroll
-      for (int wi = 0; wi < 4; ++wi) {
-        const int d = ((half * HP + pi) * 4 + wi) * 2;
-        st.acc[d] = fma_lo(p, buf[pi][wi], st.acc[d]);
-        st.acc[d + 1] = fma_hi(p, buf[pi][wi], st.acc[d + 1]);
-      }
-  };
-  const int last = nb - 1;
-  fill(a, krs, 0, 0);
-  fill(b, krs, 0, 1);
+  for (int jj = 0; jj < J; ++jj) CLS::load(vs[jj], vrs, min(jj, last), vc, vm);
 #pragma unroll 1
-  for (int j = 0; j < nb; ++j) {
-    const uint32_t vb = uint32_t(j) * BLOCKB;
-    const uint32_t kn = uint32_t(min(j + 1, last)) * BLOCKB;
-    float a0 = 0.f, a1 = 0.f;
-    qk(a, 0, a0, a1);
-    sched_fence();
-    fill(a, vrs, vb, 0);
-    sched_fence();
-    qk(b, 1, a0, a1);
-    sched_fence();
-    fill(b, vrs, vb, 1);
-    sched_fence();
-    float s[1], p[1];
-    s[0] = (j * kTB + lane < valid) ? (a0 + a1) * scale_log2 : -INFINITY;
-    softmax_step<G, 1>(s, p, st);
-    pv(a, 0, p[0]);
-    sched_fence();
-    fill(a, krs, kn, 0);
-    sched_fence();
-    pv(b, 1, p[0]);
-    sched_fence();
-    fill(b, krs, kn, 1);
-    sched_fence();
+  for (int u0 = 0; u0 < nu; u0 += J) {
+    float s[J], p[J];
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      s[jj] = CLS::half_logit(ks[jj], q, qsum);
+      sched_fence();
+      CLS::load(ks[jj], krs, min(u0 + J + jj, last), vc, vm);
+      sched_fence();
+    }
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      const float full = (s[jj] + __shfl_xor(s[jj], 32)) * scale_log2;   // both halves of the token
+      s[jj] = ((u0 + jj) * UT + t < valid) ? full : -INFINITY;
+    }
+    softmax_step<NGH, J>(s, p, st);
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      CLS::accumulate(vs[jj], p[jj], st);
+      sched_fence();
+      CLS::load(vs[jj], vrs, min(u0 + J + jj, last), vc, vm);
+      sched_fence();
+    }
+  }
+}
+#endif
+
+// Writes this wave's partial state `pid`: (m, l, o[D]) reduced over its lanes.
+template <int NGH, int GL>
+__device__ __forceinline__ void flush_partial(const DecodeParams& prm, const LaneState<NGH>& st, float* red, int pid,
+                                              int r, int lane) {
+  const int rep = prm.rep;
+  float mw = st.m;
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) mw = fmaxf(mw, __shfl_xor(mw, o));
+  const float f = __builtin_amdgcn_exp2f(st.m - mw);
+  float lw = st.l * f;
+#pragma unroll
+  for (int o = 16; o > 0; o >>= 1) lw += __shfl_xor(lw, o);
+  float* out = prm.ws + (int64_t(pid) * rep + r) * (D + kPartialFloats);
+  if (lane == 0) {
+    out[0] = mw;
+    out[1] = lw;
+  }
+  float(*tile)[17] = reinterpret_cast<float(*)[17]>(red + r * 64 * 17);
+#pragma unroll
+  for (int ch = 0; ch < DH / 16; ++ch) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      const int d = ch * 16 + c;
+      tile[lane][c] = (st.acc[d] + st.zacc[d / GL]) * f;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // lane (c, quarter) adds 16 rows; quarters 0,1 hold channel half 0 and quarters 2,3 half 1
+    const int c = lane & 15, quarter = lane >> 4;
+    float sum = 0.f;
+#pragma unroll
+    for (int row = 0; row < 16; ++row) sum += tile[quarter * 16 + row][c];
+    sum += __shfl_xor(sum, 16);
+    if ((quarter & 1) == 0) out[kPartialFloats + (quarter >> 1) * DH + ch * 16 + c] = sum;
   }
 }
 
-template <int G>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void decode_partial_kernel(DecodeParams prm) {
+// Streams the consecutive segments of class CLS that start at `sg` inside the worker's block
+// range [g, g1); returns with `sg` on the first segment of another class (or past the range).
+// The accumulators live and die inside this function, one instance per class.
+template <class CLS, int G>
+__device__ __forceinline__ void run_class(const DecodeParams& prm, int cls, Segment& sg, int& s, int& g, int g1,
+                                          int& pid, float* red, int r, int lane) {
   constexpr int NG = D / G;
-  extern __shared__ float red[];   // [rep][64][17]: one 16-channel reduction tile per wave
-
-  const PlanHeader* hd = static_cast<const PlanHeader*>(prm.plan);
-  const int w = blockIdx.x;
-  const int lane = threadIdx.x & 63;
-  const int r = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // query head inside the group
-  const int rep = hd->rep;
-  const int32_t* wg = plan_array<int32_t>(prm.plan, hd->off_worker_gblk);
-  int g = wg[w];
-  const int g1 = wg[w + 1];
-  if (g >= g1) return;
-  int s = plan_array<int32_t>(prm.plan, hd->off_worker_seg)[w];
-  int pid = plan_array<int32_t>(prm.plan, hd->off_worker_pid)[w];
-  const Segment* segs = plan_array<Segment>(prm.plan, hd->off_segments);
-
-  LaneState<G> st;
-  uint32_t q[D / 2];
-  float qsum[NG];
-  int cur_bh = -1;
-
-  auto reset = [&]() {
-#pragma unroll
-    for (int d = 0; d < D; ++d) st.acc[d] = 0.f;
-#pragma unroll
-    for (int gq = 0; gq < NG; ++gq) st.zacc[gq] = 0.f;
-    st.m = kNegBig;
-    st.l = 0.f;
-  };
-
-  auto flush = [&]() {
-    // merge the 64 lane states: common maximum, then sums
-    float mw = st.m;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mw = fmaxf(mw, __shfl_xor(mw, o));
-    const float f = __builtin_amdgcn_exp2f(st.m - mw);
-    float lw = st.l * f;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) lw += __shfl_xor(lw, o);
-    float* out = prm.ws + (int64_t(pid) * rep + r) * (D + kPartialFloats);
-    if (lane == 0) {
-      out[0] = mw;
-      out[1] = lw;
-    }
-    float(*tile)[17] = reinterpret_cast<float(*)[17]>(red + r * 64 * 17);
-#pragma unroll
-    for (int ch = 0; ch < D / 16; ++ch) {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int c = 0; c < 16; ++c) {
-        const int d = ch * 16 + c;
-        tile[lane][c] = (st.acc[d] + st.zacc[d / G]) * f;
-      }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      const int c = lane & 15, quarter = lane >> 4;
-      float sum = 0.f;
-#pragma unroll
-      for (int row = 0; row < 16; ++row) sum += tile[quarter * 16 + row][c];
-      sum += __shfl_xor(sum, 16);
-      sum += __shfl_xor(sum, 32);
-      if (lane < 16) out[kPartialFloats + ch * 16 + c] = sum;
-    }
-  };
-
-  while (g < g1) {
-    const Segment sg = segs[s];
+  constexpr int NGH = NG >= 2 ? NG / 2 : 1;
+  constexpr int GL = G < DH ? G : DH;
+  const int t = lane & 31, h = lane >> 5;
+  const int rep = prm.rep;
+  LaneState<NGH> st;
+  uint32_t q[DH / 2];
+  float qsum[NGH];
+  int cur_bh = -1, cur_b = 0, cur_h = 0;
+  while (true) {
     if (sg.bh != cur_bh) {
       if (cur_bh >= 0) {
-        flush();
+        flush_partial<NGH, GL>(prm, st, red, pid, r, lane);
         ++pid;
       }
-      cur_bh = sg.bh;
-      reset();
+      cur_bh = sg.bh, cur_b = sg.b, cur_h = sg.h;
+#pragma unroll
+      for (int d = 0; d < DH; ++d) st.acc[d] = 0.f;
+#pragma unroll
+      for (int gq = 0; gq < NGH; ++gq) st.zacc[gq] = 0.f;
+      st.m = kNegBig;
+      st.l = 0.f;
       const int hq = sg.h * rep + r;
-      const_u32_ptr qp = (const_u32_ptr)(prm.q + (int64_t(sg.b) * hd->num_q_heads + hq) * (D / 2));
+      const u32x4* qp = reinterpret_cast<const u32x4*>(prm.q + (int64_t(sg.b) * prm.num_q_heads + hq) * (D / 2) +
+                                                       h * (DH / 2));
 #pragma unroll
-      for (int i = 0; i < D / 2; ++i) q[i] = qp[i];
+      for (int i = 0; i < DH / 8; ++i) {
+        const u32x4 v = qp[i];
+        q[4 * i] = v.x, q[4 * i + 1] = v.y, q[4 * i + 2] = v.z, q[4 * i + 3] = v.w;
+      }
 #pragma unroll
-      for (int gq = 0; gq < NG; ++gq) {
+      for (int gq = 0; gq < NGH; ++gq) {
         float a = 0.f;
 #pragma unroll
-        for (int i = 0; i < G / 2; ++i) a = dot2(q[gq * (G / 2) + i], 0x3C003C00u, a);   // (1.0, 1.0)
+        for (int i = 0; i < GL / 2; ++i) a = dot2(q[gq * (GL / 2) + i], 0x3C003C00u, a);   // (1.0, 1.0)
         qsum[gq] = a;
       }
     }
     const int jb = g - sg.gblk0;
     const int je = min(sg.nblk, g1 - sg.gblk0);
     const int nb = je - jb;
-    if (nb <= 0) break;   // cannot happen with a plan written by cocktail_plan; guarantees termination
-    // valid tokens of this range: up to the end of the segment or of the range, whichever comes first
+    if (nb <= 0) {   // cannot happen with a plan written by cocktail_plan; guarantees termination
+      g = g1;
+      break;
+    }
+    // valid tokens of this run: up to the end of the segment or of the run, whichever comes first
     const int valid = min(sg.ntok - jb * kTB, nb * kTB);
     const int64_t first = int64_t(sg.blk0 + jb);
-    if (sg.cls == 0) {
-      using C = QuantClass<2, G>;
-      process_quant<C, G, 4>(prm.k[0] + first * C::BLOCKB, prm.v[0] + first * C::BLOCKB, nb, valid,
-                                             lane, q, qsum, prm.scale_log2, st);
-    } else if (sg.cls == 1) {
-      using C = QuantClass<4, G>;
-      process_quant<C, G, 2>(prm.k[1] + first * C::BLOCKB, prm.v[1] + first * C::BLOCKB, nb, valid, lane, q, qsum,
-                             prm.scale_log2, st);
-    } else {
-      constexpr int BB = kTB * 2 * D;
-      process_half<G>(prm.k[2] + first * BB, prm.v[2] + first * BB, nb, valid, lane, q, prm.scale_log2, st);
-    }
+    process_run<CLS, NGH>(prm.k[cls] + first * CLS::BLOCKB, prm.v[cls] + first * CLS::BLOCKB, nb, valid, t, h, q,
+                          qsum, prm.scale_log2, st);
     g = sg.gblk0 + je;
-    ++s;
+    if (g >= g1) break;
+    sg = uni(prm.segs[++s]);
+    if (sg.cls != cls) break;
   }
-  flush();
+  flush_partial<NGH, GL>(prm, st, red, pid, r, lane);
+  ++pid;
+}
+
+// Streams one work item: the block range [g0, g1) of the global order.
+template <int G>
+__device__ __forceinline__ void process_item(const DecodeParams& prm, const WorkerRec& rec, float* red, int r,
+                                             int lane) {
+  int g = uni(rec.g0);
+  const int g1 = uni(rec.g1);
+  if (g >= g1) return;
+  int s = uni(rec.seg0);
+  int pid = uni(rec.pid0);
+  Segment sg = uni(rec.first);
+  while (g < g1) {
+    if (sg.cls == 0) {
+      run_class<QuantClass<2, G>, G>(prm, 0, sg, s, g, g1, pid, red, r, lane);
+    } else if (sg.cls == 1) {
+      run_class<QuantClass<4, G>, G>(prm, 1, sg, s, g, g1, pid, red, r, lane);
+    } else {
+      run_class<HalfClass<G>, G>(prm, 2, sg, s, g, g1, pid, red, r, lane);
+    }
+  }
+}
+
+// One workgroup per work item.  The first `num_workers` items are large static ranges that fill
+// every wave slot of the chip; items behind them (if the plan has any) are small and the hardware
+// dispatcher hands them out as slots become free.
+template <int G>
+__global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams prm) {
+  extern __shared__ float red[];   // [rep][64][17] reduction tiles
+  const int lane = threadIdx.x & 63;
+  const int r = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // query head inside the group
+#ifdef COCKTAIL_TRACE
+  const uint64_t t_start = __builtin_amdgcn_s_memrealtime();
+#endif
+  process_item<G>(prm, prm.recs[blockIdx.x], red, r, lane);
+#ifdef COCKTAIL_TRACE
+  if (threadIdx.x == 0) {
+    uint64_t* tr = prm.trace + blockIdx.x * 4;
+    tr[0] = t_start;
+    tr[1] = __builtin_amdgcn_s_memrealtime();
+    tr[2] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));    // HW_ID
+    tr[3] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));   // XCC_ID
+  }
+#endif
 }
 
 // Exact merge of the partial states of one (sequence, query head):
-//   M = max m_i,  L = sum l_i 2^(m_i - M),  out = sum o_i 2^(m_i - M) / L.
-// 256 threads: 32 channel quads x 8 slices of the partial list.
-__global__ __launch_bounds__(256) void decode_merge_kernel(const void* plan, const float* ws, _Float16* out,
-                                                           float* lse) {
+//   M = max m_i,  L = sum l_i 2^(m_i - M),  out = sum o_i 2^(m_i - M) / L,  lse = ln2 (M + log2 L).
+// 256 threads: 32 channel quads x 8 slices of the partial list.  A (sequence, query head) without
+// any partial (empty sequence) gets zeros and lse = -inf.
+__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams prm) {
   __shared__ float sm_max[4];
   __shared__ float sm_l[8];
   __shared__ float sm_o[8][D];
-  const PlanHeader* hd = static_cast<const PlanHeader*>(plan);
   const int bhq = blockIdx.x;
-  const int rep = hd->rep;
-  const int b = bhq / hd->num_q_heads;
-  const int hq = bhq - b * hd->num_q_heads;
-  const int bh = b * hd->num_kv_heads + hq / rep;
+  const int rep = prm.rep;
+  const int b = bhq / prm.num_q_heads;
+  const int hq = bhq - b * prm.num_q_heads;
+  const int bh = b * prm.num_kv_heads + hq / rep;
   const int r = hq % rep;
-  const int32_t* bh_pid = plan_array<int32_t>(plan, hd->off_bh_pid);
-  const int p0 = bh_pid[bh], p1 = bh_pid[bh + 1];
+  const int32_t* ranges = prm.bh_pid + bh * 12;   // six [begin, end) ranges: class x (static, dynamic)
+  int n = 0;
+#pragma unroll
+  for (int k = 0; k < 6; ++k) n += ranges[2 * k + 1] - ranges[2 * k];
+  // i-th partial of this head: the six ranges back to back
+  auto pid_of = [&](int i) {
+    int pid = 0;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) {
+      const int len = ranges[2 * k + 1] - ranges[2 * k];
+      if (i >= 0 && i < len) pid = ranges[2 * k] + i;
+      i -= len;
+    }
+    return pid;
+  };
   const int tid = threadIdx.x;
   constexpr int STRIDE = D + kPartialFloats;
   float mx = -INFINITY;
-  for (int p = p0 + tid; p < p1; p += 256) mx = fmaxf(mx, ws[(int64_t(p) * rep + r) * STRIDE]);
+  for (int i = tid; i < n; i += 256) mx = fmaxf(mx, prm.ws[(int64_t(pid_of(i)) * rep + r) * STRIDE]);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
   if ((tid & 63) == 0) sm_max[tid >> 6] = mx;
@@ -472,8 +585,8 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const void* plan, con
   mx = fmaxf(fmaxf(sm_max[0], sm_max[1]), fmaxf(sm_max[2], sm_max[3]));
   const int quad = tid & 31, slice = tid >> 5;
   float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f, big_l = 0.f;
-  for (int p = p0 + slice; p < p1; p += 8) {
-    const float* part = ws + (int64_t(p) * rep + r) * STRIDE;
+  for (int i = slice; i < n; i += 8) {
+    const float* part = prm.ws + (int64_t(pid_of(i)) * rep + r) * STRIDE;
     const float wgt = __builtin_amdgcn_exp2f(part[0] - mx);
     big_l += part[1] * wgt;
     const float2 v0 = *reinterpret_cast<const float2*>(part + kPartialFloats + quad * 4);
@@ -489,8 +602,8 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(const void* plan, con
 #pragma unroll
     for (int sidx = 0; sidx < 8; ++sidx) l += sm_l[sidx], o += sm_o[sidx][tid];
     const bool empty = !(l > 0.f);
-    out[int64_t(bhq) * D + tid] = static_cast<_Float16>(empty ? 0.f : o / l);
-    if (lse && tid == 0) lse[bhq] = empty ? -INFINITY : (mx + log2f(l)) * 0.6931471805599453f;
+    prm.out[int64_t(bhq) * D + tid] = static_cast<_Float16>(empty ? 0.f : o / l);
+    if (prm.lse && tid == 0) prm.lse[bhq] = empty ? -INFINITY : (mx + log2f(l)) * 0.6931471805599453f;
   }
 }
 
@@ -508,7 +621,7 @@ extern "C" int cocktail_default_workers(const cocktail_shape* shape, int32_t* nu
     return fail(COCKTAIL_EHIP, "no HIP device available");
   }
   const int rep = shape->num_q_heads / shape->num_kv_heads;
-  const int waves_per_cu = 4;   // one wave per SIMD, 512 registers each
+  const int waves_per_cu = 8;   // two waves per SIMD at <= 256 VGPRs
   int per_cu = waves_per_cu / rep;
   if (per_cu < 1) per_cu = 1;
   *num_workers = prop.multiProcessorCount * per_cu;
@@ -540,7 +653,10 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
     return fail(COCKTAIL_ENOSPACE, "workspace holds %zu bytes, %lld needed", workspace_bytes,
                 (long long)hd->workspace_bytes);
   DecodeParams p;
-  p.plan = cache->plan_dev;
+  const char* pd = static_cast<const char*>(cache->plan_dev);
+  p.recs = reinterpret_cast<const WorkerRec*>(pd + hd->off_worker_rec);
+  p.segs = reinterpret_cast<const Segment*>(pd + hd->off_segments);
+  p.bh_pid = reinterpret_cast<const int32_t*>(pd + hd->off_bh_pid);
   p.q = static_cast<const uint32_t*>(q);
   for (int c = 0; c < 3; ++c) {
     if (hd->class_bytes[c] > 0 && (!cache->k[c] || !cache->v[c]))
@@ -551,22 +667,28 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
     p.v[c] = static_cast<const char*>(cache->v[c]);
   }
   p.ws = static_cast<float*>(workspace);
+  p.out = static_cast<_Float16*>(out);
+  p.lse = lse;
   if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt(static_cast<float>(shape->head_dim));
   p.scale_log2 = sm_scale * 1.4426950408889634f;
+  p.rep = hd->rep, p.num_q_heads = hd->num_q_heads, p.num_kv_heads = hd->num_kv_heads;
+#ifdef COCKTAIL_TRACE
+  // debugging builds only: the caller provides 32 bytes per worker behind the regular workspace
+  p.trace = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + ((hd->workspace_bytes + 255) & ~int64_t(255)));
+#endif
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (hd->total_gblocks > 0) {
-    const dim3 grid(hd->num_workers, 1, 1), block(64 * hd->rep, 1, 1);
+    const dim3 grid(hd->num_workers + hd->num_items, 1, 1), block(64 * hd->rep, 1, 1);
     const size_t lds = size_t(hd->rep) * 64 * 17 * sizeof(float);
     switch (shape->group_size) {
-      case 32: hipLaunchKernelGGL(decode_partial_kernel<32>, grid, block, lds, st, p); break;
-      case 64: hipLaunchKernelGGL(decode_partial_kernel<64>, grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL(decode_partial_kernel<128>, grid, block, lds, st, p); break;
+      case 32: hipLaunchKernelGGL(decode_attention_kernel<32>, grid, block, lds, st, p); break;
+      case 64: hipLaunchKernelGGL(decode_attention_kernel<64>, grid, block, lds, st, p); break;
+      default: hipLaunchKernelGGL(decode_attention_kernel<128>, grid, block, lds, st, p); break;
     }
     const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_partial launch failed: %s", hipGetErrorString(e));
+    if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_attention launch failed: %s", hipGetErrorString(e));
   }
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(shape->batch * shape->num_q_heads), dim3(256), 0, st,
-                     cache->plan_dev, static_cast<const float*>(workspace), static_cast<_Float16*>(out), lse);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(shape->batch * shape->num_q_heads), dim3(256), 0, st, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_merge launch failed: %s", hipGetErrorString(e));
   return COCKTAIL_OK;

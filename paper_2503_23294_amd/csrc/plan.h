@@ -10,7 +10,7 @@
 namespace cocktail {
 
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
-constexpr uint32_t kPlanVersion = 3;
+constexpr uint32_t kPlanVersion = 8;
 constexpr int kTB = 64;                        // tokens per block
 constexpr int kNumClasses = 3;
 constexpr int kPartialFloats = 2;              // (m, l) in front of the D output values
@@ -20,9 +20,19 @@ struct Segment {
   int32_t b, h, cls, ntok;   // ntok: valid tokens of the whole run (last block may be partial)
   int32_t blk0;              // first block, index into the class buffer
   int32_t nblk;
-  int32_t gblk0;             // first block in the global order (b, h, class, block)
+  int32_t gblk0;             // first block in the global order (static part of every class, then dynamic part)
   int32_t bh;                // b * Hkv + h
 };
+
+// Everything a decode workgroup needs to start streaming, in one 64-byte record.
+struct WorkerRec {
+  int32_t g0, g1;            // global block range [g0, g1)
+  int32_t seg0;              // index of the segment holding g0
+  int32_t pid0;              // first partial id this worker writes
+  Segment first;             // copy of segments[seg0]
+  int32_t pad[4];
+};
+static_assert(sizeof(WorkerRec) == 64, "WorkerRec is one 64-byte line");
 
 struct PlanHeader {
   uint32_t magic, version;
@@ -49,11 +59,10 @@ struct PlanHeader {
   int32_t off_blk_base;       // int32 [B+1][3] first block of sequence b in class buffer c
   int32_t off_nblk;           // int32 [B][3]  blocks per head
   int32_t off_segments;       // Segment [num_segments]
-  int32_t off_worker_gblk;    // int32 [P+1]   global block range of each worker
-  int32_t off_worker_seg;     // int32 [P+1]   segment holding worker_gblk[w]
-  int32_t off_worker_pid;     // int32 [P+1]   first partial id of each worker
-  int32_t off_bh_pid;         // int32 [B*Hkv+1] partial id range of each (b, kv head)
-  int32_t pad1[3];
+  int32_t off_bh_pid;         // int32 [B*Hkv][3][2][2] partial ids [begin, end) of each (b, kv head, class, part)
+  int32_t off_worker_rec;     // WorkerRec [P + Q]: P static ranges, then the Q small items in dispatch order
+  int32_t num_items;          // Q
+  int32_t pad1[4];
 };
 
 template <typename T>
