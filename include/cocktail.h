@@ -183,6 +183,20 @@ int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const 
  */
 int cocktail_default_workers(const cocktail_shape* shape, int32_t* num_workers);
 
+/*
+ * Measurement aid, not a step of the method: enqueues a plain 128-bit streaming read of
+ * `buf` (2048 single-wave workgroups, each over one contiguous range), so that a benchmark
+ * can report the HBM read rate this GPU reaches with loads alone beside the rate of the
+ * decode kernel (whose cost the paper attributes to loading the KV cache, Sec. I).
+ *
+ *   buf         DEVICE, 16-byte aligned, `bytes` >= 16 MiB readable bytes
+ *   sink        DEVICE, 4 bytes the kernel may write
+ *   bytes_read  HOST out: bytes the launch reads (`bytes` rounded down to 16 MiB)
+ *
+ * Errors: EINVAL, EALIGN, EHIP.
+ */
+int cocktail_stream_read_probe(const void* buf, size_t bytes, void* sink, size_t* bytes_read, void* stream);
+
 /* Message of the last failure on the calling thread ("" if none).  Static storage. */
 const char* cocktail_last_error(void);
 

@@ -123,3 +123,14 @@ def cocktail_decode_attention(cache: PackedCache, q: torch.Tensor, sm_scale: flo
                                           out.data_ptr(), lse.data_ptr(), cache.workspace.data_ptr(),
                                           cache.workspace.numel(), _stream_ptr(stream)))
     return out, lse
+
+
+def cocktail_stream_read_probe(buf: torch.Tensor, sink: torch.Tensor,
+                               stream: Optional[torch.cuda.Stream] = None) -> int:
+    """Enqueues a plain streaming read of `buf` (device, uint8); returns the bytes the launch reads."""
+    if not (buf.is_cuda and sink.is_cuda and buf.is_contiguous()):
+        raise ValueError("buf and sink must be contiguous device tensors")
+    n = C.c_size_t(0)
+    check(lib().cocktail_stream_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(),
+                                           C.byref(n), _stream_ptr(stream)))
+    return int(n.value)

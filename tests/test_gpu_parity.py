@@ -205,6 +205,21 @@ def test_rejects_bad_device_arguments():
     c.cache.workspace = small_ws
 
 
+def test_stream_read_probe_reads_what_it_reports_and_rejects_small_buffers():
+    dev = torch.device("cuda:0")
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    buf = torch.zeros((48 << 20) + 4096, dtype=torch.uint8, device=dev)
+    assert ck.cocktail_stream_read_probe(buf, sink) == 48 << 20     # rounded down to 2048 waves x 8 KiB
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0                                    # zeros never match the sentinel
+    with pytest.raises(ck.CocktailError) as e:
+        ck.cocktail_stream_read_probe(buf[:1 << 20], sink)
+    assert e.value.code == -1
+    with pytest.raises(ck.CocktailError) as e:
+        ck.cocktail_stream_read_probe(buf[8:], sink)
+    assert e.value.code == -3
+
+
 # ---- full-size configurations, launch configuration of the bench, sampled heads ----------------
 def _sample_heads(w, n, seed):
     rng = np.random.default_rng(seed)

@@ -204,3 +204,7 @@ def test_gpu_entry_points_validate_on_host_before_launching():
     p16 = ck.cocktail_plan(sh16, [16], [2, 4], 4)
     cache.plan_host = p16.blob.ctypes.data
     assert L.cocktail_decode_attention(C.byref(sh16), 16, C.byref(cache), 0.0, 16, None, 16, 1 << 20, None) == _lib.EUNSUPPORTED
+    n = C.c_size_t(0)
+    assert L.cocktail_stream_read_probe(None, 1 << 30, 16, C.byref(n), None) == _lib.EINVAL
+    assert L.cocktail_stream_read_probe(8, 1 << 30, 16, C.byref(n), None) == _lib.EALIGN
+    assert L.cocktail_stream_read_probe(16, 1 << 20, 16, C.byref(n), None) == _lib.EINVAL
