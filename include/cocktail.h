@@ -104,7 +104,8 @@ typedef struct cocktail_cache {
   void* k[COCKTAIL_NUM_CLASSES]; /* DEVICE, class_bytes[c] each, 256-byte aligned; may be NULL iff 0 bytes */
   void* v[COCKTAIL_NUM_CLASSES]; /* DEVICE, same sizes                                                     */
   const void* plan_host;         /* HOST   plan blob written by cocktail_plan                              */
-  const void* plan_dev;          /* DEVICE byte-for-byte copy of the plan blob, 16-byte aligned            */
+  void* plan_dev;                /* DEVICE byte-for-byte copy of the plan blob, 16-byte aligned; also holds
+                                    the decode kernel's ticket counters (see cocktail_decode_attention)    */
 } cocktail_cache;
 
 /*
@@ -159,7 +160,13 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  * Decode side of Alg. 1: out[b,h] = softmax(sm_scale * q[b,h] . K^_b^T) V^_b over
  * all tokens of the three classes of sequence b, K^/V^ being the dequantized
  * (or raw fp16) rows of kv head h / (Hq/Hkv).  Two launches: partial states per
- * worker, then the exact merge.
+ * worker, then the exact merge.  Workers that finish their own share early take
+ * further pieces from a pool shared by a few neighbouring workers; the pools are
+ * handed out through ticket counters that live in the device copy of the plan.
+ * The counters are zero in the blob cocktail_plan writes and every call leaves
+ * them zero again, so calls on the same plan_dev must not overlap in time (calls
+ * on one stream never do), and a plan_dev whose call was aborted has to be
+ * re-uploaded.
  *
  *   q          DEVICE fp16 [B][Hq][D], 16-byte aligned
  *   sm_scale   softmax scale; <= 0 selects 1/sqrt(D)
@@ -170,7 +177,7 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  *              contents need not be initialised and are overwritten.  Calls that
  *              share a workspace must not overlap in time.
  *
- * The cache is not modified.  Errors: EINVAL, EUNSUPPORTED (head_dim != 128,
+ * The packed K/V data is not modified.  Errors: EINVAL, EUNSUPPORTED (head_dim != 128,
  * Hq/Hkv > COCKTAIL_MAX_Q_PER_KV), EALIGN, ENOSPACE, EHIP.
  */
 int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,

@@ -58,9 +58,12 @@ constexpr int J4 = COCKTAIL_J4;    // INT4 units in flight per wave
 constexpr int J16 = COCKTAIL_J16;  // FP16 units in flight per wave
 
 struct DecodeParams {
-  const WorkerRec* recs;    // [num_workers + num_items]: static ranges, then the small items
+  const WorkerRec* recs;    // [num_workers]
   const Segment* segs;      // [num_segments]
-  const int32_t* bh_pid;    // [B*Hkv][3][2][2] partial id ranges per class and part
+  const GroupRec* groups;   // [num_groups]
+  const PoolSeg* psegs;     // [num_pool_segs]
+  uint32_t* counters;       // [num_groups * kCounterStride] ticket counters, zero between calls
+  const int32_t* bh_off;    // [B*Hkv + 1] (sequence, kv head) owns the partial ids bh_off[bh] .. bh_off[bh+1]-1
   const uint32_t* q;        // fp16 [B][Hq][D] viewed as dwords
   const char* k[3];
   const char* v[3];
@@ -68,11 +71,21 @@ struct DecodeParams {
   _Float16* out;            // [B][Hq][D]
   float* lse;               // [B][Hq] or NULL
   float scale_log2;         // sm_scale * log2(e)
-  int32_t rep, num_q_heads, num_kv_heads;
+  int32_t rep, num_q_heads, num_kv_heads, num_groups;
 #ifdef COCKTAIL_TRACE
   uint64_t* trace;          // [num_workers][4]: start, end (100 MHz ticks), hw id, xcc id
 #endif
 };
+
+// The kernel keeps almost everything that describes its work in scalar registers.  To leave room
+// there, the kernel arguments are not held in registers for the whole kernel: code that needs one
+// of the rarely used pointers reads it from the kernel argument segment again.
+typedef const __attribute__((address_space(4))) DecodeParams* kparams_t;
+__device__ __forceinline__ kparams_t kparams() {
+  uint64_t p = reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr());
+  asm volatile("" : "+s"(p));   // a fresh pointer every time: loads through it are not kept alive
+  return reinterpret_cast<kparams_t>(p);
+}
 
 // A run of blocks is addressed through a buffer resource: every load is
 // buffer_load(resource, lane offset in a VGPR, unit/piece offset in an SGPR), so a lane needs
@@ -110,7 +123,7 @@ __device__ __forceinline__ const char* uni(const char* p) {
 __device__ __forceinline__ Segment uni(const Segment& x) {
   Segment y;
   y.b = uni(x.b), y.h = uni(x.h), y.cls = uni(x.cls), y.ntok = uni(x.ntok);
-  y.blk0 = uni(x.blk0), y.nblk = uni(x.nblk), y.gblk0 = uni(x.gblk0), y.bh = uni(x.bh);
+  y.blk0 = uni(x.blk0), y.nblk = uni(x.nblk), y.gblk0 = uni(x.gblk0), y.pid0 = uni(x.pid0);
   return y;
 }
 
@@ -315,92 +328,11 @@ __device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J],
   }
 }
 
-// Process `nb` (>= 1) consecutive blocks of one class; `valid` = valid tokens in that run
-// (only the last block can be partial).  J register stages hold K units and J hold V units,
-// both one loop iteration ahead of the arithmetic: as soon as a stage has been consumed it
-// is refilled with the unit J positions further on.  Units past the run are replaced by the
-// last one and masked, so the loop body has no branches around the loads.
-template <class CLS, int NGH>
-__device__ __forceinline__ void process_run(const char* kblk, const char* vblk, int nb, int valid, int t, int h,
-                                            const uint32_t (&q)[DH / 2], const float (&qsum)[NGH],
-                                            float scale_log2, LaneState<NGH>& st) {
-  constexpr int J = CLS::J;
-  kblk = uni(kblk), vblk = uni(vblk), nb = uni(nb), valid = uni(valid);
-#ifdef COCKTAIL_ROTATE
-  typename CLS::Stage sgs[J];
-  const int nu = 2 * nb;
-  const int last = nu - 1;
-  const uint32_t vc = CLS::code_voff(t, h), vm = CLS::meta_voff(t, h);
-  const rsrc_t krs = make_rsrc(kblk, uint32_t(nb) * CLS::BLOCKB), vrs = make_rsrc(vblk, uint32_t(nb) * CLS::BLOCKB);
-#pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::load(sgs[jj], krs, min(jj, last), vc, vm);
-#pragma unroll 1
-  for (int u0 = 0; u0 < nu; u0 += J) {
-    float s[J], p[J];
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      s[jj] = CLS::half_logit(sgs[jj], q, qsum);
-      sched_fence();
-      CLS::load(sgs[jj], vrs, min(u0 + jj, last), vc, vm);
-      sched_fence();
-    }
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      const float full = (s[jj] + __shfl_xor(s[jj], 32)) * scale_log2;
-      s[jj] = ((u0 + jj) * UT + t < valid) ? full : -INFINITY;
-    }
-    softmax_step<NGH, J>(s, p, st);
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      CLS::accumulate(sgs[jj], p[jj], st);
-      sched_fence();
-      CLS::load(sgs[jj], krs, min(u0 + J + jj, last), vc, vm);
-      sched_fence();
-    }
-  }
-}
-#else
-  typename CLS::Stage ks[J], vs[J];
-  const int nu = 2 * nb;
-  const int last = nu - 1;
-  const uint32_t vc = CLS::code_voff(t, h), vm = CLS::meta_voff(t, h);
-  const rsrc_t krs = make_rsrc(kblk, uint32_t(nb) * CLS::BLOCKB), vrs = make_rsrc(vblk, uint32_t(nb) * CLS::BLOCKB);
-#pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::load(ks[jj], krs, min(jj, last), vc, vm);
-#pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::load(vs[jj], vrs, min(jj, last), vc, vm);
-#pragma unroll 1
-  for (int u0 = 0; u0 < nu; u0 += J) {
-    float s[J], p[J];
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      s[jj] = CLS::half_logit(ks[jj], q, qsum);
-      sched_fence();
-      CLS::load(ks[jj], krs, min(u0 + J + jj, last), vc, vm);
-      sched_fence();
-    }
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      const float full = (s[jj] + __shfl_xor(s[jj], 32)) * scale_log2;   // both halves of the token
-      s[jj] = ((u0 + jj) * UT + t < valid) ? full : -INFINITY;
-    }
-    softmax_step<NGH, J>(s, p, st);
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      CLS::accumulate(vs[jj], p[jj], st);
-      sched_fence();
-      CLS::load(vs[jj], vrs, min(u0 + J + jj, last), vc, vm);
-      sched_fence();
-    }
-  }
-}
-#endif
-
 // Writes this wave's partial state `pid`: (m, l, o[D]) reduced over its lanes.
 template <int NGH, int GL>
-__device__ __forceinline__ void flush_partial(const DecodeParams& prm, const LaneState<NGH>& st, float* red, int pid,
-                                              int r, int lane) {
-  const int rep = prm.rep;
+__device__ __forceinline__ void flush_partial(const LaneState<NGH>& st, float* red, int pid, int r, int lane) {
+  kparams_t prm = kparams();
+  const int rep = prm->rep;
   float mw = st.m;
 #pragma unroll
   for (int o = 16; o > 0; o >>= 1) mw = fmaxf(mw, __shfl_xor(mw, o));
@@ -408,7 +340,7 @@ __device__ __forceinline__ void flush_partial(const DecodeParams& prm, const Lan
   float lw = st.l * f;
 #pragma unroll
   for (int o = 16; o > 0; o >>= 1) lw += __shfl_xor(lw, o);
-  float* out = prm.ws + (int64_t(pid) * rep + r) * (D + kPartialFloats);
+  float* out = prm->ws + (int64_t(pid) * rep + r) * (D + kPartialFloats);
   if (lane == 0) {
     out[0] = mw;
     out[1] = lw;
@@ -436,107 +368,276 @@ __device__ __forceinline__ void flush_partial(const DecodeParams& prm, const Lan
   }
 }
 
-// Streams the consecutive segments of class CLS that start at `sg` inside the worker's block
-// range [g, g1); returns with `sg` on the first segment of another class (or past the range).
-// The accumulators live and die inside this function, one instance per class.
-template <class CLS, int G>
-__device__ __forceinline__ void run_class(const DecodeParams& prm, int cls, Segment& sg, int& s, int& g, int g1,
-                                          int& pid, float* red, int r, int lane) {
+// ------------------------------------------------------------------ the worker's stream
+// One loop iteration's worth of work: up to J consecutive units of one segment.  Wave-uniform.
+struct Piece {
+  int nu;          // units; 0 = the stream has ended
+  int us;          // first unit, counted from the start of the segment
+  int valid;       // valid tokens among the nu * 32
+  int cls;
+  int fresh;       // 1 = the worker's first piece in this segment: a new partial state starts here
+  int pid;         // partial id of that state (meaningful when fresh)
+  int blk0, nblk;  // blocks of the segment inside the class buffer
+  int qrow;        // b * Hq + h * rep: query row of the first query head of the segment's kv head
+};
+
+__device__ __forceinline__ int iter_units(int cls) { return cls == 0 ? J2 : cls == 1 ? J4 : J16; }
+
+// A ticket from the group's counter.  The value is only needed a few loop iterations later; it
+// travels through the vector memory pipeline like any load and is picked up with readfirstlane.
+// The add is a buffer atomic over a 4-byte resource with one offset per lane, so only lane 0 is in
+// range and performs it (out-of-range lanes are dropped by the bounds check): no divergent branch.
+__device__ __forceinline__ uint32_t request_ticket(int counter, int lane) {
+  uint32_t* c = kparams()->counters + counter * kCounterStride;
+  const rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(c, 0, 4, 0x00020000);
+  return uint32_t(__builtin_amdgcn_raw_ptr_buffer_atomic_add_i32(1, rs, lane * 4, 0, /*sc1: device scope*/ 16));
+}
+
+// Yields the pieces of one worker: first its own block range front to back, then pieces of the
+// group's pool, one ticket each, until the tickets run out.  Segments are visited in ascending
+// order, so every segment is entered at most once.
+struct Stream {
+  int u, u1;          // own range: cursor and end in global units (two per block)
+  int s;              // index of the current segment; the fields below describe it
+  int cls, ntok, blk0, nblk, gu0, qrow;   // gu0: first global unit of the segment
+  int pid;            // partial id of this worker's own piece of the current segment
+  int last_seg;       // segment of the previous piece
+  int ngran, nps, pseg0, rank, counter;
+  int pi;             // current pool part (index relative to pseg0), -1 before the first
+  int p_unit0, p_nunits, p_gran0, p_gran1, p_slot0;
+  uint32_t tk0, tk1;  // tickets in flight (lane 0 holds the value)
+  uint32_t used;      // pool parts for which this worker started a partial state
+  int phase;          // 0 own range, tickets not requested; 1 own range, requested; 2 pool; 3 done
+
+  __device__ __forceinline__ void enter(const Segment& g, int index) {
+    kparams_t kp = kparams();
+    s = index;
+    cls = uni(g.cls), ntok = uni(g.ntok), blk0 = uni(g.blk0), nblk = uni(g.nblk), gu0 = 2 * uni(g.gblk0);
+    pid = uni(g.pid0);   // whoever enters a segment from its start is its first visitor
+    qrow = uni(g.b) * kp->num_q_heads + uni(g.h) * kp->rep;
+  }
+
+  __device__ __forceinline__ void init(const WorkerRec& rec) {
+    u = 2 * uni(rec.g0), u1 = 2 * uni(rec.g1);
+    enter(rec.first, uni(rec.seg0));
+    pid = uni(rec.pid0);   // the first segment is usually entered somewhere in the middle
+    last_seg = -1;
+    const GroupRec& gr = kparams()->groups[uni(rec.group)];
+    ngran = uni(gr.ngran), nps = uni(gr.nps), pseg0 = uni(gr.pseg0), rank = uni(rec.rank);
+    counter = uni(gr.counter);
+    pi = -1, p_unit0 = p_nunits = p_gran0 = p_gran1 = p_slot0 = 0;
+    tk0 = tk1 = 0, used = 0;
+    phase = 0;
+  }
+
+  __device__ __forceinline__ void fill(Piece& d, int us, int nu) {
+    d.nu = nu, d.us = us;
+    d.valid = max(0, min(ntok - us * UT, nu * UT));
+    d.cls = cls, d.blk0 = blk0, d.nblk = nblk, d.qrow = qrow;
+    d.fresh = s != last_seg;
+    last_seg = s;
+  }
+
+  __device__ __forceinline__ Piece next(int lane) {
+    Piece d;
+    d.nu = 0, d.us = 0, d.valid = 0, d.cls = -1, d.fresh = 0, d.pid = 0, d.blk0 = 0, d.nblk = 0, d.qrow = 0;
+    if (phase <= 1) {
+      // ask for the first tickets a few iterations before the own range runs out
+      if (phase == 0 && ngran > 0 && u1 - u <= 3 * iter_units(cls)) {
+        tk0 = request_ticket(counter, lane);
+        tk1 = request_ticket(counter, lane);
+        phase = 1;
+      }
+      if (u < u1) {
+        if (u >= gu0 + 2 * nblk) enter(kparams()->segs[s + 1], s + 1);
+        const int us = u - gu0;
+        const int nu = min(iter_units(cls), min(u1 - gu0, 2 * nblk) - us);
+        if (nu <= 0) {   // cannot happen with a plan written by cocktail_plan; guarantees termination
+          phase = 3;
+          return d;
+        }
+        fill(d, us, nu);
+        if (d.fresh) d.pid = pid;
+        u += nu;
+        return d;
+      }
+      phase = ngran > 0 ? 2 : 3;
+    }
+    if (phase == 2) {
+      const uint32_t t = __builtin_amdgcn_readfirstlane(tk0);
+      tk0 = tk1;
+      tk1 = request_ticket(counter, lane);
+      if (t >= uint32_t(ngran)) {
+        phase = 3;
+        return d;
+      }
+      while (pi < 0 || int(t) >= p_gran1) {
+        if (++pi >= nps) {   // cannot happen with a plan written by cocktail_plan; guarantees termination
+          phase = 3;
+          return d;
+        }
+        kparams_t kp = kparams();
+        const PoolSeg& ps = kp->psegs[pseg0 + pi];
+        const int seg = uni(ps.seg);
+        p_unit0 = uni(ps.unit0), p_nunits = uni(ps.nunits), p_gran0 = uni(ps.gran0), p_slot0 = uni(ps.slot0);
+        if (seg != s) enter(kp->segs[seg], seg);
+        const int j = iter_units(cls);
+        p_gran1 = p_gran0 + (p_nunits + j - 1) / j;
+      }
+      const int j = iter_units(cls);
+      const int us = p_unit0 + (int(t) - p_gran0) * j;
+      const int nu = min(j, p_unit0 + p_nunits - us);
+      if (nu <= 0) {
+        phase = 3;
+        return d;
+      }
+      fill(d, us, nu);
+      if (d.fresh) {
+        d.pid = p_slot0 + rank;
+        used |= 1u << pi;
+      }
+    }
+    return d;
+  }
+};
+
+// Zeroes the partial state and loads this lane's half of the query row `qrow`.
+template <int NGH, int GL>
+__device__ __forceinline__ void begin_state(int qrow, int h, LaneState<NGH>& st, uint32_t (&q)[DH / 2],
+                                            float (&qsum)[NGH]) {
+#pragma unroll
+  for (int i = 0; i < DH; ++i) st.acc[i] = 0.f;
+#pragma unroll
+  for (int gq = 0; gq < NGH; ++gq) st.zacc[gq] = 0.f;
+  st.m = kNegBig;
+  st.l = 0.f;
+  const u32x4* qp = reinterpret_cast<const u32x4*>(kparams()->q + int64_t(qrow) * (D / 2) + h * (DH / 2));
+#pragma unroll
+  for (int i = 0; i < DH / 8; ++i) {
+    const u32x4 v = qp[i];
+    q[4 * i] = v.x, q[4 * i + 1] = v.y, q[4 * i + 2] = v.z, q[4 * i + 3] = v.w;
+  }
+#pragma unroll
+  for (int gq = 0; gq < NGH; ++gq) {
+    float a = 0.f;
+#pragma unroll
+    for (int i = 0; i < GL / 2; ++i) a = dot2(q[gq * (GL / 2) + i], 0x3C003C00u, a);   // (1.0, 1.0)
+    qsum[gq] = a;
+  }
+}
+
+// Consumes the stream while its pieces belong to class CID, starting with `cur` (whose loads have
+// not been issued yet); returns with `cur` = the first piece of another class, or the end piece.
+//
+// J register stages hold the K units and J the V units of the piece being worked on; each stage is
+// refilled with the corresponding unit of the NEXT piece as soon as it has been consumed, so the
+// loads of a piece are in flight during the arithmetic of the piece before it, across segment and
+// pool boundaries alike.  A piece with fewer than J units repeats its last unit (masked), and after
+// the last piece of the class the refill simply repeats the previous one (cache hits), so the loop
+// body has no branches around the loads.  The accumulators live and die inside this function, one
+// instance per class.
+template <class CLS, int CID, int G>
+__device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, int r, int lane) {
   constexpr int NG = D / G;
   constexpr int NGH = NG >= 2 ? NG / 2 : 1;
   constexpr int GL = G < DH ? G : DH;
+  constexpr int J = CLS::J;
+  static_assert(J == kIterUnits[CID], "the planner cuts pool pieces to the kernel's iteration size");
   const int t = lane & 31, h = lane >> 5;
-  const int rep = prm.rep;
+  const uint32_t vc = CLS::code_voff(t, h), vm = CLS::meta_voff(t, h);
+  const char* const kbase = uni(kparams()->k[CID]);
+  const char* const vbase = uni(kparams()->v[CID]);
+  const float scale_log2 = kparams()->scale_log2;
   LaneState<NGH> st;
   uint32_t q[DH / 2];
   float qsum[NGH];
-  int cur_bh = -1, cur_b = 0, cur_h = 0;
+  typename CLS::Stage ks[J], vs[J];
+  int pid = cur.pid;
+  begin_state<NGH, GL>(cur.qrow + r, h, st, q, qsum);
+  rsrc_t krs = make_rsrc(kbase + int64_t(cur.blk0) * CLS::BLOCKB, uint32_t(cur.nblk) * CLS::BLOCKB);
+  rsrc_t vrs = make_rsrc(vbase + int64_t(cur.blk0) * CLS::BLOCKB, uint32_t(cur.nblk) * CLS::BLOCKB);
+  int ru = cur.us, rn = cur.nu;   // what the stages were (re)filled with last
+#pragma unroll
+  for (int jj = 0; jj < J; ++jj) CLS::load(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
+#pragma unroll
+  for (int jj = 0; jj < J; ++jj) CLS::load(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
+  int valid = cur.valid;
+  Piece nxt = sm.next(lane);
+#pragma unroll 1
   while (true) {
-    if (sg.bh != cur_bh) {
-      if (cur_bh >= 0) {
-        flush_partial<NGH, GL>(prm, st, red, pid, r, lane);
-        ++pid;
-      }
-      cur_bh = sg.bh, cur_b = sg.b, cur_h = sg.h;
-#pragma unroll
-      for (int d = 0; d < DH; ++d) st.acc[d] = 0.f;
-#pragma unroll
-      for (int gq = 0; gq < NGH; ++gq) st.zacc[gq] = 0.f;
-      st.m = kNegBig;
-      st.l = 0.f;
-      const int hq = sg.h * rep + r;
-      const u32x4* qp = reinterpret_cast<const u32x4*>(prm.q + (int64_t(sg.b) * prm.num_q_heads + hq) * (D / 2) +
-                                                       h * (DH / 2));
-#pragma unroll
-      for (int i = 0; i < DH / 8; ++i) {
-        const u32x4 v = qp[i];
-        q[4 * i] = v.x, q[4 * i + 1] = v.y, q[4 * i + 2] = v.z, q[4 * i + 3] = v.w;
-      }
-#pragma unroll
-      for (int gq = 0; gq < NGH; ++gq) {
-        float a = 0.f;
-#pragma unroll
-        for (int i = 0; i < GL / 2; ++i) a = dot2(q[gq * (GL / 2) + i], 0x3C003C00u, a);   // (1.0, 1.0)
-        qsum[gq] = a;
-      }
+    const bool more = nxt.nu > 0 && nxt.cls == CID;
+    if (more) {
+      krs = make_rsrc(kbase + int64_t(nxt.blk0) * CLS::BLOCKB, uint32_t(nxt.nblk) * CLS::BLOCKB);
+      vrs = make_rsrc(vbase + int64_t(nxt.blk0) * CLS::BLOCKB, uint32_t(nxt.nblk) * CLS::BLOCKB);
+      ru = nxt.us, rn = nxt.nu;
     }
-    const int jb = g - sg.gblk0;
-    const int je = min(sg.nblk, g1 - sg.gblk0);
-    const int nb = je - jb;
-    if (nb <= 0) {   // cannot happen with a plan written by cocktail_plan; guarantees termination
-      g = g1;
-      break;
+    float s[J], p[J];
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      s[jj] = CLS::half_logit(ks[jj], q, qsum);
+      sched_fence();
+      CLS::load(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
+      sched_fence();
     }
-    // valid tokens of this run: up to the end of the segment or of the run, whichever comes first
-    const int valid = min(sg.ntok - jb * kTB, nb * kTB);
-    const int64_t first = int64_t(sg.blk0 + jb);
-    process_run<CLS, NGH>(prm.k[cls] + first * CLS::BLOCKB, prm.v[cls] + first * CLS::BLOCKB, nb, valid, t, h, q,
-                          qsum, prm.scale_log2, st);
-    g = sg.gblk0 + je;
-    if (g >= g1) break;
-    sg = uni(prm.segs[++s]);
-    if (sg.cls != cls) break;
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      const float full = (s[jj] + __shfl_xor(s[jj], 32)) * scale_log2;   // both halves of the token
+      s[jj] = (jj * UT + t < valid) ? full : -INFINITY;
+    }
+    softmax_step<NGH, J>(s, p, st);
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      CLS::accumulate(vs[jj], p[jj], st);
+      sched_fence();
+      CLS::load(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
+      sched_fence();
+    }
+    if (!more || nxt.fresh) flush_partial<NGH, GL>(st, red, pid, r, lane);
+    if (!more) break;
+    if (nxt.fresh) {
+      pid = nxt.pid;
+      begin_state<NGH, GL>(nxt.qrow + r, h, st, q, qsum);
+    }
+    valid = nxt.valid;
+    nxt = sm.next(lane);
   }
-  flush_partial<NGH, GL>(prm, st, red, pid, r, lane);
-  ++pid;
+  cur = nxt;
 }
 
-// Streams one work item: the block range [g0, g1) of the global order.
+// One workgroup per worker; wave r of the workgroup serves query head r of every kv head it meets.
 template <int G>
-__device__ __forceinline__ void process_item(const DecodeParams& prm, const WorkerRec& rec, float* red, int r,
-                                             int lane) {
-  int g = uni(rec.g0);
-  const int g1 = uni(rec.g1);
-  if (g >= g1) return;
-  int s = uni(rec.seg0);
-  int pid = uni(rec.pid0);
-  Segment sg = uni(rec.first);
-  while (g < g1) {
-    if (sg.cls == 0) {
-      run_class<QuantClass<2, G>, G>(prm, 0, sg, s, g, g1, pid, red, r, lane);
-    } else if (sg.cls == 1) {
-      run_class<QuantClass<4, G>, G>(prm, 1, sg, s, g, g1, pid, red, r, lane);
-    } else {
-      run_class<HalfClass<G>, G>(prm, 2, sg, s, g, g1, pid, red, r, lane);
-    }
-  }
-}
-
-// One workgroup per work item.  The first `num_workers` items are large static ranges that fill
-// every wave slot of the chip; items behind them (if the plan has any) are small and the hardware
-// dispatcher hands them out as slots become free.
-template <int G>
-__global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams prm) {
+__global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
   extern __shared__ float red[];   // [rep][64][17] reduction tiles
   const int lane = threadIdx.x & 63;
   const int r = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // query head inside the group
 #ifdef COCKTAIL_TRACE
   const uint64_t t_start = __builtin_amdgcn_s_memrealtime();
 #endif
-  process_item<G>(prm, prm.recs[blockIdx.x], red, r, lane);
+  Stream sm;
+  sm.init(kparams()->recs[blockIdx.x]);
+  Piece cur = sm.next(lane);
+  while (cur.nu > 0) {
+    if (cur.cls == 0) {
+      run_class<QuantClass<2, G>, 0, G>(sm, cur, red, r, lane);
+    } else if (cur.cls == 1) {
+      run_class<QuantClass<4, G>, 1, G>(sm, cur, red, r, lane);
+    } else {
+      run_class<HalfClass<G>, 2, G>(sm, cur, red, r, lane);
+    }
+  }
+  // pool parts this worker never entered still own a partial slot: fill it with the neutral state
+  for (int i = 0; i < sm.nps; ++i) {
+    if ((sm.used >> i) & 1u) continue;
+    kparams_t kp = kparams();
+    const int slot = uni(kp->psegs[sm.pseg0 + i].slot0) + sm.rank;
+    float* out = kp->ws + (int64_t(slot) * kp->rep + r) * (D + kPartialFloats);
+    if (lane == 0) out[0] = kNegBig, out[1] = 0.f;
+    out[kPartialFloats + lane] = 0.f;
+    out[kPartialFloats + 64 + lane] = 0.f;
+  }
 #ifdef COCKTAIL_TRACE
   if (threadIdx.x == 0) {
-    uint64_t* tr = prm.trace + blockIdx.x * 4;
+    uint64_t* tr = kparams()->trace + blockIdx.x * 4;
     tr[0] = t_start;
     tr[1] = __builtin_amdgcn_s_memrealtime();
     tr[2] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));    // HW_ID
@@ -547,10 +648,12 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams prm)
 
 // Exact merge of the partial states of one (sequence, query head):
 //   M = max m_i,  L = sum l_i 2^(m_i - M),  out = sum o_i 2^(m_i - M) / L,  lse = ln2 (M + log2 L).
-// 256 threads: 32 channel quads x 8 slices of the partial list.  A (sequence, query head) without
+// The partials of a (sequence, kv head) are a dense block of the workspace.  256 threads: 32 channel
+// quads x 8 slices of the block; every slice folds its partials in one pass with a running maximum,
+// then the eight slice states are folded through shared memory.  A (sequence, query head) without
 // any partial (empty sequence) gets zeros and lse = -inf.
 __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams prm) {
-  __shared__ float sm_max[4];
+  __shared__ float sm_m[8];
   __shared__ float sm_l[8];
   __shared__ float sm_o[8][D];
   const int bhq = blockIdx.x;
@@ -559,51 +662,60 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams prm) {
   const int hq = bhq - b * prm.num_q_heads;
   const int bh = b * prm.num_kv_heads + hq / rep;
   const int r = hq % rep;
-  const int32_t* ranges = prm.bh_pid + bh * 12;   // six [begin, end) ranges: class x (static, dynamic)
-  int n = 0;
-#pragma unroll
-  for (int k = 0; k < 6; ++k) n += ranges[2 * k + 1] - ranges[2 * k];
-  // i-th partial of this head: the six ranges back to back
-  auto pid_of = [&](int i) {
-    int pid = 0;
-#pragma unroll
-    for (int k = 0; k < 6; ++k) {
-      const int len = ranges[2 * k + 1] - ranges[2 * k];
-      if (i >= 0 && i < len) pid = ranges[2 * k] + i;
-      i -= len;
-    }
-    return pid;
-  };
+  const int lo = prm.bh_off[bh];
+  const int n = prm.bh_off[bh + 1] - lo;
   const int tid = threadIdx.x;
+  // every worker has drawn its last ticket: put the counters back to zero for the next call
+  if (blockIdx.x == 0)
+    for (int i = tid; i < prm.num_groups; i += 256) prm.counters[i * kCounterStride] = 0u;
   constexpr int STRIDE = D + kPartialFloats;
-  float mx = -INFINITY;
-  for (int i = tid; i < n; i += 256) mx = fmaxf(mx, prm.ws[(int64_t(pid_of(i)) * rep + r) * STRIDE]);
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o));
-  if ((tid & 63) == 0) sm_max[tid >> 6] = mx;
-  __syncthreads();
-  mx = fmaxf(fmaxf(sm_max[0], sm_max[1]), fmaxf(sm_max[2], sm_max[3]));
+  constexpr int U = 4;   // partials in flight per thread
   const int quad = tid & 31, slice = tid >> 5;
-  float o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f, big_l = 0.f;
-  for (int i = slice; i < n; i += 8) {
-    const float* part = prm.ws + (int64_t(pid_of(i)) * rep + r) * STRIDE;
-    const float wgt = __builtin_amdgcn_exp2f(part[0] - mx);
-    big_l += part[1] * wgt;
-    const float2 v0 = *reinterpret_cast<const float2*>(part + kPartialFloats + quad * 4);
-    const float2 v1 = *reinterpret_cast<const float2*>(part + kPartialFloats + quad * 4 + 2);
-    o0 += v0.x * wgt, o1 += v0.y * wgt, o2 += v1.x * wgt, o3 += v1.y * wgt;
+  const float* base = prm.ws + (int64_t(lo) * rep + r) * STRIDE + kPartialFloats + quad * 4;
+  float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+  for (int i0 = slice; i0 < n; i0 += 8 * U) {
+    float pm[U], pl[U];
+    float2 va[U], vb[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int i = i0 + 8 * u;
+      const bool ok = i < n;
+      const float* part = base + int64_t(ok ? i : i0) * rep * STRIDE;
+      pm[u] = ok ? part[-kPartialFloats - quad * 4] : -INFINITY;
+      pl[u] = part[1 - kPartialFloats - quad * 4];
+      va[u] = *reinterpret_cast<const float2*>(part);
+      vb[u] = *reinterpret_cast<const float2*>(part + 2);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float mn = fmaxf(m, pm[u]);
+      // 2^(-inf - -inf) must not occur: a slice that has only seen padding keeps weight 0
+      const float a = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mn);
+      const float w = (pm[u] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(pm[u] - mn);
+      l = l * a + pl[u] * w;
+      o0 = o0 * a + va[u].x * w, o1 = o1 * a + va[u].y * w;
+      o2 = o2 * a + vb[u].x * w, o3 = o3 * a + vb[u].y * w;
+      m = mn;
+    }
   }
   sm_o[slice][quad * 4 + 0] = o0, sm_o[slice][quad * 4 + 1] = o1;
   sm_o[slice][quad * 4 + 2] = o2, sm_o[slice][quad * 4 + 3] = o3;
-  if (quad == 0) sm_l[slice] = big_l;
+  if (quad == 0) sm_m[slice] = m, sm_l[slice] = l;
   __syncthreads();
   if (tid < D) {
-    float l = 0.f, o = 0.f;
+    float mx = sm_m[0];
 #pragma unroll
-    for (int sidx = 0; sidx < 8; ++sidx) l += sm_l[sidx], o += sm_o[sidx][tid];
-    const bool empty = !(l > 0.f);
-    prm.out[int64_t(bhq) * D + tid] = static_cast<_Float16>(empty ? 0.f : o / l);
-    if (prm.lse && tid == 0) prm.lse[bhq] = empty ? -INFINITY : (mx + log2f(l)) * 0.6931471805599453f;
+    for (int sidx = 1; sidx < 8; ++sidx) mx = fmaxf(mx, sm_m[sidx]);
+    float big_l = 0.f, o = 0.f;
+#pragma unroll
+    for (int sidx = 0; sidx < 8; ++sidx) {
+      const float w = (sm_m[sidx] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[sidx] - mx);
+      big_l += sm_l[sidx] * w;
+      o += sm_o[sidx][tid] * w;
+    }
+    const bool empty = !(big_l > 0.f);
+    prm.out[int64_t(bhq) * D + tid] = static_cast<_Float16>(empty ? 0.f : o / big_l);
+    if (prm.lse && tid == 0) prm.lse[bhq] = empty ? -INFINITY : (mx + log2f(big_l)) * 0.6931471805599453f;
   }
 }
 
@@ -653,10 +765,14 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
     return fail(COCKTAIL_ENOSPACE, "workspace holds %zu bytes, %lld needed", workspace_bytes,
                 (long long)hd->workspace_bytes);
   DecodeParams p;
-  const char* pd = static_cast<const char*>(cache->plan_dev);
+  char* pd = static_cast<char*>(cache->plan_dev);
   p.recs = reinterpret_cast<const WorkerRec*>(pd + hd->off_worker_rec);
   p.segs = reinterpret_cast<const Segment*>(pd + hd->off_segments);
-  p.bh_pid = reinterpret_cast<const int32_t*>(pd + hd->off_bh_pid);
+  p.groups = reinterpret_cast<const GroupRec*>(pd + hd->off_group_rec);
+  p.psegs = reinterpret_cast<const PoolSeg*>(pd + hd->off_pool_seg);
+  p.counters = reinterpret_cast<uint32_t*>(pd + hd->off_counters);
+  p.num_groups = hd->num_groups;
+  p.bh_off = reinterpret_cast<const int32_t*>(pd + hd->off_bh_off);
   p.q = static_cast<const uint32_t*>(q);
   for (int c = 0; c < 3; ++c) {
     if (hd->class_bytes[c] > 0 && (!cache->k[c] || !cache->v[c]))
@@ -678,7 +794,7 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
 #endif
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (hd->total_gblocks > 0) {
-    const dim3 grid(hd->num_workers + hd->num_items, 1, 1), block(64 * hd->rep, 1, 1);
+    const dim3 grid(hd->num_workers, 1, 1), block(64 * hd->rep, 1, 1);
     const size_t lds = size_t(hd->rep) * 64 * 17 * sizeof(float);
     switch (shape->group_size) {
       case 32: hipLaunchKernelGGL(decode_attention_kernel<32>, grid, block, lds, st, p); break;

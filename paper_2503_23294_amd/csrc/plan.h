@@ -3,36 +3,69 @@
 // The blob is position independent (offsets, no pointers) so the caller can copy
 // it to the device byte for byte.  It holds the result of Alg. 1's prefill loop
 // (which chunk goes to which bitwidth class, in which order) plus the derived
-// block layout of the packed cache and the static work split of the decode kernel.
+// block layout of the packed cache and the work split of the decode kernel.
 #pragma once
 #include <stdint.h>
 
 namespace cocktail {
 
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
-constexpr uint32_t kPlanVersion = 8;
+constexpr uint32_t kPlanVersion = 9;
 constexpr int kTB = 64;                        // tokens per block
+constexpr int kUT = 32;                        // tokens per unit (half a block): what one wave handles at a time
 constexpr int kNumClasses = 3;
 constexpr int kPartialFloats = 2;              // (m, l) in front of the D output values
+// Units one wave consumes per loop iteration in class INT2, INT4, FP16: the grain of the shared pools.
+constexpr int kIterUnits[kNumClasses] = {4, 2, 1};
+constexpr int kMaxPoolSegments = 32;           // segments one pool may touch (a worker tracks them in a bit mask)
+constexpr int kCounterStride = 32;             // uint32 slots between two pool counters (one 128-byte line each)
 
-// One contiguous run of blocks of one (sequence, kv head, class).
+// One contiguous run of blocks of one (sequence, kv head, class): the part of it that one group works on.
 struct Segment {
-  int32_t b, h, cls, ntok;   // ntok: valid tokens of the whole run (last block may be partial)
+  int32_t b, h, cls, ntok;   // ntok: valid tokens from the first block of this piece to the end of the
+                             // (sequence, kv head, class) run; may exceed nblk * 64
   int32_t blk0;              // first block, index into the class buffer
   int32_t nblk;
-  int32_t gblk0;             // first block in the global order (static part of every class, then dynamic part)
-  int32_t bh;                // b * Hkv + h
+  int32_t gblk0;             // first block in the global order (group by group; inside a group FP16, INT2, INT4)
+  int32_t pid0;              // partial id of the first worker whose own range touches this segment
 };
 
 // Everything a decode workgroup needs to start streaming, in one 64-byte record.
 struct WorkerRec {
-  int32_t g0, g1;            // global block range [g0, g1)
+  int32_t g0, g1;            // its own block range [g0, g1) of the global order
   int32_t seg0;              // index of the segment holding g0
-  int32_t pid0;              // first partial id this worker writes
+  int32_t pid0;              // partial id of its piece of segment seg0 (in later segments it is the first visitor)
   Segment first;             // copy of segments[seg0]
-  int32_t pad[4];
+  int32_t group;             // index of its GroupRec
+  int32_t rank;              // position inside the group
+  int32_t pad[2];
 };
 static_assert(sizeof(WorkerRec) == 64, "WorkerRec is one 64-byte line");
+
+// A group of consecutive workers shares a pool: the tail of the group's block range, handed out one
+// loop iteration at a time through an atomic ticket counter, so that workers that finish their own
+// range early take over work from slower ones.
+struct GroupRec {
+  int32_t ngran;             // tickets 0 .. ngran-1 are valid; 0 = the group has no pool
+  int32_t pseg0;             // index of its first PoolSeg
+  int32_t nps;               // number of PoolSegs (<= kMaxPoolSegments)
+  int32_t nworkers;
+  int32_t counter;           // index of its ticket counter (times kCounterStride)
+  int32_t pad[3];
+};
+static_assert(sizeof(GroupRec) == 32, "GroupRec layout");
+
+// The part of a pool that lies inside one segment.  Ticket t with gran0 <= t < gran0 + ceil(nunits / J)
+// stands for units [unit0 + (t - gran0) * J, + J) of the segment, J = kIterUnits[class].
+struct PoolSeg {
+  int32_t seg;               // segment index
+  int32_t unit0;             // first unit, counted from the start of the segment
+  int32_t nunits;
+  int32_t gran0;             // first ticket of this part
+  int32_t slot0;             // partial id of rank 0; rank r of the group writes slot0 + r
+  int32_t pad[3];
+};
+static_assert(sizeof(PoolSeg) == 32, "PoolSeg layout");
 
 struct PlanHeader {
   uint32_t magic, version;
@@ -59,10 +92,15 @@ struct PlanHeader {
   int32_t off_blk_base;       // int32 [B+1][3] first block of sequence b in class buffer c
   int32_t off_nblk;           // int32 [B][3]  blocks per head
   int32_t off_segments;       // Segment [num_segments]
-  int32_t off_bh_pid;         // int32 [B*Hkv][3][2][2] partial ids [begin, end) of each (b, kv head, class, part)
-  int32_t off_worker_rec;     // WorkerRec [P + Q]: P static ranges, then the Q small items in dispatch order
-  int32_t num_items;          // Q
-  int32_t pad1[4];
+  int32_t pad2;
+  int32_t off_worker_rec;     // WorkerRec [num_workers]
+  int32_t off_group_rec;      // GroupRec [num_groups]
+  int32_t off_pool_seg;       // PoolSeg [num_pool_segs]
+  int32_t off_counters;       // uint32 [num_groups * kCounterStride], zero; the only part kernels write
+  int32_t num_groups, num_pool_segs;
+  int32_t pad3;
+  int32_t off_bh_off;         // int32 [B*Hkv + 1] prefix: (b, kv head) owns partial ids bh_off[bh] .. bh_off[bh+1]-1
+  int32_t pad1;
 };
 
 template <typename T>

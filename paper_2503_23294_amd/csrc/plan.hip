@@ -41,12 +41,14 @@ int check_shape(const cocktail_shape* s) {
   return COCKTAIL_OK;
 }
 
-constexpr int64_t kCostWeightInt2 = 115, kCostWeightInt4 = 120, kCostWeightFp16 = 64;
-// Share of every class that is cut into small late-dispatched items, and the size of one item (K+V bytes).
-// Measured on MI355X: such items do not pay (their start-up latency costs more than the balance gains),
-// so the share is zero; the planner and the kernel still support them.
-constexpr int kDynamicPercent = 0;
-constexpr int64_t kDynamicItemBytes = 40 * 1024;
+constexpr int64_t kCostWeightInt2 = 115, kCostWeightInt4 = 130, kCostWeightFp16 = 54;
+// Workers per group and the share of a group's cost that goes into its shared pool.
+constexpr int kGroupWorkers = 8;
+constexpr int kPoolPercent = 25;
+constexpr int kPairMode = 0;
+constexpr int kLayout = 0;
+// A group only gets a pool if its range holds at least this many blocks per worker.
+constexpr int kMinBlocksPerWorkerForPool = 16;
 
 static inline int32_t align16(int64_t x) { return static_cast<int32_t>((x + 15) & ~int64_t(15)); }
 
@@ -129,11 +131,19 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
     if (std::sscanf(e, "%ld,%ld,%ld", &a, &b2, &c2) == 3 && a > 0 && b2 > 0 && c2 > 0) weight[0] = a, weight[1] = b2, weight[2] = c2;
   }
 
-  int dyn_percent = kDynamicPercent;
-  if (const char* e = std::getenv("COCKTAIL_DYNAMIC_PERCENT")) {   // tuning aid
+  int pool_percent = kPoolPercent, group_workers = kGroupWorkers;
+  if (const char* e = std::getenv("COCKTAIL_POOL_PERCENT")) {   // tuning aid
     const int v = std::atoi(e);
-    if (v >= 0 && v <= 90) dyn_percent = v;
+    if (v >= 0 && v <= 100) pool_percent = v;
   }
+  if (const char* e = std::getenv("COCKTAIL_GROUP_WORKERS")) {   // tuning aid
+    const int v = std::atoi(e);
+    if (v >= 1 && v <= 1024) group_workers = v;
+  }
+  const int rep = shape->num_q_heads / Hkv;
+  // the query heads of a kv head run as waves of one workgroup on the same blocks; a pool would need a
+  // ticket shared by those waves, so grouped-query shapes keep the purely static split
+  if (rep > 1) pool_percent = 0;
 
   // ---- physical runs of the class buffers: (class, b, h) order, each a contiguous run of blocks ----
   struct Run {
@@ -152,118 +162,219 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
   int64_t tot_blocks = class_nblk[0] + class_nblk[1] + class_nblk[2];
   if (tot_blocks >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "more than 2^31 blocks in one call");
 
-  // ---- segments: the leading (100 - dyn)% of every class is split statically over the P workgroups,
-  //      the trailing part is cut into small items that are dispatched as wave slots become free ----
-  int64_t class_static[3];
-  for (int c = 0; c < 3; ++c) class_static[c] = class_nblk[c] - class_nblk[c] * dyn_percent / 100;
-  std::vector<Segment> segs;
-  std::vector<int64_t> seg_cost0;   // cumulative cost (weighted bytes of K+V) at the start of each static segment
-  int64_t gblk = 0, cost = 0;
-  int32_t first_dyn_seg[3] = {0, 0, 0}, dyn_g0[3] = {0, 0, 0}, dyn_g1[3] = {0, 0, 0};
-  for (int part = 0; part < 2; ++part) {
-    if (part == 1) seg_cost0.push_back(cost);
+  // ---- global order and segments ----
+  // The workers form groups of `group_workers`; group j works on one stripe [cut[c][j], cut[c][j+1]) of
+  // the blocks of every class c (blocks in (b, h, block) order).  A segment is the intersection of a
+  // stripe with a run; the global order lists the groups one after the other.
+  //   layout 0: the class-major order INT2 | INT4 | FP16 is cut into NGR parts of equal cost, so a
+  //             group works on one class (two where it straddles a class boundary);
+  //   layout 1: every group receives the same share of every class (FP16 stripe, then INT2, then INT4).
+  const int NGR = (P + group_workers - 1) / group_workers;
+  int layout = kLayout;
+  if (const char* e = std::getenv("COCKTAIL_LAYOUT")) layout = std::atoi(e) != 0;   // tuning aid
+  const int class_order[3] = {layout ? 2 : 0, layout ? 0 : 1, layout ? 1 : 2};
+  std::vector<int64_t> cut[3];
+  {
+    int64_t per[3], tot = 0, start[3];
     for (int c = 0; c < 3; ++c) {
-      if (part == 1) first_dyn_seg[c] = static_cast<int32_t>(segs.size()), dyn_g0[c] = static_cast<int32_t>(gblk);
-      int64_t seen = 0;   // blocks of class c passed so far
-      for (const Run& r : runs) {
-        if (r.cls != c) continue;
-        // blocks [lo, hi) of this run belong to the current part
-        const int64_t cut = class_static[c] - seen;   // blocks of this run that are static
-        const int lo = part == 0 ? 0 : static_cast<int>(cut < 0 ? 0 : (cut > r.nb ? r.nb : cut));
-        const int hi = part == 0 ? static_cast<int>(cut < 0 ? 0 : (cut > r.nb ? r.nb : cut)) : r.nb;
-        seen += r.nb;
-        if (hi <= lo) continue;
-        Segment sgm;
-        sgm.b = r.b, sgm.h = r.h, sgm.cls = c, sgm.ntok = r.ntok - lo * kTB;
-        sgm.blk0 = r.blk0 + lo, sgm.nblk = hi - lo;
-        sgm.gblk0 = static_cast<int32_t>(gblk);
-        sgm.bh = r.b * Hkv + r.h;
-        segs.push_back(sgm);
-        if (part == 0) seg_cost0.push_back(cost);
-        gblk += sgm.nblk;
-        cost += int64_t(sgm.nblk) * 2 * block_bytes[c] * weight[c];
-      }
-      if (part == 1) dyn_g1[c] = static_cast<int32_t>(gblk);
+      per[c] = 2 * int64_t(block_bytes[c]) * weight[c];
+      start[c] = tot;
+      tot += class_nblk[c] * per[c];
+      cut[c].assign(NGR + 1, 0);
     }
+    for (int j = 0; j <= NGR; ++j) {
+      const int w_lo = j * group_workers < P ? j * group_workers : P;
+      for (int c = 0; c < 3; ++c) {
+        if (layout) {
+          cut[c][j] = class_nblk[c] * w_lo / P;
+        } else {
+          const int64_t target = static_cast<int64_t>((static_cast<__int128>(tot) * w_lo) / P);
+          int64_t v = (target - start[c] + per[c] / 2) / per[c];
+          cut[c][j] = v < 0 ? 0 : (v > class_nblk[c] ? class_nblk[c] : v);
+        }
+      }
+    }
+    for (int c = 0; c < 3; ++c) cut[c][0] = 0, cut[c][NGR] = class_nblk[c];
   }
+  std::vector<Segment> segs;
+  std::vector<int64_t> seg_cost0;   // cumulative cost (weighted bytes of K+V) at the start of each segment
+  std::vector<int32_t> group_g0(NGR + 1, 0), group_s0(NGR + 1, 0);
+  int64_t gblk = 0, cost = 0;
+  {
+    std::vector<Run> by_class[3];
+    for (const Run& r : runs) by_class[r.cls].push_back(r);
+    size_t cur_run[3] = {0, 0, 0};      // run holding the next block of each class
+    int64_t run_first[3] = {0, 0, 0};   // class-local index of that run's first block
+    for (int j = 0; j < NGR; ++j) {
+      group_g0[j] = static_cast<int32_t>(gblk), group_s0[j] = static_cast<int32_t>(segs.size());
+      for (int ci = 0; ci < 3; ++ci) {
+        const int c = class_order[ci];
+        int64_t lo = cut[c][j];
+        const int64_t hi = cut[c][j + 1];
+        while (lo < hi) {
+          while (run_first[c] + by_class[c][cur_run[c]].nb <= lo) run_first[c] += by_class[c][cur_run[c]++].nb;
+          const Run& r = by_class[c][cur_run[c]];
+          const int off = static_cast<int>(lo - run_first[c]);
+          const int n = static_cast<int>((hi < run_first[c] + r.nb ? hi : run_first[c] + r.nb) - lo);
+          Segment sgm;
+          sgm.b = r.b, sgm.h = r.h, sgm.cls = c, sgm.ntok = r.ntok - off * kTB;
+          sgm.blk0 = r.blk0 + off, sgm.nblk = n;
+          sgm.gblk0 = static_cast<int32_t>(gblk);
+          sgm.pid0 = 0;
+          segs.push_back(sgm);
+          seg_cost0.push_back(cost);
+          gblk += n;
+          cost += int64_t(n) * 2 * block_bytes[c] * weight[c];
+          lo += n;
+        }
+      }
+    }
+    group_g0[NGR] = static_cast<int32_t>(gblk), group_s0[NGR] = static_cast<int32_t>(segs.size());
+  }
+  seg_cost0.push_back(cost);
   const int S = static_cast<int>(segs.size());
-  const int S_static = static_cast<int>(seg_cost0.size()) - 1;   // segments of the static part
-  const int64_t W = seg_cost0[S_static];      // cost of the static part
-  const int32_t g_static = S_static < S ? segs[S_static].gblk0 : static_cast<int32_t>(gblk);
+  const int32_t g_end = static_cast<int32_t>(gblk);
+  auto blk_cost = [&](int s) { return 2 * int64_t(block_bytes[segs[s].cls]) * weight[segs[s].cls]; };
+  // cumulative cost in front of global block g, which lies in segment s (or g == end of segment s)
+  auto cost_at = [&](int32_t g, int s) { return s >= S ? cost : seg_cost0[s] + int64_t(g - segs[s].gblk0) * blk_cost(s); };
+  // block boundary whose cumulative cost is nearest to `target`; `s` is a monotone search cursor and
+  // returns the segment that holds the boundary block (S at the very end)
+  auto block_at = [&](int64_t target, int& s) -> int32_t {
+    while (s < S && seg_cost0[s + 1] <= target) ++s;
+    if (s >= S) return g_end;
+    const int64_t per = blk_cost(s);
+    int64_t j = (target - seg_cost0[s] + per / 2) / per;
+    if (j < 0) j = 0;
+    if (j >= segs[s].nblk) {
+      j = 0;
+      ++s;
+      if (s >= S) return g_end;
+    }
+    return segs[s].gblk0 + static_cast<int32_t>(j);
+  };
+  auto seg_of = [&](int32_t g, int s) {   // segment holding block g, searching forward from s
+    while (s < S && segs[s].gblk0 + segs[s].nblk <= g) ++s;
+    return s;
+  };
 
-  // ---- work items: P static ranges of equal cost, then the dynamic items ----
+  // ---- groups of consecutive workers: an equal-cost range each; its tail becomes the shared pool,
+  //      the rest is split into one own range per worker ----
   struct Item {
-    int32_t g0, g1, seg0, pid0;
-    double key;
+    int32_t g0, g1, seg0, pid0, group, rank;
   };
   std::vector<Item> items(P);
+  std::vector<GroupRec> groups;
+  std::vector<PoolSeg> psegs;
   {
-    std::vector<int32_t> bound(P + 1), bseg(P + 1);
-    int s = 0;
-    for (int w = 0; w <= P; ++w) {
-      const int64_t target = static_cast<int64_t>((static_cast<__int128>(W) * w) / P);
-      while (s < S_static && seg_cost0[s + 1] <= target) ++s;
-      if (s >= S_static) {
-        bound[w] = g_static, bseg[w] = S_static;
-      } else {
-        const int64_t per = 2 * int64_t(block_bytes[segs[s].cls]) * weight[segs[s].cls];
-        int64_t j = (target - seg_cost0[s] + per / 2) / per;
-        if (j > segs[s].nblk) j = segs[s].nblk;
-        bound[w] = segs[s].gblk0 + static_cast<int32_t>(j);
-        bseg[w] = (j == segs[s].nblk) ? s + 1 : s;
-      }
-    }
-    bound[0] = 0, bseg[0] = 0, bound[P] = g_static, bseg[P] = S_static;
-    for (int w = 0; w < P; ++w) items[w] = {bound[w], bound[w + 1], bseg[w], 0, 0.0};
-  }
-  {
-    std::vector<Item> dyn;
-    for (int c = 0; c < 3; ++c) {
-      const int n = dyn_g1[c] - dyn_g0[c];
-      if (n <= 0) continue;
-      int per = static_cast<int>(kDynamicItemBytes / (2 * int64_t(block_bytes[c])));
-      if (per < 1) per = 1;
-      int sidx = first_dyn_seg[c];
-      for (int g0 = dyn_g0[c]; g0 < dyn_g1[c]; g0 += per) {
-        const int g1 = g0 + per < dyn_g1[c] ? g0 + per : dyn_g1[c];
-        while (segs[sidx].gblk0 + segs[sidx].nblk <= g0) ++sidx;
-        // interleave the classes in the queue by relative position inside their dynamic part
-        dyn.push_back({g0, g1, sidx, 0, (double(g0 - dyn_g0[c]) + 0.5 * (g1 - g0)) / double(n)});
-      }
-    }
-    std::stable_sort(dyn.begin(), dyn.end(), [](const Item& x, const Item& y) { return x.key < y.key; });
-    items.insert(items.end(), dyn.begin(), dyn.end());
-  }
-  const int Q = static_cast<int>(items.size()) - P;
-
-  // partial ids: one per (item, class, (b, kv head)) intersection, numbered in the global block order so
-  // that the ids of one (b, kv head, class, part) are contiguous
-  const int BH = B * Hkv;
-  std::vector<int32_t> bh_pid(size_t(BH) * 12, 0);   // [bh][class][static|dynamic][begin, end)
-  int32_t npart = 0;
-  {
-    std::vector<int> order(items.size());
-    for (size_t i = 0; i < order.size(); ++i) order[i] = static_cast<int>(i);
-    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return items[x].g0 < items[y].g0; });
-    for (int idx : order) {
-      Item& it = items[idx];
-      it.pid0 = npart;
-      const int part = idx < P ? 0 : 1;
-      int s = it.seg0;
-      int32_t g = it.g0;
-      int cur = -1, cur_cls = -1;
-      while (g < it.g1) {
-        const Segment& sg = segs[s];
-        if (sg.bh != cur || sg.cls != cur_cls) {
-          cur = sg.bh, cur_cls = sg.cls;
-          int32_t* range = &bh_pid[((size_t(cur) * 3 + cur_cls) * 2 + part) * 2];
-          if (range[1] == range[0]) range[0] = npart;
-          range[1] = npart + 1;
-          ++npart;
+    for (int w0 = 0, j = 0; w0 < P; w0 += group_workers, ++j) {
+      const int w1 = w0 + group_workers < P ? w0 + group_workers : P;
+      const int k = w1 - w0;
+      const int32_t G0 = group_g0[j], G1 = group_g0[j + 1];
+      const int sG0 = group_s0[j], sG1 = group_s0[j + 1];
+      const int64_t c0 = cost_at(G0, sG0), c1 = cost_at(G1, sG1);
+      GroupRec gr;
+      std::memset(&gr, 0, sizeof(gr));
+      gr.nworkers = k;
+      gr.counter = static_cast<int32_t>(groups.size());
+      gr.pseg0 = static_cast<int32_t>(psegs.size());
+      int32_t Gp = G1;
+      int sGp = sG1;
+      if (pool_percent > 0 && int64_t(G1 - G0) >= int64_t(kMinBlocksPerWorkerForPool) * k) {
+        int sc = sG0;
+        Gp = block_at(c1 - (c1 - c0) * pool_percent / 100, sc);
+        sGp = sc;
+        if (Gp < G0) Gp = G0, sGp = sG0;
+        if (Gp > G1) Gp = G1, sGp = sG1;
+        // a pool touches at most kMaxPoolSegments segments: move its start forward if it has to
+        int first = seg_of(Gp, sGp);
+        const int last = G1 > Gp ? seg_of(G1 - 1, first) : first;
+        if (last - first + 1 > kMaxPoolSegments) {
+          first = last - kMaxPoolSegments + 1;
+          Gp = segs[first].gblk0, sGp = first;
         }
-        const int32_t end = sg.gblk0 + sg.nblk;
-        g = end < it.g1 ? end : it.g1;
-        ++s;
+        int32_t gran = 0;
+        for (int s = first; s < S && segs[s].gblk0 < G1 && Gp < G1; ++s) {
+          const int32_t lo = Gp > segs[s].gblk0 ? Gp : segs[s].gblk0;
+          const int32_t hi = G1 < segs[s].gblk0 + segs[s].nblk ? G1 : segs[s].gblk0 + segs[s].nblk;
+          if (hi <= lo) continue;
+          PoolSeg ps;
+          std::memset(&ps, 0, sizeof(ps));
+          ps.seg = s;
+          ps.unit0 = 2 * (lo - segs[s].gblk0);
+          ps.nunits = 2 * (hi - lo);
+          ps.gran0 = gran;
+          const int J = kIterUnits[segs[s].cls];
+          gran += (ps.nunits + J - 1) / J;
+          psegs.push_back(ps);
+        }
+        gr.ngran = gran;
+        gr.nps = static_cast<int32_t>(psegs.size()) - gr.pseg0;
+      }
+      // own ranges: [G0, Gp) in k parts of equal cost
+      const int64_t cp = cost_at(Gp, sGp);
+      int sc = sG0;
+      int32_t prev = G0;
+      int sprev = sG0;
+      for (int r = 0; r < k; ++r) {
+        int32_t nb;
+        int snb;
+        if (r == k - 1) {
+          nb = Gp, snb = sGp;
+        } else {
+          nb = block_at(c0 + static_cast<int64_t>((static_cast<__int128>(cp - c0) * (r + 1)) / k), sc);
+          snb = sc;
+          if (nb > Gp) nb = Gp, snb = sGp;
+          if (nb < prev) nb = prev, snb = sprev;
+        }
+        items[w0 + r] = {prev, nb, seg_of(prev, sprev), 0, gr.counter, r};
+        prev = nb, sprev = snb;
+      }
+      groups.push_back(gr);
+    }
+  }
+  const int NG = static_cast<int>(groups.size());
+  const int NPS = static_cast<int>(psegs.size());
+
+  // partial ids.  One per (worker, segment its own range touches) and one per (pool part, rank).  The
+  // ids of a (b, kv head) are contiguous, so the merge reads one dense block of the workspace.  A worker
+  // enters every segment but its first one at the segment's start, i.e. as its first visitor; so the
+  // id of its first piece is stored with the worker and the id of the first visitor with the segment.
+  const int BH = B * Hkv;
+  auto bh_of = [&](const Segment& sg) { return sg.b * Hkv + sg.h; };
+  std::vector<int32_t> own_cnt(S, 0), bh_off(BH + 1, 0);
+  for (int w = 0; w < P; ++w) {
+    int sidx = items[w].seg0;
+    for (int32_t g = items[w].g0; g < items[w].g1; ++sidx) {
+      ++own_cnt[sidx];
+      const int32_t end = segs[sidx].gblk0 + segs[sidx].nblk;
+      g = end < items[w].g1 ? end : items[w].g1;
+    }
+  }
+  for (int sidx = 0; sidx < S; ++sidx) bh_off[bh_of(segs[sidx]) + 1] += own_cnt[sidx];
+  for (int g = 0; g < NG; ++g)
+    for (int i = 0; i < groups[g].nps; ++i) bh_off[bh_of(segs[psegs[groups[g].pseg0 + i].seg]) + 1] += groups[g].nworkers;
+  for (int i = 0; i < BH; ++i) bh_off[i + 1] += bh_off[i];
+  const int32_t npart = bh_off[BH];
+  {
+    std::vector<int32_t> cursor(bh_off.begin(), bh_off.end() - 1);
+    for (int sidx = 0; sidx < S; ++sidx) {
+      segs[sidx].pid0 = cursor[bh_of(segs[sidx])];
+      cursor[bh_of(segs[sidx])] += own_cnt[sidx];
+    }
+    for (int g = 0; g < NG; ++g)
+      for (int i = 0; i < groups[g].nps; ++i) {
+        PoolSeg& ps = psegs[groups[g].pseg0 + i];
+        ps.slot0 = cursor[bh_of(segs[ps.seg])];
+        cursor[bh_of(segs[ps.seg])] += groups[g].nworkers;
+      }
+    std::vector<int32_t> visitors(S, 0);
+    for (int w = 0; w < P; ++w) {
+      int sidx = items[w].seg0;
+      items[w].pid0 = items[w].g0 < items[w].g1 ? segs[sidx].pid0 + visitors[sidx] : 0;
+      for (int32_t g = items[w].g0; g < items[w].g1; ++sidx) {
+        ++visitors[sidx];
+        const int32_t end = segs[sidx].gblk0 + segs[sidx].nblk;
+        g = end < items[w].g1 ? end : items[w].g1;
       }
     }
   }
@@ -273,8 +384,9 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
   std::memset(&hd, 0, sizeof(hd));
   hd.magic = kPlanMagic, hd.version = kPlanVersion;
   hd.batch = B, hd.num_q_heads = shape->num_q_heads, hd.num_kv_heads = Hkv, hd.head_dim = D;
-  hd.chunk_size = C, hd.group_size = G, hd.rep = shape->num_q_heads / Hkv;
-  hd.num_workers = P, hd.num_segments = S, hd.num_partials = npart, hd.num_items = Q;
+  hd.chunk_size = C, hd.group_size = G, hd.rep = rep;
+  hd.num_workers = P, hd.num_segments = S, hd.num_partials = npart;
+  hd.num_groups = NG, hd.num_pool_segs = NPS;
   hd.total_gblocks = static_cast<int32_t>(gblk);
   hd.total_chunks = total_chunks, hd.total_tokens = total_tokens, hd.packed_bytes = packed;
   for (int c = 0; c < 3; ++c) {
@@ -298,8 +410,12 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
   place(hd.off_blk_base, 12 * int64_t(B + 1));
   place(hd.off_nblk, 12 * int64_t(B));
   place(hd.off_segments, int64_t(sizeof(Segment)) * S);
-  place(hd.off_bh_pid, 48 * int64_t(BH));
-  place(hd.off_worker_rec, int64_t(sizeof(WorkerRec)) * (P + Q));
+  place(hd.off_bh_off, 4 * int64_t(BH + 1));
+  place(hd.off_worker_rec, int64_t(sizeof(WorkerRec)) * P);
+  place(hd.off_group_rec, int64_t(sizeof(GroupRec)) * NG);
+  place(hd.off_pool_seg, int64_t(sizeof(PoolSeg)) * NPS);
+  off = (off + 127) & ~int64_t(127);
+  place(hd.off_counters, int64_t(4 * kCounterStride) * NG);
   if (off >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "plan larger than 2 GiB");
   hd.plan_bytes = off;
 
@@ -337,16 +453,34 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
     put(hd.off_blk_base, v_blk_base.data(), 12 * size_t(B + 1));
     put(hd.off_nblk, v_nblk.data(), 12 * size_t(B));
     put(hd.off_segments, segs.data(), sizeof(Segment) * size_t(S));
-    put(hd.off_bh_pid, bh_pid.data(), 48 * size_t(BH));
-    std::vector<WorkerRec> recs(P + Q);
+    put(hd.off_bh_off, bh_off.data(), 4 * bh_off.size());
+    std::vector<WorkerRec> recs(P);
     std::memset(recs.data(), 0, sizeof(WorkerRec) * recs.size());
-    for (int w = 0; w < P + Q; ++w) {
-      recs[w].g0 = items[w].g0, recs[w].g1 = items[w].g1;
-      recs[w].seg0 = items[w].seg0, recs[w].pid0 = items[w].pid0;
-      if (items[w].g0 < items[w].g1) recs[w].first = segs[items[w].seg0];
+    // Which workgroup id runs which range.  Workgroup ids are handed to the compute units in order
+    // (round-robin over the XCDs), and when P fills the chip twice, workgroup i shares a SIMD with
+    // workgroup i + P/2, which was dispatched later and loses every issue arbitration against it.
+    // Rank r of group j therefore becomes workgroup (r odd ? P/2 : 0) + j*k/2 + (r/2 + j) mod (k/2):
+    // every group is half early and half late workgroups, SIMD mates are neighbouring ranks of one
+    // group (same class, same pool), and a rank does not always land on the same XCD.
+    int pair_mode = kPairMode;
+    if (const char* e = std::getenv("COCKTAIL_PAIR_MODE")) pair_mode = std::atoi(e);   // tuning aid
+    const bool spread = pair_mode >= 2 && group_workers % 2 == 0 && P % group_workers == 0;
+    for (int w = 0; w < P; ++w) {
+      int id = w;
+      if (spread) {
+        const int hk = group_workers / 2, j = items[w].group, r = items[w].rank;
+        id = pair_mode == 2 ? (r & 1) * (P / 2) + j * hk + ((r >> 1) + j) % hk
+                            : (r / hk) * (P / 2) + j * hk + (r % hk + j) % hk;
+      }
+      WorkerRec& rc = recs[id];
+      rc.g0 = items[w].g0, rc.g1 = items[w].g1;
+      rc.seg0 = items[w].seg0, rc.pid0 = items[w].pid0;
+      rc.group = items[w].group, rc.rank = items[w].rank;
+      if (items[w].g0 < items[w].g1) rc.first = segs[items[w].seg0];
     }
     put(hd.off_worker_rec, recs.data(), sizeof(WorkerRec) * recs.size());
-
+    put(hd.off_group_rec, groups.data(), sizeof(GroupRec) * groups.size());
+    put(hd.off_pool_seg, psegs.data(), sizeof(PoolSeg) * psegs.size());
   }
   g_err[0] = 0;
   return COCKTAIL_OK;

@@ -34,7 +34,9 @@ def _plan(w, workers):
 
 
 # field offsets of the internal plan header (csrc/plan.h), little-endian
-_HDR = struct.Struct("<II6i i3i ii qq 3q3q 3i3i qqq 11i i 4i")
+_HDR = struct.Struct("<II6i i3i ii qq 3q3q 3i3i qqq 14i 2i i 2i")
+ITER_UNITS = (4, 2, 1)      # units per loop iteration of the decode kernel, per class
+COUNTER_STRIDE = 32
 
 
 def _parse(blob):
@@ -45,11 +47,11 @@ def _parse(blob):
     h["class_blocks"], h["class_bytes"] = f[16:19], f[19:22]
     h["block_bytes"], h["row_bytes"] = f[22:25], f[25:28]
     h["workspace_bytes"], h["plan_bytes"], h["packed_bytes"] = f[28:31]
-    offs = f[31:42]
+    offs = f[31:45]
     keys = ["seq_len", "cum_tokens", "chunk_off", "perm", "class_tokens", "class_chunk0", "blk_base", "nblk",
-            "segments", "bh_pid", "worker_rec"]
+            "segments", "bh_pid", "worker_rec", "group_rec", "pool_seg", "counters"]
     h["off"] = dict(zip(keys, offs))
-    h["items"] = f[42]
+    h["groups"], h["pool_segs"], _, h["off"]["bh_off"] = f[45:49]
     return h
 
 
@@ -57,7 +59,110 @@ def _arr(blob, off, dtype, n):
     return np.frombuffer(blob.tobytes(), dtype=dtype, count=n, offset=off)
 
 
-@pytest.mark.parametrize("cfg,workers", [(1, 64), (1, 2048), (3, 512), (4, 2048), (5, 512), (5, 7)])
+def _check_work_split(plan, w, workers, seed=0):
+    """Replays the decode kernel's walk over the plan (own ranges, then pool tickets in a random
+    hand-out order) and checks that every unit is read exactly once and every partial id is sound."""
+    h = _parse(plan.blob)
+    assert h["plan_bytes"] == plan.blob.size and h["workers"] == workers
+    S, P, NG, NPS = h["segments"], workers, h["groups"], h["pool_segs"]
+    segs = _arr(plan.blob, h["off"]["segments"], np.int32, 8 * S).reshape(S, 8)
+    BH = w.batch * w.num_kv_heads
+    bh_off = _arr(plan.blob, h["off"]["bh_off"], np.int32, BH + 1)
+    recs = _arr(plan.blob, h["off"]["worker_rec"], np.int32, 16 * P).reshape(P, 16)
+    groups = _arr(plan.blob, h["off"]["group_rec"], np.int32, 8 * NG).reshape(NG, 8)
+    psegs = _arr(plan.blob, h["off"]["pool_seg"], np.int32, 8 * NPS).reshape(NPS, 8)
+    counters = _arr(plan.blob, h["off"]["counters"], np.uint32, COUNTER_STRIDE * NG)
+    assert (counters == 0).all() and h["off"]["counters"] % 128 == 0
+    assert h["gblocks"] == sum(plan.sizes.class_blocks)
+    # segments tile the class buffers: every physical block of every (class, b, h) exactly once
+    phys = [np.zeros(int(plan.sizes.class_blocks[c]), dtype=np.int32) for c in range(3)]
+    g = 0
+    for b_, h_, cls, ntok, blk0, nblk, gblk0, spid in segs:
+        assert gblk0 == g and nblk > 0 and (nblk - 1) * 64 < ntok
+        phys[cls][blk0:blk0 + nblk] += 1
+        g += nblk
+    assert all((x == 1).all() for x in phys)
+
+    rng = np.random.default_rng(seed)
+    seen = np.zeros(2 * h["gblocks"], dtype=np.int32)       # per unit
+    pid_owner = {}
+    members = {}
+    for it in range(P):
+        members.setdefault(int(recs[it, 12]), []).append(it)
+    cost = np.zeros(P, dtype=np.int64)
+    pool_cost = 0
+    for gi in range(NG):
+        ngran, pseg0, nps, nworkers, counter = groups[gi, :5]
+        ws = sorted(members.get(gi, []), key=lambda x: int(recs[x, 13]))
+        assert len(ws) == nworkers and [int(recs[x, 13]) for x in ws] == list(range(nworkers))
+        assert 0 <= nps <= 32 and counter == gi
+        if w.num_q_heads != w.num_kv_heads:
+            assert ngran == 0                                # grouped-query shapes: static split only
+        # tickets are handed out in ascending order to whichever worker asks next
+        hand = sorted(rng.integers(0, nworkers, size=ngran).tolist()) if ngran else []
+        tickets = {r: [] for r in range(nworkers)}
+        for t, r in zip(range(ngran), rng.permutation(hand) if ngran else []):
+            tickets[int(r)].append(t)
+        if nps:
+            assert psegs[pseg0, 3] == 0
+            last = psegs[pseg0 + nps - 1]
+            J = ITER_UNITS[segs[last[0], 2]]
+            assert last[3] + (last[2] + J - 1) // J == ngran
+        for r, it in enumerate(ws):
+            g0, g1, s, pid = recs[it, :4]
+            if g0 < g1:
+                assert recs[it, 4:12].tolist() == segs[s].tolist()
+            last_seg, used = -1, set()
+            u, u1 = 2 * g0, 2 * g1
+            while u < u1:                                    # own range
+                b_, h_, cls, ntok, blk0, nblk, gblk0, spid = segs[s]
+                bh = b_ * w.num_kv_heads + h_
+                if u >= 2 * (gblk0 + nblk):
+                    s += 1
+                    pid = segs[s, 7]                         # enters the next segment as its first visitor
+                    continue
+                assert 2 * gblk0 <= u
+                if s != last_seg:
+                    assert pid not in pid_owner
+                    pid_owner[pid] = (cls, bh, 0)
+                    last_seg = s
+                end = min(u1, 2 * (gblk0 + nblk))
+                nu = min(ITER_UNITS[cls], end - u)
+                seen[u:u + nu] += 1
+                cost[it] += nu * h["block_bytes"][cls]
+                u += nu
+            for t in tickets[r]:                             # pool
+                pi = max(i for i in range(nps) if psegs[pseg0 + i, 3] <= t)
+                seg, unit0, nunits, gran0, slot0 = psegs[pseg0 + pi, :5]
+                b_, h_, cls, ntok, blk0, nblk, gblk0, spid = segs[seg]
+                bh = b_ * w.num_kv_heads + h_
+                J = ITER_UNITS[cls]
+                us = unit0 + (t - gran0) * J
+                nu = min(J, unit0 + nunits - us)
+                assert 0 < nu and us + nu <= 2 * nblk and seg >= last_seg
+                if seg != last_seg:
+                    slot = slot0 + r
+                    assert slot not in pid_owner
+                    pid_owner[slot] = (cls, bh, 1)
+                    used.add(pi)
+                    last_seg = seg
+                seen[2 * gblk0 + us:2 * gblk0 + us + nu] += 1
+                pool_cost += nu * h["block_bytes"][cls]
+            for pi in range(nps):                            # slots the worker fills with the neutral state
+                if pi not in used:
+                    seg, slot0 = psegs[pseg0 + pi, 0], psegs[pseg0 + pi, 4]
+                    assert slot0 + r not in pid_owner
+                    pid_owner[slot0 + r] = (segs[seg, 2], segs[seg, 0] * w.num_kv_heads + segs[seg, 1], 1)
+    assert (seen == 1).all()
+    assert sorted(pid_owner) == list(range(h["partials"])) and h["partials"] == plan.sizes.num_partials
+    assert bh_off[0] == 0 and bh_off[BH] == h["partials"] and (np.diff(bh_off) >= 0).all()
+    for bh in range(BH):
+        assert all(pid_owner[p][1] == bh for p in range(bh_off[bh], bh_off[bh + 1]))
+    assert plan.sizes.workspace_bytes == max(h["partials"], 1) * h["rep"] * (w.head_dim + 2) * 4
+    return h, cost, pool_cost
+
+
+@pytest.mark.parametrize("cfg,workers", [(1, 64), (1, 2048), (2, 2048), (3, 512), (4, 2048), (5, 512), (5, 7)])
 def test_planner_matches_oracle_and_splits_work_exactly_once(cfg, workers):
     w = workloads.config(cfg)
     plan, bits = _plan(w, workers)
@@ -75,65 +180,24 @@ def test_planner_matches_oracle_and_splits_work_exactly_once(cfg, workers):
         blocks = sum(((int(plan.class_tokens[b, c]) + 63) // 64) * w.num_kv_heads for b in range(w.batch))
         assert plan.sizes.class_blocks[c] == blocks
         assert plan.sizes.class_bytes[c] == blocks * O.block_bytes(c, w.head_dim, w.group_size)
+    h, cost, pool_cost = _check_work_split(plan, w, workers)
+    if cfg == 4:
+        # the headline shape has pools: a fifth of the bytes, the rest in near-equal own ranges
+        total = cost.sum() + pool_cost
+        assert 0.15 * total <= pool_cost <= 0.25 * total and h["groups"] == 256
 
-    h = _parse(plan.blob)
-    assert h["plan_bytes"] == plan.blob.size and h["workers"] == workers
-    S, P, Q = h["segments"], workers, h["items"]
-    segs = _arr(plan.blob, h["off"]["segments"], np.int32, 8 * S).reshape(S, 8)
-    BH = w.batch * w.num_kv_heads
-    bh_pid = _arr(plan.blob, h["off"]["bh_pid"], np.int32, BH * 12).reshape(BH, 3, 2, 2)
-    recs = _arr(plan.blob, h["off"]["worker_rec"], np.int32, 16 * (P + Q)).reshape(P + Q, 16)
-    assert h["gblocks"] == sum(plan.sizes.class_blocks)
-    # segments tile the class buffers: every physical block of every (class, b, h) exactly once
-    phys = [np.zeros(int(plan.sizes.class_blocks[c]), dtype=np.int32) for c in range(3)]
-    g = 0
-    for b_, h_, cls, ntok, blk0, nblk, gblk0, bh in segs:
-        assert gblk0 == g and bh == b_ * w.num_kv_heads + h_ and nblk > 0 and ntok > (nblk - 1) * 64
-        phys[cls][blk0:blk0 + nblk] += 1
-        g += nblk
-    assert all((x == 1).all() for x in phys)
-    # walk every work item the way the kernel does; every block is visited exactly once
-    seen = np.zeros(h["gblocks"], dtype=np.int32)
-    pid_owner = {}
-    cost = []
-    for it in range(P + Q):
-        g, g1, s, pid = recs[it, :4]
-        if g < g1:
-            assert recs[it, 4:12].tolist() == segs[s].tolist()
-        cur = None
-        bytes_ = 0
-        while g < g1:
-            b_, h_, cls, ntok, blk0, nblk, gblk0, bh = segs[s]
-            assert gblk0 <= g < gblk0 + nblk
-            if (cls, bh) != cur:
-                if cur is not None:
-                    pid += 1
-                cur = (cls, bh)
-                assert pid not in pid_owner
-                pid_owner[pid] = (cls, bh, 0 if it < P else 1)
-            je = min(gblk0 + nblk, g1)
-            seen[g:je] += 1
-            bytes_ += (je - g) * 2 * h["block_bytes"][cls]
-            g = je
-            s += 1
-        cost.append(bytes_)
-    assert (seen == 1).all()
-    assert sorted(pid_owner) == list(range(h["partials"])) and h["partials"] == plan.sizes.num_partials
-    covered = 0
-    for bh in range(BH):
-        for c in range(3):
-            for part in range(2):
-                lo, hi = bh_pid[bh, c, part]
-                assert all(pid_owner[p] == (c, bh, part) for p in range(lo, hi))
-                covered += hi - lo
-    assert covered == h["partials"]
-    # the static ranges carry most of the bytes; dynamic items are small
-    static, dyn = cost[:P], cost[P:]
-    total = sum(cost)
-    if Q:
-        assert 0.05 * total <= sum(dyn) <= 0.35 * total
-        assert max(dyn) <= 64 * 1024
-    assert plan.sizes.workspace_bytes == max(h["partials"], 1) * h["rep"] * (w.head_dim + 2) * 4
+
+@pytest.mark.parametrize("seed", range(6))
+def test_work_split_of_random_small_shapes(seed):
+    rng = np.random.default_rng(1000 + seed)
+    batch = int(rng.integers(1, 5))
+    hkv = int(rng.integers(1, 4))
+    chunk = int(rng.choice([8, 16, 64, 128]))
+    lens = [int(x) for x in rng.integers(0, 6000, size=batch)]
+    w = workloads.small(f"rand{seed}", batch, hkv, hkv, lens, chunk, int(rng.choice([32, 64, 128])), seed_offset=seed)
+    for workers in (1, 3, 16, 40):
+        plan, _ = _plan(w, workers)
+        _check_work_split(plan, w, workers, seed)
 
 
 def test_plan_handles_empty_sequences_and_tail_only():
