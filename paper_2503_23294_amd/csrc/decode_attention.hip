@@ -422,9 +422,9 @@ struct Stream {
     enter(rec.first, uni(rec.seg0));
     pid = uni(rec.pid0);   // the first segment is usually entered somewhere in the middle
     last_seg = -1;
-    const GroupRec& gr = kparams()->groups[uni(rec.group)];
-    ngran = uni(gr.ngran), nps = uni(gr.nps), pseg0 = uni(gr.pseg0), rank = uni(rec.rank);
-    counter = uni(gr.counter);
+    const int rn = uni(rec.rank_nps);
+    ngran = uni(rec.ngran), nps = rn >> 16, pseg0 = uni(rec.pseg0), rank = rn & 0xffff;
+    counter = uni(rec.group);
     pi = -1, p_unit0 = p_nunits = p_gran0 = p_gran1 = p_slot0 = 0;
     tk0 = tk1 = 0, used = 0;
     phase = 0;
@@ -553,7 +553,6 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
   float qsum[NGH];
   typename CLS::Stage ks[J], vs[J];
   int pid = cur.pid;
-  begin_state<NGH, GL>(cur.qrow + r, h, st, q, qsum);
   rsrc_t krs = make_rsrc(kbase + int64_t(cur.blk0) * CLS::BLOCKB, uint32_t(cur.nblk) * CLS::BLOCKB);
   rsrc_t vrs = make_rsrc(vbase + int64_t(cur.blk0) * CLS::BLOCKB, uint32_t(cur.nblk) * CLS::BLOCKB);
   int ru = cur.us, rn = cur.nu;   // what the stages were (re)filled with last
@@ -561,6 +560,8 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
   for (int jj = 0; jj < J; ++jj) CLS::load(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
 #pragma unroll
   for (int jj = 0; jj < J; ++jj) CLS::load(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
+  sched_fence();
+  begin_state<NGH, GL>(cur.qrow + r, h, st, q, qsum);   // the query arrives while the first units are on their way
   int valid = cur.valid;
   Piece nxt = sm.next(lane);
 #pragma unroll 1

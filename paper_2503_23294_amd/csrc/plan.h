@@ -36,9 +36,9 @@ struct WorkerRec {
   int32_t seg0;              // index of the segment holding g0
   int32_t pid0;              // partial id of its piece of segment seg0 (in later segments it is the first visitor)
   Segment first;             // copy of segments[seg0]
-  int32_t group;             // index of its GroupRec
-  int32_t rank;              // position inside the group
-  int32_t pad[2];
+  int32_t group;             // index of its GroupRec and of the group's ticket counter
+  int32_t rank_nps;          // position inside the group | (GroupRec::nps << 16)
+  int32_t ngran, pseg0;      // copies of the GroupRec fields, so that a worker starts from one record
 };
 static_assert(sizeof(WorkerRec) == 64, "WorkerRec is one 64-byte line");
 

@@ -475,7 +475,9 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
       WorkerRec& rc = recs[id];
       rc.g0 = items[w].g0, rc.g1 = items[w].g1;
       rc.seg0 = items[w].seg0, rc.pid0 = items[w].pid0;
-      rc.group = items[w].group, rc.rank = items[w].rank;
+      rc.group = items[w].group;
+      rc.rank_nps = items[w].rank | (groups[items[w].group].nps << 16);
+      rc.ngran = groups[items[w].group].ngran, rc.pseg0 = groups[items[w].group].pseg0;
       if (items[w].g0 < items[w].g1) rc.first = segs[items[w].seg0];
     }
     put(hd.off_worker_rec, recs.data(), sizeof(WorkerRec) * recs.size());

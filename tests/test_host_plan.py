@@ -93,8 +93,9 @@ def _check_work_split(plan, w, workers, seed=0):
     pool_cost = 0
     for gi in range(NG):
         ngran, pseg0, nps, nworkers, counter = groups[gi, :5]
-        ws = sorted(members.get(gi, []), key=lambda x: int(recs[x, 13]))
-        assert len(ws) == nworkers and [int(recs[x, 13]) for x in ws] == list(range(nworkers))
+        ws = sorted(members.get(gi, []), key=lambda x: int(recs[x, 13]) & 0xffff)
+        assert len(ws) == nworkers and [int(recs[x, 13]) & 0xffff for x in ws] == list(range(nworkers))
+        assert all(recs[x, 13] >> 16 == nps and recs[x, 14] == ngran and recs[x, 15] == pseg0 for x in ws)
         assert 0 <= nps <= 32 and counter == gi
         if w.num_q_heads != w.num_kv_heads:
             assert ngran == 0                                # grouped-query shapes: static split only
