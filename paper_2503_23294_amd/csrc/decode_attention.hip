@@ -2,18 +2,19 @@
 // and FP16 classes of the packed cache.
 //
 // Design (gfx950, wave64):
-//  * The packed cache of a layer is one long stream of 64-token blocks.  The host
-//    planner cuts that stream into `num_workers` contiguous ranges of equal cost;
-//    workgroup w streams range w and emits one partial softmax state per
-//    (sequence, kv head) it touches.
+//  * The host planner puts all 64-token blocks of a layer into one global order and cuts it into
+//    groups of a few workers.  A worker (workgroup) streams its own block range and then takes
+//    pieces of the group's shared pool through an atomic ticket counter, so that the workers of a
+//    group finish together; it emits one partial softmax state per (sequence, kv head) segment it
+//    touches.
 //  * Inside a wave a token is owned by a PAIR of lanes: lane l works on token
 //    l % 32 of a 32-token unit and on channels [64*(l/32), 64*(l/32)+64).  The block
 //    layout stores the j-th 16-byte piece of all 64 tokens contiguously, so each
 //    half-wave reads one contiguous 512-byte run per load instruction, and the q.k
 //    dot product needs a single cross-lane add per token.  A lane keeps 64 output
-//    accumulators and its half of the query in registers; the whole kernel stays
-//    far below 256 VGPRs so that two waves share every SIMD and one wave's loads
-//    hide behind the other's arithmetic.
+//    accumulators and its half of the query in registers; the kernel stays below
+//    256 VGPRs so that two waves share every SIMD and one wave's loads hide behind
+//    the other's arithmetic.
 //  * Codes are expanded without any conversion: a code field masked out of a
 //    half-word IS an fp16 subnormal of value code * 2^(pos-24), which v_dot2_f32_f16
 //    and v_fma_mix_f32 consume exactly; the power of two is folded into per-group
@@ -22,7 +23,8 @@
 //      sum p v^  = sum_t (p_t scale_tg) code_t + sum_t p_t zero_tg
 //  * Loads go through buffer resources (one VGPR of address per lane) and are
 //    software pipelined by hand: J register stages of K units and J of V units are
-//    refilled one loop iteration ahead of the arithmetic.
+//    refilled one loop iteration ahead of the arithmetic, with the units of whatever
+//    piece comes next (same segment, next segment, or a pool piece).
 //  * Softmax is online per lane pair: logits of J units, one lazy rescale when the
 //    reference maximum grows by more than 2^8, then the V pass.  (m, l, o[D])
 //    partials go to the workspace and a second small kernel merges them exactly
