@@ -166,7 +166,9 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  * The counters are zero in the blob cocktail_plan writes and every call leaves
  * them zero again, so calls on the same plan_dev must not overlap in time (calls
  * on one stream never do), and a plan_dev whose call was aborted has to be
- * re-uploaded.
+ * re-uploaded.  Which worker takes which pool piece differs from call to call, so
+ * two calls on the same inputs agree to fp32 summation order, not bit for bit
+ * (shapes with Hq > Hkv use no pools and are reproducible bit for bit).
  *
  *   q          DEVICE fp16 [B][Hq][D], 16-byte aligned
  *   sm_scale   softmax scale; <= 0 selects 1/sqrt(D)

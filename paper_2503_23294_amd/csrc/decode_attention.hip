@@ -423,6 +423,7 @@ struct Stream {
     u = 2 * uni(rec.g0), u1 = 2 * uni(rec.g1);
     enter(rec.first, uni(rec.seg0));
     pid = uni(rec.pid0);   // the first segment is usually entered somewhere in the middle
+    if (u >= u1) s = -1;   // no own range: `first` describes nothing, the first pool piece enters its segment
     last_seg = -1;
     const int rn = uni(rec.rank_nps);
     ngran = uni(rec.ngran), nps = rn >> 16, pseg0 = uni(rec.pseg0), rank = rn & 0xffff;

@@ -180,6 +180,49 @@ def test_more_workers_than_blocks_and_repeatability():
     assert torch.equal(out2, c.out_dev) and torch.equal(lse2, c.lse_dev)
 
 
+def _counters(c):
+    """The decode kernel's ticket counters inside the device copy of the plan (internal layout: csrc/plan.h)."""
+    import struct
+    f = struct.unpack_from("<II6i i3i ii qq 3q3q 3i3i qqq 14i 2i i 2i", c.plan.blob.tobytes(), 0)
+    off, ngroups = f[44], f[45]
+    return c.cache.plan_dev[off:off + 128 * ngroups].cpu().numpy().view(np.uint32)[::32], f[46]
+
+
+@pytest.mark.parametrize("workers", [1, 3, 8, 13, 24])
+def test_shared_pools_with_few_workers(workers):
+    """Few workers on a multi-sequence MHA shape: every group has a pool that spans several segments."""
+    w = workloads.small(f"pools{workers}", 3, 2, 2, [3000, 1500, 4500], 64, 32, mix=(0.2, 0.4, 0.4),
+                        seed_offset=40 + workers)
+    _announce(w.name)
+    c = Case(w, workers=workers)
+    cnt, pool_segs = _counters(c)
+    assert pool_segs > 0, "this shape is meant to exercise the pools"
+    assert (cnt == 0).all(), "a call must leave the ticket counters at zero"
+    c.check_all()
+    for _ in range(3):                       # tickets are handed out anew on every call
+        out, lse = ck.cocktail_decode_attention(c.cache, c.q_dev)
+        torch.cuda.synchronize()
+        assert (_counters(c)[0] == 0).all()
+        c.out, c.lse = out.cpu().numpy(), lse.cpu().numpy()
+        for b in range(w.batch):
+            for h in range(w.num_kv_heads):
+                c.check_head(b, h)
+
+
+@pytest.mark.parametrize("env", [{"COCKTAIL_POOL_PERCENT": "100"}, {"COCKTAIL_POOL_PERCENT": "0"},
+                                 {"COCKTAIL_GROUP_WORKERS": "3", "COCKTAIL_POOL_PERCENT": "50"},
+                                 {"COCKTAIL_LAYOUT": "1"}, {"COCKTAIL_LAYOUT": "1", "COCKTAIL_PAIR_MODE": "2"},
+                                 {"COCKTAIL_PAIR_MODE": "3", "COCKTAIL_GROUP_WORKERS": "4"},
+                                 {"COCKTAIL_COST_WEIGHTS": "1,1,1"}])
+def test_planner_tuning_knobs_keep_parity(env, monkeypatch):
+    """Every work split the planner can be asked for reads each token exactly once."""
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    w = workloads.small("knobs", 2, 4, 4, [4096, 2304], 128, 64, mix=(0.15, 0.35, 0.5), seed_offset=77)
+    _announce(f"{w.name} {env}")
+    Case(w, workers=16).check_all()
+
+
 def test_runs_on_a_side_stream():
     w = workloads.small("stream", 1, 2, 2, [512], 64, 32, seed_offset=4)
     _announce(w.name)

@@ -188,6 +188,19 @@ def test_planner_matches_oracle_and_splits_work_exactly_once(cfg, workers):
         assert 0.15 * total <= pool_cost <= 0.25 * total and h["groups"] == 256
 
 
+@pytest.mark.parametrize("env", [{"COCKTAIL_POOL_PERCENT": "100"}, {"COCKTAIL_POOL_PERCENT": "0"},
+                                 {"COCKTAIL_GROUP_WORKERS": "3", "COCKTAIL_POOL_PERCENT": "50"},
+                                 {"COCKTAIL_LAYOUT": "1"}, {"COCKTAIL_LAYOUT": "1", "COCKTAIL_PAIR_MODE": "2"},
+                                 {"COCKTAIL_PAIR_MODE": "3", "COCKTAIL_GROUP_WORKERS": "4"}])
+def test_work_split_under_tuning_knobs(env, monkeypatch):
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    for cfg, workers in ((2, 2048), (4, 2048), (1, 64)):
+        w = workloads.config(cfg)
+        plan, _ = _plan(w, workers)
+        _check_work_split(plan, w, workers)
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_work_split_of_random_small_shapes(seed):
     rng = np.random.default_rng(1000 + seed)
