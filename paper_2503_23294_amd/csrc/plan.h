@@ -67,6 +67,18 @@ struct PoolSeg {
 };
 static_assert(sizeof(PoolSeg) == 32, "PoolSeg layout");
 
+// One 64-token block of the packed cache as the reorder+quantize kernel sees it (one record per
+// block, class by class in (b, h, block) order, i.e. in the order of the class buffers).
+struct RQItem {
+  int64_t ragged_row;        // row index of the block's first token in the ragged source layout
+  int32_t b, h;
+  int32_t t0;                // source token of row 0 if the block's rows are consecutive source tokens, else -1
+  int32_t cls_nvalid;        // class | valid rows << 8
+  int32_t j;                 // block index inside its (b, h, class) run
+  int32_t pad;
+};
+static_assert(sizeof(RQItem) == 32, "RQItem layout");
+
 struct PlanHeader {
   uint32_t magic, version;
   int32_t batch, num_q_heads, num_kv_heads, head_dim, chunk_size, group_size;
@@ -100,7 +112,7 @@ struct PlanHeader {
   int32_t num_groups, num_pool_segs;
   int32_t pad3;
   int32_t off_bh_off;         // int32 [B*Hkv + 1] prefix: (b, kv head) owns partial ids bh_off[bh] .. bh_off[bh+1]-1
-  int32_t pad1;
+  int32_t off_rq_items;       // RQItem [sum of class_blocks]
 };
 
 template <typename T>

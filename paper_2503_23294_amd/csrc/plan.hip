@@ -379,6 +379,43 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
     }
   }
 
+  // ---- reorder+quantize records: one per block of the class buffers ----
+  std::vector<RQItem> rq_items;
+  rq_items.reserve(tot_blocks);
+  for (int c = 0; c < 3; ++c)
+    for (int b = 0; b < B; ++b) {
+      const int nb = v_nblk[3 * b + c], ntok = v_ct[3 * b + c];
+      if (nb == 0) continue;
+      const int n = seq_lens[b] / C;
+      const int32_t* pb = v_perm.data() + v_chunk_off[b];
+      const int cc0 = v_cc0[3 * b + c];
+      const int tail = seq_lens[b] - n * C;
+      const int chunk_tokens = c == 2 ? ntok - tail : ntok;
+      auto src_token = [&](int r) {   // source token of row r of the class (Alg. 1 order; tail after the FP16 chunks)
+        if (r < chunk_tokens) return pb[cc0 + r / C] * C + r % C;
+        return n * C + (r - chunk_tokens);
+      };
+      std::vector<RQItem> head_items(nb);
+      for (int j = 0; j < nb; ++j) {
+        RQItem& it = head_items[j];
+        std::memset(&it, 0, sizeof(it));
+        const int r0 = j * kTB;
+        const int nvalid = ntok - r0 < kTB ? ntok - r0 : kTB;
+        const int t0 = src_token(r0);
+        // rows are consecutive tokens iff the last one is (chunks keep their order, so tokens in between are too)
+        it.t0 = src_token(r0 + nvalid - 1) == t0 + nvalid - 1 ? t0 : -1;
+        it.b = b, it.j = j;
+        it.cls_nvalid = c | (nvalid << 8);
+      }
+      for (int h = 0; h < Hkv; ++h)
+        for (int j = 0; j < nb; ++j) {
+          RQItem it = head_items[j];
+          it.h = h;
+          it.ragged_row = (v_cum[b] * Hkv + int64_t(h) * seq_lens[b]) + (it.t0 >= 0 ? it.t0 : 0);
+          rq_items.push_back(it);
+        }
+    }
+
   // ---- sizes and blob layout ----
   PlanHeader hd;
   std::memset(&hd, 0, sizeof(hd));
@@ -414,6 +451,7 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
   place(hd.off_worker_rec, int64_t(sizeof(WorkerRec)) * P);
   place(hd.off_group_rec, int64_t(sizeof(GroupRec)) * NG);
   place(hd.off_pool_seg, int64_t(sizeof(PoolSeg)) * NPS);
+  place(hd.off_rq_items, int64_t(sizeof(RQItem)) * int64_t(rq_items.size()));
   off = (off + 127) & ~int64_t(127);
   place(hd.off_counters, int64_t(4 * kCounterStride) * NG);
   if (off >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "plan larger than 2 GiB");
@@ -483,6 +521,7 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
     put(hd.off_worker_rec, recs.data(), sizeof(WorkerRec) * recs.size());
     put(hd.off_group_rec, groups.data(), sizeof(GroupRec) * groups.size());
     put(hd.off_pool_seg, psegs.data(), sizeof(PoolSeg) * psegs.size());
+    put(hd.off_rq_items, rq_items.data(), sizeof(RQItem) * rq_items.size());
   }
   g_err[0] = 0;
   return COCKTAIL_OK;

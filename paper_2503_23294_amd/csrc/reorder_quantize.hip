@@ -12,6 +12,7 @@ namespace cocktail {
 
 struct RQParams {
   const void* plan;
+  const RQItem* items;     // one record per block, in launch order
   const _Float16* src[2];  // K, V
   char* dst[2][3];         // [K|V][class]
   int64_t stride_b, stride_h, stride_t;
@@ -52,69 +53,53 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   constexpr int NG = D / G;
   __shared__ __attribute__((aligned(16))) char lds[kTB * 2 * D];
 
-  const PlanHeader* hd = static_cast<const PlanHeader*>(p.plan);
   const int which = blockIdx.y;  // 0 = K, 1 = V
-  int idx = blockIdx.x;
-  int cls;
-  if (idx < p.cls_end0) {
-    cls = 0;
-  } else if (idx < p.cls_end1) {
-    cls = 1, idx -= p.cls_end0;
-  } else {
-    cls = 2, idx -= p.cls_end1;
-  }
-  const int B = hd->batch, Hkv = hd->num_kv_heads, C = hd->chunk_size;
-  const int32_t* blk_base = plan_array<int32_t>(p.plan, hd->off_blk_base);
-  // sequence b with blk_base[b][cls] <= idx < blk_base[b+1][cls]
-  int lo = 0, hi = B;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (blk_base[3 * mid + cls] <= idx) lo = mid; else hi = mid;
-  }
-  // skip sequences without blocks in this class that share the same base
-  int b = lo;
-  while (blk_base[3 * (b + 1) + cls] <= idx) ++b;
-  const int nblk = plan_array<int32_t>(p.plan, hd->off_nblk)[3 * b + cls];
-  const int local = idx - blk_base[3 * b + cls];
-  const int h = local / nblk;
-  const int j = local - h * nblk;
-  const int ntok = plan_array<int32_t>(p.plan, hd->off_class_tokens)[3 * b + cls];
-  const int T = plan_array<int32_t>(p.plan, hd->off_seq_len)[b];
-  const int32_t* chunk_off = plan_array<int32_t>(p.plan, hd->off_chunk_off);
-  const int N = chunk_off[b + 1] - chunk_off[b];
-  const int32_t* perm = plan_array<int32_t>(p.plan, hd->off_perm) + chunk_off[b];
-  const int cc0 = plan_array<int32_t>(p.plan, hd->off_class_chunk0)[3 * b + cls];
-  const int tail = T - N * C;
-  const int chunk_tokens = (cls == 2) ? ntok - tail : ntok;  // tokens of this class that come from chunks
-
-  int64_t base;
-  int64_t sh;
+  // everything about this block comes from one record; only blocks whose rows are not consecutive
+  // source tokens (a chunk boundary or the tail inside the block) look the rows up one by one
+  const RQItem& item = p.items[blockIdx.x];
+  const int cn = __builtin_amdgcn_readfirstlane(item.cls_nvalid);
+  const int cls = cn & 0xff, nvalid = cn >> 8;
+  const int t0 = __builtin_amdgcn_readfirstlane(item.t0);
+  const int j = __builtin_amdgcn_readfirstlane(item.j);
+  const int b = __builtin_amdgcn_readfirstlane(item.b), h = __builtin_amdgcn_readfirstlane(item.h);
+  const _Float16* src;       // row 0 of the block (consecutive rows) or token 0 of the head (row by row)
   if (p.ragged) {
-    const int64_t cum = plan_array<int64_t>(p.plan, hd->off_cum_tokens)[b];
-    sh = int64_t(T) * p.stride_t;
-    base = cum * Hkv * p.stride_t + h * sh;
+    src = p.src[which] + item.ragged_row * p.stride_t;
   } else {
-    base = b * p.stride_b + h * p.stride_h;
+    src = p.src[which] + b * p.stride_b + h * p.stride_h + int64_t(t0 >= 0 ? t0 : 0) * p.stride_t;
   }
-  const _Float16* src = p.src[which] + base;
+  const PlanHeader* hd = static_cast<const PlanHeader*>(p.plan);
+  int C = 1, N = 0, cc0 = 0, chunk_tokens = 0;
+  const int32_t* perm = nullptr;
+  if (t0 < 0) {
+    C = hd->chunk_size;
+    const int32_t* chunk_off = plan_array<int32_t>(p.plan, hd->off_chunk_off);
+    N = chunk_off[b + 1] - chunk_off[b];
+    perm = plan_array<int32_t>(p.plan, hd->off_perm) + chunk_off[b];
+    cc0 = plan_array<int32_t>(p.plan, hd->off_class_chunk0)[3 * b + cls];
+    const int ntok = plan_array<int32_t>(p.plan, hd->off_class_tokens)[3 * b + cls];
+    const int T = plan_array<int32_t>(p.plan, hd->off_seq_len)[b];
+    chunk_tokens = (cls == 2) ? ntok - (T - N * C) : ntok;   // tokens of this class that come from chunks
+  }
 
   const int tid = threadIdx.x;
   const int seg = tid & 15;        // 8 channels seg*8 .. seg*8+7
-  const int r0 = j * kTB;
   const int row_bytes = (cls == 0) ? D / 4 : (cls == 1) ? D / 2 : 2 * D;
 
 #pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
     const int i = pass * 16 + (tid >> 4);
-    const int r = r0 + i;
     u32x4 raw = {0u, 0u, 0u, 0u};
-    if (r < ntok) {
-      int t;
-      if (r < chunk_tokens) {
-        const int slot = r / C;
-        t = perm[cc0 + slot] * C + (r - slot * C);
-      } else {
-        t = N * C + (r - chunk_tokens);   // Sec. III-A: tail tokens follow the FP16 chunks
+    if (i < nvalid) {
+      int t = i;                        // relative to row 0 of the block
+      if (t0 < 0) {
+        const int r = j * kTB + i;      // row inside the class run of (b, h)
+        if (r < chunk_tokens) {
+          const int slot = r / C;
+          t = perm[cc0 + slot] * C + (r - slot * C);
+        } else {
+          t = N * C + (r - chunk_tokens);   // Sec. III-A: tail tokens follow the FP16 chunks
+        }
       }
       raw = *reinterpret_cast<const u32x4*>(src + int64_t(t) * p.stride_t + seg * 8);
     }
@@ -166,8 +151,10 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
     }
   }
   __syncthreads();
-  const int bb = hd->block_bytes[cls];
-  char* dst = p.dst[which][cls] + int64_t(plan_array<int32_t>(p.plan, hd->off_blk_base)[3 * b + cls] + local) * bb;
+  constexpr int NGc = D / G;
+  const int bb = kTB * (row_bytes + (cls == 2 ? 0 : 4 * NGc));
+  const int first = cls == 0 ? 0 : cls == 1 ? p.cls_end0 : p.cls_end1;   // first record of this class
+  char* dst = p.dst[which][cls] + int64_t(int(blockIdx.x) - first) * bb;
   for (int o = tid * 16; o < bb; o += 256 * 16)
     *reinterpret_cast<u32x4*>(dst + o) = *reinterpret_cast<const u32x4*>(lds + o);
 }
@@ -201,6 +188,7 @@ extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void
     return fail(COCKTAIL_EINVAL, "stride_b and stride_h must be non-negative multiples of 8");
   RQParams p;
   p.plan = cache->plan_dev;
+  p.items = reinterpret_cast<const RQItem*>(static_cast<const char*>(cache->plan_dev) + hd->off_rq_items);
   p.src[0] = static_cast<const _Float16*>(k_src);
   p.src[1] = static_cast<const _Float16*>(v_src);
   int64_t tot = 0;
