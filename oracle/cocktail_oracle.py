@@ -17,6 +17,9 @@ What it computes, in the paper's order:
                   in the order INT2, INT4, FP16, one softmax over the
                   concatenation, three att x V products summed.  Evaluated in
                   float64 on the dequantised values.
+  append_tokens   Sec. III-A: the K/V rows of tokens generated during decoding are
+                  kept in FP16 after the context; attention then runs over the
+                  three context blocks followed by those rows.
   pack_* / unpack_*   the byte layout of the packed cache (an encoding this
                   build defines; the paper is silent on it).
 
@@ -24,7 +27,9 @@ Parity pins (tests/test_oracle_pins.py): all-FP16 equals textbook attention and
 torch's scaled_dot_product_attention; invariance to the chunk permutation
 (Sec. III-C, Eq. 4-5); |x - dequant(x)| <= scale/2; closed-form groups; a
 scalar-loop brute force on tiny inputs; partial-softmax merge identity; pack
-round trips; the KV-size figure of Sec. I.  No function here is unpinned.
+round trips; the KV-size figure of Sec. I; appended tokens equal textbook
+attention over the concatenation and behave exactly like the FP16 remainder of a
+longer context.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -209,6 +214,8 @@ class OracleCache:
     num_kv_heads: int
     plans: List[SeqPlan]
     seqs: List[List[ClassCache]]         # [B][3]
+    app_k: List[np.ndarray] = None       # [B] fp16 [Hkv, n_app, D]: rows appended during decoding
+    app_v: List[np.ndarray] = None
 
 
 def reorder_quantize(k_seqs: Sequence[np.ndarray], v_seqs: Sequence[np.ndarray],
@@ -235,7 +242,34 @@ def reorder_quantize(k_seqs: Sequence[np.ndarray], v_seqs: Sequence[np.ndarray],
             ccs.append(cc)
         plans.append(sp)
         seqs.append(ccs)
-    return OracleCache(d, group, chunk_size, hkv, plans, seqs)
+    empty = [np.zeros((hkv, 0, d), dtype=np.float16) for _ in plans]
+    return OracleCache(d, group, chunk_size, hkv, plans, seqs, empty, [e.copy() for e in empty])
+
+
+def append_tokens(cache: OracleCache, k_new: np.ndarray, v_new: np.ndarray) -> None:
+    """Sec. III-A: one generated token per sequence joins the cache in FP16, behind everything else.
+
+    k_new, v_new: fp16 [B, Hkv, D].
+    """
+    for b in range(len(cache.seqs)):
+        cache.app_k[b] = np.concatenate([cache.app_k[b], k_new[b][:, None, :].astype(np.float16)], axis=1)
+        cache.app_v[b] = np.concatenate([cache.app_v[b], v_new[b][:, None, :].astype(np.float16)], axis=1)
+
+
+def pack_append_buffer(cache: OracleCache, which: str, capacity: int) -> np.ndarray:
+    """Byte image of the append buffer: per (sequence, kv head) ceil(capacity/64) FP16 blocks in the
+    block layout of the FP16 class; rows not appended yet are zero bytes."""
+    nblk = (capacity + TOKENS_PER_BLOCK - 1) // TOKENS_PER_BLOCK
+    rb = 2 * cache.head_dim
+    parts = []
+    for b in range(len(cache.seqs)):
+        src = cache.app_k[b] if which == "k" else cache.app_v[b]
+        for h in range(cache.num_kv_heads):
+            rows = np.zeros((nblk * TOKENS_PER_BLOCK, rb), dtype=np.uint8)
+            n = src.shape[1]
+            rows[:n] = np.ascontiguousarray(src[h]).view(np.uint8).reshape(n, rb)
+            parts.append(_pack_head_blocks(rows, None).reshape(-1))
+    return np.concatenate(parts) if parts else np.zeros(0, dtype=np.uint8)
 
 
 def _rows_and_meta(cc: ClassCache, which: str, h: int):
@@ -294,7 +328,7 @@ def unpack_class_buffer(buf: np.ndarray, cache_like: OracleCache, cls: int):
 
 
 def dequantized_kv(cache: OracleCache, b: int, h: int) -> Tuple[np.ndarray, np.ndarray]:
-    """float64 [n_total, D] K-hat and V-hat of (b, kv head h) in cache order INT2 | INT4 | FP16."""
+    """float64 [n_total, D] K-hat and V-hat of (b, kv head h) in cache order INT2 | INT4 | FP16 | appended."""
     ks, vs = [], []
     for cc in cache.seqs[b]:
         if cc.bits == 16:
@@ -303,6 +337,9 @@ def dequantized_kv(cache: OracleCache, b: int, h: int) -> Tuple[np.ndarray, np.n
         else:
             ks.append(dequantize(cc.k_codes[h], cc.k_scale[h], cc.k_zero[h], cache.group))
             vs.append(dequantize(cc.v_codes[h], cc.v_scale[h], cc.v_zero[h], cache.group))
+    if cache.app_k is not None:
+        ks.append(cache.app_k[b][h].astype(np.float64))
+        vs.append(cache.app_v[b][h].astype(np.float64))
     return np.concatenate(ks, axis=0), np.concatenate(vs, axis=0)
 
 

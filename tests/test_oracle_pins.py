@@ -352,3 +352,56 @@ def test_kv_size_figure_from_paper():
     assert abs(got - float(gb)) / float(gb) <= float(tol)
     # the same count from the packed-bytes formula with every token in the FP16 class
     assert O.packed_bytes((0, 0, int(tokens)), int(heads), int(hd), 64) * int(layers) / 1e9 == got
+
+
+# -- appended decode tokens (Sec. III-A: generated tokens stay FP16 behind the context) --------
+def _new_tokens(w, step):
+    rng = np.random.default_rng([workloads.BASE_SEED, 991, step])
+    shape = (w.batch, w.num_kv_heads, w.head_dim)
+    return (rng.standard_normal(shape, dtype=np.float32).astype(np.float16),
+            rng.standard_normal(shape, dtype=np.float32).astype(np.float16))
+
+
+def test_appended_tokens_all_fp16_equal_textbook_attention_over_the_concatenation():
+    w = workloads.small("app16", 2, 4, 2, [80, 33], 16, 32, mix=(1.0, 0.0, 0.0), seed_offset=21)
+    ks, vs = _seqs(w)
+    cache = O.reorder_quantize(ks, vs, workloads.chunk_bits(w), w.chunk_size, w.group_size)
+    q = workloads.query(w, 0)
+    for step in range(5):
+        kn, vn = _new_tokens(w, step)
+        O.append_tokens(cache, kn, vn)
+        ks = [np.concatenate([k, kn[b][:, None, :]], axis=1) for b, k in enumerate(ks)]
+        vs = [np.concatenate([v, vn[b][:, None, :]], axis=1) for b, v in enumerate(vs)]
+        out, lse = O.decode_attention(q, cache)
+        for b in range(w.batch):
+            for h in range(w.num_q_heads):
+                ref, rl = _textbook(q[b, h], ks[b][h // 2], vs[b][h // 2], 1 / np.sqrt(128))
+                np.testing.assert_allclose(out[b, h], ref, rtol=0, atol=1e-12)
+                assert abs(lse[b, h] - rl) < 1e-12
+
+
+def test_appended_tokens_behave_like_the_fp16_remainder_of_a_longer_context():
+    """T context tokens + n appended ones == a (T + n)-token context whose last n tokens do not fill a
+    chunk and therefore stay FP16 (Sec. III-A), for the same chunk bitwidths."""
+    t, n, chunk = 4 * 24, 7, 24
+    w_long = workloads.small("applong", 1, 2, 2, [t + n], chunk, 32, mix=(0.2, 0.4, 0.4), seed_offset=23)
+    ks, vs = _seqs(w_long)
+    bits = workloads.chunk_bits(w_long)
+    assert len(bits[0]) == t // chunk and len(set(bits[0].tolist())) >= 2
+    long_cache = O.reorder_quantize(ks, vs, bits, chunk, 32)
+    cache = O.reorder_quantize([ks[0][:, :t]], [vs[0][:, :t]], bits, chunk, 32)
+    for i in range(n):
+        O.append_tokens(cache, ks[0][None, :, t + i], vs[0][None, :, t + i])
+    q = workloads.query(w_long, 0)
+    a, la = O.decode_attention(q, cache)
+    b_, lb = O.decode_attention(q, long_cache)
+    np.testing.assert_allclose(a, b_, rtol=0, atol=1e-13)
+    np.testing.assert_allclose(la, lb, rtol=0, atol=1e-13)
+    # and the append buffer's byte image holds exactly those rows, in the FP16 block layout
+    img = O.pack_append_buffer(cache, "k", 70)
+    assert img.size == 2 * 2 * 64 * 256                      # 2 heads x 2 blocks
+    blocks = img.reshape(2, 2, 64 * 256)
+    for h in range(2):
+        rows = blocks[h, 0].reshape(16, 64, 16).transpose(1, 0, 2).reshape(64, 256)
+        assert np.array_equal(rows[:n], ks[0][h, t:t + n].view(np.uint8).reshape(n, 256))
+        assert not rows[n:].any() and not blocks[h, 1].any()
