@@ -95,7 +95,8 @@ typedef struct cocktail_sizes {
   int32_t num_workers;                         /* workgroups the decode kernel is launched with    */
   int32_t num_partials;                        /* partial softmax states written per call          */
   int32_t num_segments;
-  int32_t reserved;
+  int32_t append_capacity;                     /* tokens per sequence the append buffers can take  */
+  int64_t append_bytes;                        /* bytes of the K append buffer, and of the V one   */
 } cocktail_sizes;
 
 /* The packed mixed-precision cache of one layer: the six lists of Alg. 1
@@ -106,6 +107,10 @@ typedef struct cocktail_cache {
   const void* plan_host;         /* HOST   plan blob written by cocktail_plan                              */
   void* plan_dev;                /* DEVICE byte-for-byte copy of the plan blob, 16-byte aligned; also holds
                                     the decode kernel's ticket counters (see cocktail_decode_attention)    */
+  void* k_app;                   /* DEVICE append_bytes each, 256-byte aligned: K/V rows of the tokens     */
+  void* v_app;                   /*        generated during decoding; NULL iff append_capacity == 0         */
+  int32_t num_appended;          /* tokens appended so far to every sequence, 0 .. append_capacity         */
+  int32_t reserved;
 } cocktail_cache;
 
 /*
@@ -133,6 +138,17 @@ int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_lens, const ui
                   int32_t num_workers, cocktail_sizes* sizes, void* plan_host, size_t plan_capacity,
                   int32_t* class_tokens, int32_t* perm);
 
+/*
+ * cocktail_plan with room for generated tokens.  The paper keeps the K/V of the tokens produced during
+ * decoding in FP16 behind the context (Sec. III-A); `append_capacity` (>= 0) is the number of such
+ * tokens per sequence the cache can take.  They live in two extra buffers (cocktail_cache::k_app,
+ * v_app; sizes->append_bytes each): per (sequence, kv head) ceil(append_capacity / 64) blocks in the
+ * block layout of the FP16 class, ordered (b, h, block).  cocktail_plan is this call with capacity 0.
+ */
+int cocktail_plan_append(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
+                         int32_t num_workers, int32_t append_capacity, cocktail_sizes* sizes, void* plan_host,
+                         size_t plan_capacity, int32_t* class_tokens, int32_t* perm);
+
 /* Source layouts accepted by cocktail_reorder_quantize (element = one fp16). */
 #define COCKTAIL_SRC_STRIDED 0 /* element (b,h,t,d) at b*stride_b + h*stride_h + t*stride_t + d        */
 #define COCKTAIL_SRC_RAGGED 1  /* sequences concatenated; sequence b is [Hkv][T_b] rows of stride_t
@@ -145,7 +161,8 @@ int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_lens, const ui
  *
  *   k_src, v_src  DEVICE fp16, 16-byte aligned, head_dim contiguous; strides in
  *                 elements, multiples of 8
- *   cache         k/v buffers are written completely (padding included);
+ *   cache         k/v buffers are written completely (padding included), the append
+ *                 buffers (if any) are zeroed; num_appended is not read;
  *                 plan_host/plan_dev must come from cocktail_plan for this shape
  *   stream        hipStream_t (NULL = default stream)
  *
@@ -170,6 +187,7 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  * two calls on the same inputs agree to fp32 summation order, not bit for bit
  * (shapes with Hq > Hkv use no pools and are reproducible bit for bit).
  *
+ *   cache      num_appended tokens of the append buffers are attended to after the context
  *   q          DEVICE fp16 [B][Hq][D], 16-byte aligned
  *   sm_scale   softmax scale; <= 0 selects 1/sqrt(D)
  *   out        DEVICE fp16 [B][Hq][D]; a sequence with no tokens yields zeros
@@ -185,6 +203,20 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
 int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
                               float sm_scale, void* out, float* lse, void* workspace,
                               size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. III-A: stores the K/V rows of one generated token per sequence, in FP16, as token `position`
+ * (0-based) of the append buffers.  The caller then sets cache->num_appended = position + 1 (or higher)
+ * for the following cocktail_decode_attention calls, which attend to the context and to the first
+ * num_appended appended tokens of every sequence.
+ *
+ *   k_new, v_new  DEVICE fp16 [B][Hkv][D], 16-byte aligned
+ *   position      0 <= position < append_capacity of the plan
+ *
+ * One kernel launch.  Errors: EINVAL (no append buffers, position out of range, NULL), EALIGN, EHIP.
+ */
+int cocktail_append_fp16(const cocktail_shape* shape, const void* k_new, const void* v_new,
+                         const cocktail_cache* cache, int32_t position, void* stream);
 
 /*
  * Number of decode workgroups that fills the current HIP device for this shape

@@ -31,17 +31,23 @@ class Sizes(C.Structure):
     _fields_ = [("total_chunks", C.c_int64), ("class_tokens", C.c_int64 * 3), ("class_blocks", C.c_int64 * 3),
                 ("class_bytes", C.c_int64 * 3), ("plan_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
                 ("packed_bytes", C.c_int64), ("num_workers", C.c_int32), ("num_partials", C.c_int32),
-                ("num_segments", C.c_int32), ("reserved", C.c_int32)]
+                ("num_segments", C.c_int32), ("append_capacity", C.c_int32), ("append_bytes", C.c_int64)]
 
 
 class Cache(C.Structure):
-    _fields_ = [("k", C.c_void_p * 3), ("v", C.c_void_p * 3), ("plan_host", C.c_void_p), ("plan_dev", C.c_void_p)]
+    _fields_ = [("k", C.c_void_p * 3), ("v", C.c_void_p * 3), ("plan_host", C.c_void_p), ("plan_dev", C.c_void_p),
+                ("k_app", C.c_void_p), ("v_app", C.c_void_p), ("num_appended", C.c_int32), ("reserved", C.c_int32)]
 
 
 EXPORTS = {
     "cocktail_plan": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.c_int32,
                                 C.POINTER(Sizes), C.c_void_p, C.c_size_t, C.POINTER(C.c_int32),
                                 C.POINTER(C.c_int32)]),
+    "cocktail_plan_append": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.c_int32,
+                                       C.c_int32, C.POINTER(Sizes), C.c_void_p, C.c_size_t, C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_int32)]),
+    "cocktail_append_fp16": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.POINTER(Cache), C.c_int32,
+                                       C.c_void_p]),
     "cocktail_reorder_quantize": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
                                             C.c_int64, C.c_int64, C.POINTER(Cache), C.c_void_p]),
     "cocktail_decode_attention": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float, C.c_void_p,

@@ -39,8 +39,12 @@ def cocktail_default_workers(shape: Shape) -> int:
     return int(n.value)
 
 
-def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[int], num_workers: int) -> Plan:
-    """Host-only: Alg. 1's prefill partition plus cache layout and decode work split."""
+def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[int], num_workers: int,
+                  append_capacity: int = 0) -> Plan:
+    """Host-only: Alg. 1's prefill partition plus cache layout and decode work split.
+
+    append_capacity > 0 reserves room for that many generated tokens per sequence (cocktail_plan_append).
+    """
     sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
     cb = np.ascontiguousarray(np.asarray(chunk_bits, dtype=np.uint8).reshape(-1))
     if sl.shape != (shape.batch,):
@@ -51,12 +55,14 @@ def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[in
     sizes = Sizes()
     slp = sl.ctypes.data_as(C.POINTER(C.c_int32))
     cbp = cb.ctypes.data_as(C.POINTER(C.c_uint8)) if cb.size else None
-    check(lib().cocktail_plan(C.byref(shape), slp, cbp, num_workers, C.byref(sizes), None, 0, None, None))
+    check(lib().cocktail_plan_append(C.byref(shape), slp, cbp, num_workers, append_capacity, C.byref(sizes), None, 0,
+                                     None, None))
     blob = np.zeros(int(sizes.plan_bytes), dtype=np.uint8)
     ct = np.zeros((shape.batch, 3), dtype=np.int32)
     perm = np.zeros(max(int(sizes.total_chunks), 1), dtype=np.int32)
-    check(lib().cocktail_plan(C.byref(shape), slp, cbp, num_workers, C.byref(sizes), blob.ctypes.data, blob.size,
-                              ct.ctypes.data_as(C.POINTER(C.c_int32)), perm.ctypes.data_as(C.POINTER(C.c_int32))))
+    check(lib().cocktail_plan_append(C.byref(shape), slp, cbp, num_workers, append_capacity, C.byref(sizes),
+                                     blob.ctypes.data, blob.size, ct.ctypes.data_as(C.POINTER(C.c_int32)),
+                                     perm.ctypes.data_as(C.POINTER(C.c_int32))))
     return Plan(shape, sizes, blob, ct, perm[:int(sizes.total_chunks)], sl)
 
 
@@ -79,6 +85,12 @@ class PackedCache:
             self.desc.v[c] = self.v[c].data_ptr() if self.v[c].numel() else None
         self.desc.plan_host = plan.blob.ctypes.data
         self.desc.plan_dev = self.plan_dev.data_ptr()
+        nb = int(plan.sizes.append_bytes)
+        self.k_app = torch.empty(nb, dtype=torch.uint8, device=device) if nb else None
+        self.v_app = torch.empty(nb, dtype=torch.uint8, device=device) if nb else None
+        self.desc.k_app = self.k_app.data_ptr() if nb else None
+        self.desc.v_app = self.v_app.data_ptr() if nb else None
+        self.desc.num_appended = 0
         self.workspace = torch.empty(int(plan.sizes.workspace_bytes), dtype=torch.uint8, device=device)
 
 
@@ -104,6 +116,22 @@ def cocktail_reorder_quantize(cache: PackedCache, k_src: torch.Tensor, v_src: to
     check(lib().cocktail_reorder_quantize(C.byref(sh), k_src.data_ptr(), v_src.data_ptr(),
                                           _lib.SRC_RAGGED if ragged else _lib.SRC_STRIDED, stride_b, stride_h, st,
                                           C.byref(cache.desc), _stream_ptr(stream)))
+
+
+def cocktail_append_fp16(cache: PackedCache, k_new: torch.Tensor, v_new: torch.Tensor,
+                         position: Optional[int] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Stores one generated token per sequence (device fp16 [B, Hkv, D]) as appended token `position`
+    (default: the next free one) and makes the following decode calls attend to it."""
+    sh = cache.plan.shape
+    for t in (k_new, v_new):
+        if t.dtype != torch.float16 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError("k_new and v_new must be contiguous float16 device tensors")
+        if tuple(t.shape) != (sh.batch, sh.num_kv_heads, sh.head_dim):
+            raise ValueError("k_new and v_new must have shape [B, Hkv, D]")
+    pos = int(cache.desc.num_appended) if position is None else int(position)
+    check(lib().cocktail_append_fp16(C.byref(sh), k_new.data_ptr(), v_new.data_ptr(), C.byref(cache.desc), pos,
+                                     _stream_ptr(stream)))
+    cache.desc.num_appended = max(int(cache.desc.num_appended), pos + 1)
 
 
 def cocktail_decode_attention(cache: PackedCache, q: torch.Tensor, sm_scale: float = 0.0,

@@ -1,0 +1,59 @@
+// Sec. III-A: the K/V rows of tokens generated during decoding join the cache in FP16, behind the
+// context.  They go into the append buffers: per (sequence, kv head) a few 64-token blocks in the
+// block layout of the FP16 class (16-byte piece p of token i at (p*64 + i)*16).
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+#include "plan.h"
+
+namespace cocktail {
+
+// One thread moves one 16-byte piece: thread -> ((b, h), piece); blockIdx.y = 0 for K, 1 for V.
+__global__ __launch_bounds__(256) void append_fp16_kernel(const u32x4* __restrict__ k_new,
+                                                           const u32x4* __restrict__ v_new, char* __restrict__ k_app,
+                                                           char* __restrict__ v_app, int position, int app_blocks,
+                                                           int num_bh) {
+  constexpr int kPieces = 2 * 128 / 16;        // 16-byte pieces of one fp16 row
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  if (idx >= num_bh * kPieces) return;
+  const int bh = idx / kPieces, p = idx % kPieces;
+  const u32x4* src = blockIdx.y ? v_new : k_new;
+  char* dst = blockIdx.y ? v_app : k_app;
+  const size_t block = size_t(bh) * app_blocks + position / kTB;
+  *reinterpret_cast<u32x4*>(dst + block * (kTB * 2 * 128) + (size_t(p) * kTB + position % kTB) * 16) = src[idx];
+}
+
+}  // namespace cocktail
+
+using namespace cocktail;
+
+extern "C" int cocktail_append_fp16(const cocktail_shape* shape, const void* k_new, const void* v_new,
+                                    const cocktail_cache* cache, int32_t position, void* stream) {
+  if (int rc = check_shape(shape)) return rc;
+  if (!cache || !cache->plan_host) return fail(COCKTAIL_EINVAL, "cache or its plan is NULL");
+  const PlanHeader* hd = static_cast<const PlanHeader*>(cache->plan_host);
+  if (hd->magic != kPlanMagic || hd->version != kPlanVersion)
+    return fail(COCKTAIL_EINVAL, "plan_host is not a plan written by this library version");
+  if (hd->batch != shape->batch || hd->num_kv_heads != shape->num_kv_heads || hd->head_dim != shape->head_dim ||
+      hd->chunk_size != shape->chunk_size || hd->group_size != shape->group_size ||
+      hd->num_q_heads != shape->num_q_heads)
+    return fail(COCKTAIL_EINVAL, "plan was made for a different shape");
+  if (shape->head_dim != 128) return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
+  if (hd->append_capacity <= 0) return fail(COCKTAIL_EINVAL, "the plan was made without append buffers");
+  if (position < 0 || position >= hd->append_capacity)
+    return fail(COCKTAIL_EINVAL, "position %d outside the append capacity %d", position, hd->append_capacity);
+  if (!k_new || !v_new || !cache->k_app || !cache->v_app)
+    return fail(COCKTAIL_EINVAL, "k_new, v_new and the append buffers must not be NULL");
+  if ((reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new) |
+       reinterpret_cast<uintptr_t>(cache->k_app) | reinterpret_cast<uintptr_t>(cache->v_app)) & 15)
+    return fail(COCKTAIL_EALIGN, "k_new, v_new and the append buffers must be 16-byte aligned");
+  const int num_bh = hd->batch * hd->num_kv_heads;
+  const dim3 grid((num_bh * 16 + 255) / 256, 2, 1);
+  hipLaunchKernelGGL(append_fp16_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
+                     static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
+                     static_cast<char*>(cache->k_app), static_cast<char*>(cache->v_app), position, hd->append_blocks,
+                     num_bh);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(COCKTAIL_EHIP, "append launch failed: %s", hipGetErrorString(e));
+  return COCKTAIL_OK;
+}

@@ -69,11 +69,15 @@ struct DecodeParams {
   const uint32_t* q;        // fp16 [B][Hq][D] viewed as dwords
   const char* k[3];
   const char* v[3];
+  const char* k_app;        // append buffers: [B*Hkv][app_blocks] FP16 blocks, or NULL
+  const char* v_app;
   float* ws;                // [num_partials][rep][D + 2]
   _Float16* out;            // [B][Hq][D]
   float* lse;               // [B][Hq] or NULL
   float scale_log2;         // sm_scale * log2(e)
   int32_t rep, num_q_heads, num_kv_heads, num_groups;
+  int32_t num_workers;      // workgroups behind these serve the appended tokens, one per (sequence, kv head)
+  int32_t num_appended, app_blocks;
 #ifdef COCKTAIL_TRACE
   uint64_t* trace;          // [num_workers][4]: start, end (100 MHz ticks), hw id, xcc id
 #endif
@@ -540,7 +544,7 @@ __device__ __forceinline__ void begin_state(int qrow, int h, LaneState<NGH>& st,
 // body has no branches around the loads.  The accumulators live and die inside this function, one
 // instance per class.
 template <class CLS, int CID, int G>
-__device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, int r, int lane) {
+__device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, int r, int lane, bool app = false) {
   constexpr int NG = D / G;
   constexpr int NGH = NG >= 2 ? NG / 2 : 1;
   constexpr int GL = G < DH ? G : DH;
@@ -548,8 +552,8 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
   static_assert(J == kIterUnits[CID], "the planner cuts pool pieces to the kernel's iteration size");
   const int t = lane & 31, h = lane >> 5;
   const uint32_t vc = CLS::code_voff(t, h), vm = CLS::meta_voff(t, h);
-  const char* const kbase = uni(kparams()->k[CID]);
-  const char* const vbase = uni(kparams()->v[CID]);
+  const char* const kbase = uni(app ? kparams()->k_app : kparams()->k[CID]);   // app: the append buffers
+  const char* const vbase = uni(app ? kparams()->v_app : kparams()->v[CID]);
   const float scale_log2 = kparams()->scale_log2;
   LaneState<NGH> st;
   uint32_t q[DH / 2];
@@ -608,6 +612,42 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
   cur = nxt;
 }
 
+// The neutral partial state (weight zero in the merge) for a slot nobody had tokens for.
+__device__ __forceinline__ void write_neutral(int slot, int r, int lane) {
+  kparams_t kp = kparams();
+  float* out = kp->ws + (int64_t(slot) * kp->rep + r) * (D + kPartialFloats);
+  if (lane == 0) out[0] = kNegBig, out[1] = 0.f;
+  out[kPartialFloats + lane] = 0.f;
+  out[kPartialFloats + 64 + lane] = 0.f;
+}
+
+// Workgroups behind the regular workers: workgroup num_workers + bh attends to the tokens appended to
+// (sequence, kv head) bh during decoding (Sec. III-A), an FP16 run of num_appended tokens in the
+// append buffers, and writes the last partial of bh's range.
+template <int G>
+__device__ __forceinline__ void appended_tokens(int bh, float* red, int r, int lane) {
+  kparams_t kp = kparams();
+  const int n = kp->num_appended;
+  const int pid = uni(kp->bh_off[bh + 1]) - 1;
+  if (n <= 0) {
+    write_neutral(pid, r, lane);
+    return;
+  }
+  Stream sm;
+  sm.u = 0, sm.u1 = (n + UT - 1) / UT;
+  sm.s = 0;
+  sm.cls = 2, sm.ntok = n, sm.blk0 = bh * kp->app_blocks, sm.nblk = kp->app_blocks, sm.gu0 = 0;
+  sm.qrow = (bh / kp->num_kv_heads) * kp->num_q_heads + (bh % kp->num_kv_heads) * kp->rep;
+  sm.pid = pid;
+  sm.last_seg = -1;
+  sm.ngran = 0, sm.nps = 0, sm.pseg0 = 0, sm.rank = 0, sm.counter = 0;
+  sm.pi = -1, sm.p_unit0 = sm.p_nunits = sm.p_gran0 = sm.p_gran1 = sm.p_slot0 = 0;
+  sm.tk0 = sm.tk1 = 0, sm.used = 0;
+  sm.phase = 0;
+  Piece cur = sm.next(lane);
+  if (cur.nu > 0) run_class<HalfClass<G>, 2, G>(sm, cur, red, r, lane, true);
+}
+
 // One workgroup per worker; wave r of the workgroup serves query head r of every kv head it meets.
 template <int G>
 __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
@@ -617,6 +657,10 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
 #ifdef COCKTAIL_TRACE
   const uint64_t t_start = __builtin_amdgcn_s_memrealtime();
 #endif
+  if (int(blockIdx.x) >= kparams()->num_workers) {
+    appended_tokens<G>(int(blockIdx.x) - kparams()->num_workers, red, r, lane);
+    return;
+  }
   Stream sm;
   sm.init(kparams()->recs[blockIdx.x]);
   Piece cur = sm.next(lane);
@@ -632,12 +676,7 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
   // pool parts this worker never entered still own a partial slot: fill it with the neutral state
   for (int i = 0; i < sm.nps; ++i) {
     if ((sm.used >> i) & 1u) continue;
-    kparams_t kp = kparams();
-    const int slot = uni(kp->psegs[sm.pseg0 + i].slot0) + sm.rank;
-    float* out = kp->ws + (int64_t(slot) * kp->rep + r) * (D + kPartialFloats);
-    if (lane == 0) out[0] = kNegBig, out[1] = 0.f;
-    out[kPartialFloats + lane] = 0.f;
-    out[kPartialFloats + 64 + lane] = 0.f;
+    write_neutral(uni(kparams()->psegs[sm.pseg0 + i].slot0) + sm.rank, r, lane);
   }
 #ifdef COCKTAIL_TRACE
   if (threadIdx.x == 0) {
@@ -776,6 +815,20 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
   p.psegs = reinterpret_cast<const PoolSeg*>(pd + hd->off_pool_seg);
   p.counters = reinterpret_cast<uint32_t*>(pd + hd->off_counters);
   p.num_groups = hd->num_groups;
+  p.num_workers = hd->num_workers;
+  p.k_app = p.v_app = nullptr;
+  p.num_appended = 0, p.app_blocks = hd->append_blocks;
+  if (hd->append_capacity > 0) {
+    if (!cache->k_app || !cache->v_app) return fail(COCKTAIL_EINVAL, "the plan has append buffers but k_app or v_app is NULL");
+    if ((reinterpret_cast<uintptr_t>(cache->k_app) | reinterpret_cast<uintptr_t>(cache->v_app)) & 15)
+      return fail(COCKTAIL_EALIGN, "append buffers must be 16-byte aligned");
+    if (cache->num_appended < 0 || cache->num_appended > hd->append_capacity)
+      return fail(COCKTAIL_EINVAL, "num_appended %d outside [0, %d]", cache->num_appended, hd->append_capacity);
+    p.k_app = static_cast<const char*>(cache->k_app), p.v_app = static_cast<const char*>(cache->v_app);
+    p.num_appended = cache->num_appended;
+  } else if (cache->num_appended != 0) {
+    return fail(COCKTAIL_EINVAL, "num_appended is %d but the plan was made without append buffers", cache->num_appended);
+  }
   p.bh_off = reinterpret_cast<const int32_t*>(pd + hd->off_bh_off);
   p.q = static_cast<const uint32_t*>(q);
   for (int c = 0; c < 3; ++c) {
@@ -797,8 +850,9 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
   p.trace = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + ((hd->workspace_bytes + 255) & ~int64_t(255)));
 #endif
   hipStream_t st = static_cast<hipStream_t>(stream);
-  if (hd->total_gblocks > 0) {
-    const dim3 grid(hd->num_workers, 1, 1), block(64 * hd->rep, 1, 1);
+  const int app_groups = hd->append_capacity > 0 ? hd->batch * hd->num_kv_heads : 0;
+  if (hd->total_gblocks > 0 || app_groups > 0) {
+    const dim3 grid(hd->num_workers + app_groups, 1, 1), block(64 * hd->rep, 1, 1);
     const size_t lds = size_t(hd->rep) * 64 * 17 * sizeof(float);
     switch (shape->group_size) {
       case 32: hipLaunchKernelGGL(decode_attention_kernel<32>, grid, block, lds, st, p); break;

@@ -104,14 +104,15 @@ struct PlanHeader {
   int32_t off_blk_base;       // int32 [B+1][3] first block of sequence b in class buffer c
   int32_t off_nblk;           // int32 [B][3]  blocks per head
   int32_t off_segments;       // Segment [num_segments]
-  int32_t pad2;
+  int32_t append_capacity;    // tokens per sequence the append buffers hold (0 = none)
   int32_t off_worker_rec;     // WorkerRec [num_workers]
   int32_t off_group_rec;      // GroupRec [num_groups]
   int32_t off_pool_seg;       // PoolSeg [num_pool_segs]
   int32_t off_counters;       // uint32 [num_groups * kCounterStride], zero; the only part kernels write
   int32_t num_groups, num_pool_segs;
-  int32_t pad3;
-  int32_t off_bh_off;         // int32 [B*Hkv + 1] prefix: (b, kv head) owns partial ids bh_off[bh] .. bh_off[bh+1]-1
+  int32_t append_blocks;      // blocks per (sequence, kv head) in the append buffers
+  int32_t off_bh_off;         // int32 [B*Hkv + 1] prefix: (b, kv head) owns partial ids bh_off[bh] .. bh_off[bh+1]-1;
+                              // with append buffers the last id of each range is that of the appended tokens
   int32_t off_rq_items;       // RQItem [sum of class_blocks]
 };
 

@@ -62,7 +62,16 @@ extern "C" int cocktail_version(void) { return (0 << 16) | 4; }
 extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
                              int32_t num_workers, cocktail_sizes* sizes, void* plan_host, size_t plan_capacity,
                              int32_t* class_tokens, int32_t* perm) {
+  return cocktail_plan_append(shape, seq_lens, chunk_bits, num_workers, 0, sizes, plan_host, plan_capacity,
+                              class_tokens, perm);
+}
+
+extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
+                                    int32_t num_workers, int32_t append_capacity, cocktail_sizes* sizes,
+                                    void* plan_host, size_t plan_capacity, int32_t* class_tokens, int32_t* perm) {
   if (int rc = check_shape(shape)) return rc;
+  if (append_capacity < 0 || append_capacity > (1 << 24))
+    return fail(COCKTAIL_EINVAL, "append_capacity %d out of range [0, 2^24]", append_capacity);
   if (!seq_lens || !sizes) return fail(COCKTAIL_EINVAL, "seq_lens and sizes must not be NULL");
   if (num_workers < 1 || num_workers > (1 << 20))
     return fail(COCKTAIL_EINVAL, "num_workers %d out of range [1, 2^20]", num_workers);
@@ -73,6 +82,8 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
   int64_t total_chunks = 0, total_tokens = 0;
   for (int b = 0; b < B; ++b) {
     if (seq_lens[b] < 0) return fail(COCKTAIL_EINVAL, "seq_lens[%d] = %d is negative", b, seq_lens[b]);
+    if (seq_lens[b] >= (1 << 24))   // the kernels address the blocks of one (b, h, class) run with 32-bit byte offsets
+      return fail(COCKTAIL_EUNSUPPORTED, "seq_lens[%d] = %d: at most 2^24 - 1 tokens per sequence", b, seq_lens[b]);
     total_chunks += seq_lens[b] / C;
     total_tokens += seq_lens[b];
   }
@@ -353,6 +364,8 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
   for (int sidx = 0; sidx < S; ++sidx) bh_off[bh_of(segs[sidx]) + 1] += own_cnt[sidx];
   for (int g = 0; g < NG; ++g)
     for (int i = 0; i < groups[g].nps; ++i) bh_off[bh_of(segs[psegs[groups[g].pseg0 + i].seg]) + 1] += groups[g].nworkers;
+  if (append_capacity > 0)   // one more partial per (b, kv head): the appended tokens; it is the last of its range
+    for (int i = 0; i < BH; ++i) ++bh_off[i + 1];
   for (int i = 0; i < BH; ++i) bh_off[i + 1] += bh_off[i];
   const int32_t npart = bh_off[BH];
   {
@@ -424,6 +437,7 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
   hd.chunk_size = C, hd.group_size = G, hd.rep = rep;
   hd.num_workers = P, hd.num_segments = S, hd.num_partials = npart;
   hd.num_groups = NG, hd.num_pool_segs = NPS;
+  hd.append_capacity = append_capacity, hd.append_blocks = (append_capacity + kTB - 1) / kTB;
   hd.total_gblocks = static_cast<int32_t>(gblk);
   hd.total_chunks = total_chunks, hd.total_tokens = total_tokens, hd.packed_bytes = packed;
   for (int c = 0; c < 3; ++c) {
@@ -468,6 +482,8 @@ extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_len
   sizes->workspace_bytes = hd.workspace_bytes;
   sizes->packed_bytes = packed;
   sizes->num_workers = P, sizes->num_partials = npart, sizes->num_segments = S;
+  sizes->append_capacity = append_capacity;
+  sizes->append_bytes = int64_t(BH) * hd.append_blocks * kTB * 2 * D;
 
   if (class_tokens) std::memcpy(class_tokens, v_ct.data(), sizeof(int32_t) * v_ct.size());
   if (perm && total_chunks) std::memcpy(perm, v_perm.data(), sizeof(int32_t) * v_perm.size());

@@ -159,6 +159,13 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
     *reinterpret_cast<u32x4*>(dst + o) = *reinterpret_cast<const u32x4*>(lds + o);
 }
 
+// Zeroes `n16` 16-byte words (the append buffers start out empty; rows that are never appended must
+// read as finite values because the decode kernel loads whole 32-token units and masks afterwards).
+__global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* __restrict__ p, size_t n16) {
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (size_t i = size_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += size_t(gridDim.x) * 256) p[i] = z;
+}
+
 }  // namespace cocktail
 
 using namespace cocktail;
@@ -208,9 +215,18 @@ extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void
   p.cls_end0 = static_cast<int32_t>(hd->class_blocks[0]);
   p.cls_end1 = p.cls_end0 + static_cast<int32_t>(hd->class_blocks[1]);
   p.cls_end2 = static_cast<int32_t>(tot);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (hd->append_capacity > 0) {
+    if (!cache->k_app || !cache->v_app) return fail(COCKTAIL_EINVAL, "the plan has append buffers but k_app or v_app is NULL");
+    if ((reinterpret_cast<uintptr_t>(cache->k_app) | reinterpret_cast<uintptr_t>(cache->v_app)) & 15)
+      return fail(COCKTAIL_EALIGN, "append buffers must be 16-byte aligned");
+    const size_t n16 = size_t(hd->batch) * hd->num_kv_heads * hd->append_blocks * (kTB * 2 * 128 / 16);
+    const unsigned blocks = static_cast<unsigned>(n16 / 256 < 4096 ? (n16 + 255) / 256 : 4096);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, static_cast<u32x4*>(cache->k_app), n16);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, static_cast<u32x4*>(cache->v_app), n16);
+  }
   if (tot == 0) return COCKTAIL_OK;
   const dim3 grid(static_cast<unsigned>(tot), 2, 1), block(256, 1, 1);
-  hipStream_t st = static_cast<hipStream_t>(stream);
   switch (shape->group_size) {
     case 32: hipLaunchKernelGGL((reorder_quantize_kernel<128, 32>), grid, block, 0, st, p); break;
     case 64: hipLaunchKernelGGL((reorder_quantize_kernel<128, 64>), grid, block, 0, st, p); break;

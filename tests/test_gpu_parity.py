@@ -223,6 +223,56 @@ def test_planner_tuning_knobs_keep_parity(env, monkeypatch):
     Case(w, workers=16).check_all()
 
 
+@pytest.mark.parametrize("rep,capacity,steps", [(1, 70, 70), (4, 130, 37), (2, 1, 1)])
+def test_appended_decode_tokens(rep, capacity, steps):
+    """Sec. III-A: generated tokens are appended in FP16; every decode step attends to all of them."""
+    w = workloads.small(f"append_r{rep}", 2, 2 * rep, 2, [64 * 9 + 5, 300], 64, 32, mix=(0.2, 0.4, 0.4),
+                        seed_offset=60 + rep)
+    _announce(w.name)
+    dev = _dev()
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = workloads.chunk_bits(w)
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), 12, append_capacity=capacity)
+    cache = ck.PackedCache(plan, dev)
+    cache.k_app.fill_(0xAB), cache.v_app.fill_(0xAB)       # reorder+quantize must clear the append buffers
+    k, v = workloads.kv_flat(w, 0)
+    ck.cocktail_reorder_quantize(cache, torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev), ragged=True)
+    ks, vs = [], []
+    for b in range(w.batch):
+        kh, vh = zip(*[workloads.kv_head(w, 0, b, h) for h in range(w.num_kv_heads)])
+        ks.append(np.stack(kh)), vs.append(np.stack(vh))
+    oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    q = workloads.query(w, 0)
+    q_dev = torch.from_numpy(q).to(dev)
+    rng = np.random.default_rng([workloads.BASE_SEED, 4242, rep])
+
+    def compare():
+        out, lse = ck.cocktail_decode_attention(cache, q_dev)
+        torch.cuda.synchronize()
+        ref, rl = O.decode_attention(q, oc)
+        got = out.cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref).max(axis=2) / np.abs(ref).max(axis=2)
+        assert err.max() <= TOL, f"after {cache.desc.num_appended} appended tokens: max rel err {err.max():.3e}"
+        assert np.abs(lse.cpu().numpy() - rl).max() <= 1e-4 * max(1.0, np.abs(rl).max())
+
+    compare()                                               # nothing appended yet
+    for step in range(steps):
+        kn = rng.standard_normal((w.batch, w.num_kv_heads, w.head_dim), dtype=np.float32).astype(np.float16)
+        vn = rng.standard_normal((w.batch, w.num_kv_heads, w.head_dim), dtype=np.float32).astype(np.float16)
+        kn[:, :, 3] *= np.float16(6.0)                      # keep the new tokens relevant to the softmax
+        ck.cocktail_append_fp16(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
+        O.append_tokens(oc, kn, vn)
+        if step in (0, 1, 31, 32, 63, 64, steps - 1):
+            compare()
+    torch.cuda.synchronize()
+    assert cache.desc.num_appended == steps
+    for which, buf in (("k", cache.k_app), ("v", cache.v_app)):      # append buffers bit-exact, unused rows zero
+        assert np.array_equal(buf.cpu().numpy(), O.pack_append_buffer(oc, which, capacity))
+    if steps == capacity:
+        with pytest.raises(ck.CocktailError):
+            ck.cocktail_append_fp16(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
+
+
 def test_runs_on_a_side_stream():
     w = workloads.small("stream", 1, 2, 2, [512], 64, 32, seed_offset=4)
     _announce(w.name)

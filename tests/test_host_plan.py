@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "cocktail.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
-    declared = set(re.findall(r"\b(cocktail_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(cocktail_[a-z0-9_]+)\s*\(", hdr))
     assert declared == set(_lib.EXPORTS), declared ^ set(_lib.EXPORTS)
     handle = _lib.lib()
     for name in declared:
@@ -286,3 +286,47 @@ def test_gpu_entry_points_validate_on_host_before_launching():
     assert L.cocktail_stream_read_probe(None, 1 << 30, 16, C.byref(n), None) == _lib.EINVAL
     assert L.cocktail_stream_read_probe(8, 1 << 30, 16, C.byref(n), None) == _lib.EALIGN
     assert L.cocktail_stream_read_probe(16, 1 << 20, 16, C.byref(n), None) == _lib.EINVAL
+
+
+def test_append_capacity_sizes_and_validation():
+    w = workloads.config(1)
+    sh = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = np.concatenate(workloads.chunk_bits(w))
+    p0 = ck.cocktail_plan(sh, w.seq_lens, bits, 64)
+    p1 = ck.cocktail_plan(sh, w.seq_lens, bits, 64, append_capacity=130)
+    assert p0.sizes.append_capacity == 0 and p0.sizes.append_bytes == 0
+    assert p1.sizes.append_capacity == 130
+    assert p1.sizes.append_bytes == w.batch * w.num_kv_heads * 3 * 64 * 256     # 3 blocks of 64 fp16 rows per head
+    # one more partial per (sequence, kv head), at the end of its range
+    assert p1.sizes.num_partials == p0.sizes.num_partials + w.batch * w.num_kv_heads
+    _check_work_split(p0, w, 64)
+    h = _parse(p1.blob)
+    bh_off = _arr(p1.blob, h["off"]["bh_off"], np.int32, w.batch * w.num_kv_heads + 1)
+    bh_off0 = _arr(p0.blob, _parse(p0.blob)["off"]["bh_off"], np.int32, w.batch * w.num_kv_heads + 1)
+    assert (np.diff(bh_off) == np.diff(bh_off0) + 1).all()
+    L = _lib.lib()
+    sizes = _lib.Sizes()
+    lp = np.asarray(w.seq_lens, np.int32).ctypes.data_as(C.POINTER(C.c_int32))
+    bp = bits.ctypes.data_as(C.POINTER(C.c_uint8))
+    assert L.cocktail_plan_append(C.byref(sh), lp, bp, 4, -1, C.byref(sizes), None, 0, None, None) == _lib.EINVAL
+    cache = _lib.Cache()
+    cache.plan_host = p0.blob.ctypes.data
+    assert L.cocktail_append_fp16(C.byref(sh), 16, 16, C.byref(cache), 0, None) == _lib.EINVAL   # no append buffers
+    cache.plan_host = p1.blob.ctypes.data
+    assert L.cocktail_append_fp16(C.byref(sh), 16, 16, C.byref(cache), 0, None) == _lib.EINVAL   # NULL buffers
+    cache.k_app, cache.v_app = 4096, 4096
+    assert L.cocktail_append_fp16(C.byref(sh), 16, 16, C.byref(cache), 130, None) == _lib.EINVAL
+    assert L.cocktail_append_fp16(C.byref(sh), 16, 16, C.byref(cache), -1, None) == _lib.EINVAL
+    assert L.cocktail_append_fp16(C.byref(sh), 8, 16, C.byref(cache), 0, None) == _lib.EALIGN
+    assert L.cocktail_append_fp16(C.byref(sh), None, 16, C.byref(cache), 0, None) == _lib.EINVAL
+    # decode: num_appended must fit the plan
+    cache.plan_dev = 4096
+    cache.num_appended = 131
+    assert L.cocktail_decode_attention(C.byref(sh), 16, C.byref(cache), 0.0, 16, None, 16, 1 << 30, None) == _lib.EINVAL
+    cache.plan_host = p0.blob.ctypes.data
+    cache.num_appended = 1
+    assert L.cocktail_decode_attention(C.byref(sh), 16, C.byref(cache), 0.0, 16, None, 16, 1 << 30, None) == _lib.EINVAL
+    big = ck.make_shape(1, 1, 1, 128, 64, 32)
+    with pytest.raises(ck.CocktailError) as e:
+        ck.cocktail_plan(big, [1 << 24], np.full((1 << 24) // 64, 2, np.uint8), 4)
+    assert e.value.code == _lib.EUNSUPPORTED
