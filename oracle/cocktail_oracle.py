@@ -17,6 +17,9 @@ What it computes, in the paper's order:
                   in the order INT2, INT4, FP16, one softmax over the
                   concatenation, three att x V products summed.  Evaluated in
                   float64 on the dequantised values.
+  chunk_bitwidths Sec. III-B, Eq. 1-3: cosine similarity of the query embedding with every
+                  chunk embedding, the two thresholds from the extreme scores, and the
+                  bitwidth of every chunk by the comparisons of Alg. 1's prefill loop.
   append_tokens   Sec. III-A: the K/V rows of tokens generated during decoding are
                   kept in FP16 after the context; attention then runs over the
                   three context blocks followed by those rows.
@@ -29,7 +32,9 @@ torch's scaled_dot_product_attention; invariance to the chunk permutation
 scalar-loop brute force on tiny inputs; partial-softmax merge identity; pack
 round trips; the KV-size figure of Sec. I; appended tokens equal textbook
 attention over the concatenation and behave exactly like the FP16 remainder of a
-longer context.  No function here is unpinned.
+longer context; the similarity scores equal scikit-learn's cosine_similarity,
+and the thresholds a worked example, their limiting cases and their monotonicity
+in alpha and beta.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -403,3 +408,48 @@ def packed_bytes(class_tokens: Sequence[int], num_kv_heads: int, head_dim: int, 
     """Algorithmic bytes (K + V) of the packed cache of one sequence: codes + fp16 scale/zero per group."""
     per = [head_dim * 2 // 8 + 4 * head_dim // group, head_dim * 4 // 8 + 4 * head_dim // group, head_dim * 2]
     return 2 * num_kv_heads * sum(n * p for n, p in zip(class_tokens, per))
+
+
+# ---------------------------------------------------------------------- chunk-level quantization search
+def similarity_scores(query_emb: np.ndarray, chunk_emb: np.ndarray) -> np.ndarray:
+    """Sec. III-B, Eq. 1: cosine similarity of one query embedding [E] with every chunk embedding [N, E].
+
+    Evaluated in float64 and rounded once to float32, the precision in which the thresholds are
+    compared.  A zero vector has no direction: its score is taken as 0.
+    """
+    q = query_emb.astype(np.float64)
+    c = chunk_emb.astype(np.float64)
+    dots = c @ q
+    denom = np.sqrt(q @ q) * np.sqrt(np.einsum("ne,ne->n", c, c))
+    s = np.divide(dots, denom, out=np.zeros_like(dots), where=denom > 0)
+    return s.astype(np.float32)
+
+
+def thresholds(scores: np.ndarray, alpha: float, beta: float):
+    """Sec. III-B, Eq. 2-3 in float32, one rounding per operation:
+    T_low = s_min + (s_max - s_min) * alpha,  T_high = s_max - (s_max - s_min) * beta."""
+    smin, smax = np.float32(scores.min()), np.float32(scores.max())
+    d = np.float32(smax - smin)
+    t_low = np.float32(smin + np.float32(d * np.float32(alpha)))
+    t_high = np.float32(smax - np.float32(d * np.float32(beta)))
+    return t_low, t_high
+
+
+def chunk_bitwidths(query_emb: np.ndarray, chunk_emb: np.ndarray, alpha: float, beta: float):
+    """Chunk-level quantization search for one sequence (Sec. III-B) with the comparison order of
+    Alg. 1's prefill loop: s < T_low -> INT2, else s > T_high -> FP16, else INT4.
+
+    Returns (bits uint8 [N] with values 2 / 4 / 16, scores float32 [N]).
+    """
+    n = chunk_emb.shape[0]
+    if n == 0:
+        return np.zeros(0, dtype=np.uint8), np.zeros(0, dtype=np.float32)
+    s = similarity_scores(query_emb, chunk_emb)
+    t_low, t_high = thresholds(s, alpha, beta)
+    bits = np.full(n, 4, dtype=np.uint8)
+    for i in range(n):
+        if s[i] < t_low:
+            bits[i] = 2
+        elif s[i] > t_high:
+            bits[i] = 16
+    return bits, s

@@ -405,3 +405,61 @@ def test_appended_tokens_behave_like_the_fp16_remainder_of_a_longer_context():
         rows = blocks[h, 0].reshape(16, 64, 16).transpose(1, 0, 2).reshape(64, 256)
         assert np.array_equal(rows[:n], ks[0][h, t:t + n].view(np.uint8).reshape(n, 256))
         assert not rows[n:].any() and not blocks[h, 1].any()
+
+
+# -- chunk-level quantization search (Sec. III-B, Eq. 1-3) --------------------------------------
+def test_similarity_scores_equal_sklearn_cosine_and_closed_forms():
+    from sklearn.metrics.pairwise import cosine_similarity
+    q, cs = workloads.embeddings(5, [300, 1])
+    s = O.similarity_scores(q[0], cs[0])
+    ref = cosine_similarity(cs[0].astype(np.float64), q[0:1].astype(np.float64))[:, 0]
+    assert s.dtype == np.float32
+    np.testing.assert_allclose(s, ref, rtol=0, atol=6e-8)             # one float32 rounding
+    e = np.eye(4, dtype=np.float32)
+    c = np.stack([e[0], e[1], -e[0], 3 * e[0] + 4 * e[1], np.zeros(4, np.float32)])
+    np.testing.assert_array_equal(O.similarity_scores(2 * e[0], c), np.float32([1, 0, -1, 0.6, 0]))
+    # Eq. 1 does not depend on the lengths of the vectors (powers of two keep it bit for bit)
+    np.testing.assert_array_equal(O.similarity_scores(4 * q[0], 0.5 * cs[0]), s)
+
+
+def test_thresholds_worked_example_limits_and_order_of_comparisons():
+    s = np.float32([0.1, 0.5, 0.9])
+    t_low, t_high = O.thresholds(s, 0.6, 0.1)                        # Eq. 2: 0.1 + 0.8*0.6, Eq. 3: 0.9 - 0.8*0.1
+    assert abs(t_low - 0.58) < 1e-6 and abs(t_high - 0.82) < 1e-6
+    e = np.eye(3, dtype=np.float32)
+    q = e[0]
+    c = np.stack([0.1 * e[0] + np.sqrt(1 - 0.01) * e[1], 0.5 * e[0] + np.sqrt(0.75) * e[1],
+                  0.9 * e[0] + np.sqrt(1 - 0.81) * e[1]]).astype(np.float32)
+    bits, sc = O.chunk_bitwidths(q, c, 0.6, 0.1)
+    np.testing.assert_allclose(sc, s, atol=1e-6)
+    assert bits.tolist() == [2, 2, 16]
+    # alpha = beta = 0: T_low = s_min, T_high = s_max, nothing lies strictly outside -> all INT4
+    assert O.chunk_bitwidths(q, c, 0.0, 0.0)[0].tolist() == [4, 4, 4]
+    # overlapping thresholds: the INT2 test comes first in Alg. 1's loop
+    assert O.chunk_bitwidths(q, c, 0.9, 0.9)[0].tolist() == [2, 2, 16]
+    # alpha = beta = 1: T_low = s_max, T_high = s_min; only the top chunk is not below T_low, and it is above T_high
+    assert O.chunk_bitwidths(q, c, 1.0, 1.0)[0].tolist() == [2, 2, 16]
+    # a single chunk, or equal scores: both thresholds equal the score -> INT4
+    assert O.chunk_bitwidths(q, c[:1], 0.6, 0.1)[0].tolist() == [4]
+    assert O.chunk_bitwidths(q, np.stack([c[1], c[1]]), 0.6, 0.1)[0].tolist() == [4, 4]
+    assert O.chunk_bitwidths(q, c[:0], 0.6, 0.1)[0].size == 0
+
+
+def test_more_alpha_means_more_int2_and_more_beta_means_more_fp16():
+    """Sec. IV-C: a larger alpha sends more chunks to INT2, a larger beta keeps more in FP16."""
+    q, cs = workloads.embeddings(6, [4096])
+    prev2 = prev16 = -1
+    for a in (0.0, 0.2, 0.4, 0.6, 0.8):
+        bits, s = O.chunk_bitwidths(q[0], cs[0], a, 0.1)
+        n2 = int((bits == 2).sum())
+        assert n2 >= prev2
+        prev2 = n2
+        assert bits[np.argmax(s)] == 16 and (a == 0.0 or bits[np.argmin(s)] == 2)
+    for b_ in (0.0, 0.1, 0.2, 0.3):
+        bits, _ = O.chunk_bitwidths(q[0], cs[0], 0.6, b_)
+        n16 = int((bits == 16).sum())
+        assert n16 >= prev16
+        prev16 = n16
+    bits, _ = O.chunk_bitwidths(q[0], cs[0], 0.6, 0.1)                # the paper's defaults
+    share = [(bits == v).mean() for v in (2, 4, 16)]
+    assert share[0] > 0.5 and 0 < share[2] < 0.1                      # most chunks are irrelevant to the query

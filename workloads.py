@@ -32,7 +32,7 @@ import numpy as np
 
 BASE_SEED = 250323294
 
-_TAG_K, _TAG_V, _TAG_Q, _TAG_BITS, _TAG_OUTLIER, _TAG_LEN, _TAG_MIX = range(7)
+_TAG_K, _TAG_V, _TAG_Q, _TAG_BITS, _TAG_OUTLIER, _TAG_LEN, _TAG_MIX, _TAG_EMB = range(8)
 
 
 @dataclass(frozen=True)
@@ -170,3 +170,22 @@ def kv_flat(w: Workload, layer: int, threads: int = 8,
         for j in jobs:
             fill(j)
     return k, v
+
+
+def embeddings(name_seed: int, num_chunks: Sequence[int], embed_dim: int = 768,
+               relevant_share: float = 0.08) -> Tuple[np.ndarray, List[np.ndarray]]:
+    """Query and chunk embeddings for the chunk-level quantization search (Sec. III-B).
+
+    Stand-ins for the encoder outputs (the paper uses a 768-wide retrieval encoder): Gaussian chunk
+    embeddings of which a small share leans towards the query, the rest does not (Sec. I, Fig. 1: few
+    chunks are relevant to a query).  Returns q fp32 [B, E] and per sequence c fp32 [N_b, E].
+    """
+    q = np.empty((len(num_chunks), embed_dim), dtype=np.float32)
+    cs = []
+    for b, n in enumerate(num_chunks):
+        r = _rng(int(name_seed), b, _TAG_EMB)
+        q[b] = r.standard_normal(embed_dim, dtype=np.float32)
+        c = r.standard_normal((int(n), embed_dim), dtype=np.float32)
+        lean = np.where(r.random(int(n)) < relevant_share, r.uniform(0.5, 2.0, int(n)), r.uniform(0.0, 0.3, int(n)))
+        cs.append((c + lean[:, None].astype(np.float32) * q[b]).astype(np.float32))
+    return q, cs
