@@ -219,6 +219,27 @@ int cocktail_append_fp16(const cocktail_shape* shape, const void* k_new, const v
                          const cocktail_cache* cache, int32_t position, void* stream);
 
 /*
+ * Chunk-level quantization search (Sec. III-B): scores[i] = cosine similarity of sequence b's query
+ * embedding with chunk embedding i (Eq. 1); per sequence T_low = s_min + (s_max - s_min) * alpha and
+ * T_high = s_max - (s_max - s_min) * beta (Eq. 2-3); chunk_bits[i] = 2 if scores[i] < T_low, else 16
+ * if scores[i] > T_high, else 4 (the comparisons of Alg. 1's prefill loop, in that order).  The
+ * embeddings come from the caller's encoder.  Arithmetic: sums in binary64, the score rounded once
+ * to binary32 (0 if either vector is zero), thresholds and comparisons in unfused binary32.
+ *
+ *   chunk_off   DEVICE int32 [B+1]  prefix sum of the chunk counts N_b (chunk_off[B] = total_chunks)
+ *   query_emb   DEVICE fp32 [B][E]
+ *   chunk_emb   DEVICE fp32 [total_chunks][E], sequence after sequence
+ *   alpha, beta in [0, 1] (the paper uses 0.6 and 0.1)
+ *   scores      DEVICE fp32 [total_chunks] out
+ *   chunk_bits  DEVICE uint8 [total_chunks] out, values 2 / 4 / 16: copy to the host for cocktail_plan
+ *
+ * Two kernel launches.  Errors: EINVAL, EALIGN, EHIP.
+ */
+int cocktail_chunk_bitwidths(int32_t batch, int32_t embed_dim, int32_t total_chunks, const int32_t* chunk_off,
+                             const float* query_emb, const float* chunk_emb, float alpha, float beta, float* scores,
+                             uint8_t* chunk_bits, void* stream);
+
+/*
  * Number of decode workgroups that fills the current HIP device for this shape
  * (compute units x resident waves per unit / (Hq/Hkv)).  Needs a GPU: EHIP otherwise.
  */

@@ -48,6 +48,8 @@ EXPORTS = {
                                        C.POINTER(C.c_int32)]),
     "cocktail_append_fp16": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.POINTER(Cache), C.c_int32,
                                        C.c_void_p]),
+    "cocktail_chunk_bitwidths": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "cocktail_reorder_quantize": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
                                             C.c_int64, C.c_int64, C.POINTER(Cache), C.c_void_p]),
     "cocktail_decode_attention": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float, C.c_void_p,

@@ -162,3 +162,26 @@ def cocktail_stream_read_probe(buf: torch.Tensor, sink: torch.Tensor,
     check(lib().cocktail_stream_read_probe(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(),
                                            C.byref(n), _stream_ptr(stream)))
     return int(n.value)
+
+
+def cocktail_chunk_bitwidths(query_emb: torch.Tensor, chunk_emb: torch.Tensor, num_chunks: Sequence[int],
+                             alpha: float = 0.6, beta: float = 0.1, stream: Optional[torch.cuda.Stream] = None):
+    """Chunk-level quantization search.  query_emb: device fp32 [B, E]; chunk_emb: device fp32 [sum N_b, E].
+    Returns (chunk_bits uint8 [sum N_b], scores fp32 [sum N_b]), both on the device."""
+    for t in (query_emb, chunk_emb):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError("embeddings must be contiguous float32 device tensors")
+    batch, e = query_emb.shape
+    off = np.zeros(batch + 1, dtype=np.int32)
+    off[1:] = np.cumsum(np.asarray(num_chunks, dtype=np.int64))
+    total = int(off[-1])
+    if chunk_emb.shape != (total, e) or len(num_chunks) != batch:
+        raise ValueError("chunk_emb must have shape [sum(num_chunks), E] and num_chunks one entry per sequence")
+    off_dev = torch.from_numpy(off).to(query_emb.device)
+    scores = torch.empty(total, dtype=torch.float32, device=query_emb.device)
+    bits = torch.empty(total, dtype=torch.uint8, device=query_emb.device)
+    check(lib().cocktail_chunk_bitwidths(batch, e, total, off_dev.data_ptr(), query_emb.data_ptr(),
+                                         chunk_emb.data_ptr() if total else None, float(alpha), float(beta),
+                                         scores.data_ptr() if total else None, bits.data_ptr() if total else None,
+                                         _stream_ptr(stream)))
+    return bits, scores

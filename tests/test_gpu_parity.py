@@ -273,6 +273,30 @@ def test_appended_decode_tokens(rep, capacity, steps):
             ck.cocktail_append_fp16(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
 
 
+@pytest.mark.parametrize("alpha,beta", [(0.6, 0.1), (0.0, 0.0), (0.3, 0.5), (1.0, 1.0)])
+def test_chunk_level_quantization_search(alpha, beta):
+    """Sec. III-B: scores and bitwidths of every chunk, bit for bit (the arithmetic is fixed on both sides)."""
+    num_chunks = [4096, 256, 1, 0, 1000]              # 128K tokens in 32-token chunks, ..., one chunk, none
+    _announce(f"search alpha={alpha} beta={beta}")
+    q, cs = workloads.embeddings(11, num_chunks)
+    cs[4][17] = 0.0                                    # a zero embedding scores 0
+    dev = _dev()
+    bits, scores = ck.cocktail_chunk_bitwidths(torch.from_numpy(q).to(dev), torch.from_numpy(np.concatenate(cs)).to(dev),
+                                               num_chunks, alpha, beta)
+    torch.cuda.synchronize()
+    bits, scores = bits.cpu().numpy(), scores.cpu().numpy()
+    pos = 0
+    for b, n in enumerate(num_chunks):
+        rb, rs = O.chunk_bitwidths(q[b], cs[b], alpha, beta)
+        assert np.array_equal(scores[pos:pos + n], rs), f"scores of sequence {b} differ"
+        assert np.array_equal(bits[pos:pos + n], rb), f"bitwidths of sequence {b} differ"
+        pos += n
+    # the result feeds the planner directly
+    shape = ck.make_shape(len(num_chunks), 2, 2, 128, 32, 32)
+    plan = ck.cocktail_plan(shape, [32 * n for n in num_chunks], bits, 64)
+    assert int(plan.sizes.total_chunks) == sum(num_chunks)
+
+
 def test_runs_on_a_side_stream():
     w = workloads.small("stream", 1, 2, 2, [512], 64, 32, seed_offset=4)
     _announce(w.name)

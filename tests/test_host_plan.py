@@ -330,3 +330,17 @@ def test_append_capacity_sizes_and_validation():
     with pytest.raises(ck.CocktailError) as e:
         ck.cocktail_plan(big, [1 << 24], np.full((1 << 24) // 64, 2, np.uint8), 4)
     assert e.value.code == _lib.EUNSUPPORTED
+
+
+def test_chunk_bitwidths_validates_on_host():
+    L = _lib.lib()
+    args = (4096, 4096, 4096, 0.6, 0.1, 4096, 4096, None)   # chunk_off, query, chunks, alpha, beta, scores, bits, stream
+    assert L.cocktail_chunk_bitwidths(0, 768, 10, *args) == _lib.EINVAL
+    assert L.cocktail_chunk_bitwidths(1, 0, 10, *args) == _lib.EINVAL
+    assert L.cocktail_chunk_bitwidths(1, 768, -1, *args) == _lib.EINVAL
+    assert L.cocktail_chunk_bitwidths(1, 768, 10, 4096, 4096, 4096, 1.5, 0.1, 4096, 4096, None) == _lib.EINVAL
+    assert L.cocktail_chunk_bitwidths(1, 768, 10, 4096, 4096, 4096, 0.6, -0.1, 4096, 4096, None) == _lib.EINVAL
+    assert L.cocktail_chunk_bitwidths(1, 768, 10, None, 4096, 4096, 0.6, 0.1, 4096, 4096, None) == _lib.EINVAL
+    assert L.cocktail_chunk_bitwidths(1, 768, 10, 4096, 4096, None, 0.6, 0.1, 4096, 4096, None) == _lib.EINVAL
+    assert L.cocktail_chunk_bitwidths(1, 768, 10, 4096, 4098, 4096, 0.6, 0.1, 4096, 4096, None) == _lib.EALIGN
+    assert L.cocktail_chunk_bitwidths(1, 768, 0, 4096, 4096, None, 0.6, 0.1, None, None, None) == _lib.OK   # nothing to do
