@@ -691,14 +691,16 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
 
 // Exact merge of the partial states of one (sequence, query head):
 //   M = max m_i,  L = sum l_i 2^(m_i - M),  out = sum o_i 2^(m_i - M) / L,  lse = ln2 (M + log2 L).
-// The partials of a (sequence, kv head) are a dense block of the workspace.  256 threads: 32 channel
-// quads x 8 slices of the block; every slice folds its partials in one pass with a running maximum,
-// then the eight slice states are folded through shared memory.  A (sequence, query head) without
-// any partial (empty sequence) gets zeros and lse = -inf.
-__global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams prm) {
-  __shared__ float sm_m[8];
-  __shared__ float sm_l[8];
-  __shared__ float sm_o[8][D];
+// The partials of a (sequence, kv head) are a dense block of the workspace.  512 threads: 32 channel
+// quads x 16 slices of the block; a slice loads eight partials at a time (128 in flight per workgroup,
+// usually the whole block in one round) and folds them with a running maximum, then the sixteen
+// slice states are folded through shared memory.  A (sequence, query head) without any partial
+// (empty sequence) gets zeros and lse = -inf.
+constexpr int kMergeSlices = 16;
+__global__ __launch_bounds__(32 * kMergeSlices) void decode_merge_kernel(DecodeParams prm) {
+  __shared__ float sm_m[kMergeSlices];
+  __shared__ float sm_l[kMergeSlices];
+  __shared__ float sm_o[kMergeSlices][D];
   const int bhq = blockIdx.x;
   const int rep = prm.rep;
   const int b = bhq / prm.num_q_heads;
@@ -710,18 +712,18 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams prm) {
   const int tid = threadIdx.x;
   // every worker has drawn its last ticket: put the counters back to zero for the next call
   if (blockIdx.x == 0)
-    for (int i = tid; i < prm.num_groups; i += 256) prm.counters[i * kCounterStride] = 0u;
+    for (int i = tid; i < prm.num_groups; i += 32 * kMergeSlices) prm.counters[i * kCounterStride] = 0u;
   constexpr int STRIDE = D + kPartialFloats;
-  constexpr int U = 4;   // partials in flight per thread
+  constexpr int U = 8;   // partials in flight per thread
   const int quad = tid & 31, slice = tid >> 5;
   const float* base = prm.ws + (int64_t(lo) * rep + r) * STRIDE + kPartialFloats + quad * 4;
   float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
-  for (int i0 = slice; i0 < n; i0 += 8 * U) {
+  for (int i0 = slice; i0 < n; i0 += kMergeSlices * U) {
     float pm[U], pl[U];
     float2 va[U], vb[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int i = i0 + 8 * u;
+      const int i = i0 + kMergeSlices * u;
       const bool ok = i < n;
       const float* part = base + int64_t(ok ? i : i0) * rep * STRIDE;
       pm[u] = ok ? part[-kPartialFloats - quad * 4] : -INFINITY;
@@ -748,10 +750,10 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(DecodeParams prm) {
   if (tid < D) {
     float mx = sm_m[0];
 #pragma unroll
-    for (int sidx = 1; sidx < 8; ++sidx) mx = fmaxf(mx, sm_m[sidx]);
+    for (int sidx = 1; sidx < kMergeSlices; ++sidx) mx = fmaxf(mx, sm_m[sidx]);
     float big_l = 0.f, o = 0.f;
 #pragma unroll
-    for (int sidx = 0; sidx < 8; ++sidx) {
+    for (int sidx = 0; sidx < kMergeSlices; ++sidx) {
       const float w = (sm_m[sidx] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(sm_m[sidx] - mx);
       big_l += sm_l[sidx] * w;
       o += sm_o[sidx][tid] * w;
@@ -862,7 +864,7 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_attention launch failed: %s", hipGetErrorString(e));
   }
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(shape->batch * shape->num_q_heads), dim3(256), 0, st, p);
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(shape->batch * shape->num_q_heads), dim3(32 * kMergeSlices), 0, st, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_merge launch failed: %s", hipGetErrorString(e));
   return COCKTAIL_OK;
