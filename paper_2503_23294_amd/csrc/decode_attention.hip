@@ -315,10 +315,14 @@ __device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J],
   float smax = s[0];
 #pragma unroll
   for (int jj = 1; jj < J; ++jj) smax = fmaxf(smax, s[jj]);
-  // the reference maximum only moves when it is exceeded by more than 2^8
+  // the reference maximum only moves when it is exceeded by more than 2^8, and then for the whole
+  // wave at once (to the largest logit any lane has seen): the lanes share one reference, so the
+  // number of rescales per state is that of one running maximum, not of 64 independent ones
   const bool grow = smax > st.m + kRescaleThreshold;
   if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
-    const float mnew = grow ? smax : st.m;
+    float mnew = fmaxf(smax, st.m);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mnew = fmaxf(mnew, __shfl_xor(mnew, o));
     const float alpha = __builtin_amdgcn_exp2f(st.m - mnew);
     st.m = mnew;
     st.l *= alpha;

@@ -47,6 +47,10 @@ constexpr int kGroupWorkers = 8;
 constexpr int kPoolPercent = 25;
 constexpr int kPairMode = 0;
 constexpr int kLayout = 0;
+// Relative speed of a worker of class [self] whose SIMD mate works on class [mate] (INT2, INT4, FP16), traced on
+// MI355X at equal weighted cost: two bandwidth-bound or two ALU-bound waves on a SIMD get in each other's way,
+// an INT4 wave next to an FP16 wave runs well ahead.
+constexpr double kPairSpeed[3][3] = {{0.87, 1.0, 1.0}, {1.0, 1.17, 1.27}, {0.97, 1.06, 0.9}};
 // A group only gets a pool if its range holds at least this many blocks per worker.
 constexpr int kMinBlocksPerWorkerForPool = 16;
 
@@ -181,6 +185,8 @@ extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* 
   //             group works on one class (two where it straddles a class boundary);
   //   layout 1: every group receives the same share of every class (FP16 stripe, then INT2, then INT4).
   const int NGR = (P + group_workers - 1) / group_workers;
+  bool pair_speed_on = true;
+  if (const char* e = std::getenv("COCKTAIL_PAIR_SPEED")) pair_speed_on = std::atoi(e) != 0;   // tuning aid
   int layout = kLayout;
   if (const char* e = std::getenv("COCKTAIL_LAYOUT")) layout = std::atoi(e) != 0;   // tuning aid
   const int class_order[3] = {layout ? 2 : 0, layout ? 0 : 1, layout ? 1 : 2};
@@ -193,13 +199,36 @@ extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* 
       tot += class_nblk[c] * per[c];
       cut[c].assign(NGR + 1, 0);
     }
+    // Share of the total cost in front of every group.  Equal shares per worker to begin with; then,
+    // if the workgroups fill the chip twice (workgroup i and i + P/2 share a SIMD), a few rounds that
+    // scale every worker's share by the measured relative speed of its class next to its mate's class.
+    std::vector<double> wcap(P, 1.0), gfrac(NGR + 1, 0.0);
+    const bool pair_speed = pair_speed_on && !layout && rep == 1 && P % 2 == 0 && P >= 2 * group_workers;
+    for (int round = 0; round < (pair_speed ? 4 : 1); ++round) {
+      double total_cap = 0.0;
+      for (int w = 0; w < P; ++w) total_cap += wcap[w];
+      double acc = 0.0;
+      for (int j = 0; j < NGR; ++j) {
+        gfrac[j] = acc / total_cap;
+        for (int w = j * group_workers; w < P && w < (j + 1) * group_workers; ++w) acc += wcap[w];
+      }
+      gfrac[NGR] = 1.0;
+      if (!pair_speed || round == 3) break;
+      std::vector<int> wclass(P);
+      for (int w = 0; w < P; ++w) {
+        const int j = w / group_workers, k = (j + 1) * group_workers <= P ? group_workers : P - j * group_workers;
+        const double x = double(tot) * (gfrac[j] + (w - j * group_workers + 0.5) / k * (gfrac[j + 1] - gfrac[j]));
+        wclass[w] = x < double(start[1]) ? 0 : (x < double(start[2]) ? 1 : 2);
+      }
+      for (int w = 0; w < P; ++w) wcap[w] = kPairSpeed[wclass[w]][wclass[(w + P / 2) % P]];
+    }
     for (int j = 0; j <= NGR; ++j) {
-      const int w_lo = j * group_workers < P ? j * group_workers : P;
       for (int c = 0; c < 3; ++c) {
         if (layout) {
+          const int w_lo = j * group_workers < P ? j * group_workers : P;
           cut[c][j] = class_nblk[c] * w_lo / P;
         } else {
-          const int64_t target = static_cast<int64_t>((static_cast<__int128>(tot) * w_lo) / P);
+          const int64_t target = static_cast<int64_t>(double(tot) * gfrac[j]);
           int64_t v = (target - start[c] + per[c] / 2) / per[c];
           cut[c][j] = v < 0 ? 0 : (v > class_nblk[c] ? class_nblk[c] : v);
         }
