@@ -23,4 +23,20 @@ typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 __host__ __device__ inline h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
 __host__ __device__ inline uint32_t as_u32(h2 v) { return __builtin_bit_cast(uint32_t, v); }
 
+#ifdef __HIPCC__
+// Reads a plan record through the scalar data path: the records are written by the host only, and
+// every wave reads them at a wave-uniform address, so they can go straight into scalar registers.
+template <class T>
+__device__ __forceinline__ T load_record(const T* p) {
+  static_assert(sizeof(T) % 4 == 0, "records are made of 32-bit fields");
+  struct Words {
+    int32_t w[sizeof(T) / 4];
+  } tmp;
+  const auto* src = reinterpret_cast<const __attribute__((address_space(4))) int32_t*>(reinterpret_cast<uint64_t>(p));
+#pragma unroll
+  for (size_t i = 0; i < sizeof(T) / 4; ++i) tmp.w[i] = src[i];
+  return __builtin_bit_cast(T, tmp);
+}
+#endif
+
 }  // namespace cocktail

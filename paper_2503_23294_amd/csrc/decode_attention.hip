@@ -460,7 +460,7 @@ struct Stream {
         phase = 1;
       }
       if (u < u1) {
-        if (u >= gu0 + 2 * nblk) enter(kparams()->segs[s + 1], s + 1);
+        if (u >= gu0 + 2 * nblk) enter(load_record(kparams()->segs + s + 1), s + 1);
         const int us = u - gu0;
         const int nu = min(iter_units(cls), min(u1 - gu0, 2 * nblk) - us);
         if (nu <= 0) {   // cannot happen with a plan written by cocktail_plan; guarantees termination
@@ -488,10 +488,10 @@ struct Stream {
           return d;
         }
         kparams_t kp = kparams();
-        const PoolSeg& ps = kp->psegs[pseg0 + pi];
+        const PoolSeg ps = load_record(kp->psegs + pseg0 + pi);
         const int seg = uni(ps.seg);
         p_unit0 = uni(ps.unit0), p_nunits = uni(ps.nunits), p_gran0 = uni(ps.gran0), p_slot0 = uni(ps.slot0);
-        if (seg != s) enter(kp->segs[seg], seg);
+        if (seg != s) enter(load_record(kp->segs + seg), seg);
         const int j = iter_units(cls);
         p_gran1 = p_gran0 + (p_nunits + j - 1) / j;
       }
@@ -666,7 +666,7 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
     return;
   }
   Stream sm;
-  sm.init(kparams()->recs[blockIdx.x]);
+  sm.init(load_record(kparams()->recs + blockIdx.x));
   Piece cur = sm.next(lane);
   while (cur.nu > 0) {
     if (cur.cls == 0) {
@@ -680,7 +680,7 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
   // pool parts this worker never entered still own a partial slot: fill it with the neutral state
   for (int i = 0; i < sm.nps; ++i) {
     if ((sm.used >> i) & 1u) continue;
-    write_neutral(uni(kparams()->psegs[sm.pseg0 + i].slot0) + sm.rank, r, lane);
+    write_neutral(load_record(kparams()->psegs + sm.pseg0 + i).slot0 + sm.rank, r, lane);
   }
 #ifdef COCKTAIL_TRACE
   if (threadIdx.x == 0) {

@@ -56,12 +56,9 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   const int which = blockIdx.y;  // 0 = K, 1 = V
   // everything about this block comes from one record; only blocks whose rows are not consecutive
   // source tokens (a chunk boundary or the tail inside the block) look the rows up one by one
-  const RQItem& item = p.items[blockIdx.x];
-  const int cn = __builtin_amdgcn_readfirstlane(item.cls_nvalid);
-  const int cls = cn & 0xff, nvalid = cn >> 8;
-  const int t0 = __builtin_amdgcn_readfirstlane(item.t0);
-  const int j = __builtin_amdgcn_readfirstlane(item.j);
-  const int b = __builtin_amdgcn_readfirstlane(item.b), h = __builtin_amdgcn_readfirstlane(item.h);
+  const RQItem item = load_record(p.items + blockIdx.x);
+  const int cls = item.cls_nvalid & 0xff, nvalid = item.cls_nvalid >> 8;
+  const int t0 = item.t0, j = item.j, b = item.b, h = item.h;
   const _Float16* src;       // row 0 of the block (consecutive rows) or token 0 of the head (row by row)
   if (p.ragged) {
     src = p.src[which] + item.ragged_row * p.stride_t;
