@@ -62,7 +62,6 @@ constexpr int J16 = COCKTAIL_J16;  // FP16 units in flight per wave
 struct DecodeParams {
   const WorkerRec* recs;    // [num_workers]
   const Segment* segs;      // [num_segments]
-  const GroupRec* groups;   // [num_groups]
   const PoolSeg* psegs;     // [num_pool_segs]
   uint32_t* counters;       // [num_groups * kCounterStride] ticket counters, zero between calls
   const int32_t* bh_off;    // [B*Hkv + 1] (sequence, kv head) owns the partial ids bh_off[bh] .. bh_off[bh+1]-1
@@ -817,7 +816,6 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
   char* pd = static_cast<char*>(cache->plan_dev);
   p.recs = reinterpret_cast<const WorkerRec*>(pd + hd->off_worker_rec);
   p.segs = reinterpret_cast<const Segment*>(pd + hd->off_segments);
-  p.groups = reinterpret_cast<const GroupRec*>(pd + hd->off_group_rec);
   p.psegs = reinterpret_cast<const PoolSeg*>(pd + hd->off_pool_seg);
   p.counters = reinterpret_cast<uint32_t*>(pd + hd->off_counters);
   p.num_groups = hd->num_groups;

@@ -54,6 +54,39 @@ constexpr double kPairSpeed[3][3] = {{0.87, 1.0, 1.0}, {1.0, 1.17, 1.27}, {0.97,
 // A group only gets a pool if its range holds at least this many blocks per worker.
 constexpr int kMinBlocksPerWorkerForPool = 16;
 
+// The split parameters.  The defaults are what was measured best on MI355X; the environment variables
+// are tuning aids for experiments and are read once per cocktail_plan call.
+struct Tuning {
+  int64_t weight[3] = {kCostWeightInt2, kCostWeightInt4, kCostWeightFp16};   // COCKTAIL_COST_WEIGHTS="a,b,c"
+  int pool_percent = kPoolPercent;      // COCKTAIL_POOL_PERCENT   0..100
+  int group_workers = kGroupWorkers;    // COCKTAIL_GROUP_WORKERS  1..1024
+  bool pair_speed = true;               // COCKTAIL_PAIR_SPEED     0 | 1
+  int layout = kLayout;                 // COCKTAIL_LAYOUT         0 | 1
+  int pair_mode = kPairMode;            // COCKTAIL_PAIR_MODE      0 | 2 | 3
+};
+
+static Tuning read_tuning() {
+  Tuning t;
+  if (const char* e = std::getenv("COCKTAIL_COST_WEIGHTS")) {
+    long a = 0, b = 0, c = 0;
+    if (std::sscanf(e, "%ld,%ld,%ld", &a, &b, &c) == 3 && a > 0 && b > 0 && c > 0) t.weight[0] = a, t.weight[1] = b, t.weight[2] = c;
+  }
+  auto int_knob = [](const char* name, int lo, int hi, int& out) {
+    if (const char* e = std::getenv(name)) {
+      const int v = std::atoi(e);
+      if (v >= lo && v <= hi) out = v;
+    }
+  };
+  int ps = 1;
+  int_knob("COCKTAIL_POOL_PERCENT", 0, 100, t.pool_percent);
+  int_knob("COCKTAIL_GROUP_WORKERS", 1, 1024, t.group_workers);
+  int_knob("COCKTAIL_PAIR_SPEED", 0, 1, ps);
+  int_knob("COCKTAIL_LAYOUT", 0, 1, t.layout);
+  int_knob("COCKTAIL_PAIR_MODE", 0, 3, t.pair_mode);
+  t.pair_speed = ps != 0;
+  return t;
+}
+
 static inline int32_t align16(int64_t x) { return static_cast<int32_t>((x + 15) & ~int64_t(15)); }
 
 }  // namespace cocktail
@@ -140,21 +173,10 @@ extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* 
   // Relative time per byte of the three classes in the decode kernel (1/64 units).  The FP16 class is
   // a pure stream; the quantised classes also keep the vector ALU busy, so a byte of them takes longer.
   // Measured on MI355X with all three classes running side by side.
-  int64_t weight[3] = {kCostWeightInt2, kCostWeightInt4, kCostWeightFp16};
-  if (const char* e = std::getenv("COCKTAIL_COST_WEIGHTS")) {   // tuning aid: "w2,w4,w16"
-    long a = 0, b2 = 0, c2 = 0;
-    if (std::sscanf(e, "%ld,%ld,%ld", &a, &b2, &c2) == 3 && a > 0 && b2 > 0 && c2 > 0) weight[0] = a, weight[1] = b2, weight[2] = c2;
-  }
-
-  int pool_percent = kPoolPercent, group_workers = kGroupWorkers;
-  if (const char* e = std::getenv("COCKTAIL_POOL_PERCENT")) {   // tuning aid
-    const int v = std::atoi(e);
-    if (v >= 0 && v <= 100) pool_percent = v;
-  }
-  if (const char* e = std::getenv("COCKTAIL_GROUP_WORKERS")) {   // tuning aid
-    const int v = std::atoi(e);
-    if (v >= 1 && v <= 1024) group_workers = v;
-  }
+  const Tuning tune = read_tuning();
+  const int64_t* weight = tune.weight;
+  int pool_percent = tune.pool_percent;
+  const int group_workers = tune.group_workers;
   const int rep = shape->num_q_heads / Hkv;
   // the query heads of a kv head run as waves of one workgroup on the same blocks; a pool would need a
   // ticket shared by those waves, so grouped-query shapes keep the purely static split
@@ -185,10 +207,8 @@ extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* 
   //             group works on one class (two where it straddles a class boundary);
   //   layout 1: every group receives the same share of every class (FP16 stripe, then INT2, then INT4).
   const int NGR = (P + group_workers - 1) / group_workers;
-  bool pair_speed_on = true;
-  if (const char* e = std::getenv("COCKTAIL_PAIR_SPEED")) pair_speed_on = std::atoi(e) != 0;   // tuning aid
-  int layout = kLayout;
-  if (const char* e = std::getenv("COCKTAIL_LAYOUT")) layout = std::atoi(e) != 0;   // tuning aid
+  const bool pair_speed_on = tune.pair_speed;
+  const int layout = tune.layout;
   const int class_order[3] = {layout ? 2 : 0, layout ? 0 : 1, layout ? 1 : 2};
   std::vector<int64_t> cut[3];
   {
@@ -542,11 +562,12 @@ extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* 
     // Which workgroup id runs which range.  Workgroup ids are handed to the compute units in order
     // (round-robin over the XCDs), and when P fills the chip twice, workgroup i shares a SIMD with
     // workgroup i + P/2, which was dispatched later and loses every issue arbitration against it.
-    // Rank r of group j therefore becomes workgroup (r odd ? P/2 : 0) + j*k/2 + (r/2 + j) mod (k/2):
-    // every group is half early and half late workgroups, SIMD mates are neighbouring ranks of one
-    // group (same class, same pool), and a rank does not always land on the same XCD.
-    int pair_mode = kPairMode;
-    if (const char* e = std::getenv("COCKTAIL_PAIR_MODE")) pair_mode = std::atoi(e);   // tuning aid
+    //   mode 0 (default): range w runs as workgroup w.  With the class-major layout the INT2 ranges
+    //           get INT4 / FP16 ranges as SIMD mates, the mix that keeps both the vector ALU and the
+    //           memory pipeline busy.
+    //   mode 2: rank r of group j becomes workgroup (r odd ? P/2 : 0) + j*k/2 + (r/2 + j) mod (k/2):
+    //           SIMD mates are neighbouring ranks of one group.  Mode 3: mates are ranks r and r + k/2.
+    const int pair_mode = tune.pair_mode;
     const bool spread = pair_mode >= 2 && group_workers % 2 == 0 && P % group_workers == 0;
     for (int w = 0; w < P; ++w) {
       int id = w;
