@@ -337,6 +337,16 @@ def test_stream_read_probe_reads_what_it_reports_and_rejects_small_buffers():
     assert e.value.code == -3
 
 
+def test_one_million_token_context():
+    """A single very long sequence: block offsets inside one (sequence, head, class) run reach hundreds of
+    megabytes, and one head's partials come from every worker."""
+    w = workloads.small("million", 1, 2, 1, [(1 << 20) + 37], 1024, 64, mix=(0.3, 0.3, 0.4), seed_offset=123)
+    _announce(w.name)
+    c = Case(w)
+    worst = c.check_all()
+    _announce(f"{w.name} worst rel err {worst:.2e}")
+
+
 # ---- full-size configurations, launch configuration of the bench, sampled heads ----------------
 def _sample_heads(w, n, seed):
     rng = np.random.default_rng(seed)
