@@ -337,6 +337,15 @@ def test_stream_read_probe_reads_what_it_reports_and_rejects_small_buffers():
     assert e.value.code == -3
 
 
+@pytest.mark.parametrize("chunk", [8, 16, 32, 64, 128, 256])
+def test_chunk_sizes_of_the_papers_sweep(chunk):
+    """The chunk sizes the paper sweeps (Table III); 32 is its default."""
+    w = workloads.small(f"chunk{chunk}", 2, 4, 4, [2048 + 3 * chunk + 5, 1024 + chunk // 2], chunk, 32,
+                        mix=(0.1, 0.3, 0.6), seed_offset=300 + chunk)
+    _announce(w.name)
+    Case(w, workers=24).check_all()
+
+
 def test_one_million_token_context():
     """A single very long sequence: block offsets inside one (sequence, head, class) run reach hundreds of
     megabytes, and one head's partials come from every worker."""
