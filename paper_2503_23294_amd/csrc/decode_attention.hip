@@ -386,9 +386,7 @@ struct Piece {
   int cls;
   int fresh;       // 1 = the worker's first piece in this segment: a new partial state starts here
   int pid;         // partial id of that state (meaningful when fresh)
-  int blk0, nblk;  // blocks of the segment inside the class buffer
-  int qrow;        // b * Hq + h * rep: query row of the first query head of the segment's kv head
-};
+};                 // the segment it lies in is the stream's current one (blk0, nblk, qrow there)
 
 __device__ __forceinline__ int iter_units(int cls) { return cls == 0 ? J2 : cls == 1 ? J4 : J16; }
 
@@ -443,14 +441,14 @@ struct Stream {
   __device__ __forceinline__ void fill(Piece& d, int us, int nu) {
     d.nu = nu, d.us = us;
     d.valid = max(0, min(ntok - us * UT, nu * UT));
-    d.cls = cls, d.blk0 = blk0, d.nblk = nblk, d.qrow = qrow;
+    d.cls = cls;
     d.fresh = s != last_seg;
     last_seg = s;
   }
 
   __device__ __forceinline__ Piece next(int lane) {
     Piece d;
-    d.nu = 0, d.us = 0, d.valid = 0, d.cls = -1, d.fresh = 0, d.pid = 0, d.blk0 = 0, d.nblk = 0, d.qrow = 0;
+    d.nu = 0, d.us = 0, d.valid = 0, d.cls = -1, d.fresh = 0, d.pid = 0;
     if (phase <= 1) {
       // ask for the first tickets a few iterations before the own range runs out
       if (phase == 0 && ngran > 0 && u1 - u <= 3 * iter_units(cls)) {
@@ -563,23 +561,24 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
   float qsum[NGH];
   typename CLS::Stage ks[J], vs[J];
   int pid = cur.pid;
-  rsrc_t krs = make_rsrc(kbase + int64_t(cur.blk0) * CLS::BLOCKB, uint32_t(cur.nblk) * CLS::BLOCKB);
-  rsrc_t vrs = make_rsrc(vbase + int64_t(cur.blk0) * CLS::BLOCKB, uint32_t(cur.nblk) * CLS::BLOCKB);
+  // `cur` is the piece the stream produced last, so the stream's segment fields describe it
+  rsrc_t krs = make_rsrc(kbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
+  rsrc_t vrs = make_rsrc(vbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
   int ru = cur.us, rn = cur.nu;   // what the stages were (re)filled with last
 #pragma unroll
   for (int jj = 0; jj < J; ++jj) CLS::load(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
 #pragma unroll
   for (int jj = 0; jj < J; ++jj) CLS::load(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
   sched_fence();
-  begin_state<NGH, GL>(cur.qrow + r, h, st, q, qsum);   // the query arrives while the first units are on their way
+  begin_state<NGH, GL>(sm.qrow + r, h, st, q, qsum);   // the query arrives while the first units are on their way
   int valid = cur.valid;
   Piece nxt = sm.next(lane);
 #pragma unroll 1
   while (true) {
     const bool more = nxt.nu > 0 && nxt.cls == CID;
     if (more) {
-      krs = make_rsrc(kbase + int64_t(nxt.blk0) * CLS::BLOCKB, uint32_t(nxt.nblk) * CLS::BLOCKB);
-      vrs = make_rsrc(vbase + int64_t(nxt.blk0) * CLS::BLOCKB, uint32_t(nxt.nblk) * CLS::BLOCKB);
+      krs = make_rsrc(kbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
+      vrs = make_rsrc(vbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
       ru = nxt.us, rn = nxt.nu;
     }
     float s[J], p[J];
@@ -607,7 +606,7 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
     if (!more) break;
     if (nxt.fresh) {
       pid = nxt.pid;
-      begin_state<NGH, GL>(nxt.qrow + r, h, st, q, qsum);
+      begin_state<NGH, GL>(sm.qrow + r, h, st, q, qsum);
     }
     valid = nxt.valid;
     nxt = sm.next(lane);
