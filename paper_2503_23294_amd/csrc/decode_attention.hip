@@ -678,7 +678,8 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
   // pool parts this worker never entered still own a partial slot: fill it with the neutral state
   for (int i = 0; i < sm.nps; ++i) {
     if ((sm.used >> i) & 1u) continue;
-    write_neutral(load_record(kparams()->psegs + sm.pseg0 + i).slot0 + sm.rank, r, lane);
+    const PoolSeg ps = load_record(kparams()->psegs + sm.pseg0 + i);
+    if (sm.rank < ps.nslots) write_neutral(ps.slot0 + sm.rank, r, lane);
   }
 #ifdef COCKTAIL_TRACE
   if (threadIdx.x == 0) {

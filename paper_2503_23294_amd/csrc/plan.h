@@ -62,8 +62,10 @@ struct PoolSeg {
   int32_t unit0;             // first unit, counted from the start of the segment
   int32_t nunits;
   int32_t gran0;             // first ticket of this part
-  int32_t slot0;             // partial id of rank 0; rank r of the group writes slot0 + r
-  int32_t pad[3];
+  int32_t slot0;             // partial id of rank 0; rank r < nslots of the group writes slot0 + r
+  int32_t nslots;            // ranks that can start a partial state here: those whose own range ends in an
+                             // earlier segment (the others arrive with the state of this segment)
+  int32_t pad[2];
 };
 static_assert(sizeof(PoolSeg) == 32, "PoolSeg layout");
 

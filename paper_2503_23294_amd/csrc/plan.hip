@@ -411,8 +411,21 @@ extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* 
     }
   }
   for (int sidx = 0; sidx < S; ++sidx) bh_off[bh_of(segs[sidx]) + 1] += own_cnt[sidx];
-  for (int g = 0; g < NG; ++g)
-    for (int i = 0; i < groups[g].nps; ++i) bh_off[bh_of(segs[psegs[groups[g].pseg0 + i].seg]) + 1] += groups[g].nworkers;
+  // A pool part needs a partial slot for every rank that can enter its segment from another one.  Own
+  // ranges and pool parts both ascend, so these are the leading ranks: those whose own range is empty or
+  // ends in an earlier segment.
+  for (int g = 0, w0 = 0; g < NG; w0 += groups[g].nworkers, ++g)
+    for (int i = 0; i < groups[g].nps; ++i) {
+      PoolSeg& ps = psegs[groups[g].pseg0 + i];
+      int n = 0;
+      for (int r = 0; r < groups[g].nworkers; ++r) {
+        const Item& it = items[w0 + r];
+        const bool ends_here = it.g0 < it.g1 && seg_of(it.g1 - 1, it.seg0) == ps.seg;
+        if (!ends_here) n = r + 1;
+      }
+      ps.nslots = n;
+      bh_off[bh_of(segs[ps.seg]) + 1] += n;
+    }
   if (append_capacity > 0)   // one more partial per (b, kv head): the appended tokens; it is the last of its range
     for (int i = 0; i < BH; ++i) ++bh_off[i + 1];
   for (int i = 0; i < BH; ++i) bh_off[i + 1] += bh_off[i];
@@ -427,7 +440,7 @@ extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* 
       for (int i = 0; i < groups[g].nps; ++i) {
         PoolSeg& ps = psegs[groups[g].pseg0 + i];
         ps.slot0 = cursor[bh_of(segs[ps.seg])];
-        cursor[bh_of(segs[ps.seg])] += groups[g].nworkers;
+        cursor[bh_of(segs[ps.seg])] += ps.nslots;
       }
     std::vector<int32_t> visitors(S, 0);
     for (int w = 0; w < P; ++w) {

@@ -143,6 +143,7 @@ def _check_work_split(plan, w, workers, seed=0):
                 assert 0 < nu and us + nu <= 2 * nblk and seg >= last_seg
                 if seg != last_seg:
                     slot = slot0 + r
+                    assert r < psegs[pseg0 + pi, 5], "a rank that can enter this part from outside has a slot"
                     assert slot not in pid_owner
                     pid_owner[slot] = (cls, bh, 1)
                     used.add(pi)
@@ -150,7 +151,7 @@ def _check_work_split(plan, w, workers, seed=0):
                 seen[2 * gblk0 + us:2 * gblk0 + us + nu] += 1
                 pool_cost += nu * h["block_bytes"][cls]
             for pi in range(nps):                            # slots the worker fills with the neutral state
-                if pi not in used:
+                if pi not in used and r < psegs[pseg0 + pi, 5]:
                     seg, slot0 = psegs[pseg0 + pi, 0], psegs[pseg0 + pi, 4]
                     assert slot0 + r not in pid_owner
                     pid_owner[slot0 + r] = (segs[seg, 2], segs[seg, 0] * w.num_kv_heads + segs[seg, 1], 1)
