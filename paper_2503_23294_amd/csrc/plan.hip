@@ -41,7 +41,7 @@ int check_shape(const cocktail_shape* s) {
   return COCKTAIL_OK;
 }
 
-constexpr int64_t kCostWeightInt2 = 115, kCostWeightInt4 = 130, kCostWeightFp16 = 54;
+constexpr int64_t kCostWeightInt2 = 1150, kCostWeightInt4 = 1300, kCostWeightFp16 = 530;
 // Workers per group and the share of a group's cost that goes into its shared pool.
 constexpr int kGroupWorkers = 8;
 constexpr int kPoolPercent = 25;
