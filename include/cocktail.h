@@ -138,16 +138,22 @@ int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_lens, const ui
                   int32_t num_workers, cocktail_sizes* sizes, void* plan_host, size_t plan_capacity,
                   int32_t* class_tokens, int32_t* perm);
 
-/*
- * cocktail_plan with room for generated tokens.  The paper keeps the K/V of the tokens produced during
- * decoding in FP16 behind the context (Sec. III-A); `append_capacity` (>= 0) is the number of such
- * tokens per sequence the cache can take.  They live in two extra buffers (cocktail_cache::k_app,
- * v_app; sizes->append_bytes each): per (sequence, kv head) ceil(append_capacity / 64) blocks in the
- * block layout of the FP16 class, ordered (b, h, block).  cocktail_plan is this call with capacity 0.
- */
-int cocktail_plan_append(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
-                         int32_t num_workers, int32_t append_capacity, cocktail_sizes* sizes, void* plan_host,
-                         size_t plan_capacity, int32_t* class_tokens, int32_t* perm);
+/* Options of cocktail_plan_ex; zero-initialise, then set what is needed. */
+typedef struct cocktail_plan_options {
+  int32_t append_capacity; /* >= 0: generated tokens per sequence the cache can take (Sec. III-A keeps their K/V
+                              in FP16 behind the context).  They live in two extra buffers
+                              (cocktail_cache::k_app, v_app; sizes->append_bytes each): per (sequence, kv head)
+                              ceil(append_capacity / 64) blocks in the block layout of the FP16 class, ordered
+                              (b, h, block).                                                                  */
+  int32_t reproducible;    /* != 0: purely static split of the decode work (no shared pools): calls on the same
+                              inputs then agree bit for bit, at some cost in speed                            */
+  int32_t reserved[6];     /* must be zero                                                                    */
+} cocktail_plan_options;
+
+/* cocktail_plan with options (NULL = defaults = cocktail_plan). */
+int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
+                     int32_t num_workers, const cocktail_plan_options* options, cocktail_sizes* sizes,
+                     void* plan_host, size_t plan_capacity, int32_t* class_tokens, int32_t* perm);
 
 /* Source layouts accepted by cocktail_reorder_quantize (element = one fp16). */
 #define COCKTAIL_SRC_STRIDED 0 /* element (b,h,t,d) at b*stride_b + h*stride_h + t*stride_t + d        */
@@ -185,7 +191,8 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  * on one stream never do), and a plan_dev whose call was aborted has to be
  * re-uploaded.  Which worker takes which pool piece differs from call to call, so
  * two calls on the same inputs agree to fp32 summation order, not bit for bit
- * (shapes with Hq > Hkv use no pools and are reproducible bit for bit).
+ * (shapes with Hq > Hkv use no pools and are reproducible bit for bit, and so is any plan made with
+ * cocktail_plan_options::reproducible).
  *
  *   cache      num_appended tokens of the append buffers are attended to after the context
  *   q          DEVICE fp16 [B][Hq][D], 16-byte aligned

@@ -34,6 +34,10 @@ class Sizes(C.Structure):
                 ("num_segments", C.c_int32), ("append_capacity", C.c_int32), ("append_bytes", C.c_int64)]
 
 
+class PlanOptions(C.Structure):
+    _fields_ = [("append_capacity", C.c_int32), ("reproducible", C.c_int32), ("reserved", C.c_int32 * 6)]
+
+
 class Cache(C.Structure):
     _fields_ = [("k", C.c_void_p * 3), ("v", C.c_void_p * 3), ("plan_host", C.c_void_p), ("plan_dev", C.c_void_p),
                 ("k_app", C.c_void_p), ("v_app", C.c_void_p), ("num_appended", C.c_int32), ("reserved", C.c_int32)]
@@ -43,9 +47,9 @@ EXPORTS = {
     "cocktail_plan": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.c_int32,
                                 C.POINTER(Sizes), C.c_void_p, C.c_size_t, C.POINTER(C.c_int32),
                                 C.POINTER(C.c_int32)]),
-    "cocktail_plan_append": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.c_int32,
-                                       C.c_int32, C.POINTER(Sizes), C.c_void_p, C.c_size_t, C.POINTER(C.c_int32),
-                                       C.POINTER(C.c_int32)]),
+    "cocktail_plan_ex": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.c_int32,
+                                   C.POINTER(PlanOptions), C.POINTER(Sizes), C.c_void_p, C.c_size_t,
+                                   C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "cocktail_append_fp16": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.POINTER(Cache), C.c_int32,
                                        C.c_void_p]),
     "cocktail_chunk_bitwidths": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,

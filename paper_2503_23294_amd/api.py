@@ -40,10 +40,11 @@ def cocktail_default_workers(shape: Shape) -> int:
 
 
 def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[int], num_workers: int,
-                  append_capacity: int = 0) -> Plan:
-    """Host-only: Alg. 1's prefill partition plus cache layout and decode work split.
+                  append_capacity: int = 0, reproducible: bool = False) -> Plan:
+    """Host-only: Alg. 1's prefill partition plus cache layout and decode work split (cocktail_plan_ex).
 
-    append_capacity > 0 reserves room for that many generated tokens per sequence (cocktail_plan_append).
+    append_capacity > 0 reserves room for that many generated tokens per sequence; reproducible=True
+    asks for a purely static decode split (bitwise identical results from call to call).
     """
     sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
     cb = np.ascontiguousarray(np.asarray(chunk_bits, dtype=np.uint8).reshape(-1))
@@ -55,14 +56,15 @@ def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[in
     sizes = Sizes()
     slp = sl.ctypes.data_as(C.POINTER(C.c_int32))
     cbp = cb.ctypes.data_as(C.POINTER(C.c_uint8)) if cb.size else None
-    check(lib().cocktail_plan_append(C.byref(shape), slp, cbp, num_workers, append_capacity, C.byref(sizes), None, 0,
-                                     None, None))
+    opt = _lib.PlanOptions(int(append_capacity), int(bool(reproducible)))
+    check(lib().cocktail_plan_ex(C.byref(shape), slp, cbp, num_workers, C.byref(opt), C.byref(sizes), None, 0, None,
+                                 None))
     blob = np.zeros(int(sizes.plan_bytes), dtype=np.uint8)
     ct = np.zeros((shape.batch, 3), dtype=np.int32)
     perm = np.zeros(max(int(sizes.total_chunks), 1), dtype=np.int32)
-    check(lib().cocktail_plan_append(C.byref(shape), slp, cbp, num_workers, append_capacity, C.byref(sizes),
-                                     blob.ctypes.data, blob.size, ct.ctypes.data_as(C.POINTER(C.c_int32)),
-                                     perm.ctypes.data_as(C.POINTER(C.c_int32))))
+    check(lib().cocktail_plan_ex(C.byref(shape), slp, cbp, num_workers, C.byref(opt), C.byref(sizes),
+                                 blob.ctypes.data, blob.size, ct.ctypes.data_as(C.POINTER(C.c_int32)),
+                                 perm.ctypes.data_as(C.POINTER(C.c_int32))))
     return Plan(shape, sizes, blob, ct, perm[:int(sizes.total_chunks)], sl)
 
 

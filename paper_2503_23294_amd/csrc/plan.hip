@@ -99,14 +99,19 @@ extern "C" int cocktail_version(void) { return (0 << 16) | 4; }
 extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
                              int32_t num_workers, cocktail_sizes* sizes, void* plan_host, size_t plan_capacity,
                              int32_t* class_tokens, int32_t* perm) {
-  return cocktail_plan_append(shape, seq_lens, chunk_bits, num_workers, 0, sizes, plan_host, plan_capacity,
-                              class_tokens, perm);
+  return cocktail_plan_ex(shape, seq_lens, chunk_bits, num_workers, nullptr, sizes, plan_host, plan_capacity,
+                          class_tokens, perm);
 }
 
-extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
-                                    int32_t num_workers, int32_t append_capacity, cocktail_sizes* sizes,
-                                    void* plan_host, size_t plan_capacity, int32_t* class_tokens, int32_t* perm) {
+extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
+                                int32_t num_workers, const cocktail_plan_options* options, cocktail_sizes* sizes,
+                                void* plan_host, size_t plan_capacity, int32_t* class_tokens, int32_t* perm) {
   if (int rc = check_shape(shape)) return rc;
+  const int32_t append_capacity = options ? options->append_capacity : 0;
+  const bool reproducible = options && options->reproducible != 0;
+  if (options)
+    for (int32_t v : options->reserved)
+      if (v != 0) return fail(COCKTAIL_EINVAL, "cocktail_plan_options::reserved must be zero");
   if (append_capacity < 0 || append_capacity > (1 << 24))
     return fail(COCKTAIL_EINVAL, "append_capacity %d out of range [0, 2^24]", append_capacity);
   if (!seq_lens || !sizes) return fail(COCKTAIL_EINVAL, "seq_lens and sizes must not be NULL");
@@ -180,7 +185,7 @@ extern "C" int cocktail_plan_append(const cocktail_shape* shape, const int32_t* 
   const int rep = shape->num_q_heads / Hkv;
   // the query heads of a kv head run as waves of one workgroup on the same blocks; a pool would need a
   // ticket shared by those waves, so grouped-query shapes keep the purely static split
-  if (rep > 1) pool_percent = 0;
+  if (rep > 1 || reproducible) pool_percent = 0;
 
   // ---- physical runs of the class buffers: (class, b, h) order, each a contiguous run of blocks ----
   struct Run {

@@ -297,6 +297,29 @@ def test_chunk_level_quantization_search(alpha, beta):
     assert int(plan.sizes.total_chunks) == sum(num_chunks)
 
 
+def test_reproducible_plan_gives_bitwise_identical_results():
+    w = workloads.small("repro", 2, 2, 2, [6000, 3000], 64, 64, mix=(0.2, 0.4, 0.4), seed_offset=88)
+    _announce(w.name)
+    dev = _dev()
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = np.concatenate(workloads.chunk_bits(w))
+    k, v = workloads.kv_flat(w, 0)
+    k_dev, v_dev = torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)
+    q_dev = torch.from_numpy(workloads.query(w, 0)).to(dev)
+    outs = []
+    for reproducible in (True, False):
+        plan = ck.cocktail_plan(shape, w.seq_lens, bits, 8, reproducible=reproducible)
+        cache = ck.PackedCache(plan, dev)
+        ck.cocktail_reorder_quantize(cache, k_dev, v_dev, ragged=True)
+        runs = [ck.cocktail_decode_attention(cache, q_dev)[0].clone() for _ in range(4)]
+        torch.cuda.synchronize()
+        if reproducible:
+            assert all(torch.equal(runs[0], r) for r in runs[1:])
+        outs.append(runs[0].float())
+    # both splits compute the same attention
+    assert (outs[0] - outs[1]).abs().max() <= 2e-3 * outs[0].abs().max()
+
+
 def test_runs_on_a_side_stream():
     w = workloads.small("stream", 1, 2, 2, [512], 64, 32, seed_offset=4)
     _announce(w.name)

@@ -309,7 +309,17 @@ def test_append_capacity_sizes_and_validation():
     sizes = _lib.Sizes()
     lp = np.asarray(w.seq_lens, np.int32).ctypes.data_as(C.POINTER(C.c_int32))
     bp = bits.ctypes.data_as(C.POINTER(C.c_uint8))
-    assert L.cocktail_plan_append(C.byref(sh), lp, bp, 4, -1, C.byref(sizes), None, 0, None, None) == _lib.EINVAL
+    bad = _lib.PlanOptions(-1, 0)
+    assert L.cocktail_plan_ex(C.byref(sh), lp, bp, 4, C.byref(bad), C.byref(sizes), None, 0, None, None) == _lib.EINVAL
+    bad = _lib.PlanOptions(0, 0)
+    bad.reserved[2] = 1
+    assert L.cocktail_plan_ex(C.byref(sh), lp, bp, 4, C.byref(bad), C.byref(sizes), None, 0, None, None) == _lib.EINVAL
+    assert L.cocktail_plan_ex(C.byref(sh), lp, bp, 4, None, C.byref(sizes), None, 0, None, None) == _lib.OK
+    w4 = workloads.config(4)
+    sh4 = ck.make_shape(w4.batch, w4.num_q_heads, w4.num_kv_heads, w4.head_dim, w4.chunk_size, w4.group_size)
+    bits4 = np.concatenate(workloads.chunk_bits(w4))
+    assert _parse(ck.cocktail_plan(sh4, w4.seq_lens, bits4, 2048).blob)["pool_segs"] > 0
+    assert _parse(ck.cocktail_plan(sh4, w4.seq_lens, bits4, 2048, reproducible=True).blob)["pool_segs"] == 0
     cache = _lib.Cache()
     cache.plan_host = p0.blob.ctypes.data
     assert L.cocktail_append_fp16(C.byref(sh), 16, 16, C.byref(cache), 0, None) == _lib.EINVAL   # no append buffers
