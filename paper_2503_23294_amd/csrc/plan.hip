@@ -52,17 +52,23 @@ constexpr int kLayout = 0;
 // an INT4 wave next to an FP16 wave runs well ahead.
 constexpr double kPairSpeed[3][3] = {{0.87, 1.0, 1.0}, {1.0, 1.17, 1.27}, {0.97, 1.06, 0.9}};
 // A group only gets a pool if its range holds at least this many blocks per worker.
-constexpr int kMinBlocksPerWorkerForPool = 16;
+constexpr int kMinBlocksPerWorkerForPool = 4;
+// Groups with short ranges (below this many blocks per worker) put a larger share into the pool: there the
+// differences between compute units weigh more than the cost of the tickets.
+constexpr int kShortRangeBlocks = 16;
+constexpr int kShortRangePoolPercent = 40;
 
 // The split parameters.  The defaults are what was measured best on MI355X; the environment variables
 // are tuning aids for experiments and are read once per cocktail_plan call.
 struct Tuning {
   int64_t weight[3] = {kCostWeightInt2, kCostWeightInt4, kCostWeightFp16};   // COCKTAIL_COST_WEIGHTS="a,b,c"
   int pool_percent = kPoolPercent;      // COCKTAIL_POOL_PERCENT   0..100
+  bool pool_percent_set = false;        // the environment fixed the share for every group
   int group_workers = kGroupWorkers;    // COCKTAIL_GROUP_WORKERS  1..1024
   bool pair_speed = true;               // COCKTAIL_PAIR_SPEED     0 | 1
   int layout = kLayout;                 // COCKTAIL_LAYOUT         0 | 1
   int pair_mode = kPairMode;            // COCKTAIL_PAIR_MODE      0 | 2 | 3
+  int min_pool_blocks = kMinBlocksPerWorkerForPool;   // COCKTAIL_MIN_POOL_BLOCKS  1..4096
 };
 
 static Tuning read_tuning() {
@@ -79,10 +85,12 @@ static Tuning read_tuning() {
   };
   int ps = 1;
   int_knob("COCKTAIL_POOL_PERCENT", 0, 100, t.pool_percent);
+  t.pool_percent_set = std::getenv("COCKTAIL_POOL_PERCENT") != nullptr;
   int_knob("COCKTAIL_GROUP_WORKERS", 1, 1024, t.group_workers);
   int_knob("COCKTAIL_PAIR_SPEED", 0, 1, ps);
   int_knob("COCKTAIL_LAYOUT", 0, 1, t.layout);
   int_knob("COCKTAIL_PAIR_MODE", 0, 3, t.pair_mode);
+  int_knob("COCKTAIL_MIN_POOL_BLOCKS", 1, 4096, t.min_pool_blocks);
   t.pair_speed = ps != 0;
   return t;
 }
@@ -344,9 +352,11 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
       gr.pseg0 = static_cast<int32_t>(psegs.size());
       int32_t Gp = G1;
       int sGp = sG1;
-      if (pool_percent > 0 && int64_t(G1 - G0) >= int64_t(kMinBlocksPerWorkerForPool) * k) {
+      if (pool_percent > 0 && int64_t(G1 - G0) >= int64_t(tune.min_pool_blocks) * k) {
         int sc = sG0;
-        Gp = block_at(c1 - (c1 - c0) * pool_percent / 100, sc);
+        const int share = int64_t(G1 - G0) < int64_t(kShortRangeBlocks) * k && !tune.pool_percent_set
+                              ? kShortRangePoolPercent : pool_percent;
+        Gp = block_at(c1 - (c1 - c0) * share / 100, sc);
         sGp = sc;
         if (Gp < G0) Gp = G0, sGp = sG0;
         if (Gp > G1) Gp = G1, sGp = sG1;
