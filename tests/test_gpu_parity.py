@@ -297,6 +297,27 @@ def test_chunk_level_quantization_search(alpha, beta):
     assert int(plan.sizes.total_chunks) == sum(num_chunks)
 
 
+def test_many_calls_with_changing_ticket_order_all_agree():
+    """The hand-out order of the pool pieces changes from call to call; every call must still read each
+    token exactly once.  200 calls on a pooled shape against the oracle's answer."""
+    w = workloads.small("soak", 2, 4, 4, [9000, 5000], 128, 32, mix=(0.15, 0.35, 0.5), seed_offset=91)
+    _announce(w.name)
+    c = Case(w, workers=40)
+    assert _counters(c)[1] > 0
+    c.check_all()
+    ref = c.out_dev.float()
+    scale = ref.abs().amax(dim=2, keepdim=True)
+    worst = 0.0
+    for i in range(200):
+        out, _ = ck.cocktail_decode_attention(c.cache, c.q_dev)
+        err = ((out.float() - ref).abs() / scale).max().item()
+        worst = max(worst, err)
+        assert err <= 1e-3, f"call {i}: deviates from the first call by {err:.3e}"
+    torch.cuda.synchronize()
+    assert (_counters(c)[0] == 0).all()
+    _announce(f"{w.name}: largest deviation between calls {worst:.2e}")
+
+
 def test_reproducible_plan_gives_bitwise_identical_results():
     w = workloads.small("repro", 2, 2, 2, [6000, 3000], 64, 64, mix=(0.2, 0.4, 0.4), seed_offset=88)
     _announce(w.name)
