@@ -34,6 +34,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <cstdlib>
 
 #include "common.h"
 #include "plan.h"
@@ -99,8 +100,15 @@ typedef __amdgpu_buffer_rsrc_t rsrc_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const char* base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, bytes, 0x00020000);
 }
+// Cache policy of the K/V loads.  Every byte of a large cache is read exactly once per call, so the loads
+// are marked non-temporal (they do not displace anything in the L2 and the memory-side cache, which on
+// MI355X is worth 10 % of HBM throughput); grouped-query shapes, whose waves re-read each other's lines
+// from the L2, and small caches that stay resident between calls use the default policy.
+constexpr int kAuxDefault = 0, kAuxNonTemporal = 2;
+constexpr int64_t kNonTemporalMinBytes = int64_t(64) << 20;   // packed K+V bytes of one call
+template <int AUX>
 __device__ __forceinline__ u32x4 load16(rsrc_t rs, uint32_t voff, uint32_t soff) {
-  return __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0);
+  return __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, AUX);
 }
 
 __device__ __forceinline__ float dot2(uint32_t qpair, uint32_t kv, float acc) {
@@ -172,17 +180,18 @@ struct QuantClass {
   }
 
   // unit u of the run = tokens [32u, 32u+32): block u/2, first or second half of its token slots
+  template <int AUX>
   __device__ static __forceinline__ void load(Stage& s, rsrc_t rs, int u, uint32_t vc, uint32_t vm) {
     const uint32_t boff = uint32_t(u >> 1) * BLOCKB;
     const uint32_t sub = uint32_t(u & 1);
 #pragma unroll
-    for (int p = 0; p < PH; ++p) s.pc[p] = load16(rs, vc, boff + sub * (UT * 16) + p * (kTB * 16));
+    for (int p = 0; p < PH; ++p) s.pc[p] = load16<AUX>(rs, vc, boff + sub * (UT * 16) + p * (kTB * 16));
     const uint32_t moff = boff + kTB * ROWB + sub * (UT * 4 * NG);
     if constexpr (NGH == 2) {
-      const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, vm, moff, 0);
+      const u32x2 t = __builtin_amdgcn_raw_buffer_load_b64(rs, vm, moff, AUX);
       s.meta[0] = t.x, s.meta[1] = t.y;
     } else {
-      s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, vm, moff, 0);
+      s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, vm, moff, AUX);
     }
   }
 
@@ -274,10 +283,11 @@ struct HalfClass {
   __device__ static __forceinline__ uint32_t code_voff(int t, int h) { return (PH * h * kTB + t) * 16u; }
   __device__ static __forceinline__ uint32_t meta_voff(int, int) { return 0; }
 
+  template <int AUX>
   __device__ static __forceinline__ void load(Stage& s, rsrc_t rs, int u, uint32_t vc, uint32_t) {
     const uint32_t boff = uint32_t(u >> 1) * BLOCKB + uint32_t(u & 1) * (UT * 16);
 #pragma unroll
-    for (int p = 0; p < PH; ++p) s.pc[p] = load16(rs, vc, boff + p * (kTB * 16));
+    for (int p = 0; p < PH; ++p) s.pc[p] = load16<AUX>(rs, vc, boff + p * (kTB * 16));
   }
 
   __device__ static __forceinline__ float half_logit(const Stage& s, const uint32_t (&q)[DH / 2],
@@ -544,7 +554,7 @@ __device__ __forceinline__ void begin_state(int qrow, int h, LaneState<NGH>& st,
 // the last piece of the class the refill simply repeats the previous one (cache hits), so the loop
 // body has no branches around the loads.  The accumulators live and die inside this function, one
 // instance per class.
-template <class CLS, int CID, int G>
+template <class CLS, int CID, int G, int AUX>
 __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, int r, int lane, bool app = false) {
   constexpr int NG = D / G;
   constexpr int NGH = NG >= 2 ? NG / 2 : 1;
@@ -566,9 +576,9 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
   rsrc_t vrs = make_rsrc(vbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
   int ru = cur.us, rn = cur.nu;   // what the stages were (re)filled with last
 #pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::load(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
+  for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
 #pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::load(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
+  for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
   sched_fence();
   begin_state<NGH, GL>(sm.qrow + r, h, st, q, qsum);   // the query arrives while the first units are on their way
   int valid = cur.valid;
@@ -586,7 +596,7 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
     for (int jj = 0; jj < J; ++jj) {
       s[jj] = CLS::half_logit(ks[jj], q, qsum);
       sched_fence();
-      CLS::load(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
+      CLS::template load<AUX>(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
       sched_fence();
     }
 #pragma unroll
@@ -599,7 +609,7 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
     for (int jj = 0; jj < J; ++jj) {
       CLS::accumulate(vs[jj], p[jj], st);
       sched_fence();
-      CLS::load(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
+      CLS::template load<AUX>(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
       sched_fence();
     }
     if (!more || nxt.fresh) flush_partial<NGH, GL>(st, red, pid, r, lane);
@@ -626,7 +636,7 @@ __device__ __forceinline__ void write_neutral(int slot, int r, int lane) {
 // Workgroups behind the regular workers: workgroup num_workers + bh attends to the tokens appended to
 // (sequence, kv head) bh during decoding (Sec. III-A), an FP16 run of num_appended tokens in the
 // append buffers, and writes the last partial of bh's range.
-template <int G>
+template <int G, int AUX>
 __device__ __forceinline__ void appended_tokens(int bh, float* red, int r, int lane) {
   kparams_t kp = kparams();
   const int n = kp->num_appended;
@@ -647,11 +657,11 @@ __device__ __forceinline__ void appended_tokens(int bh, float* red, int r, int l
   sm.tk0 = sm.tk1 = 0, sm.used = 0;
   sm.phase = 0;
   Piece cur = sm.next(lane);
-  if (cur.nu > 0) run_class<HalfClass<G>, 2, G>(sm, cur, red, r, lane, true);
+  if (cur.nu > 0) run_class<HalfClass<G>, 2, G, AUX>(sm, cur, red, r, lane, true);
 }
 
 // One workgroup per worker; wave r of the workgroup serves query head r of every kv head it meets.
-template <int G>
+template <int G, int AUX>
 __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
   extern __shared__ float red[];   // [rep][64][17] reduction tiles
   const int lane = threadIdx.x & 63;
@@ -660,7 +670,7 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
   const uint64_t t_start = __builtin_amdgcn_s_memrealtime();
 #endif
   if (int(blockIdx.x) >= kparams()->num_workers) {
-    appended_tokens<G>(int(blockIdx.x) - kparams()->num_workers, red, r, lane);
+    appended_tokens<G, AUX>(int(blockIdx.x) - kparams()->num_workers, red, r, lane);
     return;
   }
   Stream sm;
@@ -668,11 +678,11 @@ __global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
   Piece cur = sm.next(lane);
   while (cur.nu > 0) {
     if (cur.cls == 0) {
-      run_class<QuantClass<2, G>, 0, G>(sm, cur, red, r, lane);
+      run_class<QuantClass<2, G>, 0, G, AUX>(sm, cur, red, r, lane);
     } else if (cur.cls == 1) {
-      run_class<QuantClass<4, G>, 1, G>(sm, cur, red, r, lane);
+      run_class<QuantClass<4, G>, 1, G, AUX>(sm, cur, red, r, lane);
     } else {
-      run_class<HalfClass<G>, 2, G>(sm, cur, red, r, lane);
+      run_class<HalfClass<G>, 2, G, AUX>(sm, cur, red, r, lane);
     }
   }
   // pool parts this worker never entered still own a partial slot: fill it with the neutral state
@@ -858,11 +868,20 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
   if (hd->total_gblocks > 0 || app_groups > 0) {
     const dim3 grid(hd->num_workers + app_groups, 1, 1), block(64 * hd->rep, 1, 1);
     const size_t lds = size_t(hd->rep) * 64 * 17 * sizeof(float);
+    // non-temporal K/V loads when nothing is read twice: one wave per workgroup, and a cache large enough
+    // that it cannot stay in the memory-side cache from one call to the next
+    static const int nt_override = [] {   // tuning aid, read once: COCKTAIL_NON_TEMPORAL=0 | 1
+      const char* e = std::getenv("COCKTAIL_NON_TEMPORAL");
+      return e ? (std::atoi(e) != 0 ? 1 : 0) : -1;
+    }();
+    const bool nt = nt_override >= 0 ? nt_override == 1 : (hd->rep == 1 && hd->packed_bytes >= kNonTemporalMinBytes);
+    void (*kern)(DecodeParams) = nullptr;
     switch (shape->group_size) {
-      case 32: hipLaunchKernelGGL(decode_attention_kernel<32>, grid, block, lds, st, p); break;
-      case 64: hipLaunchKernelGGL(decode_attention_kernel<64>, grid, block, lds, st, p); break;
-      default: hipLaunchKernelGGL(decode_attention_kernel<128>, grid, block, lds, st, p); break;
+      case 32: kern = nt ? decode_attention_kernel<32, kAuxNonTemporal> : decode_attention_kernel<32, kAuxDefault>; break;
+      case 64: kern = nt ? decode_attention_kernel<64, kAuxNonTemporal> : decode_attention_kernel<64, kAuxDefault>; break;
+      default: kern = nt ? decode_attention_kernel<128, kAuxNonTemporal> : decode_attention_kernel<128, kAuxDefault>; break;
     }
+    hipLaunchKernelGGL(kern, grid, block, lds, st, p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_attention launch failed: %s", hipGetErrorString(e));
   }

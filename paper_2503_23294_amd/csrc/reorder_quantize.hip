@@ -8,6 +8,11 @@
 #include "common.h"
 #include "plan.h"
 
+// The fp16 source is read once and the packed cache is written once: both bypass the caches
+// (non-temporal), which leaves them to the kernels that run next.
+#define RQ_LOAD(p) __builtin_nontemporal_load(p)
+#define RQ_STORE(v, p) __builtin_nontemporal_store(v, p)
+
 namespace cocktail {
 
 struct RQParams {
@@ -98,7 +103,7 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
           t = N * C + (r - chunk_tokens);   // Sec. III-A: tail tokens follow the FP16 chunks
         }
       }
-      raw = *reinterpret_cast<const u32x4*>(src + int64_t(t) * p.stride_t + seg * 8);
+      raw = RQ_LOAD(reinterpret_cast<const u32x4*>(src + int64_t(t) * p.stride_t + seg * 8));
     }
     if (cls == 2) {
       *reinterpret_cast<u32x4*>(lds + (seg * kTB + i) * 16) = raw;
@@ -153,7 +158,7 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   const int first = cls == 0 ? 0 : cls == 1 ? p.cls_end0 : p.cls_end1;   // first record of this class
   char* dst = p.dst[which][cls] + int64_t(int(blockIdx.x) - first) * bb;
   for (int o = tid * 16; o < bb; o += 256 * 16)
-    *reinterpret_cast<u32x4*>(dst + o) = *reinterpret_cast<const u32x4*>(lds + o);
+    RQ_STORE(*reinterpret_cast<const u32x4*>(lds + o), reinterpret_cast<u32x4*>(dst + o));
 }
 
 // Zeroes `n16` 16-byte words (the append buffers start out empty; rows that are never appended must

@@ -17,7 +17,7 @@ __global__ void __launch_bounds__(64) stream_read_kernel(const u32x4* __restrict
   for (size_t i = 0; i < vec_per_wave; i += 64 * kProbeUnroll) {
     u32x4 v[kProbeUnroll];
 #pragma unroll
-    for (int u = 0; u < kProbeUnroll; ++u) v[u] = p[i + u * 64];
+    for (int u = 0; u < kProbeUnroll; ++u) v[u] = __builtin_nontemporal_load(&p[i + u * 64]);   // read-once data
 #pragma unroll
     for (int u = 0; u < kProbeUnroll; ++u) acc ^= v[u];
   }
