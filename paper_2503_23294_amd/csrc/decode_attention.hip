@@ -550,9 +550,10 @@ __device__ __forceinline__ void begin_state(int qrow, int h, LaneState<NGH>& st,
 // J register stages hold the K units and J the V units of the piece being worked on; each stage is
 // refilled with the corresponding unit of the NEXT piece as soon as it has been consumed, so the
 // loads of a piece are in flight during the arithmetic of the piece before it, across segment and
-// pool boundaries alike.  A piece with fewer than J units repeats its last unit (masked), and after
-// the last piece of the class the refill simply repeats the previous one (cache hits), so the loop
-// body has no branches around the loads.  The accumulators live and die inside this function, one
+// pool boundaries alike.  A piece with fewer than J units leaves stages unused, and after the last
+// piece of the class nothing is left to fetch: those refills address the first unit past the segment,
+// which the buffer resource answers with zeros without touching memory, so the loop body has no
+// branches around the loads (the zeros are masked like padding).  The accumulators live and die inside this function, one
 // instance per class.
 template <class CLS, int CID, int G, int AUX>
 __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, int r, int lane, bool app = false) {
@@ -574,11 +575,12 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
   // `cur` is the piece the stream produced last, so the stream's segment fields describe it
   rsrc_t krs = make_rsrc(kbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
   rsrc_t vrs = make_rsrc(vbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
-  int ru = cur.us, rn = cur.nu;   // what the stages were (re)filled with last
+  int ru = cur.us, rn = cur.nu;   // the piece the stages are (re)filled with
+  int roob = 2 * sm.nblk;         // first unit past its segment: a load from there is out of range and costs nothing
 #pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
+  for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(ks[jj], krs, jj < rn ? ru + jj : roob, vc, vm);
 #pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
+  for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(vs[jj], vrs, jj < rn ? ru + jj : roob, vc, vm);
   sched_fence();
   begin_state<NGH, GL>(sm.qrow + r, h, st, q, qsum);   // the query arrives while the first units are on their way
   int valid = cur.valid;
@@ -589,14 +591,16 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
     if (more) {
       krs = make_rsrc(kbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
       vrs = make_rsrc(vbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
-      ru = nxt.us, rn = nxt.nu;
+      ru = nxt.us, rn = nxt.nu, roob = 2 * sm.nblk;
+    } else {
+      rn = 0;   // nothing follows in this class: every refill goes out of range
     }
     float s[J], p[J];
 #pragma unroll
     for (int jj = 0; jj < J; ++jj) {
       s[jj] = CLS::half_logit(ks[jj], q, qsum);
       sched_fence();
-      CLS::template load<AUX>(ks[jj], krs, ru + min(jj, rn - 1), vc, vm);
+      CLS::template load<AUX>(ks[jj], krs, jj < rn ? ru + jj : roob, vc, vm);
       sched_fence();
     }
 #pragma unroll
@@ -609,7 +613,7 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
     for (int jj = 0; jj < J; ++jj) {
       CLS::accumulate(vs[jj], p[jj], st);
       sched_fence();
-      CLS::template load<AUX>(vs[jj], vrs, ru + min(jj, rn - 1), vc, vm);
+      CLS::template load<AUX>(vs[jj], vrs, jj < rn ? ru + jj : roob, vc, vm);
       sched_fence();
     }
     if (!more || nxt.fresh) flush_partial<NGH, GL>(st, red, pid, r, lane);
