@@ -266,6 +266,19 @@ int cocktail_default_workers(const cocktail_shape* shape, int32_t* num_workers);
  */
 int cocktail_stream_read_probe(const void* buf, size_t bytes, void* sink, size_t* bytes_read, void* stream);
 
+/*
+ * Diagnostic, not a step of the method.  The quantizer (top of this file) is defined by IEEE binary32
+ * divisions; the kernel replaces them by shorter sequences that are exact on the operands that can
+ * occur.  This call checks that claim on the device for every such operand: all floats in [0, 131008]
+ * for (mx - mn) / 3 and / 15, and every positive finite fp16 value for 1 / scale.
+ *
+ *   mismatches  DEVICE uint64 [4] out, 16-byte aligned: operands on which the result differs from the
+ *               division, for / 3, / 15, 1 / scale; [3] is zero.  All zero on a correct device.
+ *
+ * Two kernel launches (about a millisecond).  Errors: EINVAL, EALIGN, EHIP.
+ */
+int cocktail_selftest_arithmetic(uint64_t* mismatches, void* stream);
+
 /* Message of the last failure on the calling thread ("" if none).  Static storage. */
 const char* cocktail_last_error(void);
 

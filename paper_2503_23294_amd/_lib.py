@@ -60,6 +60,7 @@ EXPORTS = {
                                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "cocktail_default_workers": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32)]),
     "cocktail_stream_read_probe": (C.c_int, [C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_size_t), C.c_void_p]),
+    "cocktail_selftest_arithmetic": (C.c_int, [C.c_void_p, C.c_void_p]),
     "cocktail_last_error": (C.c_char_p, []),
     "cocktail_version": (C.c_int, []),
 }

@@ -187,3 +187,10 @@ def cocktail_chunk_bitwidths(query_emb: torch.Tensor, chunk_emb: torch.Tensor, n
                                          scores.data_ptr() if total else None, bits.data_ptr() if total else None,
                                          _stream_ptr(stream)))
     return bits, scores
+
+
+def cocktail_selftest_arithmetic(device: torch.device, stream: Optional[torch.cuda.Stream] = None) -> List[int]:
+    """Runs the exhaustive check of the quantizer's division shortcuts; returns the three mismatch counts."""
+    out = torch.empty(4, dtype=torch.int64, device=device)
+    check(lib().cocktail_selftest_arithmetic(out.data_ptr(), _stream_ptr(stream)))
+    return [int(x) for x in out.cpu().tolist()[:3]]

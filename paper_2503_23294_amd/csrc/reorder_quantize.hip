@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include "common.h"
+#include "exact_div.h"
 #include "plan.h"
 
 // The fp16 source is read once and the packed cache is written once: both bypass the caches
@@ -33,7 +34,7 @@ __device__ __forceinline__ void quantize8(const float (&x)[8], float mn, float m
 #pragma clang fp contract(off)
   constexpr float qmax = float((1 << BITS) - 1);
   const float r = mx - mn;
-  const float s32 = r / qmax;
+  const float s32 = div_by_qmax<(1 << BITS) - 1>(r);   // == r / qmax, bit for bit (exact_div.h)
   scale_h = static_cast<_Float16>(s32);
   const float sc = static_cast<float>(scale_h);
   if (sc == 0.0f) {
@@ -41,7 +42,7 @@ __device__ __forceinline__ void quantize8(const float (&x)[8], float mn, float m
     for (int i = 0; i < 8; ++i) code[i] = 0;
     return;
   }
-  const float inv = 1.0f / sc;
+  const float inv = recip_of_fp16_value(sc);            // == 1.0f / sc, bit for bit (exact_div.h)
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const float d = x[i] - mn;
@@ -168,9 +169,46 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* __restrict__ p, s
   for (size_t i = size_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += size_t(gridDim.x) * 256) p[i] = z;
 }
 
+// Exhaustive check of exact_div.h against the IEEE divisions, over every operand the quantizer can see.
+__global__ __launch_bounds__(256) void selftest_div_kernel(unsigned long long* __restrict__ bad) {
+  unsigned long long n3 = 0, n15 = 0, nr = 0;
+  const uint64_t stride = uint64_t(gridDim.x) * 256;
+  // every non-negative float up to 131008 = 0x47FFE000
+  for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i <= 0x47FFE000ull; i += stride) {
+    const float r = __builtin_bit_cast(float, uint32_t(i));
+    const float a3 = r / 3.0f, b3 = div_by_qmax<3>(r), a15 = r / 15.0f, b15 = div_by_qmax<15>(r);
+    // the binary32 quotient and the fp16 scale made from it, as the quantizer makes it
+    n3 += __builtin_bit_cast(uint32_t, a3) != __builtin_bit_cast(uint32_t, b3) ||
+          __builtin_bit_cast(uint16_t, static_cast<_Float16>(a3)) != __builtin_bit_cast(uint16_t, static_cast<_Float16>(b3));
+    n15 += __builtin_bit_cast(uint32_t, a15) != __builtin_bit_cast(uint32_t, b15) ||
+           __builtin_bit_cast(uint16_t, static_cast<_Float16>(a15)) != __builtin_bit_cast(uint16_t, static_cast<_Float16>(b15));
+  }
+  // every positive finite fp16 value
+  for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x + 1; i < 0x7C00u; i += stride) {
+    const float x = static_cast<float>(__builtin_bit_cast(_Float16, uint16_t(i)));
+    nr += __builtin_bit_cast(uint32_t, 1.0f / x) != __builtin_bit_cast(uint32_t, recip_of_fp16_value(x));
+  }
+  if (n3) atomicAdd(bad + 0, n3);
+  if (n15) atomicAdd(bad + 1, n15);
+  if (nr) atomicAdd(bad + 2, nr);
+}
+
 }  // namespace cocktail
 
 using namespace cocktail;
+
+extern "C" int cocktail_selftest_arithmetic(uint64_t* mismatches, void* stream) {
+  if (!mismatches) return fail(COCKTAIL_EINVAL, "mismatches is NULL");
+  if (reinterpret_cast<uintptr_t>(mismatches) & 7) return fail(COCKTAIL_EALIGN, "mismatches must be 8-byte aligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<u32x4*>(mismatches), size_t(2));
+  hipLaunchKernelGGL(selftest_div_kernel, dim3(4096), dim3(256), 0, st,
+                     reinterpret_cast<unsigned long long*>(mismatches));
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(COCKTAIL_EHIP, "selftest launch failed: %s", hipGetErrorString(e));
+  return COCKTAIL_OK;
+}
+
 
 extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, const void* v_src,
                                          int32_t src_layout, int64_t stride_b, int64_t stride_h,

@@ -341,6 +341,11 @@ def test_reproducible_plan_gives_bitwise_identical_results():
     assert (outs[0] - outs[1]).abs().max() <= 2e-3 * outs[0].abs().max()
 
 
+def test_quantizer_division_shortcuts_are_exact_on_every_operand():
+    """The kernel's replacements for (mx - mn) / qmax and 1 / scale against the IEEE divisions, exhaustively."""
+    assert ck.cocktail_selftest_arithmetic(_dev()) == [0, 0, 0]
+
+
 def test_runs_on_a_side_stream():
     w = workloads.small("stream", 1, 2, 2, [512], 64, 32, seed_offset=4)
     _announce(w.name)

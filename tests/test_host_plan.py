@@ -355,3 +355,5 @@ def test_chunk_bitwidths_validates_on_host():
     assert L.cocktail_chunk_bitwidths(1, 768, 10, 4096, 4096, None, 0.6, 0.1, 4096, 4096, None) == _lib.EINVAL
     assert L.cocktail_chunk_bitwidths(1, 768, 10, 4096, 4098, 4096, 0.6, 0.1, 4096, 4096, None) == _lib.EALIGN
     assert L.cocktail_chunk_bitwidths(1, 768, 0, 4096, 4096, None, 0.6, 0.1, None, None, None) == _lib.OK   # nothing to do
+    assert L.cocktail_selftest_arithmetic(None, None) == _lib.EINVAL
+    assert L.cocktail_selftest_arithmetic(4, None) == _lib.EALIGN
