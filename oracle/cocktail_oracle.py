@@ -24,7 +24,8 @@ What it computes, in the paper's order:
                   kept in FP16 after the context; attention then runs over the
                   three context blocks followed by those rows.
   pack_* / unpack_*   the byte layout of the packed cache (an encoding this
-                  build defines; the paper is silent on it).
+                  build defines; the paper is silent on it).  V has a second form,
+                  "token quads" (pack_quad_blocks), for grouped-query shapes.
 
 Parity pins (tests/test_oracle_pins.py): all-FP16 equals textbook attention and
 torch's scaled_dot_product_attention; invariance to the chunk permutation
@@ -196,6 +197,71 @@ def _unpack_head_blocks(buf: np.ndarray, n: int, rb: int, mb: int):
     return codes, meta
 
 
+def pack_quad_blocks(vals: np.ndarray, bits: int, meta_bytes) -> np.ndarray:
+    """The "token quads" form of a V block (used when 2 to 4 query heads share a kv head).
+
+    vals: uint16 [n, D] codes (bits 2 or 4) or raw fp16 bit patterns (bits 16); D a multiple of 64.
+    Same block size and piece addressing as _pack_head_blocks, but a 16-byte piece no longer holds
+    one token: slot sl of piece p belongs to the token quad 4*(sl//4) .. +3 and to 16 channels.
+    With n = 16/bits values per half-word, token i of the block, channel c:
+        half  h = c // 64            lane of the quad  j = (c % 32) // 8
+        e     = 8 * ((c % 64) // 32) + c % 8          (the j-th lane's e-th channel, 0..15)
+        slot  sl = 4 * (i // 4) + j
+        word  w = 2 * (e // n) + (i % 4) // 2          (of the 4 * pieces/2 words of half h)
+        piece p = (pieces/2) * h + w // 4,  word of the piece = w % 4
+        the value sits in the low (i even) or high (i odd) half-word at bit (e % n) * bits.
+    So a word pairs two tokens of the quad for the same channels, and two consecutive words
+    cover all four.  The meta bytes (scale, zero per token and group) follow as in the row form."""
+    n, d = vals.shape
+    assert d % 64 == 0 and bits in (2, 4, 16)
+    tb = TOKENS_PER_BLOCK
+    nblk = (n + tb - 1) // tb
+    per = 16 // bits
+    rb = d * bits // 8
+    pieces = rb // 16
+    hw = np.zeros((nblk, pieces, tb, 4, 2), dtype=np.uint16)      # [block][piece][slot][word][half-word]
+    tok = np.arange(n)[:, None] + np.zeros((1, d), dtype=np.int64)
+    c = np.zeros((n, 1), dtype=np.int64) + np.arange(d)[None, :]
+    i = tok % tb
+    h = c // 64
+    j = (c % 32) // 8
+    e = 8 * ((c % 64) // 32) + c % 8
+    sl = 4 * (i // 4) + j
+    w = 2 * (e // per) + (i % 4) // 2
+    pc = (pieces // (d // 64)) * h + w // 4
+    shifted = (vals.astype(np.uint32) << ((e % per) * bits).astype(np.uint32)).astype(np.uint16)
+    np.add.at(hw, (tok // tb, pc, sl, w % 4, i % 2), shifted)      # disjoint bit fields: add = or
+    codes = hw.astype("<u2").view(np.uint8).reshape(nblk, tb * rb)
+    if meta_bytes is None:
+        return np.ascontiguousarray(codes)
+    mb = meta_bytes.shape[1]
+    mp = np.zeros((nblk * tb, mb), dtype=np.uint8)
+    mp[:n] = meta_bytes
+    return np.concatenate([codes, mp.reshape(nblk, tb * mb)], axis=1)
+
+
+def unpack_quad_blocks(buf: np.ndarray, n: int, d: int, bits: int, mb: int):
+    """Inverse of pack_quad_blocks: (uint16 [n, d] values, meta bytes or None)."""
+    tb = TOKENS_PER_BLOCK
+    nblk = buf.shape[0]
+    per = 16 // bits
+    rb = d * bits // 8
+    pieces = rb // 16
+    hw = np.ascontiguousarray(buf[:, :tb * rb]).view("<u2").reshape(nblk, pieces, tb, 4, 2)
+    out = np.zeros((n, d), dtype=np.uint16)
+    mask = (1 << bits) - 1
+    for t in range(n):
+        blk, i = divmod(t, tb)
+        for c in range(d):
+            e = 8 * ((c % 64) // 32) + c % 8
+            w = 2 * (e // per) + (i % 4) // 2
+            piece = (pieces // (d // 64)) * (c // 64) + w // 4
+            x = int(hw[blk, piece, 4 * (i // 4) + (c % 32) // 8, w % 4, i % 2])
+            out[t, c] = (x >> ((e % per) * bits)) & mask
+    meta = buf[:, tb * rb:].reshape(nblk * tb, mb)[:n] if mb else None
+    return out, meta
+
+
 @dataclass
 class ClassCache:
     """Logical content of one class for one sequence (all kv heads)."""
@@ -261,9 +327,9 @@ def append_tokens(cache: OracleCache, k_new: np.ndarray, v_new: np.ndarray) -> N
         cache.app_v[b] = np.concatenate([cache.app_v[b], v_new[b][:, None, :].astype(np.float16)], axis=1)
 
 
-def pack_append_buffer(cache: OracleCache, which: str, capacity: int) -> np.ndarray:
+def pack_append_buffer(cache: OracleCache, which: str, capacity: int, v_quads: bool = False) -> np.ndarray:
     """Byte image of the append buffer: per (sequence, kv head) ceil(capacity/64) FP16 blocks in the
-    block layout of the FP16 class; rows not appended yet are zero bytes."""
+    block layout of the FP16 class (V in token quads if v_quads); rows not appended yet are zero bytes."""
     nblk = (capacity + TOKENS_PER_BLOCK - 1) // TOKENS_PER_BLOCK
     rb = 2 * cache.head_dim
     parts = []
@@ -273,7 +339,10 @@ def pack_append_buffer(cache: OracleCache, which: str, capacity: int) -> np.ndar
             rows = np.zeros((nblk * TOKENS_PER_BLOCK, rb), dtype=np.uint8)
             n = src.shape[1]
             rows[:n] = np.ascontiguousarray(src[h]).view(np.uint8).reshape(n, rb)
-            parts.append(_pack_head_blocks(rows, None).reshape(-1))
+            if v_quads and which == "v":
+                parts.append(pack_quad_blocks(np.ascontiguousarray(rows).view("<u2"), 16, None).reshape(-1))
+            else:
+                parts.append(_pack_head_blocks(rows, None).reshape(-1))
     return np.concatenate(parts) if parts else np.zeros(0, dtype=np.uint8)
 
 
@@ -290,14 +359,27 @@ def _rows_and_meta(cc: ClassCache, which: str, h: int):
     return rows, np.ascontiguousarray(meta).view(np.uint8).reshape(cc.n_tokens, -1)
 
 
-def pack_class_buffer(cache: OracleCache, cls: int, which: str) -> np.ndarray:
-    """Bytes of the K (or V) device buffer of one class: blocks ordered by (sequence, kv head, block)."""
+def _values_and_meta(cc: ClassCache, h: int):
+    """V of head h as uint16 values per channel (codes, or fp16 bit patterns) and the meta bytes."""
+    if cc.bits == 16:
+        return np.ascontiguousarray(cc.v_raw[h]).view("<u2").reshape(cc.n_tokens, -1), None
+    meta = np.stack([cc.v_scale[h].astype("<f2"), cc.v_zero[h].astype("<f2")], axis=-1)
+    return cc.v_codes[h].astype(np.uint16), np.ascontiguousarray(meta).view(np.uint8).reshape(cc.n_tokens, -1)
+
+
+def pack_class_buffer(cache: OracleCache, cls: int, which: str, v_quads: bool = False) -> np.ndarray:
+    """Bytes of the K (or V) device buffer of one class: blocks ordered by (sequence, kv head, block).
+    v_quads: V is stored in the token-quad form (pack_quad_blocks); K is not affected."""
     parts = []
     for ccs in cache.seqs:
         cc = ccs[cls]
         if cc.n_tokens == 0:
             continue
         for h in range(cache.num_kv_heads):
+            if v_quads and which == "v":
+                vals, meta = _values_and_meta(cc, h)
+                parts.append(pack_quad_blocks(vals, cc.bits, meta).reshape(-1))
+                continue
             rows, meta = _rows_and_meta(cc, which, h)
             parts.append(_pack_head_blocks(rows, meta).reshape(-1))
     if not parts:

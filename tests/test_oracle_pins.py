@@ -463,3 +463,95 @@ def test_more_alpha_means_more_int2_and_more_beta_means_more_fp16():
     bits, _ = O.chunk_bitwidths(q[0], cs[0], 0.6, 0.1)                # the paper's defaults
     share = [(bits == v).mean() for v in (2, 4, 16)]
     assert share[0] > 0.5 and 0 < share[2] < 0.1                      # most chunks are irrelevant to the query
+
+
+# -- token-quad form of V (grouped-query shapes) --------------------------------------------
+def _quad_bytes_lane_by_lane(vals, bits, d):
+    """The token-quad block image built the way a wave reads it: for every 32-token unit, lane,
+    16-byte piece, word and half-word, which token and which channels end up there.  Pure loops."""
+    n = vals.shape[0]
+    nblk = (n + 63) // 64
+    per = 16 // bits                       # values per half-word
+    ph = (d * bits // 8) // 16 // (d // 64)  # pieces per lane (= per 64-channel half)
+    out = bytearray(nblk * 64 * d * bits // 8)
+    for blk in range(nblk):
+        for u in range(2):
+            for lane in range(64 * (d // 128) if d >= 128 else 32):
+                t, h = lane % 32, lane // 32
+                quad, j = t // 4, t % 4
+                for word in range(4 * ph):
+                    pair, tp = word // 2, word % 2
+                    for hf in range(2):
+                        tok = blk * 64 + 32 * u + 4 * quad + 2 * tp + hf
+                        x = 0
+                        for f in range(per):
+                            e = pair * per + f
+                            c = 64 * h + 32 * (e // 8) + 8 * j + e % 8
+                            if tok < n:
+                                x |= int(vals[tok, c]) << (f * bits)
+                        addr = blk * (64 * d * bits // 8) + ((ph * h + word // 4) * 64 + 32 * u + t) * 16 + (word % 4) * 4 + 2 * hf
+                        out[addr] = x & 0xff
+                        out[addr + 1] = x >> 8
+    return bytes(out)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 16])
+@pytest.mark.parametrize("d", [64, 128])
+def test_token_quad_layout_matches_a_lane_by_lane_construction(bits, d):
+    # catches: a wrong slot, word, half-word or bit position of the token-quad form; tokens past the end not zero
+    rng = np.random.default_rng(bits * 10 + d)
+    n = 64 + 37
+    vals = rng.integers(0, 1 << bits, size=(n, d), dtype=np.uint32).astype(np.uint16)
+    img = O.pack_quad_blocks(vals, bits, None)
+    assert img.shape == (2, 64 * d * bits // 8)
+    assert img.tobytes() == _quad_bytes_lane_by_lane(vals, bits, d)
+    back, meta = O.unpack_quad_blocks(img, n, d, bits, 0)
+    assert meta is None and (back == vals).all()
+
+
+def test_token_quad_class_buffer_holds_the_same_values_and_meta():
+    # catches: the quad form losing or reordering meta, touching K, or changing the block size
+    w = workloads.small("quads", 2, 8, 2, [64 * 2 + 40, 130], 8, 32, mix=(0.2, 0.3, 0.5))
+    ks, vs = _seqs(w)
+    cache = O.reorder_quantize(ks, vs, workloads.chunk_bits(w), 8, 32)
+    for cls in range(3):
+        assert O.pack_class_buffer(cache, cls, "k", v_quads=True).tobytes() == O.pack_class_buffer(cache, cls, "k").tobytes()
+        rows = O.pack_class_buffer(cache, cls, "v")
+        quads = O.pack_class_buffer(cache, cls, "v", v_quads=True)
+        assert rows.size == quads.size
+        bb = O.block_bytes(cls, 128, 32)
+        bits = O.CLASS_BITS[cls]
+        mb = 0 if cls == 2 else 4 * 128 // 32
+        pos = 0
+        for b in range(2):
+            cc = cache.seqs[b][cls]
+            if cc.n_tokens == 0:
+                continue
+            nblk = (cc.n_tokens + 63) // 64
+            for h in range(2):
+                blk = quads[pos:pos + nblk * bb].reshape(nblk, bb)
+                vals, meta = O.unpack_quad_blocks(blk, cc.n_tokens, 128, bits, mb)
+                if cls == 2:
+                    assert (vals == cc.v_raw[h].view(np.uint16)).all()
+                else:
+                    assert (vals == cc.v_codes[h]).all()
+                    # meta bytes are those of the row form
+                    assert (blk[:, 64 * 128 * bits // 8:] == rows[pos:pos + nblk * bb].reshape(nblk, bb)[:, 64 * 128 * bits // 8:]).all()
+                    m = np.ascontiguousarray(meta).view("<f2").reshape(cc.n_tokens, 4, 2)
+                    assert (m[..., 0] == cc.v_scale[h]).all() and (m[..., 1] == cc.v_zero[h]).all()
+                pos += nblk * bb
+        assert pos == quads.size
+
+
+def test_token_quad_append_buffer():
+    # catches: appended V rows not following the quad form; K rows changed
+    w = workloads.small("quadapp", 1, 4, 1, [40], 8, 32, mix=(0.3, 0.3, 0.4))
+    ks, vs = _seqs(w)
+    cache = O.reorder_quantize(ks, vs, workloads.chunk_bits(w), 8, 32)
+    rng = np.random.default_rng(5)
+    for _ in range(3):
+        O.append_tokens(cache, rng.standard_normal((1, 1, 128)).astype(np.float16), rng.standard_normal((1, 1, 128)).astype(np.float16))
+    assert O.pack_append_buffer(cache, "k", 70, v_quads=True).tobytes() == O.pack_append_buffer(cache, "k", 70).tobytes()
+    img = O.pack_append_buffer(cache, "v", 70, v_quads=True).reshape(2, -1)
+    vals, _ = O.unpack_quad_blocks(img, 70, 128, 16, 0)
+    assert (vals[:3] == cache.app_v[0][0].view(np.uint16)).all() and not vals[3:].any()
