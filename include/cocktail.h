@@ -41,6 +41,17 @@
  *           and group g of G consecutive channels, 4 bytes at (i*(D/G)+g)*4 =
  *           fp16 scale, then fp16 zero.  Value of a code: zero + code*scale.
  *   Tokens past n_{b,c} in the last block of a head are zero bytes.
+ *   V in token quads (cocktail_sizes::v_layout == COCKTAIL_V_TOKEN_QUADS; chosen
+ *   when 2 <= Hq/Hkv <= 4, where one wave serves the query heads of a kv head
+ *   with matrix instructions and needs four tokens of a channel side by side):
+ *   same block size, piece addressing and meta as above, but the 16-byte piece at
+ *   slot sl no longer holds one token.  With n = 16/bits values per half-word,
+ *   token i of the block and channel c are found at
+ *     h = c / 64, j = (c % 32) / 8, e = 8 * ((c % 64) / 32) + c % 8,
+ *     slot sl = 4 * (i / 4) + j, word w = 2 * (e / n) + (i % 4) / 2,
+ *     piece (D*bits/1024) * h + w / 4, 32-bit word w % 4 of the piece, low (i even)
+ *     or high (i odd) half-word, bits [(e % n) * bits, +bits).
+ *   K always uses the row form.
  *
  * Quantizer (the paper names `quant` without defining it; this is the reading
  * used): per token, per group of G channels along head_dim, asymmetric min/max.
@@ -63,6 +74,8 @@ extern "C" {
 #define COCKTAIL_NUM_CLASSES 3
 #define COCKTAIL_TOKENS_PER_BLOCK 64
 #define COCKTAIL_MAX_Q_PER_KV 8
+#define COCKTAIL_V_ROWS 0
+#define COCKTAIL_V_TOKEN_QUADS 1
 
 typedef enum cocktail_status {
   COCKTAIL_OK = 0,
@@ -97,6 +110,8 @@ typedef struct cocktail_sizes {
   int32_t num_segments;
   int32_t append_capacity;                     /* tokens per sequence the append buffers can take  */
   int64_t append_bytes;                        /* bytes of the K append buffer, and of the V one   */
+  int32_t v_layout;                            /* COCKTAIL_V_ROWS or COCKTAIL_V_TOKEN_QUADS: form of the V blocks */
+  int32_t reserved;
 } cocktail_sizes;
 
 /* The packed mixed-precision cache of one layer: the six lists of Alg. 1

@@ -31,7 +31,8 @@ class Sizes(C.Structure):
     _fields_ = [("total_chunks", C.c_int64), ("class_tokens", C.c_int64 * 3), ("class_blocks", C.c_int64 * 3),
                 ("class_bytes", C.c_int64 * 3), ("plan_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
                 ("packed_bytes", C.c_int64), ("num_workers", C.c_int32), ("num_partials", C.c_int32),
-                ("num_segments", C.c_int32), ("append_capacity", C.c_int32), ("append_bytes", C.c_int64)]
+                ("num_segments", C.c_int32), ("append_capacity", C.c_int32), ("append_bytes", C.c_int64),
+                ("v_layout", C.c_int32), ("reserved", C.c_int32)]
 
 
 class PlanOptions(C.Structure):

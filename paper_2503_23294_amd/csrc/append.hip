@@ -1,6 +1,7 @@
 // Sec. III-A: the K/V rows of tokens generated during decoding join the cache in FP16, behind the
 // context.  They go into the append buffers: per (sequence, kv head) a few 64-token blocks in the
-// block layout of the FP16 class (16-byte piece p of token i at (p*64 + i)*16).
+// block layout of the FP16 class (16-byte piece p of token i at (p*64 + i)*16; V in token quads where
+// the packed cache stores V that way).
 #include <hip/hip_runtime.h>
 
 #include "common.h"
@@ -12,7 +13,7 @@ namespace cocktail {
 __global__ __launch_bounds__(256) void append_fp16_kernel(const u32x4* __restrict__ k_new,
                                                            const u32x4* __restrict__ v_new, char* __restrict__ k_app,
                                                            char* __restrict__ v_app, int position, int app_blocks,
-                                                           int num_bh) {
+                                                           int num_bh, int v_quads) {
   constexpr int kPieces = 2 * 128 / 16;        // 16-byte pieces of one fp16 row
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= num_bh * kPieces) return;
@@ -20,7 +21,20 @@ __global__ __launch_bounds__(256) void append_fp16_kernel(const u32x4* __restric
   const u32x4* src = blockIdx.y ? v_new : k_new;
   char* dst = blockIdx.y ? v_app : k_app;
   const size_t block = size_t(bh) * app_blocks + position / kTB;
-  *reinterpret_cast<u32x4*>(dst + block * (kTB * 2 * 128) + (size_t(p) * kTB + position % kTB) * 16) = src[idx];
+  char* blk = dst + block * (kTB * 2 * 128);
+  const u32x4 v = src[idx];
+  if (blockIdx.y && v_quads) {
+    // the piece is channels 8p .. 8p+7 of the token: lane j = p % 4 of its quad, channels e = 8 ((p / 4) % 2) + x
+    const int i = position % kTB, h = p >> 3, j = p & 3, e0 = 8 * ((p >> 2) & 1);
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const uint32_t word = v[x >> 1];
+      *reinterpret_cast<uint16_t*>(blk + quad_halfword_offset(8, 1, i, h, j, e0 + x)) =
+          uint16_t((x & 1) ? word >> 16 : word);
+    }
+    return;
+  }
+  *reinterpret_cast<u32x4*>(blk + (size_t(p) * kTB + position % kTB) * 16) = v;
 }
 
 }  // namespace cocktail
@@ -52,7 +66,7 @@ extern "C" int cocktail_append_fp16(const cocktail_shape* shape, const void* k_n
   hipLaunchKernelGGL(append_fp16_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
                      static_cast<char*>(cache->k_app), static_cast<char*>(cache->v_app), position, hd->append_blocks,
-                     num_bh);
+                     num_bh, hd->v_layout);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(COCKTAIL_EHIP, "append launch failed: %s", hipGetErrorString(e));
   return COCKTAIL_OK;

@@ -10,7 +10,7 @@
 namespace cocktail {
 
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
-constexpr uint32_t kPlanVersion = 9;
+constexpr uint32_t kPlanVersion = 10;
 constexpr int kTB = 64;                        // tokens per block
 constexpr int kUT = 32;                        // tokens per unit (half a block): what one wave handles at a time
 constexpr int kNumClasses = 3;
@@ -19,6 +19,10 @@ constexpr int kPartialFloats = 2;              // (m, l) in front of the D outpu
 constexpr int kIterUnits[kNumClasses] = {4, 2, 1};
 constexpr int kMaxPoolSegments = 32;           // segments one pool may touch (a worker tracks them in a bit mask)
 constexpr int kCounterStride = 32;             // uint32 slots between two pool counters (one 128-byte line each)
+// Query heads per kv head for which one wave serves all of them with matrix instructions and V is
+// stored in token quads; other ratios above 1 run one wave per query head on the row form.
+constexpr int kQuadMinRep = 2, kQuadMaxRep = 4;
+__host__ __device__ inline bool uses_token_quads(int rep) { return rep >= kQuadMinRep && rep <= kQuadMaxRep; }
 
 // One contiguous run of blocks of one (sequence, kv head, class): the part of it that one group works on.
 struct Segment {
@@ -86,7 +90,8 @@ struct PlanHeader {
   int32_t batch, num_q_heads, num_kv_heads, head_dim, chunk_size, group_size;
   int32_t rep;               // Hq / Hkv
   int32_t num_workers, num_segments, num_partials;
-  int32_t total_gblocks, pad0;
+  int32_t total_gblocks;
+  int32_t v_layout;          // 0: V blocks hold token rows like K; 1: token quads (2 to 4 query heads per kv head)
   int64_t total_chunks;
   int64_t total_tokens;
   int64_t class_blocks[kNumClasses];
@@ -117,6 +122,15 @@ struct PlanHeader {
                               // with append buffers the last id of each range is that of the appended tokens
   int32_t off_rq_items;       // RQItem [sum of class_blocks]
 };
+
+// Token-quad form of a V block: byte offset, inside the block, of the half-word that holds token i
+// (0..63) of lane j's channels e .. e + per - 1 in the 64-channel half h, where per = 16 / bits values
+// fill a half-word and ph = pieces of 16 bytes per half (D * bits / 1024).  Channel of (h, j, e):
+// 64 h + 32 (e / 8) + 8 j + e % 8.
+__host__ __device__ inline uint32_t quad_halfword_offset(int ph, int per, int i, int h, int j, int e) {
+  const int w = 2 * (e / per) + ((i & 3) >> 1);
+  return uint32_t(((ph * h + (w >> 2)) * kTB + ((i & ~3) | j)) * 16 + (w & 3) * 4 + 2 * (i & 1));
+}
 
 template <typename T>
 __host__ __device__ inline const T* plan_array(const void* blob, int32_t off) {

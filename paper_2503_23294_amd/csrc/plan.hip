@@ -191,9 +191,11 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   int pool_percent = tune.pool_percent;
   const int group_workers = tune.group_workers;
   const int rep = shape->num_q_heads / Hkv;
-  // the query heads of a kv head run as waves of one workgroup on the same blocks; a pool would need a
-  // ticket shared by those waves, so grouped-query shapes keep the purely static split
-  if (rep > 1 || reproducible) pool_percent = 0;
+  // 2 to 4 query heads per kv head are served by one wave (token-quad form of V); beyond that the query
+  // heads run as waves of one workgroup on the same blocks, where a pool would need a ticket shared by
+  // those waves, so those shapes keep the purely static split
+  const bool quads = uses_token_quads(rep);
+  if ((rep > 1 && !quads) || reproducible) pool_percent = 0;
 
   // ---- physical runs of the class buffers: (class, b, h) order, each a contiguous run of blocks ----
   struct Run {
@@ -516,6 +518,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   hd.num_groups = NG, hd.num_pool_segs = NPS;
   hd.append_capacity = append_capacity, hd.append_blocks = (append_capacity + kTB - 1) / kTB;
   hd.total_gblocks = static_cast<int32_t>(gblk);
+  hd.v_layout = quads ? 1 : 0;
   hd.total_chunks = total_chunks, hd.total_tokens = total_tokens, hd.packed_bytes = packed;
   for (int c = 0; c < 3; ++c) {
     hd.class_blocks[c] = v_blk_base[3 * B + c];
@@ -560,6 +563,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   sizes->packed_bytes = packed;
   sizes->num_workers = P, sizes->num_partials = npart, sizes->num_segments = S;
   sizes->append_capacity = append_capacity;
+  sizes->v_layout = hd.v_layout, sizes->reserved = 0;
   sizes->append_bytes = int64_t(BH) * hd.append_blocks * kTB * 2 * D;
 
   if (class_tokens) std::memcpy(class_tokens, v_ct.data(), sizeof(int32_t) * v_ct.size());

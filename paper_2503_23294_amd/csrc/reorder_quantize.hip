@@ -23,6 +23,7 @@ struct RQParams {
   char* dst[2][3];         // [K|V][class]
   int64_t stride_b, stride_h, stride_t;
   int32_t ragged;
+  int32_t v_quads;         // V blocks in the token-quad form
   int32_t cls_end0, cls_end1, cls_end2;  // prefix sums of class_blocks
 };
 
@@ -87,6 +88,10 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
 
   const int tid = threadIdx.x;
   const int seg = tid & 15;        // 8 channels seg*8 .. seg*8+7
+  // token-quad form of V: this thread's channels are those of lane qj of a quad in the 64-channel half qh,
+  // its e-th channels for e = qe0 .. qe0+7
+  const bool quads = which == 1 && p.v_quads != 0;
+  const int qh = seg >> 3, qj = seg & 3, qe0 = 8 * ((seg >> 2) & 1);
   const int row_bytes = (cls == 0) ? D / 4 : (cls == 1) ? D / 2 : 2 * D;
 
 #pragma unroll
@@ -107,7 +112,14 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
       raw = RQ_LOAD(reinterpret_cast<const u32x4*>(src + int64_t(t) * p.stride_t + seg * 8));
     }
     if (cls == 2) {
-      *reinterpret_cast<u32x4*>(lds + (seg * kTB + i) * 16) = raw;
+      if (quads) {
+#pragma unroll
+        for (int x = 0; x < 8; ++x)
+          *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(8, 1, i, qh, qj, qe0 + x)) =
+              uint16_t((x & 1) ? raw[x >> 1] >> 16 : raw[x >> 1]);
+      } else {
+        *reinterpret_cast<u32x4*>(lds + (seg * kTB + i) * 16) = raw;
+      }
       continue;
     }
     float x[8];
@@ -136,7 +148,19 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
       const int g = seg / LPG;
       *reinterpret_cast<uint32_t*>(lds + kTB * row_bytes + (i * NG + g) * 4) = as_u32(m);
     }
-    if (cls == 1) {
+    if (quads) {
+      // a half-word holds consecutive channels of one token, lowest channel in the lowest bits
+      if (cls == 1) {
+        *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(2, 4, i, qh, qj, qe0)) =
+            uint16_t(c[0] | (c[1] << 4) | (c[2] << 8) | (c[3] << 12));
+        *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(2, 4, i, qh, qj, qe0 + 4)) =
+            uint16_t(c[4] | (c[5] << 4) | (c[6] << 8) | (c[7] << 12));
+      } else {
+        *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(1, 8, i, qh, qj, qe0)) =
+            uint16_t(c[0] | (c[1] << 2) | (c[2] << 4) | (c[3] << 6) | (c[4] << 8) | (c[5] << 10) | (c[6] << 12) |
+                     (c[7] << 14));
+      }
+    } else if (cls == 1) {
       // word = 8 channels: even channels in the low half-word, odd ones in the high half-word
       const uint32_t w = c[0] | (c[2] << 4) | (c[4] << 8) | (c[6] << 12) | (c[1] << 16) | (c[3] << 20) |
                          (c[5] << 24) | (c[7] << 28);
@@ -252,6 +276,7 @@ extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void
   if (tot >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "too many blocks for one launch");
   p.stride_b = stride_b, p.stride_h = stride_h, p.stride_t = stride_t;
   p.ragged = (src_layout == COCKTAIL_SRC_RAGGED);
+  p.v_quads = hd->v_layout;
   p.cls_end0 = static_cast<int32_t>(hd->class_blocks[0]);
   p.cls_end1 = p.cls_end0 + static_cast<int32_t>(hd->class_blocks[1]);
   p.cls_end2 = static_cast<int32_t>(tot);

@@ -61,6 +61,9 @@ class Case:
         torch.cuda.synchronize()
         self.out = self.out_dev.cpu().numpy()
         self.lse = self.lse_dev.cpu().numpy()
+        # V is stored in token quads where 2 to 4 query heads share a kv head
+        self.v_quads = int(self.plan.sizes.v_layout) == 1
+        assert self.v_quads == (2 <= w.num_q_heads // w.num_kv_heads <= 4)
         self.kbuf = [t.cpu().numpy() for t in self.cache.k]
         self.vbuf = [t.cpu().numpy() for t in self.cache.v]
         ct = self.plan.class_tokens.astype(np.int64)
@@ -87,7 +90,7 @@ class Case:
             lo = (self.blk_base[b, c] + h * self.nblk[b, c]) * bb
             hi = lo + self.nblk[b, c] * bb
             for which, buf in (("k", self.kbuf[c]), ("v", self.vbuf[c])):
-                ref = O.pack_class_buffer(oc, c, which)
+                ref = O.pack_class_buffer(oc, c, which, v_quads=self.v_quads)
                 got = buf[lo:hi]
                 assert ref.size == got.size
                 if not np.array_equal(ref, got):
@@ -133,7 +136,7 @@ def test_config1_all_heads(workers):
 
 
 @pytest.mark.parametrize("group", [32, 64, 128])
-@pytest.mark.parametrize("rep", [1, 2, 4, 8])
+@pytest.mark.parametrize("rep", [1, 2, 3, 4, 8])
 def test_group_sizes_and_gqa(group, rep):
     w = workloads.small(f"g{group}_r{rep}", 2, 2 * rep, 2, [64 * 5 + 32 * 3 + 7, 32 * 9], 32, group,
                         mix=(0.25, 0.35, 0.4), seed_offset=group + rep)
@@ -209,6 +212,27 @@ def test_shared_pools_with_few_workers(workers):
                 c.check_head(b, h)
 
 
+@pytest.mark.parametrize("rep,workers", [(4, 3), (4, 16), (3, 8), (2, 24)])
+def test_shared_pools_grouped_query(rep, workers):
+    """2 to 4 query heads per kv head run as one wave, so these shapes use the pools too."""
+    w = workloads.small(f"gqpools{rep}_{workers}", 3, 2 * rep, 2, [3000, 1500, 4500], 64, 32, mix=(0.2, 0.4, 0.4),
+                        seed_offset=90 + rep + workers)
+    _announce(w.name)
+    c = Case(w, workers=workers)
+    cnt, pool_segs = _counters(c)
+    assert pool_segs > 0, "this shape is meant to exercise the pools"
+    assert (cnt == 0).all(), "a call must leave the ticket counters at zero"
+    c.check_all()
+    for _ in range(2):
+        out, lse = ck.cocktail_decode_attention(c.cache, c.q_dev)
+        torch.cuda.synchronize()
+        assert (_counters(c)[0] == 0).all()
+        c.out, c.lse = out.cpu().numpy(), lse.cpu().numpy()
+        for b in range(w.batch):
+            for h in range(w.num_kv_heads):
+                c.check_head(b, h)
+
+
 @pytest.mark.parametrize("env", [{"COCKTAIL_POOL_PERCENT": "100"}, {"COCKTAIL_POOL_PERCENT": "0"},
                                  {"COCKTAIL_GROUP_WORKERS": "3", "COCKTAIL_POOL_PERCENT": "50"},
                                  {"COCKTAIL_LAYOUT": "1"}, {"COCKTAIL_LAYOUT": "1", "COCKTAIL_PAIR_MODE": "2"},
@@ -267,7 +291,7 @@ def test_appended_decode_tokens(rep, capacity, steps):
     torch.cuda.synchronize()
     assert cache.desc.num_appended == steps
     for which, buf in (("k", cache.k_app), ("v", cache.v_app)):      # append buffers bit-exact, unused rows zero
-        assert np.array_equal(buf.cpu().numpy(), O.pack_append_buffer(oc, which, capacity))
+        assert np.array_equal(buf.cpu().numpy(), O.pack_append_buffer(oc, which, capacity, v_quads=2 <= rep <= 4))
     if steps == capacity:
         with pytest.raises(ck.CocktailError):
             ck.cocktail_append_fp16(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
