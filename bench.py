@@ -73,14 +73,15 @@ def cpu_baseline(w, bits, q, gpu_out, heads, sm_scale=None):
 
 def measured_traffic(workload_name):
     """HBM bytes per decode call from the committed rocprofv3 counter summary (None if there is none)."""
-    path = os.path.join(ROOT, "profiles", f"decode_attention_{workload_name}_hbm_traffic.txt")
-    try:
-        with open(path) as f:
-            for line in f:
-                if line.startswith("traffic_bytes_per_call:"):
-                    return float(line.split(":", 1)[1].split()[0])
-    except OSError:
-        pass
+    for kernel in ("decode_attention", "decode_quads"):
+        path = os.path.join(ROOT, "profiles", f"{kernel}_{workload_name}_hbm_traffic.txt")
+        try:
+            with open(path) as f:
+                for line in f:
+                    if line.startswith("traffic_bytes_per_call:"):
+                        return float(line.split(":", 1)[1].split()[0])
+        except OSError:
+            pass
     return None
 
 
@@ -218,7 +219,8 @@ def main():
         "reorder_quantize_bytes": rq_bytes,
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic,
-                     "kernel": "decode_attention_kernel + decode_merge_kernel (one call, timed together)"},
+                     "kernel": ("decode_quads_kernel" if int(plan.sizes.v_layout) == 1 else "decode_attention_kernel")
+                               + " + decode_merge_kernel (one call, timed together)"},
     }
     if args.cpu_heads > 0:
         rng = np.random.default_rng(0)

@@ -404,7 +404,7 @@ __device__ __forceinline__ void appended_tokens_quads(int bh, float* red, int la
 
 // One single-wave workgroup per worker; the wave serves the 2 to 4 query heads of every kv head it meets.
 template <int G, int AUX>
-__global__ __launch_bounds__(64) void decode_quads_kernel(DecodeParams) {
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_quads_kernel(DecodeParams) {
   __shared__ __attribute__((aligned(16))) float red[64 * kRedStride];
   const int lane = threadIdx.x;
   if (int(blockIdx.x) >= kparams()->num_workers) {

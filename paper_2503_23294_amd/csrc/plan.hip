@@ -42,6 +42,8 @@ int check_shape(const cocktail_shape* s) {
 }
 
 constexpr int64_t kCostWeightInt2 = 1150, kCostWeightInt4 = 1300, kCostWeightFp16 = 530;
+// The same for the kernel that serves 2 to 4 query heads per wave: its arithmetic runs on the matrix unit.
+constexpr int64_t kQuadCostWeightInt2 = 1300, kQuadCostWeightInt4 = 1250, kQuadCostWeightFp16 = 450;
 // Workers per group and the share of a group's cost that goes into its shared pool.
 constexpr int kGroupWorkers = 8;
 constexpr int kPoolPercent = 25;
@@ -62,6 +64,7 @@ constexpr int kShortRangePoolPercent = 40;
 // are tuning aids for experiments and are read once per cocktail_plan call.
 struct Tuning {
   int64_t weight[3] = {kCostWeightInt2, kCostWeightInt4, kCostWeightFp16};   // COCKTAIL_COST_WEIGHTS="a,b,c"
+  bool weight_set = false;
   int pool_percent = kPoolPercent;      // COCKTAIL_POOL_PERCENT   0..100
   bool pool_percent_set = false;        // the environment fixed the share for every group
   int group_workers = kGroupWorkers;    // COCKTAIL_GROUP_WORKERS  1..1024
@@ -75,7 +78,8 @@ static Tuning read_tuning() {
   Tuning t;
   if (const char* e = std::getenv("COCKTAIL_COST_WEIGHTS")) {
     long a = 0, b = 0, c = 0;
-    if (std::sscanf(e, "%ld,%ld,%ld", &a, &b, &c) == 3 && a > 0 && b > 0 && c > 0) t.weight[0] = a, t.weight[1] = b, t.weight[2] = c;
+    if (std::sscanf(e, "%ld,%ld,%ld", &a, &b, &c) == 3 && a > 0 && b > 0 && c > 0)
+      t.weight[0] = a, t.weight[1] = b, t.weight[2] = c, t.weight_set = true;
   }
   auto int_knob = [](const char* name, int lo, int hi, int& out) {
     if (const char* e = std::getenv(name)) {
@@ -186,8 +190,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   // Relative time per byte of the three classes in the decode kernel (1/64 units).  The FP16 class is
   // a pure stream; the quantised classes also keep the vector ALU busy, so a byte of them takes longer.
   // Measured on MI355X with all three classes running side by side.
-  const Tuning tune = read_tuning();
-  const int64_t* weight = tune.weight;
+  Tuning tune = read_tuning();
   int pool_percent = tune.pool_percent;
   const int group_workers = tune.group_workers;
   const int rep = shape->num_q_heads / Hkv;
@@ -195,6 +198,9 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   // heads run as waves of one workgroup on the same blocks, where a pool would need a ticket shared by
   // those waves, so those shapes keep the purely static split
   const bool quads = uses_token_quads(rep);
+  if (quads && !tune.weight_set)
+    tune.weight[0] = kQuadCostWeightInt2, tune.weight[1] = kQuadCostWeightInt4, tune.weight[2] = kQuadCostWeightFp16;
+  const int64_t* weight = tune.weight;
   if ((rep > 1 && !quads) || reproducible) pool_percent = 0;
 
   // ---- physical runs of the class buffers: (class, b, h) order, each a contiguous run of blocks ----

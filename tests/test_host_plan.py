@@ -42,7 +42,7 @@ COUNTER_STRIDE = 32
 def _parse(blob):
     f = _HDR.unpack_from(blob.tobytes(), 0)
     names = ["magic", "version", "batch", "hq", "hkv", "d", "chunk", "group", "rep", "workers", "segments",
-             "partials", "gblocks", "pad0", "total_chunks", "total_tokens"]
+             "partials", "gblocks", "v_layout", "total_chunks", "total_tokens"]
     h = dict(zip(names, f[:16]))
     h["class_blocks"], h["class_bytes"] = f[16:19], f[19:22]
     h["block_bytes"], h["row_bytes"] = f[22:25], f[25:28]
@@ -357,3 +357,16 @@ def test_chunk_bitwidths_validates_on_host():
     assert L.cocktail_chunk_bitwidths(1, 768, 0, 4096, 4096, None, 0.6, 0.1, None, None, None) == _lib.OK   # nothing to do
     assert L.cocktail_selftest_arithmetic(None, None) == _lib.EINVAL
     assert L.cocktail_selftest_arithmetic(4, None) == _lib.EALIGN
+
+
+@pytest.mark.parametrize("rep,quads", [(1, False), (2, True), (3, True), (4, True), (5, False), (8, False)])
+def test_v_layout_follows_the_query_to_kv_head_ratio(rep, quads):
+    """Token quads exactly where one wave serves all query heads of a kv head (2 to 4); those shapes get pools."""
+    shape = ck.make_shape(2, 2 * rep, 2, 128, 64, 32)
+    bits = np.array([2, 4, 16, 2] * 16 + [4, 2] * 16, dtype=np.uint8)
+    plan = ck.cocktail_plan(shape, [64 * 64, 32 * 64], bits, 16)
+    assert int(plan.sizes.v_layout) == int(quads)
+    h = _parse(plan.blob)
+    assert h["rep"] == rep and h["v_layout"] == int(quads)
+    groups = _arr(plan.blob, h["off"]["group_rec"], np.int32, 8 * h["groups"]).reshape(-1, 8)
+    assert (groups[:, 0] > 0).any() == (rep <= 4)
