@@ -42,7 +42,7 @@
  *           fp16 scale, then fp16 zero.  Value of a code: zero + code*scale.
  *   Tokens past n_{b,c} in the last block of a head are zero bytes.
  *   V in token quads (cocktail_sizes::v_layout == COCKTAIL_V_TOKEN_QUADS; chosen
- *   when 2 <= Hq/Hkv <= 4, where one wave serves the query heads of a kv head
+ *   when 2 <= Hq/Hkv <= 8, where a wave serves four query heads of a kv head
  *   with matrix instructions and needs four tokens of a channel side by side):
  *   same block size, piece addressing and meta as above, but the 16-byte piece at
  *   slot sl no longer holds one token.  With n = 16/bits values per half-word,

@@ -369,7 +369,7 @@ extern "C" int cocktail_default_workers(const cocktail_shape* shape, int32_t* nu
   }
   const int rep = shape->num_q_heads / shape->num_kv_heads;
   const int waves_per_cu = 8;   // two waves per SIMD at <= 256 VGPRs
-  int per_cu = uses_token_quads(rep) ? waves_per_cu : waves_per_cu / rep;   // token quads: one wave per workgroup
+  int per_cu = waves_per_cu / (uses_token_quads(rep) ? quad_waves(rep) : rep);   // waves per workgroup
   if (per_cu < 1) per_cu = 1;
   *num_workers = prop.multiProcessorCount * per_cu;
   return COCKTAIL_OK;
@@ -453,7 +453,8 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
       return e ? (std::atoi(e) != 0 ? 1 : 0) : -1;
     }();
     const bool nt = nt_override >= 0 ? nt_override == 1
-                                     : ((hd->rep == 1 || quads) && hd->packed_bytes >= kNonTemporalMinBytes);
+                                     : ((hd->rep == 1 || (quads && quad_waves(hd->rep) == 1)) &&
+                                        hd->packed_bytes >= kNonTemporalMinBytes);
     if (quads) {
       const hipError_t e = launch_decode_quads(p, shape->group_size, nt, int(grid.x), st);
       if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_quads launch failed: %s", hipGetErrorString(e));

@@ -226,9 +226,10 @@ __device__ __forceinline__ void softmax_quads(const f4 (&s)[J], f4 (&p)[J], Quad
 
 // Writes the partial states `pid` of the wave's query heads: (m, l, o[D]) per head, reduced over the lanes.
 template <class CLS, int NGH, int GL>
-__device__ __forceinline__ void flush_quads(const QuadState<NGH>& st, float* red, int pid, int lane) {
+__device__ __forceinline__ void flush_quads(const QuadState<NGH>& st, float* red, int pid, int r, int lane) {
   kparams_t prm = kparams();
   const int rep = prm->rep;
+  const int heads = min(4, rep - 4 * r);   // query heads this wave really has
   // quantities kept per token lane: add up the 32 lanes of each half (both halves hold the same p)
   f4 l = st.l;
   f4 z[NGH];
@@ -240,8 +241,8 @@ __device__ __forceinline__ void flush_quads(const QuadState<NGH>& st, float* red
 #pragma unroll
     for (int g = 0; g < NGH; ++g) z[g] += shfl_xor4(z[g], o);
   }
-  float* out = prm->ws + int64_t(pid) * rep * (D + kPartialFloats);
-  if (lane < rep) {
+  float* out = prm->ws + (int64_t(pid) * rep + 4 * r) * (D + kPartialFloats);
+  if (lane < heads) {
     out[lane * (D + kPartialFloats)] = pick(st.m, lane);
     out[lane * (D + kPartialFloats) + 1] = pick(l, lane);
   }
@@ -265,15 +266,15 @@ __device__ __forceinline__ void flush_quads(const QuadState<NGH>& st, float* red
       float sum = 0.f;
 #pragma unroll
       for (int b = 0; b < 8; ++b) sum += red[(32 * hh + 4 * b + j) * kRedStride + xx * 4 + ii];
-      if (ii < rep) out[ii * (D + kPartialFloats) + kPartialFloats + 64 * hh + 32 * ps + 8 * j + xx] = sum + zv;
+      if (ii < heads) out[ii * (D + kPartialFloats) + kPartialFloats + 64 * hh + 32 * ps + 8 * j + xx] = sum + zv;
     }
   }
 }
 
 // Zeroes the partial state, loads the query rows (lane 4b+i: its half of head i) and prepares the operands.
 template <class CLS, int NGH, int GL>
-__device__ __forceinline__ void begin_quads(int qrow, int h, int lane, QuadState<NGH>& st, u32x2 (&qa)[16],
-                                            f4 (&qs)[NGH]) {
+__device__ __forceinline__ void begin_quads(int qrow, int h, int r, int lane, QuadState<NGH>& st,
+                                            u32x2 (&qa)[16], f4 (&qs)[NGH]) {
 #pragma unroll
   for (int e = 0; e < 16; ++e) st.acc[e] = splat(0.f);
 #pragma unroll
@@ -281,7 +282,7 @@ __device__ __forceinline__ void begin_quads(int qrow, int h, int lane, QuadState
   st.l = splat(0.f);
   st.m = splat(kNegBig);
   const int rep = kparams()->rep;
-  const int head = lane & 3;
+  const int head = 4 * r + (lane & 3);   // wave r of the workgroup serves query heads 4r .. 4r+3 of the kv head
   const bool real = head < rep;   // rows of heads that do not exist are zero: their logits are 0, their output is dropped
   const u32x4* qp =
       reinterpret_cast<const u32x4*>(kparams()->q + int64_t(qrow + (real ? head : 0)) * (D / 2) + h * (DH / 2));
@@ -306,7 +307,7 @@ __device__ __forceinline__ void begin_quads(int qrow, int h, int lane, QuadState
 
 // The quad kernel's version of the one-head kernel's run_class: same pipeline, four heads per wave.
 template <class CLS, int CID, int G, int AUX>
-__device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, int lane, bool app = false) {
+__device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, int r, int lane, bool app = false) {
   constexpr int NG = D / G;
   constexpr int NGH = NG >= 2 ? NG / 2 : 1;
   constexpr int GL = G < DH ? G : DH;
@@ -334,7 +335,7 @@ __device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, in
 #pragma unroll
   for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(vs[jj], vrs, jj < rn ? ru + jj : roob, vc, vm);
   sched_fence();
-  begin_quads<CLS, NGH, GL>(sm.qrow, h, lane, st, qa, qs);
+  begin_quads<CLS, NGH, GL>(sm.qrow, h, r, lane, st, qa, qs);
   int valid = cur.valid;
   Piece nxt = sm.next(lane);
 #pragma unroll 1
@@ -368,11 +369,11 @@ __device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, in
       CLS::template load<AUX>(vs[jj], vrs, jj < rn ? ru + jj : roob, vc, vm);
       sched_fence();
     }
-    if (!more || nxt.fresh) flush_quads<CLS, NGH, GL>(st, red, pid, lane);
+    if (!more || nxt.fresh) flush_quads<CLS, NGH, GL>(st, red, pid, r, lane);
     if (!more) break;
     if (nxt.fresh) {
       pid = nxt.pid;
-      begin_quads<CLS, NGH, GL>(sm.qrow, h, lane, st, qa, qs);
+      begin_quads<CLS, NGH, GL>(sm.qrow, h, r, lane, st, qa, qs);
     }
     valid = nxt.valid;
     nxt = sm.next(lane);
@@ -380,35 +381,38 @@ __device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, in
   cur = nxt;
 }
 
-// The neutral partial state for every head of a slot nobody had tokens for.
-__device__ __forceinline__ void write_neutral_heads(int slot, int lane) {
+// The neutral partial state for this wave's heads of a slot nobody had tokens for.
+__device__ __forceinline__ void write_neutral_heads(int slot, int r, int lane) {
   const int rep = kparams()->rep;
-  for (int r = 0; r < rep; ++r) write_neutral(slot, r, lane);
+  for (int i = 4 * r; i < rep && i < 4 * r + 4; ++i) write_neutral(slot, i, lane);
 }
 
 template <int G, int AUX>
-__device__ __forceinline__ void appended_tokens_quads(int bh, float* red, int lane) {
+__device__ __forceinline__ void appended_tokens_quads(int bh, float* red, int r, int lane) {
   kparams_t kp = kparams();
   const int n = kp->num_appended;
   const int pid = uni(kp->bh_off[bh + 1]) - 1;
   if (n <= 0) {
-    write_neutral_heads(pid, lane);
+    write_neutral_heads(pid, r, lane);
     return;
   }
   Stream sm;
   sm.init_run(2, n, bh * kp->app_blocks, kp->app_blocks,
               (bh / kp->num_kv_heads) * kp->num_q_heads + (bh % kp->num_kv_heads) * kp->rep, pid);
   Piece cur = sm.next(lane);
-  if (cur.nu > 0) run_quads<QuadHalf<G>, 2, G, AUX>(sm, cur, red, lane, true);
+  if (cur.nu > 0) run_quads<QuadHalf<G>, 2, G, AUX>(sm, cur, red, r, lane, true);
 }
 
-// One single-wave workgroup per worker; the wave serves the 2 to 4 query heads of every kv head it meets.
+// One workgroup per worker: one wave for 2 to 4 query heads per kv head, two waves (heads 0-3 and 4-7, both
+// walking the same blocks, so the second read of a line comes from the cache) for 5 to 8.
 template <int G, int AUX>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_quads_kernel(DecodeParams) {
-  __shared__ __attribute__((aligned(16))) float red[64 * kRedStride];
-  const int lane = threadIdx.x;
+__global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(2))) void decode_quads_kernel(DecodeParams) {
+  __shared__ __attribute__((aligned(16))) float red_all[2 * 64 * kRedStride];
+  const int lane = threadIdx.x & 63;
+  const int r = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  float* red = red_all + r * 64 * kRedStride;
   if (int(blockIdx.x) >= kparams()->num_workers) {
-    appended_tokens_quads<G, AUX>(int(blockIdx.x) - kparams()->num_workers, red, lane);
+    appended_tokens_quads<G, AUX>(int(blockIdx.x) - kparams()->num_workers, red, r, lane);
     return;
   }
   Stream sm;
@@ -416,28 +420,29 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
   Piece cur = sm.next(lane);
   while (cur.nu > 0) {
     if (cur.cls == 0) {
-      run_quads<QuadQuant<2, G>, 0, G, AUX>(sm, cur, red, lane);
+      run_quads<QuadQuant<2, G>, 0, G, AUX>(sm, cur, red, r, lane);
     } else if (cur.cls == 1) {
-      run_quads<QuadQuant<4, G>, 1, G, AUX>(sm, cur, red, lane);
+      run_quads<QuadQuant<4, G>, 1, G, AUX>(sm, cur, red, r, lane);
     } else {
-      run_quads<QuadHalf<G>, 2, G, AUX>(sm, cur, red, lane);
+      run_quads<QuadHalf<G>, 2, G, AUX>(sm, cur, red, r, lane);
     }
   }
   for (int i = 0; i < sm.nps; ++i) {
     if ((sm.used >> i) & 1u) continue;
     const PoolSeg ps = load_record(kparams()->psegs + sm.pseg0 + i);
-    if (sm.rank < ps.nslots) write_neutral_heads(ps.slot0 + sm.rank, lane);
+    if (sm.rank < ps.nslots) write_neutral_heads(ps.slot0 + sm.rank, r, lane);
   }
 }
 
 hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, int grid, hipStream_t st) {
+  const int waves = quad_waves(p.rep);
   void (*kern)(DecodeParams) = nullptr;
   switch (group_size) {
     case 32: kern = non_temporal ? decode_quads_kernel<32, kAuxNonTemporal> : decode_quads_kernel<32, kAuxDefault>; break;
     case 64: kern = non_temporal ? decode_quads_kernel<64, kAuxNonTemporal> : decode_quads_kernel<64, kAuxDefault>; break;
     default: kern = non_temporal ? decode_quads_kernel<128, kAuxNonTemporal> : decode_quads_kernel<128, kAuxDefault>; break;
   }
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(64), 0, st, p);
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * waves), 0, st, p);
   return hipGetLastError();
 }
 

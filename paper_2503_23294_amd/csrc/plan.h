@@ -19,10 +19,11 @@ constexpr int kPartialFloats = 2;              // (m, l) in front of the D outpu
 constexpr int kIterUnits[kNumClasses] = {4, 2, 1};
 constexpr int kMaxPoolSegments = 32;           // segments one pool may touch (a worker tracks them in a bit mask)
 constexpr int kCounterStride = 32;             // uint32 slots between two pool counters (one 128-byte line each)
-// Query heads per kv head for which one wave serves all of them with matrix instructions and V is
-// stored in token quads; other ratios above 1 run one wave per query head on the row form.
-constexpr int kQuadMinRep = 2, kQuadMaxRep = 4;
+// Query heads per kv head for which a wave serves four of them at a time with matrix instructions and V is
+// stored in token quads: 2 to 4 heads take one wave per workgroup, 5 to 8 two waves (one per head quad).
+constexpr int kQuadMinRep = 2, kQuadMaxRep = 8;
 __host__ __device__ inline bool uses_token_quads(int rep) { return rep >= kQuadMinRep && rep <= kQuadMaxRep; }
+__host__ __device__ inline int quad_waves(int rep) { return (rep + 3) / 4; }
 
 // One contiguous run of blocks of one (sequence, kv head, class): the part of it that one group works on.
 struct Segment {

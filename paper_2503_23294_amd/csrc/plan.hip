@@ -195,13 +195,13 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   const int group_workers = tune.group_workers;
   const int rep = shape->num_q_heads / Hkv;
   // 2 to 4 query heads per kv head are served by one wave (token-quad form of V); beyond that the query
-  // heads run as waves of one workgroup on the same blocks, where a pool would need a ticket shared by
-  // those waves, so those shapes keep the purely static split
+  // heads run as two or more waves of one workgroup on the same blocks, where a pool would need a ticket
+  // shared by those waves, so those shapes keep the purely static split
   const bool quads = uses_token_quads(rep);
   if (quads && !tune.weight_set)
     tune.weight[0] = kQuadCostWeightInt2, tune.weight[1] = kQuadCostWeightInt4, tune.weight[2] = kQuadCostWeightFp16;
   const int64_t* weight = tune.weight;
-  if ((rep > 1 && !quads) || reproducible) pool_percent = 0;
+  if ((rep > 1 && !(quads && quad_waves(rep) == 1)) || reproducible) pool_percent = 0;
 
   // ---- physical runs of the class buffers: (class, b, h) order, each a contiguous run of blocks ----
   struct Run {

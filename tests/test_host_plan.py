@@ -359,9 +359,9 @@ def test_chunk_bitwidths_validates_on_host():
     assert L.cocktail_selftest_arithmetic(4, None) == _lib.EALIGN
 
 
-@pytest.mark.parametrize("rep,quads", [(1, False), (2, True), (3, True), (4, True), (5, False), (8, False)])
+@pytest.mark.parametrize("rep,quads", [(1, False), (2, True), (3, True), (4, True), (5, True), (8, True)])
 def test_v_layout_follows_the_query_to_kv_head_ratio(rep, quads):
-    """Token quads exactly where one wave serves all query heads of a kv head (2 to 4); those shapes get pools."""
+    """Token quads where a wave serves four query heads of a kv head (ratios 2 to 8); one-wave workgroups get pools."""
     shape = ck.make_shape(2, 2 * rep, 2, 128, 64, 32)
     bits = np.array([2, 4, 16, 2] * 16 + [4, 2] * 16, dtype=np.uint8)
     plan = ck.cocktail_plan(shape, [64 * 64, 32 * 64], bits, 16)
