@@ -405,11 +405,11 @@ __device__ __forceinline__ void appended_tokens_quads(int bh, float* red, int r,
 
 // One workgroup per worker: one wave for 2 to 4 query heads per kv head, two waves (heads 0-3 and 4-7, both
 // walking the same blocks, so the second read of a line comes from the cache) for 5 to 8.
-template <int G, int AUX>
-__global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(2))) void decode_quads_kernel(DecodeParams) {
-  __shared__ __attribute__((aligned(16))) float red_all[2 * 64 * kRedStride];
+template <int G, int AUX, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2))) void decode_quads_kernel(DecodeParams) {
+  __shared__ __attribute__((aligned(16))) float red_all[WAVES * 64 * kRedStride];
   const int lane = threadIdx.x & 63;
-  const int r = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int r = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* red = red_all + r * 64 * kRedStride;
   if (int(blockIdx.x) >= kparams()->num_workers) {
     appended_tokens_quads<G, AUX>(int(blockIdx.x) - kparams()->num_workers, red, r, lane);
@@ -437,11 +437,15 @@ __global__ __launch_bounds__(128) __attribute__((amdgpu_waves_per_eu(2))) void d
 hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, int grid, hipStream_t st) {
   const int waves = quad_waves(p.rep);
   void (*kern)(DecodeParams) = nullptr;
+#define COCKTAIL_PICK(G) \
+  kern = waves == 1 ? (non_temporal ? decode_quads_kernel<G, kAuxNonTemporal, 1> : decode_quads_kernel<G, kAuxDefault, 1>) \
+                    : (non_temporal ? decode_quads_kernel<G, kAuxNonTemporal, 2> : decode_quads_kernel<G, kAuxDefault, 2>)
   switch (group_size) {
-    case 32: kern = non_temporal ? decode_quads_kernel<32, kAuxNonTemporal> : decode_quads_kernel<32, kAuxDefault>; break;
-    case 64: kern = non_temporal ? decode_quads_kernel<64, kAuxNonTemporal> : decode_quads_kernel<64, kAuxDefault>; break;
-    default: kern = non_temporal ? decode_quads_kernel<128, kAuxNonTemporal> : decode_quads_kernel<128, kAuxDefault>; break;
+    case 32: COCKTAIL_PICK(32); break;
+    case 64: COCKTAIL_PICK(64); break;
+    default: COCKTAIL_PICK(128); break;
   }
+#undef COCKTAIL_PICK
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * waves), 0, st, p);
   return hipGetLastError();
 }
