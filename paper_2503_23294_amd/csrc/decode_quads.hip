@@ -16,8 +16,11 @@
 //           instruction per channel and lane, 4 heads x 16 channels of accumulators per lane.
 //           p lives in "lane = token, register = head" form after the softmax; one more matrix
 //           instruction with B = identity turns it into "lane = head, register = token".
-//  * The reference maximum of a head is kept at least as large as every logit seen (raised to the new
-//    maximum + 8 when exceeded), so p <= 1 and p * scale always fits fp16.
+//  * p * scale has to fit fp16.  The reference m of a head's partial state (p = 2^(logit - m); any reference
+//    gives the same merged result) is therefore not tied to the largest logit but to the largest
+//    logit + e, e = binary exponent of the token's V scale: it is kept >= that sum - 15, so p * scale < 2^15,
+//    and is raised to (new largest sum) - 11 when exceeded, so the largest products sit near 2^11 whatever
+//    the magnitude of V, with some 25 binary orders of fp16 range below them.
 // Everything else (work pieces, pools, register stages, buffer loads) is shared with the one-head kernel.
 #include <hip/hip_runtime.h>
 
@@ -28,7 +31,8 @@ namespace cocktail {
 typedef _Float16 h4 __attribute__((ext_vector_type(4)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-constexpr float kHeadroom = 8.0f;   // log2 units the reference maximum is put above a new maximum
+constexpr float kTopExp = 15.0f;     // p * scale stays below 2^kTopExp (fp16 holds up to 2^16 - 32)
+constexpr float kHeadroom = 4.0f;    // log2 units left to grow into when the reference is moved
 constexpr int kRedStride = 36;      // floats per lane in the reduction tile (32 + padding, 16-byte aligned rows)
 
 __device__ __forceinline__ f4 mfma4(u32x2 a, u32x2 b, f4 c) {
@@ -132,6 +136,13 @@ struct QuadQuant : QuantClass<BITS, G> {
     return sum;
   }
 
+  // binary exponent e of this lane's V scales: every scale is below 2^e
+  __device__ static __forceinline__ float scale_exponent(const Stage& s) {
+    int e = __builtin_amdgcn_frexp_expf(static_cast<float>(as_h2(s.meta[0]).x));
+    if constexpr (NGH == 2) e = max(e, __builtin_amdgcn_frexp_expf(static_cast<float>(as_h2(s.meta[1]).x)));
+    return static_cast<float>(e);
+  }
+
   // p: the softmax weights of this lane's token for the four heads
   __device__ static __forceinline__ void accumulate(const Stage& s, f4 p, QuadState<NGH>& st, u32x2 ident) {
     u32x2 pa[NGH];   // lane = head: p_t scale_tg of the quad's four tokens
@@ -182,6 +193,8 @@ struct QuadHalf : HalfClass<G> {
     return ga[0] + ga[1];
   }
 
+  __device__ static __forceinline__ float scale_exponent(const Stage&) { return 0.f; }   // raw values: p itself is the fp16 operand
+
   __device__ static __forceinline__ void accumulate(const Stage& s, f4 p, QuadState<NGH>& st, u32x2 ident) {
     const u32x2 pa = to_h4(mfma4(to_h4(p), ident, splat(0.f)));
 #pragma unroll
@@ -193,20 +206,22 @@ struct QuadHalf : HalfClass<G> {
   }
 };
 
-// Online softmax over the J units of one iteration, four heads at a time.
+// Online softmax over the J units of one iteration, four heads at a time.  ev[jj]: exponent of the V scales
+// of this lane's token in unit jj (see the note on the reference at the top).
 template <int NGH, int J>
-__device__ __forceinline__ void softmax_quads(const f4 (&s)[J], f4 (&p)[J], QuadState<NGH>& st) {
-  f4 smax = s[0];
+__device__ __forceinline__ void softmax_quads(const f4 (&s)[J], const float (&ev)[J], f4 (&p)[J], QuadState<NGH>& st) {
+  f4 tmax = s[0] + ev[0];
 #pragma unroll
-  for (int jj = 1; jj < J; ++jj) smax = max4(smax, s[jj]);
-  const bool grow = smax[0] > st.m[0] || smax[1] > st.m[1] || smax[2] > st.m[2] || smax[3] > st.m[3];
+  for (int jj = 1; jj < J; ++jj) tmax = max4(tmax, s[jj] + ev[jj]);
+  const bool grow = tmax[0] > st.m[0] + kTopExp || tmax[1] > st.m[1] + kTopExp || tmax[2] > st.m[2] + kTopExp ||
+                    tmax[3] > st.m[3] + kTopExp;
   if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) smax = max4(smax, shfl_xor4(smax, o));
+    for (int o = 32; o > 0; o >>= 1) tmax = max4(tmax, shfl_xor4(tmax, o));
     f4 alpha;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float mnew = smax[i] > st.m[i] ? smax[i] + kHeadroom : st.m[i];
+      const float mnew = tmax[i] > st.m[i] + kTopExp ? tmax[i] - (kTopExp - kHeadroom) : st.m[i];
       alpha[i] = __builtin_amdgcn_exp2f(st.m[i] - mnew);
       st.m[i] = mnew;
     }
@@ -361,7 +376,10 @@ __device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, in
       const f4 full = (s[jj] + shfl_xor4(s[jj], 32)) * scale_log2;   // both halves of the token
       s[jj] = (jj * UT + t < valid) ? full : splat(-INFINITY);
     }
-    softmax_quads<NGH, J>(s, p, st);
+    float ev[J];
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) ev[jj] = CLS::scale_exponent(vs[jj]);
+    softmax_quads<NGH, J>(s, ev, p, st);
 #pragma unroll
     for (int jj = 0; jj < J; ++jj) {
       CLS::accumulate(vs[jj], p[jj], st, ident);

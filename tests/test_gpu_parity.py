@@ -473,3 +473,39 @@ def test_config5_ragged_dirichlet():
     heads = sorted(set(_sample_heads(w, 6, 5) + [(0, 0), (1, 7)]))   # seq 0 all-FP16, seq 1 all-INT2
     for b, h in heads:
         _announce(f"  head {b},{h}: {c.check_head(b, h):.2e}")
+
+
+@pytest.mark.parametrize("rep", [1, 4, 8])
+@pytest.mark.parametrize("kscale,vscale", [(1.0, 2.0e4), (1.0, 1.0e-3), (6.0, 1.0), (0.02, 3.0e-3), (3.0, 5.0e-5)])
+def test_value_ranges_from_tiny_to_near_the_fp16_limit(rep, kscale, vscale):
+    """V from fp16-subnormal magnitudes to values near 65504, peaked and flat softmax: same tolerance."""
+    w = workloads.small(f"range_r{rep}", 2, 2 * rep, 2, [64 * 7 + 9, 64 * 3], 64, 32, mix=(0.2, 0.4, 0.4),
+                        seed_offset=300 + rep)
+    _announce(f"{w.name} k x{kscale} v x{vscale}")
+    dev = _dev()
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = workloads.chunk_bits(w)
+    ks, vs = [], []
+    for b in range(w.batch):
+        kh, vh = zip(*[workloads.kv_head(w, 0, b, h) for h in range(w.num_kv_heads)])
+        ks.append(np.clip(np.stack(kh).astype(np.float32) * kscale, -6.0e4, 6.0e4).astype(np.float16))
+        vs.append(np.clip(np.stack(vh).astype(np.float32) * vscale, -6.0e4, 6.0e4).astype(np.float16))
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), 6)
+    cache = ck.PackedCache(plan, dev)
+    k_flat = np.concatenate([x.reshape(-1, w.head_dim) for x in ks])      # ragged: per sequence [Hkv][T_b] rows
+    v_flat = np.concatenate([x.reshape(-1, w.head_dim) for x in vs])
+    ck.cocktail_reorder_quantize(cache, torch.from_numpy(k_flat).to(dev), torch.from_numpy(v_flat).to(dev), ragged=True)
+    q = workloads.query(w, 0)
+    out, lse = ck.cocktail_decode_attention(cache, torch.from_numpy(q).to(dev))
+    torch.cuda.synchronize()
+    oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    v_quads = int(plan.sizes.v_layout) == 1
+    for c in range(3):
+        assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k"))
+        assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads))
+    ref, rl = O.decode_attention(q, oc)
+    got = out.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref).max(axis=2) / np.abs(ref).max(axis=2)
+    assert err.max() <= TOL, f"max rel err {err.max():.3e}"
+    assert np.abs(lse.cpu().numpy() - rl).max() <= 1e-4 * max(1.0, np.abs(rl).max())
