@@ -29,8 +29,8 @@
 //    reference maximum grows by more than 2^8, then the V pass.  (m, l, o[D])
 //    partials go to the workspace and a second small kernel merges them exactly
 //    (the softmax-weighted sum does not depend on how tokens are grouped, Eq. 4-5).
-//  * Grouped-query attention: the Hq/Hkv query heads of a kv head run as separate
-//    waves of one workgroup on the same blocks, so the second to last read hits cache.
+//  * This kernel serves shapes with one query head per kv head; grouped-query shapes run on the
+//    kernel of decode_quads.hip, which shares the pieces, pools and register stages with this one.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -237,12 +237,12 @@ __device__ __forceinline__ void appended_tokens(int bh, float* red, int r, int l
   if (cur.nu > 0) run_class<HalfClass<G>, 2, G, AUX>(sm, cur, red, r, lane, true);
 }
 
-// One workgroup per worker; wave r of the workgroup serves query head r of every kv head it meets.
+// One single-wave workgroup per worker (Hq = Hkv: the query head of a kv head is that head).
 template <int G, int AUX>
-__global__ __launch_bounds__(512) void decode_attention_kernel(DecodeParams) {
-  extern __shared__ float red[];   // [rep][64][17] reduction tiles
-  const int lane = threadIdx.x & 63;
-  const int r = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // query head inside the group
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_attention_kernel(DecodeParams) {
+  __shared__ float red[64 * 17];   // reduction tile of a flush
+  const int lane = threadIdx.x;
+  constexpr int r = 0;             // query head inside the kv head's group
 #ifdef COCKTAIL_TRACE
   const uint64_t t_start = __builtin_amdgcn_s_memrealtime();
 #endif
@@ -392,6 +392,7 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
     return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
   if (hd->rep > COCKTAIL_MAX_Q_PER_KV)
     return fail(COCKTAIL_EUNSUPPORTED, "Hq/Hkv = %d exceeds %d", hd->rep, COCKTAIL_MAX_Q_PER_KV);
+  static_assert(COCKTAIL_MAX_Q_PER_KV == kQuadMaxRep, "every ratio above 1 runs on the token-quad kernel");
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(workspace) |
        reinterpret_cast<uintptr_t>(cache->plan_dev)) & 15)
     return fail(COCKTAIL_EALIGN, "q, out, workspace and plan_dev must be 16-byte aligned");
@@ -444,8 +445,7 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
   const int app_groups = hd->append_capacity > 0 ? hd->batch * hd->num_kv_heads : 0;
   if (hd->total_gblocks > 0 || app_groups > 0) {
     const bool quads = hd->v_layout == COCKTAIL_V_TOKEN_QUADS;
-    const dim3 grid(hd->num_workers + app_groups, 1, 1), block(64 * hd->rep, 1, 1);
-    const size_t lds = size_t(hd->rep) * 64 * 17 * sizeof(float);
+    const dim3 grid(hd->num_workers + app_groups, 1, 1), block(64, 1, 1);
     // non-temporal K/V loads when nothing is read twice: one wave per workgroup, and a cache large enough
     // that it cannot stay in the memory-side cache from one call to the next
     static const int nt_override = [] {   // tuning aid, read once: COCKTAIL_NON_TEMPORAL=0 | 1
@@ -465,7 +465,7 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
       case 64: kern = nt ? decode_attention_kernel<64, kAuxNonTemporal> : decode_attention_kernel<64, kAuxDefault>; break;
       default: kern = nt ? decode_attention_kernel<128, kAuxNonTemporal> : decode_attention_kernel<128, kAuxDefault>; break;
     }
-    hipLaunchKernelGGL(kern, grid, block, lds, st, p);
+    hipLaunchKernelGGL(kern, grid, block, 0, st, p);
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_attention launch failed: %s", hipGetErrorString(e));
     }
