@@ -507,5 +507,6 @@ def test_value_ranges_from_tiny_to_near_the_fp16_limit(rep, kscale, vscale):
     got = out.cpu().numpy().astype(np.float64)
     assert np.isfinite(got).all()
     err = np.abs(got - ref).max(axis=2) / np.abs(ref).max(axis=2)
+    _announce(f"  max rel err {err.max():.2e}")
     assert err.max() <= TOL, f"max rel err {err.max():.3e}"
     assert np.abs(lse.cpu().numpy() - rl).max() <= 1e-4 * max(1.0, np.abs(rl).max())
