@@ -429,6 +429,9 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
   const int lane = threadIdx.x & 63;
   const int r = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   float* red = red_all + r * 64 * kRedStride;
+#ifdef COCKTAIL_TRACE
+  const uint64_t t_start = __builtin_amdgcn_s_memrealtime();
+#endif
   if (int(blockIdx.x) >= kparams()->num_workers) {
     appended_tokens_quads<G, AUX>(int(blockIdx.x) - kparams()->num_workers, red, r, lane);
     return;
@@ -450,6 +453,15 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
     const PoolSeg ps = load_record(kparams()->psegs + sm.pseg0 + i);
     if (sm.rank < ps.nslots) write_neutral_heads(ps.slot0 + sm.rank, r, lane);
   }
+#ifdef COCKTAIL_TRACE
+  if (threadIdx.x == 0) {
+    uint64_t* tr = kparams()->trace + blockIdx.x * 4;
+    tr[0] = t_start;
+    tr[1] = __builtin_amdgcn_s_memrealtime();
+    tr[2] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));    // HW_ID
+    tr[3] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));   // XCC_ID
+  }
+#endif
 }
 
 hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, int grid, hipStream_t st) {
