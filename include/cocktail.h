@@ -206,8 +206,9 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  * on one stream never do), and a plan_dev whose call was aborted has to be
  * re-uploaded.  Which worker takes which pool piece differs from call to call, so
  * two calls on the same inputs agree to fp32 summation order, not bit for bit
- * (shapes with Hq > Hkv use no pools and are reproducible bit for bit, and so is any plan made with
- * cocktail_plan_options::reproducible).
+ * (shapes with Hq/Hkv > 4 use no pools and are reproducible bit for bit, and so is any plan made with
+ * cocktail_plan_options::reproducible).  Shapes with Hq = Hkv run one query head per wave on the vector
+ * ALU; 2 <= Hq/Hkv <= 8 run four query heads per wave on 4x4x4 matrix instructions (V in token quads).
  *
  *   cache      num_appended tokens of the append buffers are attended to after the context
  *   q          DEVICE fp16 [B][Hq][D], 16-byte aligned
@@ -263,7 +264,8 @@ int cocktail_chunk_bitwidths(int32_t batch, int32_t embed_dim, int32_t total_chu
 
 /*
  * Number of decode workgroups that fills the current HIP device for this shape
- * (compute units x resident waves per unit / (Hq/Hkv)).  Needs a GPU: EHIP otherwise.
+ * (compute units x resident waves per unit / waves per workgroup; a workgroup is one wave up to
+ * Hq/Hkv = 4 and two waves up to 8).  Needs a GPU: EHIP otherwise.
  */
 int cocktail_default_workers(const cocktail_shape* shape, int32_t* num_workers);
 

@@ -70,7 +70,7 @@ __device__ __forceinline__ rsrc_t make_rsrc(const char* base, uint32_t bytes) {
 }
 // Cache policy of the K/V loads.  Every byte of a large cache is read exactly once per call, so the loads
 // are marked non-temporal (they do not displace anything in the L2 and the memory-side cache, which on
-// MI355X is worth 10 % of HBM throughput); grouped-query shapes, whose waves re-read each other's lines
+// MI355X is worth 10 % of HBM throughput); workgroups of two waves, whose waves re-read each other's lines
 // from the L2, and small caches that stay resident between calls use the default policy.
 constexpr int kAuxDefault = 0, kAuxNonTemporal = 2;
 constexpr int64_t kNonTemporalMinBytes = int64_t(64) << 20;   // packed K+V bytes of one call
@@ -441,7 +441,8 @@ __device__ __forceinline__ void write_neutral(int slot, int r, int lane) {
   out[kPartialFloats + 64 + lane] = 0.f;
 }
 
-// Launches the kernel for 2 to 4 query heads per kv head (decode_quads.hip): `grid` single-wave workgroups.
+// Launches the kernel for 2 to 8 query heads per kv head (decode_quads.hip): `grid` workgroups of one wave
+// (up to 4 heads) or two waves (5 to 8).
 hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, int grid, hipStream_t st);
 
 }  // namespace cocktail

@@ -92,7 +92,7 @@ struct PlanHeader {
   int32_t rep;               // Hq / Hkv
   int32_t num_workers, num_segments, num_partials;
   int32_t total_gblocks;
-  int32_t v_layout;          // 0: V blocks hold token rows like K; 1: token quads (2 to 4 query heads per kv head)
+  int32_t v_layout;          // 0: V blocks hold token rows like K; 1: token quads (2 to 8 query heads per kv head)
   int64_t total_chunks;
   int64_t total_tokens;
   int64_t class_blocks[kNumClasses];

@@ -42,7 +42,7 @@ int check_shape(const cocktail_shape* s) {
 }
 
 constexpr int64_t kCostWeightInt2 = 1150, kCostWeightInt4 = 1300, kCostWeightFp16 = 530;
-// The same for the kernel that serves 2 to 4 query heads per wave: its arithmetic runs on the matrix unit.
+// The same for the kernel that serves four query heads per wave: its arithmetic runs on the matrix unit.
 constexpr int64_t kQuadCostWeightInt2 = 1300, kQuadCostWeightInt4 = 1250, kQuadCostWeightFp16 = 450;
 // Workers per group and the share of a group's cost that goes into its shared pool.
 constexpr int kGroupWorkers = 8;
