@@ -510,3 +510,41 @@ def test_value_ranges_from_tiny_to_near_the_fp16_limit(rep, kscale, vscale):
     _announce(f"  max rel err {err.max():.2e}")
     assert err.max() <= TOL, f"max rel err {err.max():.3e}"
     assert np.abs(lse.cpu().numpy() - rl).max() <= 1e-4 * max(1.0, np.abs(rl).max())
+
+
+@pytest.mark.parametrize("rep", [1, 4])
+def test_decode_calls_replayed_from_a_captured_graph(rep):
+    """The decode entry point only enqueues kernels (no memset, no allocation), so a caller can capture a
+    run of calls in a HIP graph; every replay must give the eager result (and leave the counters at zero)."""
+    w = workloads.small(f"graph_r{rep}", 2, 2 * rep, 2, [3000, 1700], 64, 32, mix=(0.2, 0.4, 0.4), seed_offset=500 + rep)
+    _announce(w.name)
+    c = Case(w, workers=16)
+    c.check_all()
+    eager = c.out_dev.clone()
+    outs = [torch.empty_like(c.out_dev) for _ in range(3)]
+    lses = [torch.empty_like(c.lse_dev) for _ in range(3)]
+
+    def calls():
+        for o, l in zip(outs, lses):
+            ck.cocktail_decode_attention(c.cache, c.q_dev, c.sm_scale, out=o, lse=l)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        calls()                                   # warm-up outside the capture, as graph capture asks for
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls()
+    for replay in range(4):
+        for o in outs:
+            o.zero_()
+        ck.cocktail_decode_attention(c.cache, c.q_dev, c.sm_scale)   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (_counters(c)[0] == 0).all()
+        for o in outs:
+            assert torch.allclose(o.float(), eager.float(), rtol=0, atol=2e-3 * float(eager.float().abs().max())), \
+                f"replay {replay} differs from the eager result"
