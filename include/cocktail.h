@@ -56,7 +56,7 @@
  * Quantizer (the paper names `quant` without defining it; this is the reading
  * used): per token, per group of G channels along head_dim, asymmetric min/max.
  * Every step is one IEEE binary32 operation, round-to-nearest-even, unfused:
- *   mn, mx = min, max of the group (a zero minimum is stored as +0)
+ *   mn, mx = min, max of the group (zeros of either sign compare equal: a zero minimum or maximum is +0)
  *   scale  = fp16((f32(mx) - f32(mn)) / (2^bits - 1)),  zero = mn
  *   code   = 0 if scale == 0, else
  *            clamp(rint((f32(x) - f32(mn)) * (1.0f / f32(scale))), 0, 2^bits - 1)

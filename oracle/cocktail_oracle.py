@@ -96,7 +96,8 @@ def quantize_rows(x: np.ndarray, bits: int, group: int):
 
     x: fp16 [..., D].  Returns codes uint8 [..., D], scale fp16 [..., D/G], zero fp16 [..., D/G].
     Every step is one IEEE binary32 operation, round-to-nearest-even, unfused:
-      mn, mx = min, max of the group (exact; a zero minimum is stored as +0)
+      mn, mx = min, max of the group (exact; zeros of either sign compare equal, so a zero
+               minimum or maximum is taken as +0)
       r      = f32(mx) - f32(mn)
       scale  = f16(r / qmax)                       qmax = 2^bits - 1
       codes  = 0                                   if scale == 0
@@ -110,6 +111,7 @@ def quantize_rows(x: np.ndarray, bits: int, group: int):
     mn = xg.min(axis=-1)
     mx = xg.max(axis=-1)
     mn = np.where(mn == 0, np.float16(0.0), mn).astype(np.float16)
+    mx = np.where(mx == 0, np.float16(0.0), mx).astype(np.float16)
     mn32 = mn.astype(np.float32)
     r = mx.astype(np.float32) - mn32
     scale = (r / qmax).astype(np.float16)

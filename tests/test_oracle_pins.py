@@ -555,3 +555,17 @@ def test_token_quad_append_buffer():
     img = O.pack_append_buffer(cache, "v", 70, v_quads=True).reshape(2, -1)
     vals, _ = O.unpack_quad_blocks(img, 70, 128, 16, 0)
     assert (vals[:3] == cache.app_v[0][0].view(np.uint16)).all() and not vals[3:].any()
+
+
+def test_signed_zeros_do_not_reach_scale_or_zero():
+    # catches: the sign of a zero extreme leaking into the stored scale or zero (it would depend on element order)
+    for order in ([-0.0, 0.0], [0.0, -0.0], [-0.0, -0.0], [0.0, 0.0]):
+        x = np.array([order * 16], dtype=np.float16)
+        for bits in (2, 4):
+            codes, scale, zero = O.quantize_rows(x, bits, 32)
+            assert scale.view(np.uint16).item() == 0 and zero.view(np.uint16).item() == 0 and not codes.any()
+    # a group whose maximum is a zero and whose minimum is negative: range = -min exactly, whatever the zero's sign
+    for z in (0.0, -0.0):
+        x = np.array([[-3.0, z] + [-1.5] * 30], dtype=np.float16)
+        codes, scale, zero = O.quantize_rows(x, 2, 32)
+        assert float(scale[0, 0]) == 1.0 and float(zero[0, 0]) == -3.0 and codes[0, :3].tolist() == [0, 3, 2]
