@@ -27,10 +27,29 @@ struct RQParams {
   int32_t cls_end0, cls_end1, cls_end2;  // prefix sums of class_blocks
 };
 
-// One token-group step of the quantizer.  Every operation is a single IEEE
-// binary32 operation; contraction is disabled so that no multiply-add is fused.
+// Minimum (or maximum) over a group of LPG = 4, 8 or 16 consecutive lanes, result in every lane of the
+// group.  Data-parallel-primitive operands: the neighbour's value arrives inside the min/max
+// instruction itself (quad permutes, then mirrors of 8 and 16 lanes, whose quads are already uniform).
+template <int CTRL>
+__device__ __forceinline__ float dpp(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+template <int LPG, bool MAX>
+__device__ __forceinline__ float group_extreme(float v) {
+  auto pick = [](float a, float b) { return MAX ? fmaxf(a, b) : fminf(a, b); };
+  v = pick(v, dpp<0xB1>(v));                            // quad_perm [1,0,3,2]
+  v = pick(v, dpp<0x4E>(v));                            // quad_perm [2,3,0,1]
+  if constexpr (LPG >= 8) v = pick(v, dpp<0x141>(v));   // row_half_mirror
+  if constexpr (LPG >= 16) v = pick(v, dpp<0x140>(v));  // row_mirror
+  return v;
+}
+
+// One token-group step of the quantizer on this lane's 8 channels (raw fp16 pairs).  Every operation is
+// a single IEEE binary32 operation with the result the definition asks for: x - mn is computed as
+// fma(f32(x), 1, -mn) straight from the fp16 operand (exact conversion, one rounding: the same value),
+// the clamp is a median of three.
 template <int BITS>
-__device__ __forceinline__ void quantize8(const float (&x)[8], float mn, float mx, uint32_t (&code)[8],
+__device__ __forceinline__ void quantize8(const u32x4& raw, float mn, float mx, uint32_t (&code)[8],
                                           _Float16& scale_h) {
 #pragma clang fp contract(off)
   constexpr float qmax = float((1 << BITS) - 1);
@@ -46,9 +65,9 @@ __device__ __forceinline__ void quantize8(const float (&x)[8], float mn, float m
   const float inv = recip_of_fp16_value(sc);            // == 1.0f / sc, bit for bit (exact_div.h)
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const float d = x[i] - mn;
-    float t = __builtin_rintf(d * inv);
-    t = fminf(fmaxf(t, 0.0f), qmax);
+    const h2 pair = as_h2(raw[i >> 1]);
+    const float d = __builtin_fmaf(static_cast<float>((i & 1) ? pair.y : pair.x), 1.0f, -mn);
+    const float t = __builtin_amdgcn_fmed3f(__builtin_rintf(d * inv), 0.0f, qmax);
     code[i] = static_cast<uint32_t>(t);
   }
 }
@@ -122,25 +141,19 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
       }
       continue;
     }
-    float x[8];
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const h2 v = as_h2(raw[k]);
-      x[2 * k] = static_cast<float>(v.x);
-      x[2 * k + 1] = static_cast<float>(v.y);
-    }
-    float mn = x[0], mx = x[0];
-#pragma unroll
-    for (int k = 1; k < 8; ++k) mn = fminf(mn, x[k]), mx = fmaxf(mx, x[k]);
-#pragma unroll
-    for (int o = 1; o < LPG; o <<= 1) {
-      mn = fminf(mn, __shfl_xor(mn, o));
-      mx = fmaxf(mx, __shfl_xor(mx, o));
-    }
-    if (mn == 0.0f) mn = 0.0f;   // a zero minimum is stored as +0
+    // min and max of the lane's 8 channels on the packed fp16 pairs (exact), then across the group's lanes
+    const h2 a = as_h2(raw[0]), b = as_h2(raw[1]), c2 = as_h2(raw[2]), d2 = as_h2(raw[3]);
+    const h2 mn2 = __builtin_elementwise_min(__builtin_elementwise_min(a, b), __builtin_elementwise_min(c2, d2));
+    const h2 mx2 = __builtin_elementwise_max(__builtin_elementwise_max(a, b), __builtin_elementwise_max(c2, d2));
+    float mn = fminf(static_cast<float>(mn2.x), static_cast<float>(mn2.y));
+    float mx = fmaxf(static_cast<float>(mx2.x), static_cast<float>(mx2.y));
+    mn = group_extreme<LPG, false>(mn);
+    mx = group_extreme<LPG, true>(mx);
+    if (mn == 0.0f) mn = 0.0f;   // zeros of either sign compare equal: a zero extreme is +0
+    if (mx == 0.0f) mx = 0.0f;
     uint32_t c[8];
     _Float16 scale_h;
-    if (cls == 0) quantize8<2>(x, mn, mx, c, scale_h); else quantize8<4>(x, mn, mx, c, scale_h);
+    if (cls == 0) quantize8<2>(raw, mn, mx, c, scale_h); else quantize8<4>(raw, mn, mx, c, scale_h);
     if ((seg & (LPG - 1)) == 0) {
       h2 m;
       m.x = scale_h;

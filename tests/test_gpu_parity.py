@@ -548,3 +548,41 @@ def test_decode_calls_replayed_from_a_captured_graph(rep):
         for o in outs:
             assert torch.allclose(o.float(), eager.float(), rtol=0, atol=2e-3 * float(eager.float().abs().max())), \
                 f"replay {replay} differs from the eager result"
+
+
+@pytest.mark.parametrize("rep", [1, 4])
+def test_quantizer_corner_groups_are_bit_exact(rep):
+    """Groups of signed zeros, a zero maximum over negative values, fp16 subnormals, the largest range:
+    the packed bytes still equal the oracle's (whose definition takes a zero extreme as +0)."""
+    w = workloads.small(f"corners_r{rep}", 1, 2 * rep, 2, [64 * 4 + 20], 64, 32, mix=(0.0, 0.5, 0.5), seed_offset=700 + rep)
+    _announce(w.name)
+    dev = _dev()
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = workloads.chunk_bits(w)
+    ks, vs = [], []
+    rng = np.random.default_rng(701)
+    for b in range(w.batch):
+        kh, vh = zip(*[workloads.kv_head(w, 0, b, h) for h in range(w.num_kv_heads)])
+        k, v = np.stack(kh).copy(), np.stack(vh).copy()
+        for x in (k, v):
+            t = x.shape[1]
+            x[:, 0:t:7, 0:32] = np.float16(0.0)                                  # all +0
+            x[:, 1:t:7, 0:32] = np.float16(-0.0)                                 # all -0
+            x[:, 2:t:7, 32:64] = np.where(rng.random(32) < 0.5, np.float16(0.0), np.float16(-0.0))   # mixed zeros
+            x[:, 3:t:7, 64:96] = -np.abs(x[:, 3:t:7, 64:96])                     # negative values ...
+            x[:, 3:t:7, 70] = np.float16(-0.0)                                   # ... with a zero maximum
+            x[:, 4:t:7, 96:128] = (rng.integers(-40, 40, size=32) * 2.0 ** -24).astype(np.float16)   # subnormals
+            x[:, 5:t:7, 0] = np.float16(65504.0)
+            x[:, 5:t:7, 1] = np.float16(-65504.0)                                # the largest range
+        ks.append(k), vs.append(v)
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), 4)
+    cache = ck.PackedCache(plan, dev)
+    k_flat = np.concatenate([x.reshape(-1, w.head_dim) for x in ks])
+    v_flat = np.concatenate([x.reshape(-1, w.head_dim) for x in vs])
+    ck.cocktail_reorder_quantize(cache, torch.from_numpy(k_flat).to(dev), torch.from_numpy(v_flat).to(dev), ragged=True)
+    torch.cuda.synchronize()
+    oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    v_quads = int(plan.sizes.v_layout) == 1
+    for c in range(3):
+        assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k")), f"K class {c}"
+        assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads)), f"V class {c}"
