@@ -44,13 +44,25 @@ __device__ __forceinline__ float group_extreme(float v) {
   return v;
 }
 
-// One token-group step of the quantizer on this lane's 8 channels (raw fp16 pairs).  Every operation is
-// a single IEEE binary32 operation with the result the definition asks for: x - mn is computed as
-// fma(f32(x), 1, -mn) straight from the fp16 operand (exact conversion, one rounding: the same value),
-// the clamp is a median of three.
+// f32(lo or hi half of w) - mn in one instruction: fma(f32(x), 1.0, -mn).  The conversion is exact and the
+// fma rounds once, so this is the binary32 difference of the definition, bit for bit.
+template <int HI>
+__device__ __forceinline__ float half_minus(uint32_t w, float mn) {
+  float d;
+  if constexpr (HI) {
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "v"(mn));
+  } else {
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "v"(mn));
+  }
+  return d;
+}
+
+// One token-group step of the quantizer on this lane's 8 channels (raw fp16 pairs).  Every operation
+// gives the result of the single IEEE binary32 operation the definition asks for (x - mn: see half_minus;
+// d * inv >= 0, so only the upper clamp can act).  The codes are returned as binary32 values, which are
+// exact small integers: they are packed arithmetically (pack4) and converted once per half-word.
 template <int BITS>
-__device__ __forceinline__ void quantize8(const u32x4& raw, float mn, float mx, uint32_t (&code)[8],
-                                          _Float16& scale_h) {
+__device__ __forceinline__ void quantize8(const u32x4& raw, float mn, float mx, float (&code)[8], _Float16& scale_h) {
 #pragma clang fp contract(off)
   constexpr float qmax = float((1 << BITS) - 1);
   const float r = mx - mn;
@@ -59,17 +71,24 @@ __device__ __forceinline__ void quantize8(const u32x4& raw, float mn, float mx, 
   const float sc = static_cast<float>(scale_h);
   if (sc == 0.0f) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) code[i] = 0;
+    for (int i = 0; i < 8; ++i) code[i] = 0.0f;
     return;
   }
   const float inv = recip_of_fp16_value(sc);            // == 1.0f / sc, bit for bit (exact_div.h)
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const h2 pair = as_h2(raw[i >> 1]);
-    const float d = __builtin_fmaf(static_cast<float>((i & 1) ? pair.y : pair.x), 1.0f, -mn);
-    const float t = __builtin_amdgcn_fmed3f(__builtin_rintf(d * inv), 0.0f, qmax);
-    code[i] = static_cast<uint32_t>(t);
+    const uint32_t w = raw[i >> 1];
+    const float d = (i & 1) ? half_minus<1>(w, mn) : half_minus<0>(w, mn);
+    code[i] = fminf(__builtin_rintf(d * inv), qmax);
   }
+}
+
+// a + b 2^BITS + c 2^(2 BITS) + d 2^(3 BITS) for codes held as binary32 integers: every intermediate is an
+// integer below 2^16, so the fused multiply-adds are exact and replace the shifts and ors of a bit-field pack.
+template <int BITS>
+__device__ __forceinline__ float pack4(float a, float b, float c, float d) {
+  constexpr float S = float(1 << BITS);
+  return __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(d, S, c), S, b), S, a);
 }
 
 template <int D, int G>
@@ -151,7 +170,7 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
     mx = group_extreme<LPG, true>(mx);
     if (mn == 0.0f) mn = 0.0f;   // zeros of either sign compare equal: a zero extreme is +0
     if (mx == 0.0f) mx = 0.0f;
-    uint32_t c[8];
+    float c[8];
     _Float16 scale_h;
     if (cls == 0) quantize8<2>(raw, mn, mx, c, scale_h); else quantize8<4>(raw, mn, mx, c, scale_h);
     if ((seg & (LPG - 1)) == 0) {
@@ -165,23 +184,24 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
       // a half-word holds consecutive channels of one token, lowest channel in the lowest bits
       if (cls == 1) {
         *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(2, 4, i, qh, qj, qe0)) =
-            uint16_t(c[0] | (c[1] << 4) | (c[2] << 8) | (c[3] << 12));
+            uint16_t(static_cast<uint32_t>(pack4<4>(c[0], c[1], c[2], c[3])));
         *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(2, 4, i, qh, qj, qe0 + 4)) =
-            uint16_t(c[4] | (c[5] << 4) | (c[6] << 8) | (c[7] << 12));
+            uint16_t(static_cast<uint32_t>(pack4<4>(c[4], c[5], c[6], c[7])));
       } else {
+        const float lo = pack4<2>(c[0], c[1], c[2], c[3]), hi = pack4<2>(c[4], c[5], c[6], c[7]);
         *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(1, 8, i, qh, qj, qe0)) =
-            uint16_t(c[0] | (c[1] << 2) | (c[2] << 4) | (c[3] << 6) | (c[4] << 8) | (c[5] << 10) | (c[6] << 12) |
-                     (c[7] << 14));
+            uint16_t(static_cast<uint32_t>(__builtin_fmaf(hi, 256.0f, lo)));
       }
     } else if (cls == 1) {
       // word = 8 channels: even channels in the low half-word, odd ones in the high half-word
-      const uint32_t w = c[0] | (c[2] << 4) | (c[4] << 8) | (c[6] << 12) | (c[1] << 16) | (c[3] << 20) |
-                         (c[5] << 24) | (c[7] << 28);
-      *reinterpret_cast<uint32_t*>(lds + ((seg >> 2) * kTB + i) * 16 + (seg & 3) * 4) = w;
+      const uint32_t even = static_cast<uint32_t>(pack4<4>(c[0], c[2], c[4], c[6]));
+      const uint32_t odd = static_cast<uint32_t>(pack4<4>(c[1], c[3], c[5], c[7]));
+      *reinterpret_cast<uint32_t*>(lds + ((seg >> 2) * kTB + i) * 16 + (seg & 3) * 4) = even | (odd << 16);
     } else {
       // word = 16 channels = two lanes; this lane holds fields 0..3 (even seg) or 4..7 (odd seg) of both half-words
-      const uint32_t mine = c[0] | (c[2] << 2) | (c[4] << 4) | (c[6] << 6) | (c[1] << 16) | (c[3] << 18) |
-                            (c[5] << 20) | (c[7] << 22);
+      const uint32_t even = static_cast<uint32_t>(pack4<2>(c[0], c[2], c[4], c[6]));
+      const uint32_t odd = static_cast<uint32_t>(pack4<2>(c[1], c[3], c[5], c[7]));
+      const uint32_t mine = even | (odd << 16);
       const uint32_t other = __shfl_xor(mine, 1);
       if ((seg & 1) == 0) {
         const uint32_t w = mine | (other << 8);
