@@ -69,12 +69,9 @@ __device__ __forceinline__ void quantize8(const u32x4& raw, float mn, float mx, 
   const float s32 = div_by_qmax<(1 << BITS) - 1>(r);   // == r / qmax, bit for bit (exact_div.h)
   scale_h = static_cast<_Float16>(s32);
   const float sc = static_cast<float>(scale_h);
-  if (sc == 0.0f) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) code[i] = 0.0f;
-    return;
-  }
-  const float inv = recip_of_fp16_value(sc);            // == 1.0f / sc, bit for bit (exact_div.h)
+  // scale == 0 (a constant group, or a range that underflows fp16): all codes are 0.  No branch: the
+  // differences are finite, and finite * 0 = 0.
+  const float inv = sc == 0.0f ? 0.0f : recip_of_fp16_value(sc);   // == 1.0f / sc, bit for bit (exact_div.h)
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const uint32_t w = raw[i >> 1];
