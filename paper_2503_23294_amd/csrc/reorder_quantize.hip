@@ -27,21 +27,49 @@ struct RQParams {
   int32_t cls_end0, cls_end1, cls_end2;  // prefix sums of class_blocks
 };
 
-// Minimum (or maximum) over a group of LPG = 4, 8 or 16 consecutive lanes, result in every lane of the
-// group.  Data-parallel-primitive operands: the neighbour's value arrives inside the min/max
-// instruction itself (quad permutes, then mirrors of 8 and 16 lanes, whose quads are already uniform).
-template <int CTRL>
-__device__ __forceinline__ float dpp(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
-}
-template <int LPG, bool MAX>
-__device__ __forceinline__ float group_extreme(float v) {
-  auto pick = [](float a, float b) { return MAX ? fmaxf(a, b) : fminf(a, b); };
-  v = pick(v, dpp<0xB1>(v));                            // quad_perm [1,0,3,2]
-  v = pick(v, dpp<0x4E>(v));                            // quad_perm [2,3,0,1]
-  if constexpr (LPG >= 8) v = pick(v, dpp<0x141>(v));   // row_half_mirror
-  if constexpr (LPG >= 16) v = pick(v, dpp<0x140>(v));  // row_mirror
-  return v;
+// min (or max) of v and a neighbour lane's v in one instruction: the neighbour's value arrives as a
+// data-parallel-primitive operand.  The s_nop covers the wait states such an operand needs after the
+// instruction that wrote it (the compiler cannot see into the asm).
+#define COCKTAIL_DPP_MINMAX(NAME, OP, CTRL)                                                              \
+  __device__ __forceinline__ float NAME(float v) {                                                     \
+    float r;                                                                                           \
+    asm("s_nop 1\n\t" OP " %0, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));         \
+    return r;                                                                                          \
+  }
+COCKTAIL_DPP_MINMAX(min_xor1, "v_min_f32_dpp", "quad_perm:[1,0,3,2]")
+COCKTAIL_DPP_MINMAX(min_xor2, "v_min_f32_dpp", "quad_perm:[2,3,0,1]")
+COCKTAIL_DPP_MINMAX(min_mirror8, "v_min_f32_dpp", "row_half_mirror")
+COCKTAIL_DPP_MINMAX(min_mirror16, "v_min_f32_dpp", "row_mirror")
+COCKTAIL_DPP_MINMAX(max_xor1, "v_max_f32_dpp", "quad_perm:[1,0,3,2]")
+COCKTAIL_DPP_MINMAX(max_xor2, "v_max_f32_dpp", "quad_perm:[2,3,0,1]")
+COCKTAIL_DPP_MINMAX(max_mirror8, "v_max_f32_dpp", "row_half_mirror")
+COCKTAIL_DPP_MINMAX(max_mirror16, "v_max_f32_dpp", "row_mirror")
+#undef COCKTAIL_DPP_MINMAX
+
+// Minimum and maximum of the 8 fp16 channels in `raw`, then over the group of LPG = 4, 8 or 16 consecutive
+// lanes (quad permutes, then mirrors of 8 and 16 lanes, whose quads are already uniform); every lane of the
+// group ends up with both.  Packed fp16 min/max are exact; zeros of either sign compare equal, so a zero
+// extreme is returned as +0 (x + 0 is x, and -0 + 0 is +0).
+template <int LPG>
+__device__ __forceinline__ void group_min_max(const u32x4& raw, float& mn, float& mx) {
+  uint32_t lo01, lo23, hi01, hi23, lo, hi;
+  asm("v_pk_min_f16 %0, %1, %2" : "=v"(lo01) : "v"(raw[0]), "v"(raw[1]));
+  asm("v_pk_min_f16 %0, %1, %2" : "=v"(lo23) : "v"(raw[2]), "v"(raw[3]));
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(hi01) : "v"(raw[0]), "v"(raw[1]));
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(hi23) : "v"(raw[2]), "v"(raw[3]));
+  asm("v_pk_min_f16 %0, %1, %2" : "=v"(lo) : "v"(lo01), "v"(lo23));
+  asm("v_pk_max_f16 %0, %1, %2" : "=v"(hi) : "v"(hi01), "v"(hi23));
+  // low result half = min(low half, high half) of the pair
+  asm("v_pk_min_f16 %0, %1, %1 op_sel:[0,1] op_sel_hi:[1,0]" : "=v"(lo) : "v"(lo));
+  asm("v_pk_max_f16 %0, %1, %1 op_sel:[0,1] op_sel_hi:[1,0]" : "=v"(hi) : "v"(hi));
+  mn = static_cast<float>(as_h2(lo).x);
+  mx = static_cast<float>(as_h2(hi).x);
+  mn = min_xor2(min_xor1(mn));
+  mx = max_xor2(max_xor1(mx));
+  if constexpr (LPG >= 8) mn = min_mirror8(mn), mx = max_mirror8(mx);
+  if constexpr (LPG >= 16) mn = min_mirror16(mn), mx = max_mirror16(mx);
+  mn += 0.0f;
+  mx += 0.0f;
 }
 
 // f32(lo or hi half of w) - mn in one instruction: fma(f32(x), 1.0, -mn).  The conversion is exact and the
@@ -88,11 +116,64 @@ __device__ __forceinline__ float pack4(float a, float b, float c, float d) {
   return __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(d, S, c), S, b), S, a);
 }
 
+// Quantizes this thread's four rows (8 channels each) and writes codes and scale/zero pairs into the block
+// image in shared memory (row form, or token quads for V where the cache stores V that way).
+template <int BITS, int G, class LoadRow>
+__device__ __forceinline__ void quantize_rows(LoadRow load_row, char* lds, int row, int seg, bool quads,
+                                              int meta_base) {
+  constexpr int LPG = G / 8;   // lanes per group
+  constexpr int NG = 128 / G;
+  const int qh = seg >> 3, qj = seg & 3, qe0 = 8 * ((seg >> 2) & 1);
+  const bool writes_meta = (seg & (LPG - 1)) == 0;
+  char* const meta0 = lds + meta_base + (row * NG + seg / LPG) * 4;
+  // row form: INT4 has one word per lane; INT2 one word per lane pair, written by the even lane
+  const int word = BITS == 4 ? seg : seg >> 1;
+  char* const row0 = lds + ((word >> 2) * kTB + row) * 16 + (word & 3) * 4;
+  // token quads: one half-word per 16 / BITS channels
+  char* const quad0 = lds + quad_halfword_offset(BITS == 4 ? 2 : 1, 16 / BITS, row, qh, qj, qe0);
+  char* const quad1 = lds + quad_halfword_offset(2, 4, row, qh, qj, qe0 + 4);   // INT4: channels 4..7
+#pragma unroll
+  for (int pass = 0; pass < 4; ++pass) {
+    const u32x4 raw = load_row(pass);
+    float mn, mx;
+    group_min_max<LPG>(raw, mn, mx);
+    float c[8];
+    _Float16 scale_h;
+    quantize8<BITS>(raw, mn, mx, c, scale_h);
+    if (writes_meta) {
+      h2 m;
+      m.x = scale_h;
+      m.y = static_cast<_Float16>(mn);
+      *reinterpret_cast<uint32_t*>(meta0 + pass * (16 * NG * 4)) = as_u32(m);
+    }
+    if (quads) {
+      // a half-word holds consecutive channels of one token, lowest channel in the lowest bits
+      if constexpr (BITS == 4) {
+        *reinterpret_cast<uint16_t*>(quad0 + pass * 256) = uint16_t(static_cast<uint32_t>(pack4<4>(c[0], c[1], c[2], c[3])));
+        *reinterpret_cast<uint16_t*>(quad1 + pass * 256) = uint16_t(static_cast<uint32_t>(pack4<4>(c[4], c[5], c[6], c[7])));
+      } else {
+        const float lo = pack4<2>(c[0], c[1], c[2], c[3]), hi = pack4<2>(c[4], c[5], c[6], c[7]);
+        *reinterpret_cast<uint16_t*>(quad0 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(hi, 256.0f, lo)));
+      }
+    } else {
+      // row form: even channels in the low half-word, odd ones in the high half-word
+      const uint32_t even = static_cast<uint32_t>(pack4<BITS>(c[0], c[2], c[4], c[6]));
+      const uint32_t odd = static_cast<uint32_t>(pack4<BITS>(c[1], c[3], c[5], c[7]));
+      const uint32_t mine = even | (odd << 16);
+      if constexpr (BITS == 4) {
+        *reinterpret_cast<uint32_t*>(row0 + pass * 256) = mine;   // word = 8 channels
+      } else {
+        // word = 16 channels = two lanes: fields 0..3 of both half-words from the even lane, 4..7 from the odd one
+        const uint32_t other = __shfl_xor(mine, 1);
+        if ((seg & 1) == 0) *reinterpret_cast<uint32_t*>(row0 + pass * 256) = mine | (other << 8);
+      }
+    }
+  }
+}
+
 template <int D, int G>
 __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   static_assert(D == 128, "one 16-lane row of 8 channels per lane");
-  constexpr int LPG = G / 8;   // lanes per group
-  constexpr int NG = D / G;
   __shared__ __attribute__((aligned(16))) char lds[kTB * 2 * D];
 
   const int which = blockIdx.y;  // 0 = K, 1 = V
@@ -123,16 +204,14 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
 
   const int tid = threadIdx.x;
   const int seg = tid & 15;        // 8 channels seg*8 .. seg*8+7
-  // token-quad form of V: this thread's channels are those of lane qj of a quad in the 64-channel half qh,
-  // its e-th channels for e = qe0 .. qe0+7
-  const bool quads = which == 1 && p.v_quads != 0;
-  const int qh = seg >> 3, qj = seg & 3, qe0 = 8 * ((seg >> 2) & 1);
+  const int row = tid >> 4;        // this thread's rows of the block: row, row + 16, row + 32, row + 48
+  const bool quads = which == 1 && p.v_quads != 0;   // token-quad form of V
   const int row_bytes = (cls == 0) ? D / 4 : (cls == 1) ? D / 2 : 2 * D;
 
-#pragma unroll
-  for (int pass = 0; pass < 4; ++pass) {
-    const int i = pass * 16 + (tid >> 4);
-    u32x4 raw = {0u, 0u, 0u, 0u};
+  // row `pass * 16 + row` of the block, 8 channels of it (zeros past the last valid row)
+  auto load_row = [&](int pass) {
+    const int i = pass * 16 + row;
+    u32x4 v = {0u, 0u, 0u, 0u};
     if (i < nvalid) {
       int t = i;                        // relative to row 0 of the block
       if (t0 < 0) {
@@ -144,9 +223,21 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
           t = N * C + (r - chunk_tokens);   // Sec. III-A: tail tokens follow the FP16 chunks
         }
       }
-      raw = RQ_LOAD(reinterpret_cast<const u32x4*>(src + int64_t(t) * p.stride_t + seg * 8));
+      v = RQ_LOAD(reinterpret_cast<const u32x4*>(src + int64_t(t) * p.stride_t + seg * 8));
     }
-    if (cls == 2) {
+    return v;
+  };
+
+  // Where this thread's results go inside the block image in shared memory; every address is that of
+  // row `row` plus a fixed step per pass (16 rows further: 256 bytes in every piece, 16 meta rows).
+  // Token quads: the thread's channels are those of lane qj of a quad in the 64-channel half qh, its e-th
+  // channels for e = qe0 .. qe0+7.
+  const int qh = seg >> 3, qj = seg & 3, qe0 = 8 * ((seg >> 2) & 1);
+  if (cls == 2) {
+#pragma unroll
+    for (int pass = 0; pass < 4; ++pass) {
+      const int i = pass * 16 + row;
+      const u32x4 raw = load_row(pass);
       if (quads) {
 #pragma unroll
         for (int x = 0; x < 8; ++x)
@@ -155,57 +246,11 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
       } else {
         *reinterpret_cast<u32x4*>(lds + (seg * kTB + i) * 16) = raw;
       }
-      continue;
     }
-    // min and max of the lane's 8 channels on the packed fp16 pairs (exact), then across the group's lanes
-    const h2 a = as_h2(raw[0]), b = as_h2(raw[1]), c2 = as_h2(raw[2]), d2 = as_h2(raw[3]);
-    const h2 mn2 = __builtin_elementwise_min(__builtin_elementwise_min(a, b), __builtin_elementwise_min(c2, d2));
-    const h2 mx2 = __builtin_elementwise_max(__builtin_elementwise_max(a, b), __builtin_elementwise_max(c2, d2));
-    float mn = fminf(static_cast<float>(mn2.x), static_cast<float>(mn2.y));
-    float mx = fmaxf(static_cast<float>(mx2.x), static_cast<float>(mx2.y));
-    mn = group_extreme<LPG, false>(mn);
-    mx = group_extreme<LPG, true>(mx);
-    if (mn == 0.0f) mn = 0.0f;   // zeros of either sign compare equal: a zero extreme is +0
-    if (mx == 0.0f) mx = 0.0f;
-    float c[8];
-    _Float16 scale_h;
-    if (cls == 0) quantize8<2>(raw, mn, mx, c, scale_h); else quantize8<4>(raw, mn, mx, c, scale_h);
-    if ((seg & (LPG - 1)) == 0) {
-      h2 m;
-      m.x = scale_h;
-      m.y = static_cast<_Float16>(mn);
-      const int g = seg / LPG;
-      *reinterpret_cast<uint32_t*>(lds + kTB * row_bytes + (i * NG + g) * 4) = as_u32(m);
-    }
-    if (quads) {
-      // a half-word holds consecutive channels of one token, lowest channel in the lowest bits
-      if (cls == 1) {
-        *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(2, 4, i, qh, qj, qe0)) =
-            uint16_t(static_cast<uint32_t>(pack4<4>(c[0], c[1], c[2], c[3])));
-        *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(2, 4, i, qh, qj, qe0 + 4)) =
-            uint16_t(static_cast<uint32_t>(pack4<4>(c[4], c[5], c[6], c[7])));
-      } else {
-        const float lo = pack4<2>(c[0], c[1], c[2], c[3]), hi = pack4<2>(c[4], c[5], c[6], c[7]);
-        *reinterpret_cast<uint16_t*>(lds + quad_halfword_offset(1, 8, i, qh, qj, qe0)) =
-            uint16_t(static_cast<uint32_t>(__builtin_fmaf(hi, 256.0f, lo)));
-      }
-    } else if (cls == 1) {
-      // word = 8 channels: even channels in the low half-word, odd ones in the high half-word
-      const uint32_t even = static_cast<uint32_t>(pack4<4>(c[0], c[2], c[4], c[6]));
-      const uint32_t odd = static_cast<uint32_t>(pack4<4>(c[1], c[3], c[5], c[7]));
-      *reinterpret_cast<uint32_t*>(lds + ((seg >> 2) * kTB + i) * 16 + (seg & 3) * 4) = even | (odd << 16);
-    } else {
-      // word = 16 channels = two lanes; this lane holds fields 0..3 (even seg) or 4..7 (odd seg) of both half-words
-      const uint32_t even = static_cast<uint32_t>(pack4<2>(c[0], c[2], c[4], c[6]));
-      const uint32_t odd = static_cast<uint32_t>(pack4<2>(c[1], c[3], c[5], c[7]));
-      const uint32_t mine = even | (odd << 16);
-      const uint32_t other = __shfl_xor(mine, 1);
-      if ((seg & 1) == 0) {
-        const uint32_t w = mine | (other << 8);
-        const int word = seg >> 1;
-        *reinterpret_cast<uint32_t*>(lds + ((word >> 2) * kTB + i) * 16 + (word & 3) * 4) = w;
-      }
-    }
+  } else if (cls == 0) {
+    quantize_rows<2, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
+  } else {
+    quantize_rows<4, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
   }
   __syncthreads();
   constexpr int NGc = D / G;
