@@ -208,13 +208,17 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   const bool quads = which == 1 && p.v_quads != 0;   // token-quad form of V
   const int row_bytes = (cls == 0) ? D / 4 : (cls == 1) ? D / 2 : 2 * D;
 
-  // row `pass * 16 + row` of the block, 8 channels of it (zeros past the last valid row)
+  // row `pass * 16 + row` of the block, 8 channels of it (zeros past the last valid row).  Consecutive
+  // source rows (almost every block): one pointer per thread and a fixed step per pass.
+  const _Float16* const row_ptr = src + int64_t(row) * p.stride_t + seg * 8;
+  const int64_t pass_step = 16 * p.stride_t;
   auto load_row = [&](int pass) {
     const int i = pass * 16 + row;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (i < nvalid) {
-      int t = i;                        // relative to row 0 of the block
+      const _Float16* ptr = row_ptr + pass * pass_step;
       if (t0 < 0) {
+        int t;
         const int r = j * kTB + i;      // row inside the class run of (b, h)
         if (r < chunk_tokens) {
           const int slot = r / C;
@@ -222,8 +226,9 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
         } else {
           t = N * C + (r - chunk_tokens);   // Sec. III-A: tail tokens follow the FP16 chunks
         }
+        ptr = src + int64_t(t) * p.stride_t + seg * 8;
       }
-      v = RQ_LOAD(reinterpret_cast<const u32x4*>(src + int64_t(t) * p.stride_t + seg * 8));
+      v = RQ_LOAD(reinterpret_cast<const u32x4*>(ptr));
     }
     return v;
   };
