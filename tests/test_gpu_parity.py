@@ -586,3 +586,31 @@ def test_quantizer_corner_groups_are_bit_exact(rep):
     for c in range(3):
         assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k")), f"K class {c}"
         assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads)), f"V class {c}"
+
+
+def _random_case(seed):
+    """A random small workload: any supported head ratio, group size, chunk size, batch, lengths, mix, workers."""
+    rng = np.random.default_rng(9000 + seed)
+    rep = int(rng.choice([1, 1, 2, 3, 4, 4, 5, 6, 8]))
+    hkv = int(rng.integers(1, 4))
+    batch = int(rng.integers(1, 5))
+    group = int(rng.choice([32, 64, 128]))
+    chunk = int(rng.choice([8, 32, 64, 100, 256]))
+    lens = [int(x) for x in rng.integers(0, 2500, size=batch)]
+    if rng.random() < 0.3:
+        lens[int(rng.integers(0, batch))] = int(rng.integers(0, chunk))      # a tail-only (or empty) sequence
+    mix = rng.dirichlet([1.0, 1.0, 1.0])
+    if rng.random() < 0.25:
+        mix = np.eye(3)[int(rng.integers(0, 3))]                              # a single class
+    workers = int(rng.choice([1, 2, 5, 8, 16, 33, 64, 200]))
+    w = workloads.small(f"fuzz{seed}", batch, hkv * rep, hkv, lens, chunk, group, mix=tuple(float(x) for x in mix),
+                        seed_offset=9000 + seed)
+    return w, workers
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(seed):
+    w, workers = _random_case(seed)
+    _announce(f"{w.name}: B={w.batch} Hq={w.num_q_heads} Hkv={w.num_kv_heads} G={w.group_size} C={w.chunk_size} "
+              f"T={list(w.seq_lens)} mix={[round(m, 2) for m in w.mix]} workers={workers}")
+    Case(w, workers=workers).check_all()
