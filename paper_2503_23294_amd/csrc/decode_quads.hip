@@ -146,12 +146,21 @@ struct QuadQuant : QuantClass<BITS, G> {
   // p: the softmax weights of this lane's token for the four heads
   __device__ static __forceinline__ void accumulate(const Stage& s, f4 p, QuadState<NGH>& st, u32x2 ident) {
     u32x2 pa[NGH];   // lane = head: p_t scale_tg of the quad's four tokens
+    // The weights go to the matrix unit rounded to fp16: x -> xr.  sum_t xr_t code_t is off by
+    // sum_t (xr_t - x_t) code_t; adding c0 sum_t (x_t - xr_t), a constant per group like the zero term, leaves
+    // sum_t (xr_t - x_t)(code_t - c0), and c0 = qmax / 2 centres the codes, which halves the bound.
+    constexpr float c0 = 0.5f * float((1 << BITS) - 1);
 #pragma unroll
     for (int g = 0; g < NGH; ++g) {
       const h2 mz = as_h2(s.meta[g]);
-      st.zacc[g] += static_cast<float>(mz.y) * p;
-      const f4 x = static_cast<float>(mz.x) * p;
-      pa[g] = to_h4(mfma4(to_h4(x), ident, splat(0.f)));
+      const float sc = static_cast<float>(mz.x);
+      const u32x2 x16 = to_h4(sc * p);
+      const h2 r01 = as_h2(x16.x), r23 = as_h2(x16.y);
+      // zero_t p_t + c0 (x_t - xr_t) with x_t = scale_t p_t:  (zero_t + c0 scale_t) p_t - c0 xr_t
+      st.zacc[g] += (static_cast<float>(mz.y) + c0 * sc) * p;
+      st.zacc[g][0] -= c0 * static_cast<float>(r01.x), st.zacc[g][1] -= c0 * static_cast<float>(r01.y);
+      st.zacc[g][2] -= c0 * static_cast<float>(r23.x), st.zacc[g][3] -= c0 * static_cast<float>(r23.y);
+      pa[g] = to_h4(mfma4(x16, ident, splat(0.f)));
     }
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
