@@ -1,6 +1,7 @@
-// Decode side of Alg. 1 (Sec. III-C) when 2 to 4 query heads share a kv head (grouped-query attention).
+// Decode side of Alg. 1 (Sec. III-C) when 2 to 8 query heads share a kv head (grouped-query attention).
 //
-// One wave serves all query heads of its kv head, so every K/V byte is fetched and unpacked once.  The
+// One wave serves up to four query heads of its kv head (5 to 8 heads: two waves per workgroup, one per
+// four heads), so with up to four heads every K/V byte is fetched and unpacked once.  The
 // per-token work is a small dense contraction (4 heads x 128 channels), done with the 4x4x4 fp16 matrix
 // instruction, which multiplies sixteen independent 4x4 blocks, one per quad of lanes:
 //     D[i][j] += sum_k A[i][k] * B[k][j]     lane 4b+i holds row i of A, lane 4b+j column j of B and of D.
