@@ -342,8 +342,9 @@ def test_many_calls_with_changing_ticket_order_all_agree():
     _announce(f"{w.name}: largest deviation between calls {worst:.2e}")
 
 
-def test_reproducible_plan_gives_bitwise_identical_results():
-    w = workloads.small("repro", 2, 2, 2, [6000, 3000], 64, 64, mix=(0.2, 0.4, 0.4), seed_offset=88)
+@pytest.mark.parametrize("rep", [1, 4, 8])
+def test_reproducible_plan_gives_bitwise_identical_results(rep):
+    w = workloads.small(f"repro_r{rep}", 2, 2 * rep, 2, [6000, 3000], 64, 64, mix=(0.2, 0.4, 0.4), seed_offset=88)
     _announce(w.name)
     dev = _dev()
     shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
