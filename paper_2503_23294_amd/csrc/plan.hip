@@ -44,8 +44,12 @@ int check_shape(const cocktail_shape* s) {
 constexpr int64_t kCostWeightInt2 = 1150, kCostWeightInt4 = 1300, kCostWeightFp16 = 530;
 // The same for the kernel that serves four query heads per wave: its arithmetic runs on the matrix unit.
 constexpr int64_t kQuadCostWeightInt2 = 1300, kQuadCostWeightInt4 = 1250, kQuadCostWeightFp16 = 450;
-// Workers per group and the share of a group's cost that goes into its shared pool.
-constexpr int kGroupWorkers = 8;
+// Workers per group.  Measured on MI355X: with one query head per kv head 4 to 8 are equal on long
+// ranges (8 a hair ahead at 128K), 5 to 6 clearly best on short ones (32K: 33.2 against 35.9 us); the
+// grouped-query kernel likes 4.
+constexpr int kGroupWorkers = 8, kGroupWorkersShort = 6, kQuadGroupWorkers = 4;
+constexpr int kLongRangeBlocks = 24;   // average blocks per worker from which a range counts as long
+// The share of a group's cost that goes into its shared pool.
 constexpr int kPoolPercent = 25;
 constexpr int kPairMode = 0;
 constexpr int kLayout = 0;
@@ -67,7 +71,7 @@ struct Tuning {
   bool weight_set = false;
   int pool_percent = kPoolPercent;      // COCKTAIL_POOL_PERCENT   0..100
   bool pool_percent_set = false;        // the environment fixed the share for every group
-  int group_workers = kGroupWorkers;    // COCKTAIL_GROUP_WORKERS  1..1024
+  int group_workers = 0;                // COCKTAIL_GROUP_WORKERS  1..1024; 0 = the default for the kernel that will run
   bool pair_speed = true;               // COCKTAIL_PAIR_SPEED     0 | 1
   int layout = kLayout;                 // COCKTAIL_LAYOUT         0 | 1
   int pair_mode = kPairMode;            // COCKTAIL_PAIR_MODE      0 | 2 | 3
@@ -192,7 +196,6 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   // Measured on MI355X with all three classes running side by side.
   Tuning tune = read_tuning();
   int pool_percent = tune.pool_percent;
-  const int group_workers = tune.group_workers;
   const int rep = shape->num_q_heads / Hkv;
   // 2 to 4 query heads per kv head are served by one wave (token-quad form of V); beyond that the query
   // heads run as two or more waves of one workgroup on the same blocks, where a pool would need a ticket
@@ -219,6 +222,9 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
       }
   int64_t tot_blocks = class_nblk[0] + class_nblk[1] + class_nblk[2];
   if (tot_blocks >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "more than 2^31 blocks in one call");
+  const int group_workers = tune.group_workers > 0 ? tune.group_workers
+                            : quads                ? kQuadGroupWorkers
+                            : tot_blocks >= int64_t(kLongRangeBlocks) * P ? kGroupWorkers : kGroupWorkersShort;
 
   // ---- global order and segments ----
   // The workers form groups of `group_workers`; group j works on one stripe [cut[c][j], cut[c][j+1]) of

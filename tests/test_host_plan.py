@@ -186,7 +186,7 @@ def test_planner_matches_oracle_and_splits_work_exactly_once(cfg, workers):
     if cfg == 4:
         # the headline shape has pools: a fifth of the bytes, the rest in near-equal own ranges
         total = cost.sum() + pool_cost
-        assert 0.15 * total <= pool_cost <= 0.25 * total and h["groups"] == 256
+        assert 0.15 * total <= pool_cost <= 0.25 * total and h["groups"] == 256   # long ranges: groups of eight
 
 
 @pytest.mark.parametrize("env", [{"COCKTAIL_POOL_PERCENT": "100"}, {"COCKTAIL_POOL_PERCENT": "0"},
