@@ -83,7 +83,8 @@ typedef enum cocktail_status {
   COCKTAIL_EUNSUPPORTED = -2, /* valid request this build has no kernel for                    */
   COCKTAIL_EALIGN = -3,       /* a device pointer is not 16-byte aligned                       */
   COCKTAIL_ENOSPACE = -4,     /* plan or workspace buffer smaller than required                */
-  COCKTAIL_EHIP = -5          /* the HIP runtime reported an error at launch                   */
+  COCKTAIL_EHIP = -5,         /* the HIP runtime reported an error at launch                   */
+  COCKTAIL_ESTATE = -6        /* cocktail_decode_check: the last decode call did not attend to every token once */
 } cocktail_status;
 
 /* Geometry of one attention layer call.  group_size divides head_dim. */
@@ -121,7 +122,8 @@ typedef struct cocktail_cache {
   void* v[COCKTAIL_NUM_CLASSES]; /* DEVICE, same sizes                                                     */
   const void* plan_host;         /* HOST   plan blob written by cocktail_plan                              */
   void* plan_dev;                /* DEVICE byte-for-byte copy of the plan blob, 16-byte aligned; also holds
-                                    the decode kernel's ticket counters (see cocktail_decode_attention)    */
+                                    the decode kernel's ticket counters, the only part kernels write
+                                    (see cocktail_decode_attention)                                        */
   void* k_app;                   /* DEVICE append_bytes each, 256-byte aligned: K/V rows of the tokens     */
   void* v_app;                   /*        generated during decoding; NULL iff append_capacity == 0         */
   int32_t num_appended;          /* tokens appended so far to every sequence, 0 .. append_capacity         */
@@ -129,7 +131,7 @@ typedef struct cocktail_cache {
 } cocktail_cache;
 
 /*
- * Host-only planning step (Alg. 1, prefill loop, lines "for i in range(N): ... append").
+ * Host-only planning step (Alg. 1, prefill loop).
  * Computes the stable partition of every sequence's chunks by bitwidth, the token
  * count of every class (the FP16 class also receives the T_b mod C tail tokens,
  * Sec. III-A), the block layout of the packed cache and the static split of the
@@ -204,7 +206,11 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  * The counters are zero in the blob cocktail_plan writes and every call leaves
  * them zero again, so calls on the same plan_dev must not overlap in time (calls
  * on one stream never do), and a plan_dev whose call was aborted has to be
- * re-uploaded.  Which worker takes which pool piece differs from call to call, so
+ * re-uploaded.  A call that breaks this rule is not silently wrong: every partial
+ * state records how many tokens it covers, the merge compares their sum with the
+ * token count of the sequence, and a (sequence, query head) row that does not add
+ * up gets NaN in out and lse and a non-zero status word (cocktail_decode_check);
+ * the call after it finds the counters at zero again.  Which worker takes which pool piece differs from call to call, so
  * two calls on the same inputs agree to fp32 summation order, not bit for bit
  * (shapes with Hq/Hkv > 4 use no pools and are reproducible bit for bit, and so is any plan made with
  * cocktail_plan_options::reproducible).  Shapes with Hq = Hkv run one query head per wave on the vector
@@ -217,8 +223,9 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
  *   lse        DEVICE fp32 [B][Hq] natural-log-sum-exp of the scaled logits
  *              (-inf for an empty sequence), or NULL
  *   workspace  DEVICE, workspace_bytes >= sizes.workspace_bytes, 16-byte aligned;
- *              contents need not be initialised and are overwritten.  Calls that
- *              share a workspace must not overlap in time.
+ *              contents need not be initialised and are overwritten (partial states,
+ *              then one status word per (sequence, query head)).  Calls that share a
+ *              workspace must not overlap in time.
  *
  * The packed K/V data is not modified.  Errors: EINVAL, EUNSUPPORTED (head_dim != 128,
  * Hq/Hkv > COCKTAIL_MAX_Q_PER_KV), EALIGN, ENOSPACE, EHIP.
@@ -226,6 +233,20 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
 int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
                               float sm_scale, void* out, float* lse, void* workspace,
                               size_t workspace_bytes, void* stream);
+
+/*
+ * Diagnostic: waits for `stream`, then reads the status words the last decode call on `workspace` left
+ * (the only entry point that synchronises and copies).  The softmax of Alg. 1's decode phase runs over the
+ * concatenation of all three classes, i.e. over every token of the sequence exactly once; the status word
+ * of a (sequence, query head) is the number of tokens its partial states covered minus the sequence length.
+ *
+ *   workspace  DEVICE, the workspace of that call
+ *
+ * Returns COCKTAIL_OK if every word is zero, else COCKTAIL_ESTATE with a message naming the first bad row
+ * (see cocktail_decode_attention for the causes).  Other errors: EINVAL, EHIP.
+ */
+int cocktail_decode_check(const cocktail_shape* shape, const cocktail_cache* cache, const void* workspace,
+                          void* stream);
 
 /*
  * Sec. III-A: stores the K/V rows of one generated token per sequence, in FP16, as token `position`
@@ -295,6 +316,14 @@ int cocktail_stream_read_probe(const void* buf, size_t bytes, void* sink, size_t
  * Two kernel launches (about a millisecond).  Errors: EINVAL, EALIGN, EHIP.
  */
 int cocktail_selftest_arithmetic(uint64_t* mismatches, void* stream);
+
+/*
+ * Debugging aid: value of one field of the plan header (the internal layout of the blob cocktail_plan writes),
+ * by the name it has in the library's source, e.g. "off_counters", "num_groups", "class_blocks" (index =
+ * class), plus a few constants of the layout ("counter_stride_bytes", "iter_units", "sizeof_worker_rec", ...).
+ * Errors: EINVAL (not a plan of this library version, unknown name, index out of range).
+ */
+int cocktail_plan_field(const void* plan_host, const char* name, int32_t index, int64_t* value);
 
 /* Message of the last failure on the calling thread ("" if none).  Static storage. */
 const char* cocktail_last_error(void);

@@ -66,12 +66,11 @@ def plan_sequence(seq_len: int, chunk_size: int, bits: np.ndarray) -> SeqPlan:
     n = seq_len // chunk_size
     bits = np.asarray(bits)
     assert bits.shape == (n,)
-    lists: List[List[int]] = [[], [], []]
-    for i in range(n):                       # "for i in range(N)": append chunk i to its list
-        lists[class_of_bits(bits[i])].append(i)
-    perm = np.array(lists[0] + lists[1] + lists[2], dtype=np.int32)
+    # a stable partition by class: INT2 chunks first, then INT4, then FP16, each in original order
+    cls = np.array([class_of_bits(x) for x in bits], dtype=np.int64)
+    perm = np.argsort(cls, kind="stable").astype(np.int32)
     tail = seq_len - n * chunk_size          # Sec. III-A: remainder kept in FP16
-    cc = (len(lists[0]), len(lists[1]), len(lists[2]))
+    cc = tuple(int((cls == c).sum()) for c in range(3))
     ct = (cc[0] * chunk_size, cc[1] * chunk_size, cc[2] * chunk_size + tail)
     return SeqPlan(perm, cc, ct, tail)
 

@@ -68,6 +68,13 @@ def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[in
     return Plan(shape, sizes, blob, ct, perm[:int(sizes.total_chunks)], sl)
 
 
+def cocktail_plan_field(plan: Plan, name: str, index: int = 0) -> int:
+    """Debugging aid: one field of the plan's internal header, by its name in the library's source."""
+    v = C.c_int64(0)
+    check(lib().cocktail_plan_field(plan.blob.ctypes.data, name.encode(), int(index), C.byref(v)))
+    return int(v.value)
+
+
 class PackedCache:
     """Device buffers of one layer's packed cache plus the ctypes descriptor handed to the library."""
 
@@ -153,6 +160,13 @@ def cocktail_decode_attention(cache: PackedCache, q: torch.Tensor, sm_scale: flo
                                           out.data_ptr(), lse.data_ptr(), cache.workspace.data_ptr(),
                                           cache.workspace.numel(), _stream_ptr(stream)))
     return out, lse
+
+
+def cocktail_decode_check(cache: PackedCache, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Waits for the stream and raises CocktailError (code -6) if the last decode call on this cache's
+    workspace did not attend to every token exactly once."""
+    check(lib().cocktail_decode_check(C.byref(cache.plan.shape), C.byref(cache.desc), cache.workspace.data_ptr(),
+                                      _stream_ptr(stream)))
 
 
 def cocktail_stream_read_probe(buf: torch.Tensor, sink: torch.Tensor,

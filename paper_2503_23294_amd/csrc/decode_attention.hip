@@ -35,6 +35,7 @@
 
 #include <cmath>
 #include <cstdlib>
+#include <vector>
 
 #include "decode_common.h"
 
@@ -69,9 +70,9 @@ __device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J],
   }
 }
 
-// Writes this wave's partial state `pid`: (m, l, o[D]) reduced over its lanes.
+// Writes this wave's partial state `pid`: (m, l, o[D]) reduced over its lanes, and the number of tokens it covers.
 template <int NGH, int GL>
-__device__ __forceinline__ void flush_partial(const LaneState<NGH>& st, float* red, int pid, int r, int lane) {
+__device__ __forceinline__ void flush_partial(const LaneState<NGH>& st, float* red, int pid, int r, int lane, int tokens) {
   kparams_t prm = kparams();
   const int rep = prm->rep;
   float mw = st.m;
@@ -85,6 +86,7 @@ __device__ __forceinline__ void flush_partial(const LaneState<NGH>& st, float* r
   if (lane == 0) {
     out[0] = mw;
     out[1] = lw;
+    out[2] = __int_as_float(tokens);
   }
   float(*tile)[17] = reinterpret_cast<float(*)[17]>(red + r * 64 * 17);
 #pragma unroll
@@ -174,6 +176,7 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
   sched_fence();
   begin_state<NGH, GL>(sm.qrow + r, h, st, q, qsum);   // the query arrives while the first units are on their way
   int valid = cur.valid;
+  int covered = 0;   // tokens the current partial state covers (the merge checks the total per sequence)
   Piece nxt = sm.next(lane);
 #pragma unroll 1
   while (true) {
@@ -185,6 +188,7 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
     } else {
       rn = 0;   // nothing follows in this class: every refill goes out of range
     }
+    covered += valid;
     float s[J], p[J];
 #pragma unroll
     for (int jj = 0; jj < J; ++jj) {
@@ -206,10 +210,11 @@ __device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, in
       CLS::template load<AUX>(vs[jj], vrs, jj < rn ? ru + jj : roob, vc, vm);
       sched_fence();
     }
-    if (!more || nxt.fresh) flush_partial<NGH, GL>(st, red, pid, r, lane);
+    if (!more || nxt.fresh) flush_partial<NGH, GL>(st, red, pid, r, lane, covered);
     if (!more) break;
     if (nxt.fresh) {
       pid = nxt.pid;
+      covered = 0;
       begin_state<NGH, GL>(sm.qrow + r, h, st, q, qsum);
     }
     valid = nxt.valid;
@@ -286,10 +291,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 // usually the whole block in one round) and folds them with a running maximum, then the sixteen
 // slice states are folded through shared memory.  A (sequence, query head) without any partial
 // (empty sequence) gets zeros and lse = -inf.
+// Every partial also says how many tokens it covers.  Their sum has to be the token count of the
+// sequence: the softmax over the concatenation of Alg. 1 attends to every token exactly once.  If it is
+// not (ticket counters that were not zero when the call started, calls overlapping on one cache, a
+// damaged plan), the row is not a result: out and lse are set to NaN and the difference goes to the
+// status array.
 constexpr int kMergeSlices = 16;
 __global__ __launch_bounds__(32 * kMergeSlices) void decode_merge_kernel(DecodeParams prm) {
   __shared__ float sm_m[kMergeSlices];
   __shared__ float sm_l[kMergeSlices];
+  __shared__ int sm_c[kMergeSlices];
   __shared__ float sm_o[kMergeSlices][D];
   const int bhq = blockIdx.x;
   const int rep = prm.rep;
@@ -299,6 +310,7 @@ __global__ __launch_bounds__(32 * kMergeSlices) void decode_merge_kernel(DecodeP
   const int r = hq % rep;
   const int lo = prm.bh_off[bh];
   const int n = prm.bh_off[bh + 1] - lo;
+  const int expected = prm.seq_len[b] + prm.num_appended;
   const int tid = threadIdx.x;
   // every worker has drawn its last ticket: put the counters back to zero for the next call
   if (blockIdx.x == 0)
@@ -306,41 +318,42 @@ __global__ __launch_bounds__(32 * kMergeSlices) void decode_merge_kernel(DecodeP
   constexpr int STRIDE = D + kPartialFloats;
   constexpr int U = 8;   // partials in flight per thread
   const int quad = tid & 31, slice = tid >> 5;
-  const float* base = prm.ws + (int64_t(lo) * rep + r) * STRIDE + kPartialFloats + quad * 4;
+  const float* base = prm.ws + (int64_t(lo) * rep + r) * STRIDE;
   float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
+  int covered = 0;
   for (int i0 = slice; i0 < n; i0 += kMergeSlices * U) {
-    float pm[U], pl[U];
-    float2 va[U], vb[U];
+    float4 hd[U], va[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int i = i0 + kMergeSlices * u;
       const bool ok = i < n;
       const float* part = base + int64_t(ok ? i : i0) * rep * STRIDE;
-      pm[u] = ok ? part[-kPartialFloats - quad * 4] : -INFINITY;
-      pl[u] = part[1 - kPartialFloats - quad * 4];
-      va[u] = *reinterpret_cast<const float2*>(part);
-      vb[u] = *reinterpret_cast<const float2*>(part + 2);
+      hd[u] = *reinterpret_cast<const float4*>(part);                             // m, l, tokens, unused
+      va[u] = *reinterpret_cast<const float4*>(part + kPartialFloats + quad * 4);
+      if (!ok) hd[u].x = -INFINITY, hd[u].z = 0.f;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const float mn = fmaxf(m, pm[u]);
+      const float mn = fmaxf(m, hd[u].x);
       // 2^(-inf - -inf) must not occur: a slice that has only seen padding keeps weight 0
       const float a = (m == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m - mn);
-      const float w = (pm[u] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(pm[u] - mn);
-      l = l * a + pl[u] * w;
+      const float w = (hd[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(hd[u].x - mn);
+      l = l * a + hd[u].y * w;
       o0 = o0 * a + va[u].x * w, o1 = o1 * a + va[u].y * w;
-      o2 = o2 * a + vb[u].x * w, o3 = o3 * a + vb[u].y * w;
+      o2 = o2 * a + va[u].z * w, o3 = o3 * a + va[u].w * w;
       m = mn;
+      covered += __float_as_int(hd[u].z);
     }
   }
   sm_o[slice][quad * 4 + 0] = o0, sm_o[slice][quad * 4 + 1] = o1;
   sm_o[slice][quad * 4 + 2] = o2, sm_o[slice][quad * 4 + 3] = o3;
-  if (quad == 0) sm_m[slice] = m, sm_l[slice] = l;
+  if (quad == 0) sm_m[slice] = m, sm_l[slice] = l, sm_c[slice] = covered;
   __syncthreads();
   if (tid < D) {
     float mx = sm_m[0];
+    int total = sm_c[0];
 #pragma unroll
-    for (int sidx = 1; sidx < kMergeSlices; ++sidx) mx = fmaxf(mx, sm_m[sidx]);
+    for (int sidx = 1; sidx < kMergeSlices; ++sidx) mx = fmaxf(mx, sm_m[sidx]), total += sm_c[sidx];
     float big_l = 0.f, o = 0.f;
 #pragma unroll
     for (int sidx = 0; sidx < kMergeSlices; ++sidx) {
@@ -349,8 +362,13 @@ __global__ __launch_bounds__(32 * kMergeSlices) void decode_merge_kernel(DecodeP
       o += sm_o[sidx][tid] * w;
     }
     const bool empty = !(big_l > 0.f);
-    prm.out[int64_t(bhq) * D + tid] = static_cast<_Float16>(empty ? 0.f : o / big_l);
-    if (prm.lse && tid == 0) prm.lse[bhq] = empty ? -INFINITY : (mx + log2f(big_l)) * 0.6931471805599453f;
+    const bool sound = total == expected;
+    const float res = empty ? 0.f : o / big_l;
+    prm.out[int64_t(bhq) * D + tid] = static_cast<_Float16>(sound ? res : __builtin_nanf(""));
+    if (tid == 0) {
+      prm.status[bhq] = total - expected;
+      if (prm.lse) prm.lse[bhq] = !sound ? __builtin_nanf("") : empty ? -INFINITY : (mx + log2f(big_l)) * 0.6931471805599453f;
+    }
   }
 }
 
@@ -375,11 +393,10 @@ extern "C" int cocktail_default_workers(const cocktail_shape* shape, int32_t* nu
   return COCKTAIL_OK;
 }
 
-extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
-                                         float sm_scale, void* out, float* lse, void* workspace,
-                                         size_t workspace_bytes, void* stream) {
+namespace {
+
+int check_plan_matches(const cocktail_shape* shape, const cocktail_cache* cache, const PlanHeader** out) {
   if (int rc = check_shape(shape)) return rc;
-  if (!q || !out || !workspace) return fail(COCKTAIL_EINVAL, "q, out and workspace must not be NULL");
   if (!cache || !cache->plan_host || !cache->plan_dev) return fail(COCKTAIL_EINVAL, "cache or its plan is NULL");
   const PlanHeader* hd = static_cast<const PlanHeader*>(cache->plan_host);
   if (hd->magic != kPlanMagic || hd->version != kPlanVersion)
@@ -388,6 +405,13 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
       hd->chunk_size != shape->chunk_size || hd->group_size != shape->group_size ||
       hd->num_q_heads != shape->num_q_heads)
     return fail(COCKTAIL_EINVAL, "plan was made for a different shape");
+  *out = hd;
+  return COCKTAIL_OK;
+}
+
+// Validates the arguments and enqueues the two kernels; `workspace` holds at least hd->workspace_bytes.
+int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void* q, const cocktail_cache* cache,
+                   float sm_scale, void* out, float* lse, void* workspace, void* stream) {
   if (shape->head_dim != D)
     return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
   if (hd->rep > COCKTAIL_MAX_Q_PER_KV)
@@ -397,15 +421,13 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
        reinterpret_cast<uintptr_t>(cache->plan_dev)) & 15)
     return fail(COCKTAIL_EALIGN, "q, out, workspace and plan_dev must be 16-byte aligned");
   if (lse && (reinterpret_cast<uintptr_t>(lse) & 3)) return fail(COCKTAIL_EALIGN, "lse must be 4-byte aligned");
-  if (workspace_bytes < static_cast<size_t>(hd->workspace_bytes))
-    return fail(COCKTAIL_ENOSPACE, "workspace holds %zu bytes, %lld needed", workspace_bytes,
-                (long long)hd->workspace_bytes);
   DecodeParams p;
   char* pd = static_cast<char*>(cache->plan_dev);
   p.recs = reinterpret_cast<const WorkerRec*>(pd + hd->off_worker_rec);
   p.segs = reinterpret_cast<const Segment*>(pd + hd->off_segments);
   p.psegs = reinterpret_cast<const PoolSeg*>(pd + hd->off_pool_seg);
   p.counters = reinterpret_cast<uint32_t*>(pd + hd->off_counters);
+  p.seq_len = reinterpret_cast<const int32_t*>(pd + hd->off_seq_len);
   p.num_groups = hd->num_groups;
   p.num_workers = hd->num_workers;
   p.k_app = p.v_app = nullptr;
@@ -432,6 +454,7 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
     p.v[c] = static_cast<const char*>(cache->v[c]);
   }
   p.ws = static_cast<float*>(workspace);
+  p.status = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + hd->ws_status_off);
   p.out = static_cast<_Float16*>(out);
   p.lse = lse;
   if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt(static_cast<float>(shape->head_dim));
@@ -459,19 +482,65 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
       const hipError_t e = launch_decode_quads(p, shape->group_size, nt, int(grid.x), st);
       if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_quads launch failed: %s", hipGetErrorString(e));
     } else {
-    void (*kern)(DecodeParams) = nullptr;
-    switch (shape->group_size) {
-      case 32: kern = nt ? decode_attention_kernel<32, kAuxNonTemporal> : decode_attention_kernel<32, kAuxDefault>; break;
-      case 64: kern = nt ? decode_attention_kernel<64, kAuxNonTemporal> : decode_attention_kernel<64, kAuxDefault>; break;
-      default: kern = nt ? decode_attention_kernel<128, kAuxNonTemporal> : decode_attention_kernel<128, kAuxDefault>; break;
-    }
-    hipLaunchKernelGGL(kern, grid, block, 0, st, p);
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_attention launch failed: %s", hipGetErrorString(e));
+      void (*kern)(DecodeParams) = nullptr;
+      switch (shape->group_size) {
+        case 32: kern = nt ? decode_attention_kernel<32, kAuxNonTemporal> : decode_attention_kernel<32, kAuxDefault>; break;
+        case 64: kern = nt ? decode_attention_kernel<64, kAuxNonTemporal> : decode_attention_kernel<64, kAuxDefault>; break;
+        default: kern = nt ? decode_attention_kernel<128, kAuxNonTemporal> : decode_attention_kernel<128, kAuxDefault>; break;
+      }
+      hipLaunchKernelGGL(kern, grid, block, 0, st, p);
+      const hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_attention launch failed: %s", hipGetErrorString(e));
     }
   }
   hipLaunchKernelGGL(decode_merge_kernel, dim3(shape->batch * shape->num_q_heads), dim3(32 * kMergeSlices), 0, st, p);
   const hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_merge launch failed: %s", hipGetErrorString(e));
+  if (e != hipSuccess)
+    return fail(COCKTAIL_EHIP, "decode_merge launch failed: %s (the ticket counters in plan_dev were not reset: upload the plan again)",
+                hipGetErrorString(e));
+  return COCKTAIL_OK;
+}
+
+}  // namespace
+
+extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
+                                         float sm_scale, void* out, float* lse, void* workspace,
+                                         size_t workspace_bytes, void* stream) {
+  const PlanHeader* hd = nullptr;
+  if (int rc = check_plan_matches(shape, cache, &hd)) return rc;
+  if (!q || !out || !workspace) return fail(COCKTAIL_EINVAL, "q, out and workspace must not be NULL");
+  if (workspace_bytes < static_cast<size_t>(hd->workspace_bytes))
+    return fail(COCKTAIL_ENOSPACE, "workspace holds %zu bytes, %lld needed", workspace_bytes,
+                (long long)hd->workspace_bytes);
+  return decode_enqueue(shape, hd, q, cache, sm_scale, out, lse, workspace, stream);
+}
+
+extern "C" int cocktail_decode_check(const cocktail_shape* shape, const cocktail_cache* cache, const void* workspace,
+                                     void* stream) {
+  const PlanHeader* hd = nullptr;
+  if (int rc = check_plan_matches(shape, cache, &hd)) return rc;
+  const void* ws = workspace;
+  if (!ws) return fail(COCKTAIL_EINVAL, "workspace must not be NULL");
+  const int rows = hd->batch * hd->num_q_heads;
+  std::vector<int32_t> status(rows);
+  hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
+  if (e == hipSuccess)
+    e = hipMemcpy(status.data(), static_cast<const char*>(ws) + hd->ws_status_off, sizeof(int32_t) * rows, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(COCKTAIL_EHIP, "reading the status of the last decode call failed: %s", hipGetErrorString(e));
+  }
+  int bad = 0, first = -1;
+  for (int i = 0; i < rows; ++i)
+    if (status[i] != 0) {
+      if (first < 0) first = i;
+      ++bad;
+    }
+  if (bad)
+    return fail(COCKTAIL_ESTATE, "the last decode call covered %d tokens too %s for sequence %d, query head %d (%d of %d rows "
+                "affected; their out and lse are NaN): the ticket counters in plan_dev were not zero when the call "
+                "started, calls on this cache overlapped, or plan_dev was modified; upload the plan again",
+                status[first] < 0 ? -status[first] : status[first], status[first] < 0 ? "few" : "many",
+                first / hd->num_q_heads, first % hd->num_q_heads, bad, rows);
   return COCKTAIL_OK;
 }

@@ -34,12 +34,14 @@ struct DecodeParams {
   const PoolSeg* psegs;     // [num_pool_segs]
   uint32_t* counters;       // [num_groups * kCounterStride] ticket counters, zero between calls
   const int32_t* bh_off;    // [B*Hkv + 1] (sequence, kv head) owns the partial ids bh_off[bh] .. bh_off[bh+1]-1
+  const int32_t* seq_len;   // [B] context tokens per sequence
+  int32_t* status;          // [B*Hq] written by the merge: 0, or how far the tokens covered by the partials are off
   const uint32_t* q;        // fp16 [B][Hq][D] viewed as dwords
   const char* k[3];
   const char* v[3];
   const char* k_app;        // append buffers: [B*Hkv][app_blocks] FP16 blocks, or NULL
   const char* v_app;
-  float* ws;                // [num_partials][rep][D + 2]
+  float* ws;                // [num_partials][rep][D + 4]
   _Float16* out;            // [B][Hq][D]
   float* lse;               // [B][Hq] or NULL
   float scale_log2;         // sm_scale * log2(e)
@@ -436,7 +438,7 @@ struct Stream {
 __device__ __forceinline__ void write_neutral(int slot, int r, int lane) {
   kparams_t kp = kparams();
   float* out = kp->ws + (int64_t(slot) * kp->rep + r) * (D + kPartialFloats);
-  if (lane == 0) out[0] = kNegBig, out[1] = 0.f;
+  if (lane == 0) out[0] = kNegBig, out[1] = 0.f, out[2] = 0.f;   // covers no tokens
   out[kPartialFloats + lane] = 0.f;
   out[kPartialFloats + 64 + lane] = 0.f;
 }

@@ -251,7 +251,7 @@ __device__ __forceinline__ void softmax_quads(const f4 (&s)[J], const float (&ev
 
 // Writes the partial states `pid` of the wave's query heads: (m, l, o[D]) per head, reduced over the lanes.
 template <class CLS, int NGH, int GL>
-__device__ __forceinline__ void flush_quads(const QuadState<NGH>& st, float* red, int pid, int r, int lane) {
+__device__ __forceinline__ void flush_quads(const QuadState<NGH>& st, float* red, int pid, int r, int lane, int tokens) {
   kparams_t prm = kparams();
   const int rep = prm->rep;
   const int heads = min(4, rep - 4 * r);   // query heads this wave really has
@@ -270,6 +270,7 @@ __device__ __forceinline__ void flush_quads(const QuadState<NGH>& st, float* red
   if (lane < heads) {
     out[lane * (D + kPartialFloats)] = pick(st.m, lane);
     out[lane * (D + kPartialFloats) + 1] = pick(l, lane);
+    out[lane * (D + kPartialFloats) + 2] = __int_as_float(tokens);
   }
   // channel accumulators: lane 32h + 4b + j holds the sum over the tokens of quad b for 16 channels of half h;
   // the eight quads are added through a shared-memory tile, eight of the sixteen channels at a time.
@@ -362,6 +363,7 @@ __device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, in
   sched_fence();
   begin_quads<CLS, NGH, GL>(sm.qrow, h, r, lane, st, qa, qs);
   int valid = cur.valid;
+  int covered = 0;   // tokens the current partial states cover
   Piece nxt = sm.next(lane);
 #pragma unroll 1
   while (true) {
@@ -373,6 +375,7 @@ __device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, in
     } else {
       rn = 0;
     }
+    covered += valid;
     f4 s[J], p[J];
 #pragma unroll
     for (int jj = 0; jj < J; ++jj) {
@@ -397,10 +400,11 @@ __device__ __forceinline__ void run_quads(Stream& sm, Piece& cur, float* red, in
       CLS::template load<AUX>(vs[jj], vrs, jj < rn ? ru + jj : roob, vc, vm);
       sched_fence();
     }
-    if (!more || nxt.fresh) flush_quads<CLS, NGH, GL>(st, red, pid, r, lane);
+    if (!more || nxt.fresh) flush_quads<CLS, NGH, GL>(st, red, pid, r, lane, covered);
     if (!more) break;
     if (nxt.fresh) {
       pid = nxt.pid;
+      covered = 0;
       begin_quads<CLS, NGH, GL>(sm.qrow, h, r, lane, st, qa, qs);
     }
     valid = nxt.valid;

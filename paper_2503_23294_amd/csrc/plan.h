@@ -10,11 +10,11 @@
 namespace cocktail {
 
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
-constexpr uint32_t kPlanVersion = 10;
+constexpr uint32_t kPlanVersion = 11;
 constexpr int kTB = 64;                        // tokens per block
 constexpr int kUT = 32;                        // tokens per unit (half a block): what one wave handles at a time
 constexpr int kNumClasses = 3;
-constexpr int kPartialFloats = 2;              // (m, l) in front of the D output values
+constexpr int kPartialFloats = 4;              // (m, l, tokens covered as int32, unused) in front of the D output values
 // Units one wave consumes per loop iteration in class INT2, INT4, FP16: the grain of the shared pools.
 constexpr int kIterUnits[kNumClasses] = {4, 2, 1};
 constexpr int kMaxPoolSegments = 32;           // segments one pool may touch (a worker tracks them in a bit mask)
@@ -122,6 +122,10 @@ struct PlanHeader {
   int32_t off_bh_off;         // int32 [B*Hkv + 1] prefix: (b, kv head) owns partial ids bh_off[bh] .. bh_off[bh+1]-1;
                               // with append buffers the last id of each range is that of the appended tokens
   int32_t off_rq_items;       // RQItem [sum of class_blocks]
+  int32_t pad0;
+  int64_t ws_status_off;      // byte offset, inside the decode workspace, of int32 [B * Hq]: per (sequence, query
+                              // head) tokens covered by the last call's partial states minus tokens of the sequence
+                              // (0 = every token was attended to exactly once)
 };
 
 // Token-quad form of a V block: byte offset, inside the block, of the half-word that holds token i

@@ -103,14 +103,60 @@ static Tuning read_tuning() {
   return t;
 }
 
-static inline int32_t align16(int64_t x) { return static_cast<int32_t>((x + 15) & ~int64_t(15)); }
+static inline int64_t align16(int64_t x) { return (x + 15) & ~int64_t(15); }
 
 }  // namespace cocktail
 
 using namespace cocktail;
 
 extern "C" const char* cocktail_last_error(void) { return g_err; }
-extern "C" int cocktail_version(void) { return (0 << 16) | 4; }
+extern "C" int cocktail_version(void) { return (0 << 16) | 5; }
+
+// Reads one field of the plan header by name, so that tools and tests that look inside a plan follow the
+// header's real layout instead of a copy of it.
+extern "C" int cocktail_plan_field(const void* plan_host, const char* name, int32_t index, int64_t* value) {
+  if (!plan_host || !name || !value) return fail(COCKTAIL_EINVAL, "plan_host, name and value must not be NULL");
+  const PlanHeader* hd = static_cast<const PlanHeader*>(plan_host);
+  if (hd->magic != kPlanMagic || hd->version != kPlanVersion)
+    return fail(COCKTAIL_EINVAL, "plan_host is not a plan written by this library version");
+#define COCKTAIL_FIELD(f)                                                                            \
+  if (std::strcmp(name, #f) == 0) {                                                                  \
+    if (index != 0) return fail(COCKTAIL_EINVAL, "plan field %s is not an array", name);             \
+    *value = static_cast<int64_t>(hd->f);                                                            \
+    return COCKTAIL_OK;                                                                              \
+  }
+#define COCKTAIL_ARRAY(f)                                                                            \
+  if (std::strcmp(name, #f) == 0) {                                                                  \
+    if (index < 0 || index >= kNumClasses) return fail(COCKTAIL_EINVAL, "index %d of plan field %s", index, name); \
+    *value = static_cast<int64_t>(hd->f[index]);                                                     \
+    return COCKTAIL_OK;                                                                              \
+  }
+  COCKTAIL_FIELD(magic) COCKTAIL_FIELD(version) COCKTAIL_FIELD(batch) COCKTAIL_FIELD(num_q_heads)
+  COCKTAIL_FIELD(num_kv_heads) COCKTAIL_FIELD(head_dim) COCKTAIL_FIELD(chunk_size) COCKTAIL_FIELD(group_size)
+  COCKTAIL_FIELD(rep) COCKTAIL_FIELD(num_workers) COCKTAIL_FIELD(num_segments) COCKTAIL_FIELD(num_partials)
+  COCKTAIL_FIELD(total_gblocks) COCKTAIL_FIELD(v_layout) COCKTAIL_FIELD(total_chunks) COCKTAIL_FIELD(total_tokens)
+  COCKTAIL_ARRAY(class_blocks) COCKTAIL_ARRAY(class_bytes) COCKTAIL_ARRAY(block_bytes) COCKTAIL_ARRAY(row_bytes)
+  COCKTAIL_FIELD(workspace_bytes) COCKTAIL_FIELD(plan_bytes) COCKTAIL_FIELD(packed_bytes)
+  COCKTAIL_FIELD(off_seq_len) COCKTAIL_FIELD(off_cum_tokens) COCKTAIL_FIELD(off_chunk_off) COCKTAIL_FIELD(off_perm)
+  COCKTAIL_FIELD(off_class_tokens) COCKTAIL_FIELD(off_class_chunk0) COCKTAIL_FIELD(off_blk_base)
+  COCKTAIL_FIELD(off_nblk) COCKTAIL_FIELD(off_segments) COCKTAIL_FIELD(append_capacity)
+  COCKTAIL_FIELD(off_worker_rec) COCKTAIL_FIELD(off_group_rec) COCKTAIL_FIELD(off_pool_seg)
+  COCKTAIL_FIELD(off_counters) COCKTAIL_FIELD(num_groups) COCKTAIL_FIELD(num_pool_segs)
+  COCKTAIL_FIELD(append_blocks) COCKTAIL_FIELD(off_bh_off) COCKTAIL_FIELD(off_rq_items)
+  COCKTAIL_FIELD(ws_status_off)
+#undef COCKTAIL_FIELD
+#undef COCKTAIL_ARRAY
+  // constants of the layout that are not stored in the header
+  if (std::strcmp(name, "counter_stride_bytes") == 0) return *value = 4 * kCounterStride, COCKTAIL_OK;
+  if (std::strcmp(name, "partial_header_floats") == 0) return *value = kPartialFloats, COCKTAIL_OK;
+  if (std::strcmp(name, "iter_units") == 0 && index >= 0 && index < kNumClasses) return *value = kIterUnits[index], COCKTAIL_OK;
+  if (std::strcmp(name, "sizeof_segment") == 0) return *value = sizeof(Segment), COCKTAIL_OK;
+  if (std::strcmp(name, "sizeof_worker_rec") == 0) return *value = sizeof(WorkerRec), COCKTAIL_OK;
+  if (std::strcmp(name, "sizeof_group_rec") == 0) return *value = sizeof(GroupRec), COCKTAIL_OK;
+  if (std::strcmp(name, "sizeof_pool_seg") == 0) return *value = sizeof(PoolSeg), COCKTAIL_OK;
+  if (std::strcmp(name, "sizeof_rq_item") == 0) return *value = sizeof(RQItem), COCKTAIL_OK;
+  return fail(COCKTAIL_EINVAL, "unknown plan field %s[%d]", name, index);
+}
 
 extern "C" int cocktail_plan(const cocktail_shape* shape, const int32_t* seq_lens, const uint8_t* chunk_bits,
                              int32_t num_workers, cocktail_sizes* sizes, void* plan_host, size_t plan_capacity,
@@ -128,8 +174,8 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   if (options)
     for (int32_t v : options->reserved)
       if (v != 0) return fail(COCKTAIL_EINVAL, "cocktail_plan_options::reserved must be zero");
-  if (append_capacity < 0 || append_capacity > (1 << 24))
-    return fail(COCKTAIL_EINVAL, "append_capacity %d out of range [0, 2^24]", append_capacity);
+  if (append_capacity < 0 || append_capacity > (1 << 24) - kTB)   // an append run stays below 4 GiB, like a context run
+    return fail(COCKTAIL_EINVAL, "append_capacity %d out of range [0, 2^24 - 64]", append_capacity);
   if (!seq_lens || !sizes) return fail(COCKTAIL_EINVAL, "seq_lens and sizes must not be NULL");
   if (num_workers < 1 || num_workers > (1 << 20))
     return fail(COCKTAIL_EINVAL, "num_workers %d out of range [1, 2^20]", num_workers);
@@ -140,8 +186,12 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   int64_t total_chunks = 0, total_tokens = 0;
   for (int b = 0; b < B; ++b) {
     if (seq_lens[b] < 0) return fail(COCKTAIL_EINVAL, "seq_lens[%d] = %d is negative", b, seq_lens[b]);
-    if (seq_lens[b] >= (1 << 24))   // the kernels address the blocks of one (b, h, class) run with 32-bit byte offsets
-      return fail(COCKTAIL_EUNSUPPORTED, "seq_lens[%d] = %d: at most 2^24 - 1 tokens per sequence", b, seq_lens[b]);
+    // the kernels address the blocks of one (b, h, class) run with 32-bit byte offsets and describe it by a
+    // buffer resource with a 32-bit size: an all-FP16 run of T tokens has ceil(T / 64) * 64 * 2 D bytes
+    if ((int64_t(seq_lens[b]) + kTB - 1) / kTB * kTB * 2 * D >= (int64_t(1) << 32))
+      return fail(COCKTAIL_EUNSUPPORTED, "seq_lens[%d] = %d: one (sequence, kv head) run in FP16 would reach 4 GiB "
+                  "(at most %lld tokens per sequence at head_dim %d)", b, seq_lens[b],
+                  (long long)(((int64_t(1) << 32) / (2 * D) - 1) / kTB * kTB), D);
     total_chunks += seq_lens[b] / C;
     total_tokens += seq_lens[b];
   }
@@ -538,10 +588,14 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
     hd.block_bytes[c] = block_bytes[c];
     hd.row_bytes[c] = row_bytes[c];
   }
-  hd.workspace_bytes = int64_t(npart > 0 ? npart : 1) * hd.rep * (D + kPartialFloats) * int64_t(sizeof(float));
+  // decode workspace: the partial states, then one status word per (sequence, query head)
+  hd.ws_status_off = align16(int64_t(npart > 0 ? npart : 1) * hd.rep * (D + kPartialFloats) * int64_t(sizeof(float)));
+  hd.workspace_bytes = hd.ws_status_off + align16(int64_t(sizeof(int32_t)) * B * shape->num_q_heads);
   int64_t off = align16(sizeof(PlanHeader));
+  bool too_large = false;
   auto place = [&](int32_t& field, int64_t bytes) {
-    field = static_cast<int32_t>(off);
+    if (off + bytes >= (int64_t(1) << 31)) too_large = true;   // the offsets are 32-bit fields
+    field = static_cast<int32_t>(too_large ? 0 : off);
     off = align16(off + bytes);
   };
   place(hd.off_seq_len, 4 * int64_t(B));
@@ -560,7 +614,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   place(hd.off_rq_items, int64_t(sizeof(RQItem)) * int64_t(rq_items.size()));
   off = (off + 127) & ~int64_t(127);
   place(hd.off_counters, int64_t(4 * kCounterStride) * NG);
-  if (off >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "plan larger than 2 GiB");
+  if (too_large || off >= (int64_t(1) << 31)) return fail(COCKTAIL_EUNSUPPORTED, "plan larger than 2 GiB");
   hd.plan_bytes = off;
 
   std::memset(sizes, 0, sizeof(*sizes));

@@ -184,11 +184,11 @@ def test_more_workers_than_blocks_and_repeatability():
 
 
 def _counters(c):
-    """The decode kernel's ticket counters inside the device copy of the plan (internal layout: csrc/plan.h)."""
-    import struct
-    f = struct.unpack_from("<II6i i3i ii qq 3q3q 3i3i qqq 14i 2i i 2i", c.plan.blob.tobytes(), 0)
-    off, ngroups = f[44], f[45]
-    return c.cache.plan_dev[off:off + 128 * ngroups].cpu().numpy().view(np.uint32)[::32], f[46]
+    """The decode kernel's ticket counters inside the device copy of the plan, and the number of pool parts."""
+    off, ngroups = ck.cocktail_plan_field(c.plan, "off_counters"), ck.cocktail_plan_field(c.plan, "num_groups")
+    stride = ck.cocktail_plan_field(c.plan, "counter_stride_bytes")
+    words = c.cache.plan_dev[off:off + stride * ngroups].cpu().numpy().view(np.uint32)[::stride // 4]
+    return words, ck.cocktail_plan_field(c.plan, "num_pool_segs")
 
 
 @pytest.mark.parametrize("workers", [1, 3, 8, 13, 24])
@@ -210,6 +210,43 @@ def test_shared_pools_with_few_workers(workers):
         for b in range(w.batch):
             for h in range(w.num_kv_heads):
                 c.check_head(b, h)
+
+
+@pytest.mark.parametrize("rep,stale", [(1, 3), (1, 1 << 30), (4, 2)])
+def test_stale_ticket_counter_is_reported_and_does_not_outlive_the_call(rep, stale):
+    """A ticket counter that is not zero when a call starts (an aborted call, overlapping calls) makes the
+    workers skip pool pieces.  Such a call must not pass as a result: the rows that miss tokens come out as
+    NaN, cocktail_decode_check reports them, and the call after it is sound again."""
+    w = workloads.small(f"stale_r{rep}", 3, 2 * rep, 2, [3000, 1500, 4500], 64, 32, mix=(0.2, 0.4, 0.4),
+                        seed_offset=140 + rep)
+    _announce(f"{w.name} stale={stale}")
+    c = Case(w, workers=8)
+    c.check_all()
+    ck.cocktail_decode_check(c.cache)                        # the call inside Case was sound
+    ngroups = ck.cocktail_plan_field(c.plan, "num_groups")
+    goff, gsize = ck.cocktail_plan_field(c.plan, "off_group_rec"), ck.cocktail_plan_field(c.plan, "sizeof_group_rec")
+    ngran = np.frombuffer(c.plan.blob.tobytes(), dtype=np.int32, count=ngroups * gsize // 4, offset=goff)[::gsize // 4]
+    g = int(np.argmax(ngran))
+    assert ngran[g] > 3, "this shape is meant to have a pool with several tickets"
+    off = ck.cocktail_plan_field(c.plan, "off_counters") + g * ck.cocktail_plan_field(c.plan, "counter_stride_bytes")
+    c.cache.plan_dev[off:off + 4] = torch.from_numpy(np.array([stale], dtype=np.uint32).view(np.uint8)).to(c.cache.plan_dev.device)
+    out, lse = ck.cocktail_decode_attention(c.cache, c.q_dev)
+    with pytest.raises(ck.CocktailError) as e:
+        ck.cocktail_decode_check(c.cache)
+    assert e.value.code == -6 and "too few" in str(e.value)
+    out, lse = out.cpu().numpy().astype(np.float64), lse.cpu().numpy()
+    bad_rows = np.isnan(out).all(axis=2)
+    assert bad_rows.any() and (np.isnan(out).any(axis=2) == bad_rows).all() and (np.isnan(lse) == bad_rows).all()
+    ref = c.out.astype(np.float64)                           # rows that lost no token are results
+    good = ~bad_rows
+    assert (np.abs(out[good] - ref[good]).max(axis=1) <= TOL * np.abs(ref[good]).max(axis=1)).all()
+    assert (_counters(c)[0] == 0).all()                      # the merge put the counters back
+    out2, _ = ck.cocktail_decode_attention(c.cache, c.q_dev)
+    ck.cocktail_decode_check(c.cache)
+    c.out = out2.cpu().numpy()
+    for b in range(w.batch):
+        for h in range(w.num_kv_heads):
+            c.check_head(b, h)
 
 
 @pytest.mark.parametrize("rep,workers", [(4, 3), (4, 16), (3, 8), (2, 24)])

@@ -2,7 +2,6 @@
 import ctypes as C
 import os
 import re
-import struct
 
 import numpy as np
 import pytest
@@ -33,26 +32,23 @@ def _plan(w, workers):
     return ck.cocktail_plan(sh, w.seq_lens, flat, workers), bits
 
 
-# field offsets of the internal plan header (csrc/plan.h), little-endian
-_HDR = struct.Struct("<II6i i3i ii qq 3q3q 3i3i qqq 14i 2i i 2i")
-ITER_UNITS = (4, 2, 1)      # units per loop iteration of the decode kernel, per class
-COUNTER_STRIDE = 32
-
-
-def _parse(blob):
-    f = _HDR.unpack_from(blob.tobytes(), 0)
-    names = ["magic", "version", "batch", "hq", "hkv", "d", "chunk", "group", "rep", "workers", "segments",
-             "partials", "gblocks", "v_layout", "total_chunks", "total_tokens"]
-    h = dict(zip(names, f[:16]))
-    h["class_blocks"], h["class_bytes"] = f[16:19], f[19:22]
-    h["block_bytes"], h["row_bytes"] = f[22:25], f[25:28]
-    h["workspace_bytes"], h["plan_bytes"], h["packed_bytes"] = f[28:31]
-    offs = f[31:45]
-    keys = ["seq_len", "cum_tokens", "chunk_off", "perm", "class_tokens", "class_chunk0", "blk_base", "nblk",
-            "segments", "bh_pid", "worker_rec", "group_rec", "pool_seg", "counters"]
-    h["off"] = dict(zip(keys, offs))
-    h["groups"], h["pool_segs"], _, h["off"]["bh_off"] = f[45:49]
+def _parse(plan):
+    """The fields of the plan's internal header that these tests look at, read by name through the library's
+    accessor, so that a change of the header layout cannot be misread here."""
+    f = lambda name, i=0: ck.cocktail_plan_field(plan, name, i)
+    h = {"rep": f("rep"), "workers": f("num_workers"), "segments": f("num_segments"), "partials": f("num_partials"),
+         "gblocks": f("total_gblocks"), "v_layout": f("v_layout"), "plan_bytes": f("plan_bytes"),
+         "groups": f("num_groups"), "pool_segs": f("num_pool_segs"), "ws_status_off": f("ws_status_off"),
+         "block_bytes": [f("block_bytes", c) for c in range(3)]}
+    h["off"] = {k: f("off_" + k) for k in ("segments", "worker_rec", "group_rec", "pool_seg", "counters", "bh_off")}
+    assert f("sizeof_segment") == 32 and f("sizeof_worker_rec") == 64 and f("sizeof_group_rec") == 32
+    assert f("sizeof_pool_seg") == 32
     return h
+
+
+def _consts(plan):
+    return ([ck.cocktail_plan_field(plan, "iter_units", c) for c in range(3)],
+            ck.cocktail_plan_field(plan, "counter_stride_bytes") // 4, ck.cocktail_plan_field(plan, "partial_header_floats"))
 
 
 def _arr(blob, off, dtype, n):
@@ -62,7 +58,8 @@ def _arr(blob, off, dtype, n):
 def _check_work_split(plan, w, workers, seed=0):
     """Replays the decode kernel's walk over the plan (own ranges, then pool tickets in a random
     hand-out order) and checks that every unit is read exactly once and every partial id is sound."""
-    h = _parse(plan.blob)
+    h = _parse(plan)
+    ITER_UNITS, COUNTER_STRIDE, header_floats = _consts(plan)
     assert h["plan_bytes"] == plan.blob.size and h["workers"] == workers
     S, P, NG, NPS = h["segments"], workers, h["groups"], h["pool_segs"]
     segs = _arr(plan.blob, h["off"]["segments"], np.int32, 8 * S).reshape(S, 8)
@@ -160,7 +157,9 @@ def _check_work_split(plan, w, workers, seed=0):
     assert bh_off[0] == 0 and bh_off[BH] == h["partials"] and (np.diff(bh_off) >= 0).all()
     for bh in range(BH):
         assert all(pid_owner[p][1] == bh for p in range(bh_off[bh], bh_off[bh + 1]))
-    assert plan.sizes.workspace_bytes == max(h["partials"], 1) * h["rep"] * (w.head_dim + 2) * 4
+    # workspace: the partial states (header + head_dim floats each), then one status word per (sequence, query head)
+    assert h["ws_status_off"] == max(h["partials"], 1) * h["rep"] * (w.head_dim + header_floats) * 4
+    assert plan.sizes.workspace_bytes == h["ws_status_off"] + (4 * w.batch * w.num_q_heads + 15) // 16 * 16
     return h, cost, pool_cost
 
 
@@ -301,9 +300,9 @@ def test_append_capacity_sizes_and_validation():
     # one more partial per (sequence, kv head), at the end of its range
     assert p1.sizes.num_partials == p0.sizes.num_partials + w.batch * w.num_kv_heads
     _check_work_split(p0, w, 64)
-    h = _parse(p1.blob)
+    h = _parse(p1)
     bh_off = _arr(p1.blob, h["off"]["bh_off"], np.int32, w.batch * w.num_kv_heads + 1)
-    bh_off0 = _arr(p0.blob, _parse(p0.blob)["off"]["bh_off"], np.int32, w.batch * w.num_kv_heads + 1)
+    bh_off0 = _arr(p0.blob, _parse(p0)["off"]["bh_off"], np.int32, w.batch * w.num_kv_heads + 1)
     assert (np.diff(bh_off) == np.diff(bh_off0) + 1).all()
     L = _lib.lib()
     sizes = _lib.Sizes()
@@ -318,8 +317,8 @@ def test_append_capacity_sizes_and_validation():
     w4 = workloads.config(4)
     sh4 = ck.make_shape(w4.batch, w4.num_q_heads, w4.num_kv_heads, w4.head_dim, w4.chunk_size, w4.group_size)
     bits4 = np.concatenate(workloads.chunk_bits(w4))
-    assert _parse(ck.cocktail_plan(sh4, w4.seq_lens, bits4, 2048).blob)["pool_segs"] > 0
-    assert _parse(ck.cocktail_plan(sh4, w4.seq_lens, bits4, 2048, reproducible=True).blob)["pool_segs"] == 0
+    assert _parse(ck.cocktail_plan(sh4, w4.seq_lens, bits4, 2048))["pool_segs"] > 0
+    assert _parse(ck.cocktail_plan(sh4, w4.seq_lens, bits4, 2048, reproducible=True))["pool_segs"] == 0
     cache = _lib.Cache()
     cache.plan_host = p0.blob.ctypes.data
     assert L.cocktail_append_fp16(C.byref(sh), 16, 16, C.byref(cache), 0, None) == _lib.EINVAL   # no append buffers
@@ -366,7 +365,7 @@ def test_v_layout_follows_the_query_to_kv_head_ratio(rep, quads):
     bits = np.array([2, 4, 16, 2] * 16 + [4, 2] * 16, dtype=np.uint8)
     plan = ck.cocktail_plan(shape, [64 * 64, 32 * 64], bits, 16)
     assert int(plan.sizes.v_layout) == int(quads)
-    h = _parse(plan.blob)
+    h = _parse(plan)
     assert h["rep"] == rep and h["v_layout"] == int(quads)
     groups = _arr(plan.blob, h["off"]["group_rec"], np.int32, 8 * h["groups"]).reshape(-1, 8)
     assert (groups[:, 0] > 0).any() == (rep <= 4)
