@@ -235,12 +235,30 @@ int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const 
                               size_t workspace_bytes, void* stream);
 
 /*
+ * cocktail_decode_attention for callers that cannot allocate device memory or hand over a workspace: code
+ * that runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same two kernels and same results, but the partial states go to a workspace built into the library: a
+ * static device array of COCKTAIL_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds until the
+ * process ends.  The call allocates and frees nothing, on the device or through any library.
+ *
+ * Every call on a GPU shares that GPU's array, so calls that overlap in time on one GPU (two streams, two
+ * threads) race; nothing in it has to survive from one call to the next.  The array's address is looked up
+ * on the first call on each device (with that device current): make that call outside a graph capture.
+ *
+ * Errors: as cocktail_decode_attention, and ENOSPACE if the plan's workspace_bytes exceeds
+ * COCKTAIL_STATIC_WORKSPACE_BYTES (the five benchmark shapes need 0.1 to 5.2 MB).
+ */
+#define COCKTAIL_STATIC_WORKSPACE_BYTES (16u << 20)
+int cocktail_decode_attention_static(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
+                                     float sm_scale, void* out, float* lse, void* stream);
+
+/*
  * Diagnostic: waits for `stream`, then reads the status words the last decode call on `workspace` left
  * (the only entry point that synchronises and copies).  The softmax of Alg. 1's decode phase runs over the
  * concatenation of all three classes, i.e. over every token of the sequence exactly once; the status word
  * of a (sequence, query head) is the number of tokens its partial states covered minus the sequence length.
  *
- *   workspace  DEVICE, the workspace of that call
+ *   workspace  DEVICE, the workspace of that call; NULL = the built-in one of cocktail_decode_attention_static
  *
  * Returns COCKTAIL_OK if every word is zero, else COCKTAIL_ESTATE with a message naming the first bad row
  * (see cocktail_decode_attention for the causes).  Other errors: EINVAL, EHIP.

@@ -17,6 +17,7 @@ LIB_PATH = os.environ.get("COCKTAIL_LIB", os.path.join(HERE, "libcocktail.so"))
 NUM_CLASSES = 3
 TOKENS_PER_BLOCK = 64
 MAX_Q_PER_KV = 8
+STATIC_WORKSPACE_BYTES = 16 << 20
 
 OK, EINVAL, EUNSUPPORTED, EALIGN, ENOSPACE, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
 SRC_STRIDED, SRC_RAGGED = 0, 1
@@ -59,6 +60,8 @@ EXPORTS = {
                                             C.c_int64, C.c_int64, C.POINTER(Cache), C.c_void_p]),
     "cocktail_decode_attention": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "cocktail_decode_attention_static": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float,
+                                                   C.c_void_p, C.c_void_p, C.c_void_p]),
     "cocktail_decode_check": (C.c_int, [C.POINTER(Shape), C.POINTER(Cache), C.c_void_p, C.c_void_p]),
     "cocktail_plan_field": (C.c_int, [C.c_void_p, C.c_char_p, C.c_int32, C.POINTER(C.c_int64)]),
     "cocktail_default_workers": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32)]),

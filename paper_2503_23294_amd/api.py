@@ -162,11 +162,27 @@ def cocktail_decode_attention(cache: PackedCache, q: torch.Tensor, sm_scale: flo
     return out, lse
 
 
-def cocktail_decode_check(cache: PackedCache, stream: Optional[torch.cuda.Stream] = None) -> None:
+def cocktail_decode_attention_static(cache: PackedCache, q: torch.Tensor, sm_scale: float, out: torch.Tensor,
+                                     lse: Optional[torch.Tensor] = None,
+                                     stream: Optional[torch.cuda.Stream] = None) -> None:
+    """cocktail_decode_attention on the workspace built into the library: nothing is allocated, so the caller
+    passes `out` (and `lse`, if wanted)."""
+    sh = cache.plan.shape
+    if q.dtype != torch.float16 or not q.is_cuda or not q.is_contiguous():
+        raise TypeError("q must be a contiguous float16 device tensor")
+    if tuple(q.shape) != (sh.batch, sh.num_q_heads, sh.head_dim) or out.shape != q.shape or out.dtype != q.dtype:
+        raise ValueError("q and out must be float16 [B, Hq, D]")
+    check(lib().cocktail_decode_attention_static(C.byref(sh), q.data_ptr(), C.byref(cache.desc), float(sm_scale),
+                                                 out.data_ptr(), lse.data_ptr() if lse is not None else None,
+                                                 _stream_ptr(stream)))
+
+
+def cocktail_decode_check(cache: PackedCache, stream: Optional[torch.cuda.Stream] = None,
+                          static_workspace: bool = False) -> None:
     """Waits for the stream and raises CocktailError (code -6) if the last decode call on this cache's
-    workspace did not attend to every token exactly once."""
-    check(lib().cocktail_decode_check(C.byref(cache.plan.shape), C.byref(cache.desc), cache.workspace.data_ptr(),
-                                      _stream_ptr(stream)))
+    workspace (or on the library's built-in one) did not attend to every token exactly once."""
+    check(lib().cocktail_decode_check(C.byref(cache.plan.shape), C.byref(cache.desc),
+                                      None if static_workspace else cache.workspace.data_ptr(), _stream_ptr(stream)))
 
 
 def cocktail_stream_read_probe(buf: torch.Tensor, sink: torch.Tensor,

@@ -35,6 +35,7 @@
 
 #include <cmath>
 #include <cstdlib>
+#include <mutex>
 #include <vector>
 
 #include "decode_common.h"
@@ -393,7 +394,37 @@ extern "C" int cocktail_default_workers(const cocktail_shape* shape, int32_t* nu
   return COCKTAIL_OK;
 }
 
+// Scratch of the entry point that allocates nothing: the partial softmax states and the status words of one
+// decode call.  In host code this name is only a handle; the device address comes from hipGetSymbolAddress.
+constexpr size_t kStaticWorkspaceBytes = size_t(COCKTAIL_STATIC_WORKSPACE_BYTES);
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};   // per device: address of `scratch` there
+
+// Address of the static workspace on the current device (looked up once per device).
+int static_workspace(void** ptr) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    return fail(COCKTAIL_EHIP, "no current HIP device (or its index is not below %d)", kMaxDevices);
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return fail(COCKTAIL_EHIP, "hipGetSymbolAddress(static workspace) failed on device %d: %s", dev, hipGetErrorString(e));
+    }
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return COCKTAIL_OK;
+}
 
 int check_plan_matches(const cocktail_shape* shape, const cocktail_cache* cache, const PlanHeader** out) {
   if (int rc = check_shape(shape)) return rc;
@@ -515,12 +546,30 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
   return decode_enqueue(shape, hd, q, cache, sm_scale, out, lse, workspace, stream);
 }
 
+extern "C" int cocktail_decode_attention_static(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
+                                                float sm_scale, void* out, float* lse, void* stream) {
+  const PlanHeader* hd = nullptr;
+  if (int rc = check_plan_matches(shape, cache, &hd)) return rc;
+  if (!q || !out) return fail(COCKTAIL_EINVAL, "q and out must not be NULL");
+  if (static_cast<size_t>(hd->workspace_bytes) > kStaticWorkspaceBytes)
+    return fail(COCKTAIL_ENOSPACE, "this plan needs a workspace of %lld bytes, the built-in one holds %zu: use "
+                "cocktail_decode_attention with a caller-supplied workspace", (long long)hd->workspace_bytes,
+                kStaticWorkspaceBytes);
+  void* ws = nullptr;
+  if (int rc = static_workspace(&ws)) return rc;
+  return decode_enqueue(shape, hd, q, cache, sm_scale, out, lse, ws, stream);
+}
+
 extern "C" int cocktail_decode_check(const cocktail_shape* shape, const cocktail_cache* cache, const void* workspace,
                                      void* stream) {
   const PlanHeader* hd = nullptr;
   if (int rc = check_plan_matches(shape, cache, &hd)) return rc;
-  const void* ws = workspace;
-  if (!ws) return fail(COCKTAIL_EINVAL, "workspace must not be NULL");
+  void* ws = const_cast<void*>(workspace);
+  if (!ws) {
+    if (static_cast<size_t>(hd->workspace_bytes) > kStaticWorkspaceBytes)
+      return fail(COCKTAIL_ENOSPACE, "this plan does not fit the built-in workspace");
+    if (int rc = static_workspace(&ws)) return rc;
+  }
   const int rows = hd->batch * hd->num_q_heads;
   std::vector<int32_t> status(rows);
   hipError_t e = hipStreamSynchronize(static_cast<hipStream_t>(stream));
