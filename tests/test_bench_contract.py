@@ -17,6 +17,7 @@ def test_bench_reads_the_committed_traffic_figures():
     import bench
     import workloads
     for cfg in (4, 5):
-        t = bench.measured_traffic(workloads.config(cfg).name)
+        t, source = bench.measured_traffic(workloads.config(cfg).name)
         assert t is not None and t > 6.0e8, cfg          # HBM bytes per decode call from profiles/
-    assert bench.measured_traffic("no_such_workload") is None
+        assert os.path.exists(os.path.join(ROOT, source))
+    assert bench.measured_traffic("no_such_workload") == (None, None)
