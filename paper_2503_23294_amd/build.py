@@ -35,4 +35,11 @@ def build(verbose: bool = True, extra: list[str] | None = None, out: str = LIB) 
 
 
 if __name__ == "__main__":
-    build(extra=sys.argv[1:])
+    # python -m paper_2503_23294_amd.build [--out FILE] [extra hipcc flags, e.g. -DCOCKTAIL_TRACE]
+    argv = sys.argv[1:]
+    target = LIB
+    if "--out" in argv:
+        i = argv.index("--out")
+        target = os.path.abspath(argv[i + 1])
+        del argv[i:i + 2]
+    build(extra=argv, out=target)

@@ -15,15 +15,6 @@ constexpr int UT = 32;                      // tokens per unit (half a block)
 constexpr float kNegBig = -1.0e30f;
 constexpr float kRescaleThreshold = 8.0f;   // log2 units
 constexpr float kTwo24 = 16777216.0f;
-#ifndef COCKTAIL_J2
-#define COCKTAIL_J2 4
-#endif
-#ifndef COCKTAIL_J4
-#define COCKTAIL_J4 2
-#endif
-#ifndef COCKTAIL_J16
-#define COCKTAIL_J16 1
-#endif
 constexpr int J2 = COCKTAIL_J2;    // INT2 units in flight per wave
 constexpr int J4 = COCKTAIL_J4;    // INT4 units in flight per wave
 constexpr int J16 = COCKTAIL_J16;  // FP16 units in flight per wave

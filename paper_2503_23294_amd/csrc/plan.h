@@ -16,7 +16,16 @@ constexpr int kUT = 32;                        // tokens per unit (half a block)
 constexpr int kNumClasses = 3;
 constexpr int kPartialFloats = 4;              // (m, l, tokens covered as int32, unused) in front of the D output values
 // Units one wave consumes per loop iteration in class INT2, INT4, FP16: the grain of the shared pools.
-constexpr int kIterUnits[kNumClasses] = {4, 2, 1};
+#ifndef COCKTAIL_J2
+#define COCKTAIL_J2 4
+#endif
+#ifndef COCKTAIL_J4
+#define COCKTAIL_J4 2
+#endif
+#ifndef COCKTAIL_J16
+#define COCKTAIL_J16 1
+#endif
+constexpr int kIterUnits[kNumClasses] = {COCKTAIL_J2, COCKTAIL_J4, COCKTAIL_J16};
 constexpr int kMaxPoolSegments = 32;           // segments one pool may touch (a worker tracks them in a bit mask)
 constexpr int kCounterStride = 32;             // uint32 slots between two pool counters (one 128-byte line each)
 // Query heads per kv head for which a wave serves four of them at a time with matrix instructions and V is
