@@ -215,6 +215,69 @@ def run_config(cfg, steps, warmup, ntok, workers_arg, decode_only, cpu_heads, ca
     return entry, detail
 
 
+def paged_reorder_quantize(cfg, page_sizes, reps=8):
+    """Times reorder+quantize reading K and V from a paged cache (pages shuffled over the pool) for one
+    configuration; checks that the packed cache equals the one made from the flat source, byte for byte."""
+    import torch
+    import paper_2503_23294_amd as ck
+    import workloads
+
+    dev = torch.device("cuda:0")
+    w = workloads.config(cfg)
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(workloads.chunk_bits(w)), ck.cocktail_default_workers(shape))
+    k, v = workloads.kv_flat(w, 0, threads=16)
+    src_bytes = int(k.nbytes + v.nbytes)
+    k_dev, v_dev = torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev)
+    del k, v
+    ref, cache = ck.PackedCache(plan, dev), ck.PackedCache(plan, dev)
+    ck.cocktail_reorder_quantize(ref, k_dev, v_dev, ragged=True)
+    off = workloads.seq_token_offsets(w)
+    h, d = w.num_kv_heads, w.head_dim
+    out = []
+    for ps in page_sizes:
+        need = [-(-t // ps) for t in w.seq_lens]
+        total = sum(need)
+        g = torch.Generator(device="cpu").manual_seed(ps)
+        ids = torch.randperm(total, generator=g).to(dev)
+        table = torch.full((w.batch, max(need)), -1, dtype=torch.int32, device=dev)
+        pools = []
+        for flat in (k_dev, v_dev):
+            pool = torch.zeros((total, h, ps, d), dtype=torch.float16, device=dev)
+            pos = 0
+            for b, t in enumerate(w.seq_lens):
+                if t == 0:
+                    continue
+                seq = flat[int(off[b]) * h * d:int(off[b + 1]) * h * d].view(h, t, d)
+                padded = torch.zeros((h, need[b] * ps, d), dtype=torch.float16, device=dev)
+                padded[:, :t] = seq
+                pool[ids[pos:pos + need[b]]] = padded.view(h, need[b], ps, d).permute(1, 0, 2, 3)
+                table[b, :need[b]] = ids[pos:pos + need[b]].to(torch.int32)
+                pos += need[b]
+                del padded
+            pools.append(pool)
+        for c in cache.k + cache.v:
+            c.zero_()
+        ck.cocktail_reorder_quantize_paged(cache, pools[0], pools[1], table)
+        torch.cuda.synchronize()
+        for a, b_ in zip(cache.k + cache.v, ref.k + ref.v):
+            assert torch.equal(a, b_), "paged source: packed cache differs from the one made from the flat source"
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        for i in range(reps):
+            ev[i].record()
+            ck.cocktail_reorder_quantize_paged(cache, pools[0], pools[1], table)
+        ev[reps].record()
+        torch.cuda.synchronize()
+        us = ev[0].elapsed_time(ev[reps]) * 1e3 / reps
+        nbytes = src_bytes + int(plan.sizes.packed_bytes)
+        out.append({"page_size": ps, "us": us, "gbps": nbytes / (us * 1e-6) / 1e9,
+                    "frac_of_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS})
+        del pools, table
+    del k_dev, v_dev, ref, cache
+    torch.cuda.empty_cache()
+    return out
+
+
 def stream_read_ceiling(nbytes):
     """The rate of a plain 128-bit streaming read of about `nbytes` over two alternating buffers (GB/s)."""
     import torch
@@ -275,6 +338,7 @@ def main():
             configs.append(entry)
         configs.sort(key=lambda e: e["workload"])
     head["frac_of_stream_read"] = gbps / stream_gbps
+    paged = paged_reorder_quantize(args.config, (16, 256)) if args.other_configs and not args.decode_only else None
 
     result = {
         "metric": METRIC, "value": head["decode_us"], "unit": "us/layer", "n_gpus": 1, "steps": args.steps,
@@ -296,6 +360,7 @@ def main():
         "stream_read_gbps": stream_gbps, "frac_of_stream_read": gbps / stream_gbps,
         "reorder_quantize_us": head["reorder_quantize_us"], "reorder_quantize_gbps": head["reorder_quantize_gbps"],
         "reorder_quantize_bytes": head["reorder_quantize_bytes"],
+        "reorder_quantize_from_pages": paged,
         "roofline": {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gbps / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_source,
                      "kernel": head["kernel"] + " + decode_merge_kernel (one call, timed together)"},

@@ -197,6 +197,36 @@ int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, co
                               const cocktail_cache* cache, void* stream);
 
 /*
+ * The same prefill step from a paged KV cache, the way serving stacks keep K and V between prefill and
+ * decode: two pools of fixed-size pages (one for K, one for V, same geometry) and a page table per
+ * sequence.  Token t of sequence b, kv head h, channel d is the fp16 element at
+ *     page_table[b * table_stride + t / page_size] * stride_page + h * stride_h + (t % page_size) * stride_t + d
+ * of k_pages (v_pages).  Blocks whose 64 tokens lie inside one page are read with one base address, the
+ * others row by row; any page_size >= 1 works, multiples of 64 are fastest.
+ *
+ *   k_pages, v_pages  DEVICE fp16, 16-byte aligned; strides in elements, multiples of 8, stride_t >= head_dim
+ *   page_table        DEVICE int32 [B][table_stride]; row b names the ceil(T_b / page_size) pages of sequence b
+ *                     in token order; entries behind them are not read.  An entry outside [0, num_pages) is
+ *                     not followed: the rows of that page are quantized as zeros.
+ *   cache, stream     as cocktail_reorder_quantize
+ *
+ * Errors: EINVAL (NULL, bad page geometry, a page table row too short for its sequence), EUNSUPPORTED, EALIGN, EHIP.
+ */
+typedef struct cocktail_paged_source {
+  const void* k_pages;
+  const void* v_pages;
+  const int32_t* page_table;
+  int32_t table_stride; /* entries per page table row                      */
+  int32_t page_size;    /* tokens per page                                 */
+  int32_t num_pages;    /* pages in each pool                              */
+  int32_t reserved;     /* must be zero                                    */
+  int64_t stride_page, stride_h, stride_t;
+} cocktail_paged_source;
+
+int cocktail_reorder_quantize_paged(const cocktail_shape* shape, const cocktail_paged_source* src,
+                                    const cocktail_cache* cache, void* stream);
+
+/*
  * Decode side of Alg. 1: out[b,h] = softmax(sm_scale * q[b,h] . K^_b^T) V^_b over
  * all tokens of the three classes of sequence b, K^/V^ being the dequantized
  * (or raw fp16) rows of kv head h / (Hq/Hkv).  Two launches: partial states per

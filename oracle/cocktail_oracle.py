@@ -318,6 +318,17 @@ def reorder_quantize(k_seqs: Sequence[np.ndarray], v_seqs: Sequence[np.ndarray],
     return OracleCache(d, group, chunk_size, hkv, plans, seqs, empty, [e.copy() for e in empty])
 
 
+def gather_pages(pages: np.ndarray, table_row: Sequence[int], seq_len: int) -> np.ndarray:
+    """A sequence's K (or V) from a paged cache: pages fp16 [num_pages, Hkv, page_size, D]; token t of the
+    sequence is slot t % page_size of page table_row[t // page_size].  Returns fp16 [Hkv, seq_len, D], the
+    input of reorder_quantize (Alg. 1 starts from the K, V of the whole context)."""
+    page_size = pages.shape[2]
+    out = np.empty((pages.shape[1], seq_len, pages.shape[3]), dtype=pages.dtype)
+    for t in range(seq_len):
+        out[:, t, :] = pages[table_row[t // page_size], :, t % page_size, :]
+    return out
+
+
 def append_tokens(cache: OracleCache, k_new: np.ndarray, v_new: np.ndarray) -> None:
     """Sec. III-A: one generated token per sequence joins the cache in FP16, behind everything else.
 

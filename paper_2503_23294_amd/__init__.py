@@ -6,11 +6,11 @@ of include/cocktail.h; this package is the thin binding over it.
 from .api import (CocktailError, PackedCache, Plan, Shape, cocktail_append_fp16, cocktail_chunk_bitwidths,
                   cocktail_decode_attention, cocktail_decode_attention_static, cocktail_decode_check,
                   cocktail_default_workers, cocktail_plan_field,
-                  cocktail_plan, cocktail_reorder_quantize, cocktail_selftest_arithmetic,
+                  cocktail_plan, cocktail_reorder_quantize, cocktail_reorder_quantize_paged, cocktail_selftest_arithmetic,
                   cocktail_stream_read_probe, make_shape)
 
 __all__ = ["CocktailError", "PackedCache", "Plan", "Shape", "cocktail_append_fp16", "cocktail_chunk_bitwidths",
            "cocktail_decode_attention", "cocktail_decode_attention_static", "cocktail_decode_check",
-           "cocktail_default_workers", "cocktail_plan_field", "cocktail_plan", "cocktail_reorder_quantize", "cocktail_selftest_arithmetic",
+           "cocktail_default_workers", "cocktail_plan_field", "cocktail_plan", "cocktail_reorder_quantize", "cocktail_reorder_quantize_paged", "cocktail_selftest_arithmetic",
            "cocktail_stream_read_probe",
            "make_shape"]

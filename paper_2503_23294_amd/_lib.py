@@ -45,6 +45,12 @@ class Cache(C.Structure):
                 ("k_app", C.c_void_p), ("v_app", C.c_void_p), ("num_appended", C.c_int32), ("reserved", C.c_int32)]
 
 
+class PagedSource(C.Structure):
+    _fields_ = [("k_pages", C.c_void_p), ("v_pages", C.c_void_p), ("page_table", C.c_void_p),
+                ("table_stride", C.c_int32), ("page_size", C.c_int32), ("num_pages", C.c_int32), ("reserved", C.c_int32),
+                ("stride_page", C.c_int64), ("stride_h", C.c_int64), ("stride_t", C.c_int64)]
+
+
 EXPORTS = {
     "cocktail_plan": (C.c_int, [C.POINTER(Shape), C.POINTER(C.c_int32), C.POINTER(C.c_uint8), C.c_int32,
                                 C.POINTER(Sizes), C.c_void_p, C.c_size_t, C.POINTER(C.c_int32),
@@ -58,6 +64,7 @@ EXPORTS = {
                                            C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "cocktail_reorder_quantize": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,
                                             C.c_int64, C.c_int64, C.POINTER(Cache), C.c_void_p]),
+    "cocktail_reorder_quantize_paged": (C.c_int, [C.POINTER(Shape), C.POINTER(PagedSource), C.POINTER(Cache), C.c_void_p]),
     "cocktail_decode_attention": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "cocktail_decode_attention_static": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float,

@@ -122,9 +122,40 @@ def cocktail_reorder_quantize(cache: PackedCache, k_src: torch.Tensor, v_src: to
         raise ValueError("k_src and v_src must be device tensors")
     sh = cache.plan.shape
     st = sh.head_dim if stride_t is None else stride_t
+    if not ragged and stride_b == 0 and stride_h == 0:
+        # no strides given: a contiguous [B, Hkv, T, stride_t] tensor
+        if k_src.dim() != 4 or not k_src.is_contiguous() or k_src.shape != v_src.shape or k_src.shape[:2] != (sh.batch, sh.num_kv_heads):
+            raise ValueError("without strides k_src and v_src must be contiguous [B, Hkv, T, D] tensors")
+        st = int(k_src.stride(2)) if stride_t is None else st
+        stride_b, stride_h = int(k_src.stride(0)), int(k_src.stride(1))
     check(lib().cocktail_reorder_quantize(C.byref(sh), k_src.data_ptr(), v_src.data_ptr(),
                                           _lib.SRC_RAGGED if ragged else _lib.SRC_STRIDED, stride_b, stride_h, st,
                                           C.byref(cache.desc), _stream_ptr(stream)))
+
+
+def cocktail_reorder_quantize_paged(cache: PackedCache, k_pages: torch.Tensor, v_pages: torch.Tensor,
+                                    page_table: torch.Tensor, *, head_major: bool = True,
+                                    stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Reorder + quantise + pack from a paged KV cache.  k_pages, v_pages: device fp16 [num_pages, Hkv, page_size, D]
+    (head_major) or [num_pages, page_size, Hkv, D]; page_table: device int32 [B, max pages per sequence]."""
+    sh = cache.plan.shape
+    for t in (k_pages, v_pages):
+        if t.dtype != torch.float16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise TypeError("k_pages and v_pages must be contiguous 4-d float16 device tensors")
+    if k_pages.shape != v_pages.shape or k_pages.shape[3] != sh.head_dim:
+        raise ValueError("k_pages and v_pages must have the same shape [pages, ., ., D]")
+    if page_table.dtype != torch.int32 or not page_table.is_cuda or not page_table.is_contiguous() or page_table.dim() != 2:
+        raise TypeError("page_table must be a contiguous int32 device tensor [B, pages per sequence]")
+    if page_table.shape[0] != sh.batch:
+        raise ValueError("page_table needs one row per sequence")
+    num_pages, a, b, d = k_pages.shape
+    page_size, hkv = (b, a) if head_major else (a, b)
+    if hkv != sh.num_kv_heads:
+        raise ValueError("page pools do not hold num_kv_heads heads")
+    src = _lib.PagedSource(k_pages.data_ptr(), v_pages.data_ptr(), page_table.data_ptr(), int(page_table.shape[1]),
+                           int(page_size), int(num_pages), 0, int(k_pages.stride(0)),
+                           int(k_pages.stride(1 if head_major else 2)), int(k_pages.stride(2 if head_major else 1)))
+    check(lib().cocktail_reorder_quantize_paged(C.byref(sh), C.byref(src), C.byref(cache.desc), _stream_ptr(stream)))
 
 
 def cocktail_append_fp16(cache: PackedCache, k_new: torch.Tensor, v_new: torch.Tensor,

@@ -5,6 +5,8 @@
 // in its final layout and written out with 16-byte coalesced stores.
 #include <hip/hip_runtime.h>
 
+#include <cstring>
+
 #include "common.h"
 #include "exact_div.h"
 #include "plan.h"
@@ -24,6 +26,11 @@ struct RQParams {
   int64_t stride_b, stride_h, stride_t;
   int32_t ragged;
   int32_t v_quads;         // V blocks in the token-quad form
+  // paged source: token t of sequence b lives in page page_table[b * table_stride + t / page_size], slot t % page_size
+  const int32_t* page_table;
+  int64_t stride_page;
+  int32_t page_size, table_stride, num_pages;
+  int32_t page_shift;      // log2(page_size) if it is a power of two, else -1
   int32_t cls_end0, cls_end1, cls_end2;  // prefix sums of class_blocks
 };
 
@@ -171,7 +178,7 @@ __device__ __forceinline__ void quantize_rows(LoadRow load_row, char* lds, int r
   }
 }
 
-template <int D, int G>
+template <int D, int G, bool PAGED>
 __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   static_assert(D == 128, "one 16-lane row of 8 channels per lane");
   __shared__ __attribute__((aligned(16))) char lds[kTB * 2 * D];
@@ -183,7 +190,20 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   const int cls = item.cls_nvalid & 0xff, nvalid = item.cls_nvalid >> 8;
   const int t0 = item.t0, j = item.j, b = item.b, h = item.h;
   const _Float16* src;       // row 0 of the block (consecutive rows) or token 0 of the head (row by row)
-  if (p.ragged) {
+  bool per_row = t0 < 0;     // rows are looked up one by one
+  if constexpr (PAGED) {
+    src = p.src[which] + h * p.stride_h;     // the head inside a page; page and slot are added per block or per row
+    const int last = t0 + (item.cls_nvalid >> 8) - 1;
+    const int pg = t0 < 0 ? 0 : p.page_shift >= 0 ? t0 >> p.page_shift : t0 / p.page_size;
+    if (t0 >= 0 && (p.page_shift >= 0 ? last >> p.page_shift : last / p.page_size) == pg) {
+      // the whole block lies inside one page: consecutive rows again
+      const int page = p.page_table[int64_t(b) * p.table_stride + pg];
+      if (uint32_t(page) < uint32_t(p.num_pages)) src += int64_t(page) * p.stride_page + int64_t(t0 - pg * p.page_size) * p.stride_t;
+      else per_row = true;   // a page id outside the pool: the per-row path turns its rows into zeros
+    } else {
+      per_row = true;
+    }
+  } else if (p.ragged) {
     src = p.src[which] + item.ragged_row * p.stride_t;
   } else {
     src = p.src[which] + b * p.stride_b + h * p.stride_h + int64_t(t0 >= 0 ? t0 : 0) * p.stride_t;
@@ -212,21 +232,48 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   // source rows (almost every block): one pointer per thread and a fixed step per pass.
   const _Float16* const row_ptr = src + int64_t(row) * p.stride_t + seg * 8;
   const int64_t pass_step = 16 * p.stride_t;
+  // source token of row i of the block when the rows are looked up one by one
+  auto token_of = [&](int i) {
+    if (t0 >= 0) return t0 + i;
+    const int r = j * kTB + i;      // row inside the class run of (b, h)
+    if (r < chunk_tokens) {
+      const int slot = r / C;
+      return perm[cc0 + slot] * C + (r - slot * C);
+    }
+    return N * C + (r - chunk_tokens);   // Sec. III-A: tail tokens follow the FP16 chunks
+  };
+  // paged source, rows one by one: the page ids of this thread's four rows are fetched up front, so that
+  // the four row loads do not each wait for a table look-up first (-1: not a page of the pool)
+  int row_page[4] = {0, 0, 0, 0};
+  if constexpr (PAGED) {
+    if (per_row) {
+#pragma unroll
+      for (int pass = 0; pass < 4; ++pass) {
+        const int i = pass * 16 + row;
+        int page = -1;
+        if (i < nvalid) {
+          const int t = token_of(i);
+          page = p.page_table[int64_t(b) * p.table_stride + (p.page_shift >= 0 ? t >> p.page_shift : t / p.page_size)];
+          if (uint32_t(page) >= uint32_t(p.num_pages)) page = -1;
+        }
+        row_page[pass] = page;
+      }
+    }
+  }
   auto load_row = [&](int pass) {
     const int i = pass * 16 + row;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (i < nvalid) {
       const _Float16* ptr = row_ptr + pass * pass_step;
-      if (t0 < 0) {
-        int t;
-        const int r = j * kTB + i;      // row inside the class run of (b, h)
-        if (r < chunk_tokens) {
-          const int slot = r / C;
-          t = perm[cc0 + slot] * C + (r - slot * C);
+      if (per_row) {
+        const int t = token_of(i);
+        if constexpr (PAGED) {
+          if (row_page[pass] < 0) return v;   // the row reads as zeros
+          const int slot = p.page_shift >= 0 ? t & (p.page_size - 1) : t % p.page_size;
+          ptr = src + int64_t(row_page[pass]) * p.stride_page + int64_t(slot) * p.stride_t + seg * 8;
         } else {
-          t = N * C + (r - chunk_tokens);   // Sec. III-A: tail tokens follow the FP16 chunks
+          ptr = src + int64_t(t) * p.stride_t + seg * 8;
         }
-        ptr = src + int64_t(t) * p.stride_t + seg * 8;
       }
       v = RQ_LOAD(reinterpret_cast<const u32x4*>(ptr));
     }
@@ -314,34 +361,15 @@ extern "C" int cocktail_selftest_arithmetic(uint64_t* mismatches, void* stream) 
 }
 
 
-extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, const void* v_src,
-                                         int32_t src_layout, int64_t stride_b, int64_t stride_h,
-                                         int64_t stride_t, const cocktail_cache* cache, void* stream) {
-  if (int rc = check_shape(shape)) return rc;
-  if (!cache || !cache->plan_host || !cache->plan_dev) return fail(COCKTAIL_EINVAL, "cache or its plan is NULL");
-  const PlanHeader* hd = static_cast<const PlanHeader*>(cache->plan_host);
-  if (hd->magic != kPlanMagic || hd->version != kPlanVersion)
-    return fail(COCKTAIL_EINVAL, "plan_host is not a plan written by this library version");
-  if (hd->batch != shape->batch || hd->num_kv_heads != shape->num_kv_heads || hd->head_dim != shape->head_dim ||
-      hd->chunk_size != shape->chunk_size || hd->group_size != shape->group_size ||
-      hd->num_q_heads != shape->num_q_heads)
-    return fail(COCKTAIL_EINVAL, "plan was made for a different shape");
-  if (shape->head_dim != 128) return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
-  if (src_layout != COCKTAIL_SRC_STRIDED && src_layout != COCKTAIL_SRC_RAGGED)
-    return fail(COCKTAIL_EINVAL, "unknown src_layout %d", src_layout);
-  if (hd->total_tokens > 0 && (!k_src || !v_src)) return fail(COCKTAIL_EINVAL, "k_src or v_src is NULL");
-  if ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src) |
-       reinterpret_cast<uintptr_t>(cache->plan_dev)) & 15)
-    return fail(COCKTAIL_EALIGN, "k_src, v_src and plan_dev must be 16-byte aligned");
-  if (stride_t < shape->head_dim || (stride_t & 7))
-    return fail(COCKTAIL_EINVAL, "stride_t %lld must be >= head_dim and a multiple of 8", (long long)stride_t);
-  if (src_layout == COCKTAIL_SRC_STRIDED && (stride_b < 0 || stride_h < 0 || (stride_b & 7) || (stride_h & 7)))
-    return fail(COCKTAIL_EINVAL, "stride_b and stride_h must be non-negative multiples of 8");
-  RQParams p;
+namespace {
+
+// Checks the cache against its plan, fills the destination part of the parameters and launches: the append
+// buffers are cleared, then one launch covers K and V of all classes.
+int launch_reorder_quantize(const cocktail_shape* shape, const cocktail_cache* cache, const PlanHeader* hd, RQParams p,
+                            bool paged, void* stream) {
+  if (reinterpret_cast<uintptr_t>(cache->plan_dev) & 15) return fail(COCKTAIL_EALIGN, "plan_dev must be 16-byte aligned");
   p.plan = cache->plan_dev;
   p.items = reinterpret_cast<const RQItem*>(static_cast<const char*>(cache->plan_dev) + hd->off_rq_items);
-  p.src[0] = static_cast<const _Float16*>(k_src);
-  p.src[1] = static_cast<const _Float16*>(v_src);
   int64_t tot = 0;
   for (int c = 0; c < 3; ++c) {
     if (hd->class_bytes[c] > 0 && (!cache->k[c] || !cache->v[c]))
@@ -354,8 +382,6 @@ extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void
     tot += hd->class_blocks[c];
   }
   if (tot >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "too many blocks for one launch");
-  p.stride_b = stride_b, p.stride_h = stride_h, p.stride_t = stride_t;
-  p.ragged = (src_layout == COCKTAIL_SRC_RAGGED);
   p.v_quads = hd->v_layout;
   p.cls_end0 = static_cast<int32_t>(hd->class_blocks[0]);
   p.cls_end1 = p.cls_end0 + static_cast<int32_t>(hd->class_blocks[1]);
@@ -372,12 +398,94 @@ extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void
   }
   if (tot == 0) return COCKTAIL_OK;
   const dim3 grid(static_cast<unsigned>(tot), 2, 1), block(256, 1, 1);
+#define COCKTAIL_RQ_LAUNCH(G)                                                                      \
+  if (paged) hipLaunchKernelGGL((reorder_quantize_kernel<128, G, true>), grid, block, 0, st, p);  \
+  else hipLaunchKernelGGL((reorder_quantize_kernel<128, G, false>), grid, block, 0, st, p)
   switch (shape->group_size) {
-    case 32: hipLaunchKernelGGL((reorder_quantize_kernel<128, 32>), grid, block, 0, st, p); break;
-    case 64: hipLaunchKernelGGL((reorder_quantize_kernel<128, 64>), grid, block, 0, st, p); break;
-    default: hipLaunchKernelGGL((reorder_quantize_kernel<128, 128>), grid, block, 0, st, p); break;
+    case 32: COCKTAIL_RQ_LAUNCH(32); break;
+    case 64: COCKTAIL_RQ_LAUNCH(64); break;
+    default: COCKTAIL_RQ_LAUNCH(128); break;
   }
+#undef COCKTAIL_RQ_LAUNCH
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(COCKTAIL_EHIP, "reorder_quantize launch failed: %s", hipGetErrorString(e));
   return COCKTAIL_OK;
+}
+
+int plan_of(const cocktail_shape* shape, const cocktail_cache* cache, const PlanHeader** out) {
+  if (int rc = check_shape(shape)) return rc;
+  if (!cache || !cache->plan_host || !cache->plan_dev) return fail(COCKTAIL_EINVAL, "cache or its plan is NULL");
+  const PlanHeader* hd = static_cast<const PlanHeader*>(cache->plan_host);
+  if (hd->magic != kPlanMagic || hd->version != kPlanVersion)
+    return fail(COCKTAIL_EINVAL, "plan_host is not a plan written by this library version");
+  if (hd->batch != shape->batch || hd->num_kv_heads != shape->num_kv_heads || hd->head_dim != shape->head_dim ||
+      hd->chunk_size != shape->chunk_size || hd->group_size != shape->group_size ||
+      hd->num_q_heads != shape->num_q_heads)
+    return fail(COCKTAIL_EINVAL, "plan was made for a different shape");
+  if (shape->head_dim != 128) return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
+  *out = hd;
+  return COCKTAIL_OK;
+}
+
+}  // namespace
+
+extern "C" int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, const void* v_src,
+                                         int32_t src_layout, int64_t stride_b, int64_t stride_h,
+                                         int64_t stride_t, const cocktail_cache* cache, void* stream) {
+  const PlanHeader* hd = nullptr;
+  if (int rc = plan_of(shape, cache, &hd)) return rc;
+  if (src_layout != COCKTAIL_SRC_STRIDED && src_layout != COCKTAIL_SRC_RAGGED)
+    return fail(COCKTAIL_EINVAL, "unknown src_layout %d (a paged source goes through cocktail_reorder_quantize_paged)", src_layout);
+  if (hd->total_tokens > 0 && (!k_src || !v_src)) return fail(COCKTAIL_EINVAL, "k_src or v_src is NULL");
+  if ((reinterpret_cast<uintptr_t>(k_src) | reinterpret_cast<uintptr_t>(v_src) |
+       reinterpret_cast<uintptr_t>(cache->plan_dev)) & 15)
+    return fail(COCKTAIL_EALIGN, "k_src, v_src and plan_dev must be 16-byte aligned");
+  if (stride_t < shape->head_dim || (stride_t & 7))
+    return fail(COCKTAIL_EINVAL, "stride_t %lld must be >= head_dim and a multiple of 8", (long long)stride_t);
+  if (src_layout == COCKTAIL_SRC_STRIDED && (stride_b < 0 || stride_h < 0 || (stride_b & 7) || (stride_h & 7)))
+    return fail(COCKTAIL_EINVAL, "stride_b and stride_h must be non-negative multiples of 8");
+  RQParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.src[0] = static_cast<const _Float16*>(k_src);
+  p.src[1] = static_cast<const _Float16*>(v_src);
+  p.stride_b = stride_b, p.stride_h = stride_h, p.stride_t = stride_t;
+  p.ragged = (src_layout == COCKTAIL_SRC_RAGGED);
+  return launch_reorder_quantize(shape, cache, hd, p, false, stream);
+}
+
+extern "C" int cocktail_reorder_quantize_paged(const cocktail_shape* shape, const cocktail_paged_source* src,
+                                               const cocktail_cache* cache, void* stream) {
+  const PlanHeader* hd = nullptr;
+  if (int rc = plan_of(shape, cache, &hd)) return rc;
+  if (!src) return fail(COCKTAIL_EINVAL, "src is NULL");
+  if (src->reserved != 0) return fail(COCKTAIL_EINVAL, "cocktail_paged_source::reserved must be zero");
+  if (src->page_size < 1 || src->num_pages < 1 || src->table_stride < 0)
+    return fail(COCKTAIL_EINVAL, "page_size and num_pages must be >= 1, table_stride >= 0");
+  if (hd->total_tokens > 0 && (!src->k_pages || !src->v_pages || !src->page_table))
+    return fail(COCKTAIL_EINVAL, "k_pages, v_pages or page_table is NULL");
+  if ((reinterpret_cast<uintptr_t>(src->k_pages) | reinterpret_cast<uintptr_t>(src->v_pages)) & 15)
+    return fail(COCKTAIL_EALIGN, "k_pages and v_pages must be 16-byte aligned");
+  if (reinterpret_cast<uintptr_t>(src->page_table) & 3) return fail(COCKTAIL_EALIGN, "page_table must be 4-byte aligned");
+  if (src->stride_t < shape->head_dim || (src->stride_t & 7))
+    return fail(COCKTAIL_EINVAL, "stride_t %lld must be >= head_dim and a multiple of 8", (long long)src->stride_t);
+  if (src->stride_page < 0 || src->stride_h < 0 || (src->stride_page & 7) || (src->stride_h & 7))
+    return fail(COCKTAIL_EINVAL, "stride_page and stride_h must be non-negative multiples of 8");
+  const int32_t* seq_len = plan_array<int32_t>(cache->plan_host, hd->off_seq_len);
+  for (int b = 0; b < hd->batch; ++b) {
+    const int64_t need = (int64_t(seq_len[b]) + src->page_size - 1) / src->page_size;
+    if (need > src->table_stride)
+      return fail(COCKTAIL_EINVAL, "sequence %d has %d tokens = %lld pages of %d, but a page table row holds %d entries",
+                  b, seq_len[b], (long long)need, src->page_size, src->table_stride);
+  }
+  RQParams p;
+  std::memset(&p, 0, sizeof(p));
+  p.src[0] = static_cast<const _Float16*>(src->k_pages);
+  p.src[1] = static_cast<const _Float16*>(src->v_pages);
+  p.stride_h = src->stride_h, p.stride_t = src->stride_t, p.stride_page = src->stride_page;
+  p.page_table = src->page_table;
+  p.page_size = src->page_size, p.table_stride = src->table_stride, p.num_pages = src->num_pages;
+  p.page_shift = -1;
+  for (int sft = 0; sft < 31; ++sft)
+    if (src->page_size == (1 << sft)) p.page_shift = sft;
+  return launch_reorder_quantize(shape, cache, hd, p, true, stream);
 }

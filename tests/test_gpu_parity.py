@@ -173,6 +173,60 @@ def test_strided_padded_source():
     Case(w, workers=4, strided_pad=8).check_all()
 
 
+@pytest.mark.parametrize("page_size,head_major,rep", [(16, True, 1), (64, False, 1), (128, True, 4), (5, True, 1), (256, False, 2)])
+def test_paged_source(page_size, head_major, rep):
+    """Reorder+quantize straight from a paged KV cache with a shuffled page table: the packed cache must be the
+    one the oracle makes from the gathered K and V, byte for byte."""
+    w = workloads.small(f"paged{page_size}", 3, 2 * rep, 2, [64 * 9 + 21, 0, 700], 32, 32, mix=(0.2, 0.4, 0.4),
+                        seed_offset=600 + page_size)
+    _announce(f"{w.name} head_major={head_major} rep={rep}")
+    dev = _dev()
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = workloads.chunk_bits(w)
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), 8)
+    cache = ck.PackedCache(plan, dev)
+    for t in cache.k + cache.v:
+        t.fill_(0xAB)
+    rng = np.random.default_rng(page_size)
+    need = [(t + page_size - 1) // page_size for t in w.seq_lens]
+    num_pages = sum(need) + 5
+    ids = rng.permutation(num_pages)
+    table = np.full((w.batch, max(need) + 2), -1, dtype=np.int32)             # entries behind a sequence's pages are not read
+    kp = rng.standard_normal((num_pages, w.num_kv_heads, page_size, w.head_dim), dtype=np.float32).astype(np.float16)
+    vp = rng.standard_normal((num_pages, w.num_kv_heads, page_size, w.head_dim), dtype=np.float32).astype(np.float16)
+    pos = 0
+    for b in range(w.batch):
+        table[b, :need[b]] = ids[pos:pos + need[b]]
+        pos += need[b]
+        for h in range(w.num_kv_heads):
+            kh, vh = workloads.kv_head(w, 0, b, h)
+            for t in range(w.seq_lens[b]):
+                kp[table[b, t // page_size], h, t % page_size] = kh[t]
+                vp[table[b, t // page_size], h, t % page_size] = vh[t]
+    if not head_major:
+        kp, vp = np.ascontiguousarray(kp.transpose(0, 2, 1, 3)), np.ascontiguousarray(vp.transpose(0, 2, 1, 3))
+    ck.cocktail_reorder_quantize_paged(cache, torch.from_numpy(kp).to(dev), torch.from_numpy(vp).to(dev),
+                                       torch.from_numpy(table).to(dev), head_major=head_major)
+    torch.cuda.synchronize()
+    pools = (kp, vp) if head_major else (kp.transpose(0, 2, 1, 3), vp.transpose(0, 2, 1, 3))
+    ks = [O.gather_pages(pools[0], table[b], w.seq_lens[b]) for b in range(w.batch)]
+    vs = [O.gather_pages(pools[1], table[b], w.seq_lens[b]) for b in range(w.batch)]
+    oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    v_quads = int(plan.sizes.v_layout) == 1
+    for c in range(3):
+        assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k")), f"K class {c}"
+        assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads)), f"V class {c}"
+    q = workloads.query(w, 0)
+    out, _ = ck.cocktail_decode_attention(cache, torch.from_numpy(q).to(dev))
+    ck.cocktail_decode_check(cache)
+    ref, _ = O.decode_attention(q, oc)
+    got = out.cpu().numpy().astype(np.float64)
+    for b in range(w.batch):
+        if w.seq_lens[b]:
+            err = np.abs(got[b] - ref[b]).max(axis=1) / np.abs(ref[b]).max(axis=1)
+            assert err.max() <= TOL
+
+
 def test_more_workers_than_blocks_and_repeatability():
     w = workloads.small("tiny", 1, 1, 1, [70], 16, 32, seed_offset=2)
     _announce(w.name)

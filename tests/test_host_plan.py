@@ -288,6 +288,34 @@ def test_gpu_entry_points_validate_on_host_before_launching():
     assert L.cocktail_stream_read_probe(16, 1 << 20, 16, C.byref(n), None) == _lib.EINVAL
 
 
+def test_paged_source_is_validated_on_the_host():
+    sh = ck.make_shape(2, 2, 2, 128, 8, 32)
+    plan = ck.cocktail_plan(sh, [100, 40], [2, 4] * 6 + [16] * 5, 4)
+    L = _lib.lib()
+    cache = _lib.Cache()
+    cache.plan_host = plan.blob.ctypes.data
+    cache.plan_dev = 4096
+    ok = dict(k_pages=4096, v_pages=4096, page_table=4096, table_stride=7, page_size=16, num_pages=20, reserved=0,
+              stride_page=2 * 16 * 128, stride_h=16 * 128, stride_t=128)
+
+    def call(**kw):
+        src = _lib.PagedSource(**{**ok, **kw})
+        return L.cocktail_reorder_quantize_paged(C.byref(sh), C.byref(src), C.byref(cache), None)
+
+    assert call(table_stride=6) == _lib.EINVAL and b"page table row" in L.cocktail_last_error()   # 100 tokens = 7 pages
+    assert call(page_size=0) == _lib.EINVAL
+    assert call(num_pages=0) == _lib.EINVAL
+    assert call(k_pages=None) == _lib.EINVAL
+    assert call(page_table=None) == _lib.EINVAL
+    assert call(v_pages=4104) == _lib.EALIGN
+    assert call(stride_t=100) == _lib.EINVAL
+    assert call(stride_h=4) == _lib.EINVAL
+    assert call(reserved=1) == _lib.EINVAL
+    assert call() == _lib.EINVAL and b"cache buffer" in L.cocktail_last_error()      # geometry accepted, class buffers are NULL
+    assert L.cocktail_reorder_quantize_paged(C.byref(sh), None, C.byref(cache), None) == _lib.EINVAL
+    assert L.cocktail_reorder_quantize(C.byref(sh), 16, 16, 2, 0, 0, 128, C.byref(cache), None) == _lib.EINVAL
+
+
 def test_append_capacity_sizes_and_validation():
     w = workloads.config(1)
     sh = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)

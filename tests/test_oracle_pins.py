@@ -569,3 +569,20 @@ def test_signed_zeros_do_not_reach_scale_or_zero():
         x = np.array([[-3.0, z] + [-1.5] * 30], dtype=np.float16)
         codes, scale, zero = O.quantize_rows(x, 2, 32)
         assert float(scale[0, 0]) == 1.0 and float(zero[0, 0]) == -3.0 and codes[0, :3].tolist() == [0, 3, 2]
+
+
+def test_page_gather_by_hand_and_round_trip():
+    """gather_pages against a table typed out by hand, and as the inverse of a scatter into shuffled pages."""
+    # 3 pages of 2 tokens, 1 head, D = 1: page p, slot s holds the value 10 p + s
+    pages = np.array([[[[0.0], [1.0]]], [[[10.0], [11.0]]], [[[20.0], [21.0]]]], dtype=np.float16)
+    got = O.gather_pages(pages, [2, 0, 1], 5)                       # tokens 0,1 from page 2; 2,3 from page 0; 4 from page 1
+    assert got[0, :, 0].tolist() == [20.0, 21.0, 0.0, 1.0, 10.0]
+    rng = np.random.default_rng(5)
+    hkv, t, d, ps = 2, 37, 8, 4
+    k = rng.standard_normal((hkv, t, d)).astype(np.float16)
+    npages = (t + ps - 1) // ps
+    table = rng.permutation(npages + 3)[:npages]                    # pages anywhere in a larger pool
+    pool = np.zeros((npages + 3, hkv, ps, d), dtype=np.float16)
+    for tok in range(t):
+        pool[table[tok // ps], :, tok % ps, :] = k[:, tok, :]
+    assert np.array_equal(O.gather_pages(pool, table, t), k)
