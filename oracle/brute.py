@@ -78,17 +78,17 @@ def quantize_group(xs: Sequence[float], bits: int):
 def plan(seq_len: int, chunk: int, bits: Sequence[int]):
     n = seq_len // chunk
     order = []
-    for want in (2, 4, 16):
+    for want in (2, 4, 8, 16):
         for i in range(n):
             if bits[i] == want:
                 order.append(i)
-    tok = {2: [], 4: [], 16: []}
+    tok = {2: [], 4: [], 8: [], 16: []}
     for i in order:
         for r in range(chunk):
             tok[bits[i]].append(i * chunk + r)
     for t in range(n * chunk, seq_len):
         tok[16].append(t)
-    return order, [tok[2], tok[4], tok[16]]
+    return order, [tok[2], tok[4], tok[8], tok[16]]
 
 
 def fp16_bytes(x: float) -> bytes:

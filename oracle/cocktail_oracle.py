@@ -44,20 +44,24 @@ from typing import Dict, List, Sequence, Tuple
 
 import numpy as np
 
-CLASS_BITS = (2, 4, 16)        # class index 0, 1, 2 = Alg. 1 concat order INT2, INT4, FP16
+# Class index = position in the concatenation of Alg. 1's decode phase (INT2, INT4, FP16 there).  INT8,
+# which the paper names as a further bitwidth (Sec. I), takes its place by precision: INT2, INT4, INT8, FP16.
+CLASS_BITS = (2, 4, 8, 16)
+NUM_CLASSES = len(CLASS_BITS)
+FP16_CLASS = NUM_CLASSES - 1
 TOKENS_PER_BLOCK = 64
 
 
 def class_of_bits(bits: int) -> int:
-    return {2: 0, 4: 1, 16: 2}[int(bits)]
+    return {2: 0, 4: 1, 8: 2, 16: 3}[int(bits)]
 
 
 # --------------------------------------------------------------------------- plan
 @dataclass
 class SeqPlan:
     perm: np.ndarray            # int32 [N]: reordered position j holds original chunk perm[j]
-    class_chunks: Tuple[int, int, int]
-    class_tokens: Tuple[int, int, int]   # FP16 count includes the unchunked tail
+    class_chunks: Tuple[int, ...]        # per class
+    class_tokens: Tuple[int, ...]        # per class; the FP16 count includes the unchunked tail
     tail: int
 
 
@@ -66,12 +70,12 @@ def plan_sequence(seq_len: int, chunk_size: int, bits: np.ndarray) -> SeqPlan:
     n = seq_len // chunk_size
     bits = np.asarray(bits)
     assert bits.shape == (n,)
-    # a stable partition by class: INT2 chunks first, then INT4, then FP16, each in original order
+    # a stable partition by class: INT2 chunks first, then INT4, INT8, FP16, each in original order
     cls = np.array([class_of_bits(x) for x in bits], dtype=np.int64)
     perm = np.argsort(cls, kind="stable").astype(np.int32)
     tail = seq_len - n * chunk_size          # Sec. III-A: remainder kept in FP16
-    cc = tuple(int((cls == c).sum()) for c in range(3))
-    ct = (cc[0] * chunk_size, cc[1] * chunk_size, cc[2] * chunk_size + tail)
+    cc = tuple(int((cls == c).sum()) for c in range(NUM_CLASSES))
+    ct = tuple(cc[c] * chunk_size + (tail if c == FP16_CLASS else 0) for c in range(NUM_CLASSES))
     return SeqPlan(perm, cc, ct, tail)
 
 
@@ -79,11 +83,11 @@ def class_token_index(seq_len: int, chunk_size: int, sp: SeqPlan) -> List[np.nda
     """For each class, the original token index of every token of that class, in cache order."""
     out = []
     pos = 0
-    for c in range(3):
+    for c in range(NUM_CLASSES):
         chunks = sp.perm[pos:pos + sp.class_chunks[c]]
         pos += sp.class_chunks[c]
         idx = (chunks[:, None].astype(np.int64) * chunk_size + np.arange(chunk_size)[None, :]).reshape(-1)
-        if c == 2 and sp.tail:
+        if c == FP16_CLASS and sp.tail:
             idx = np.concatenate([idx, np.arange(seq_len - sp.tail, seq_len, dtype=np.int64)])
         out.append(idx.astype(np.int64))
     return out
@@ -102,7 +106,7 @@ def quantize_rows(x: np.ndarray, bits: int, group: int):
       codes  = 0                                   if scale == 0
              = clamp(rint((f32(x) - f32(mn)) * (1 / f32(scale))), 0, qmax)   otherwise
     """
-    assert x.dtype == np.float16 and bits in (2, 4)
+    assert x.dtype == np.float16 and bits in (2, 4, 8)
     d = x.shape[-1]
     assert d % group == 0
     qmax = np.float32((1 << bits) - 1)
@@ -214,7 +218,7 @@ def pack_quad_blocks(vals: np.ndarray, bits: int, meta_bytes) -> np.ndarray:
     So a word pairs two tokens of the quad for the same channels, and two consecutive words
     cover all four.  The meta bytes (scale, zero per token and group) follow as in the row form."""
     n, d = vals.shape
-    assert d % 64 == 0 and bits in (2, 4, 16)
+    assert d % 64 == 0 and bits in (2, 4, 8, 16)
     tb = TOKENS_PER_BLOCK
     nblk = (n + tb - 1) // tb
     per = 16 // bits
@@ -285,7 +289,7 @@ class OracleCache:
     chunk_size: int
     num_kv_heads: int
     plans: List[SeqPlan]
-    seqs: List[List[ClassCache]]         # [B][3]
+    seqs: List[List[ClassCache]]         # [B][NUM_CLASSES]
     app_k: List[np.ndarray] = None       # [B] fp16 [Hkv, n_app, D]: rows appended during decoding
     app_v: List[np.ndarray] = None
 
@@ -303,10 +307,10 @@ def reorder_quantize(k_seqs: Sequence[np.ndarray], v_seqs: Sequence[np.ndarray],
         sp = plan_sequence(t, chunk_size, bits)
         idx = class_token_index(t, chunk_size, sp)
         ccs = []
-        for c in range(3):
+        for c in range(NUM_CLASSES):
             kc, vc = k[:, idx[c], :], v[:, idx[c], :]          # the reordered, contiguous class
             cc = ClassCache(CLASS_BITS[c], len(idx[c]))
-            if c == 2:
+            if c == FP16_CLASS:
                 cc.k_raw, cc.v_raw = np.ascontiguousarray(kc), np.ascontiguousarray(vc)
             else:
                 cc.k_codes, cc.k_scale, cc.k_zero = quantize_rows(kc, CLASS_BITS[c], group)
@@ -427,7 +431,7 @@ def unpack_class_buffer(buf: np.ndarray, cache_like: OracleCache, cls: int):
 
 
 def dequantized_kv(cache: OracleCache, b: int, h: int) -> Tuple[np.ndarray, np.ndarray]:
-    """float64 [n_total, D] K-hat and V-hat of (b, kv head h) in cache order INT2 | INT4 | FP16 | appended."""
+    """float64 [n_total, D] K-hat and V-hat of (b, kv head h) in cache order INT2 | INT4 | INT8 | FP16 | appended."""
     ks, vs = [], []
     for cc in cache.seqs[b]:
         if cc.bits == 16:
@@ -500,7 +504,7 @@ def kv_bytes_fp16(layers: int, heads: int, head_dim: int, tokens: int) -> int:
 
 def packed_bytes(class_tokens: Sequence[int], num_kv_heads: int, head_dim: int, group: int) -> int:
     """Algorithmic bytes (K + V) of the packed cache of one sequence: codes + fp16 scale/zero per group."""
-    per = [head_dim * 2 // 8 + 4 * head_dim // group, head_dim * 4 // 8 + 4 * head_dim // group, head_dim * 2]
+    per = [head_dim * b // 8 + (4 * head_dim // group if b < 16 else 0) for b in CLASS_BITS]
     return 2 * num_kv_heads * sum(n * p for n, p in zip(class_tokens, per))
 
 

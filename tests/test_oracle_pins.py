@@ -95,14 +95,19 @@ def test_plan_is_stable_partition_and_tail_is_fp16():
     bits = np.array([4, 2, 16, 2, 4, 4, 16, 2], dtype=np.uint8)
     sp = O.plan_sequence(8 * 8 + 3, 8, bits)
     assert sp.perm.tolist() == [1, 3, 7, 0, 4, 5, 2, 6]          # INT2 | INT4 | FP16, each ascending
-    assert sp.class_tokens == (24, 24, 16 + 3) and sp.tail == 3
+    assert sp.class_tokens == (24, 24, 0, 16 + 3) and sp.tail == 3
     idx = O.class_token_index(67, 8, sp)
-    assert idx[2].tolist()[-3:] == [64, 65, 66]                    # tail follows the FP16 chunks
+    assert idx[O.FP16_CLASS].tolist()[-3:] == [64, 65, 66]         # tail follows the FP16 chunks
     assert sorted(np.concatenate(idx).tolist()) == list(range(67))
+    # with INT8 chunks: INT2 | INT4 | INT8 | FP16, by precision
+    bits = np.array([8, 16, 2, 8, 4, 2], dtype=np.uint8)
+    sp = O.plan_sequence(6 * 4 + 1, 4, bits)
+    assert sp.perm.tolist() == [2, 5, 4, 0, 3, 1] and sp.class_tokens == (8, 4, 8, 4 + 1)
+    assert O.class_token_index(25, 4, sp)[2].tolist() == [0, 1, 2, 3, 12, 13, 14, 15]
 
 
 # -- 3. quantisation bound and extremes ----------------------------------------------------
-@pytest.mark.parametrize("bits,group", [(2, 32), (4, 32), (2, 64), (4, 64), (2, 128), (4, 128)])
+@pytest.mark.parametrize("bits,group", [(2, 32), (4, 32), (2, 64), (4, 64), (2, 128), (4, 128), (8, 32), (8, 64), (8, 128)])
 def test_quantisation_error_at_most_half_a_step(bits, group):
     rng = np.random.default_rng(7)
     x = rng.standard_normal((512, 128)).astype(np.float32)
@@ -113,7 +118,9 @@ def test_quantisation_error_at_most_half_a_step(bits, group):
     assert codes.min() >= 0 and codes.max() <= qmax
     xh = O.dequantize(codes, scale, zero, group)
     sc = np.repeat(scale.astype(np.float64), group, axis=-1)
-    assert (np.abs(x.astype(np.float64) - xh) <= 0.5 * sc * (1 + 1e-4) + 1e-30).all()
+    # half a step, plus what the fp16 rounding of the scale (relative 2^-11) can add at the far end of the
+    # range: up to qmax * 2^-11 steps, which only shows at 8 bits
+    assert (np.abs(x.astype(np.float64) - xh) <= (0.5 * (1 + 1e-4) + qmax * 2.0 ** -11) * sc + 1e-30).all()
     cg = codes.reshape(512, 128 // group, group)
     assert (cg.min(-1) == 0).all() and (cg.max(-1) == qmax).all()   # min -> 0, max -> qmax
     xg = x.reshape(512, 128 // group, group)
@@ -126,6 +133,13 @@ def test_closed_form_groups():
     assert (c == row).all() and (s == 1).all() and (z == 0).all()
     row = np.tile(np.arange(16, dtype=np.float16), 8)[None]
     c, s, z = O.quantize_rows(row, 4, 64)
+    assert (c == row).all() and (s == 1).all() and (z == 0).all()
+    # 8 bits: integers of [0, 255] with 0 and 255 in every group: scale 1, zero 0, codes = values
+    grp = np.array([0, 255] + [17, 200, 3, 128] * 7 + [9, 77], dtype=np.float16)
+    c, s, z = O.quantize_rows(np.tile(grp, 4)[None], 8, 32)
+    assert (s == 1).all() and (z == 0).all() and (c == np.tile(grp, 4)[None]).all()
+    row = np.array([0, 255] + list(range(1, 127)), dtype=np.float16)[None]          # one group of 128 channels
+    c, s, z = O.quantize_rows(row, 8, 128)
     assert (c == row).all() and (s == 1).all() and (z == 0).all()
     const = np.full((1, 128), -2.5, dtype=np.float16)                          # constant: scale 0, exact
     c, s, z = O.quantize_rows(const, 4, 32)
@@ -169,7 +183,7 @@ def test_rounding_helper_matches_ieee():
     assert brute.rn16(Fraction(1, 2 ** 25)) == 0 and brute.rn16(Fraction(3, 2 ** 25)) == Fraction(1, 2 ** 23)
 
 
-@pytest.mark.parametrize("bits", [2, 4])
+@pytest.mark.parametrize("bits", [2, 4, 8])
 def test_quantiser_matches_exact_rational_brute_force(bits):
     rng = np.random.default_rng(11 + bits)
     x = rng.standard_normal((40, 64)).astype(np.float32)
@@ -196,11 +210,14 @@ def _tiny_case(bsz, hkv, rep, d, t_list, chunk, group, assign, seed):
     return ks, vs, q, [np.array(a, dtype=np.uint8) for a in assign]
 
 
-@pytest.mark.parametrize("d,chunk,t", [(64, 4, 14), (64, 8, 27)])
+@pytest.mark.parametrize("d,chunk,t", [(64, 4, 14), (64, 8, 27), (128, 5, 17)])
 def test_full_path_matches_brute_force_all_assignments(d, chunk, t):
     n = t // chunk
     group = 32
-    for assign in itertools.product((2, 4, 16), repeat=n):
+    every = list(itertools.product((2, 4, 8, 16), repeat=n))
+    if d > 64 or t > 20:
+        every = every[::5]             # the scalar brute force is slow: all 4^n assignments for the smallest case only
+    for assign in every:
         ks, vs, q, bits = _tiny_case(1, 2, 2, d, [t], chunk, group, [assign], seed=hash(assign) % 1000)
         cache = O.reorder_quantize(ks, vs, bits, chunk, group)
         order, tok = brute.plan(t, chunk, list(assign))
@@ -208,14 +225,14 @@ def test_full_path_matches_brute_force_all_assignments(d, chunk, t):
         assert list(cache.plans[0].class_tokens) == [len(x) for x in tok]
         kl = [[[float(x) for x in row] for row in ks[0][h]] for h in range(2)]
         vl = [[[float(x) for x in row] for row in vs[0][h]] for h in range(2)]
-        for cls, b in enumerate((2, 4, 16)):
+        for cls, b in enumerate((2, 4, 8, 16)):
             assert O.pack_class_buffer(cache, cls, "k").tobytes() == brute.build_class_bytes(kl, tok[cls], b, group)
             assert O.pack_class_buffer(cache, cls, "v").tobytes() == brute.build_class_bytes(vl, tok[cls], b, group)
         out, lse = O.decode_attention(q, cache, sm_scale=0.3)
         for hq in range(4):
             h = hq // 2
-            krows = [brute.dequant_token(kl[h][tt], b, group) for b, ts in zip((2, 4, 16), tok) for tt in ts]
-            vrows = [brute.dequant_token(vl[h][tt], b, group) for b, ts in zip((2, 4, 16), tok) for tt in ts]
+            krows = [brute.dequant_token(kl[h][tt], b, group) for b, ts in zip((2, 4, 8, 16), tok) for tt in ts]
+            vrows = [brute.dequant_token(vl[h][tt], b, group) for b, ts in zip((2, 4, 8, 16), tok) for tt in ts]
             bo, bl = brute.attention([float(x) for x in q[0, hq]], krows, vrows, 0.3)
             np.testing.assert_allclose(out[0, hq], bo, rtol=0, atol=1e-12)
             assert abs(lse[0, hq] - bl) < 1e-12
@@ -232,18 +249,19 @@ def test_ragged_batch_brute_force_block_tail():
     assert buf.size == 2 * O.block_bytes(0, 64, 32)
     assert buf.tobytes() == brute.build_class_bytes(kl, tok[0], 2, 32)
     # second sequence: 9 tail tokens only, FP16 class
-    assert cache.plans[1].class_tokens == (0, 0, 9)
-    fp = O.pack_class_buffer(cache, 2, "k")
+    assert cache.plans[1].class_tokens == (0, 0, 0, 9)
+    fp = O.pack_class_buffer(cache, O.FP16_CLASS, "k")
     kl1 = [[[float(x) for x in row] for row in ks[1][0]]]
     assert fp.tobytes() == brute.build_class_bytes(kl1, list(range(9)), 16, 32)
 
 
 # -- 5. pack / unpack round trip and byte count ---------------------------------------------
 def test_pack_round_trip_and_sizes():
-    w = workloads.small("rt", 2, 2, 2, [64 * 3 + 40, 200], 8, 32, mix=(0.2, 0.3, 0.5))
+    w = workloads.small("rt", 2, 2, 2, [64 * 3 + 40, 200], 8, 32, mix=(0.2, 0.2, 0.2, 0.4))
     ks, vs = _seqs(w)
     cache = O.reorder_quantize(ks, vs, workloads.chunk_bits(w), 8, 32)
-    for cls in range(3):
+    assert all(cache.seqs[0][c].n_tokens > 0 for c in range(O.NUM_CLASSES))
+    for cls in range(O.NUM_CLASSES):
         for which in "kv":
             buf = O.pack_class_buffer(cache, cls, which)
             nblk = sum(((s[cls].n_tokens + 63) // 64) * 2 for s in cache.seqs)
@@ -254,18 +272,20 @@ def test_pack_round_trip_and_sizes():
                 if cc.n_tokens == 0:
                     continue
                 for h in range(2):
-                    if cls == 2:
+                    if cls == O.FP16_CLASS:
                         ref = (cc.k_raw if which == "k" else cc.v_raw)[h]
                         assert (back[b][h][0] == ref).all()
                     else:
                         assert (back[b][h][0] == (cc.k_codes if which == "k" else cc.v_codes)[h]).all()
                         assert (back[b][h][1] == (cc.k_scale if which == "k" else cc.v_scale)[h]).all()
                         assert (back[b][h][2] == (cc.k_zero if which == "k" else cc.v_zero)[h]).all()
-    # algorithmic bytes: 48 / 80 / 256 per (token, head) at G=32
-    assert O.packed_bytes((1, 0, 0), 1, 128, 32) == 2 * 48
-    assert O.packed_bytes((0, 1, 0), 1, 128, 32) == 2 * 80
-    assert O.packed_bytes((0, 0, 1), 1, 128, 64) == 2 * 256
-    assert O.packed_bytes((1, 1, 0), 1, 128, 64) == 2 * (40 + 72)
+    # algorithmic bytes: 48 / 80 / 144 / 256 per (token, head) at G=32
+    assert O.packed_bytes((1, 0, 0, 0), 1, 128, 32) == 2 * 48
+    assert O.packed_bytes((0, 1, 0, 0), 1, 128, 32) == 2 * 80
+    assert O.packed_bytes((0, 0, 1, 0), 1, 128, 32) == 2 * 144
+    assert O.packed_bytes((0, 0, 0, 1), 1, 128, 64) == 2 * 256
+    assert O.packed_bytes((1, 1, 0, 0), 1, 128, 64) == 2 * (40 + 72)
+    assert O.packed_bytes((1, 1, 1, 1), 1, 64, 32) == 2 * (24 + 40 + 72 + 128)
 
 
 def test_row_word_layout_by_hand():
@@ -280,6 +300,12 @@ def test_row_word_layout_by_hand():
     w = O.pack_row_words(codes, 4)
     assert int(w[0]) == 15 | (1 << 16) | (9 << 12) | (5 << 28) and int(w[1]) == 7
     assert (O.unpack_row_words(w, 4) == codes).all()
+    # 8 bits: four channels per word, ch0 -> bits 0..7, ch1 -> bits 16..23, ch2 -> bits 8..15, ch3 -> bits 24..31
+    codes = np.zeros(64, dtype=np.uint8)
+    codes[0], codes[1], codes[2], codes[3], codes[4] = 0xA1, 0xB2, 0xC3, 0xD4, 0x7F
+    w = O.pack_row_words(codes, 8)
+    assert w.shape == (16,) and int(w[0]) == 0xD4B2C3A1 and int(w[1]) == 0x7F
+    assert (O.unpack_row_words(w, 8) == codes).all()
 
 
 # -- 6. partial-softmax merge identity -------------------------------------------------------
@@ -306,12 +332,13 @@ def test_merging_partials_equals_global_softmax():
 
 # -- 7. reorder and quantise commute; GQA = replicated MHA; ragged = separate calls ----------
 def test_quantise_then_reorder_equals_reorder_then_quantise():
-    w = workloads.small("comm", 1, 1, 1, [8 * 9], 8, 32, mix=(0.0, 0.5, 0.5))
+    w = workloads.small("comm", 1, 1, 1, [8 * 12], 8, 32, mix=(0.0, 0.3, 0.4, 0.3))
     ks, vs = _seqs(w)
     bits = workloads.chunk_bits(w)
     cache = O.reorder_quantize(ks, vs, bits, 8, 32)
-    idx = O.class_token_index(72, 8, cache.plans[0])
-    for cls, b in ((0, 2), (1, 4)):
+    idx = O.class_token_index(96, 8, cache.plans[0])
+    assert all(len(idx[c]) > 0 for c in range(3))
+    for cls, b in ((0, 2), (1, 4), (2, 8)):
         c_all, s_all, z_all = O.quantize_rows(ks[0][0], b, 32)          # quantise in original order first
         assert (c_all[idx[cls]] == cache.seqs[0][cls].k_codes[0]).all()
         assert (s_all[idx[cls]] == cache.seqs[0][cls].k_scale[0]).all()
@@ -351,7 +378,7 @@ def test_kv_size_figure_from_paper():
     got = O.kv_bytes_fp16(int(layers), int(heads), int(hd), int(tokens)) / 1e9
     assert abs(got - float(gb)) / float(gb) <= float(tol)
     # the same count from the packed-bytes formula with every token in the FP16 class
-    assert O.packed_bytes((0, 0, int(tokens)), int(heads), int(hd), 64) * int(layers) / 1e9 == got
+    assert O.packed_bytes((0, 0, 0, int(tokens)), int(heads), int(hd), 64) * int(layers) / 1e9 == got
 
 
 # -- appended decode tokens (Sec. III-A: generated tokens stay FP16 behind the context) --------
@@ -495,7 +522,7 @@ def _quad_bytes_lane_by_lane(vals, bits, d):
     return bytes(out)
 
 
-@pytest.mark.parametrize("bits", [2, 4, 16])
+@pytest.mark.parametrize("bits", [2, 4, 8, 16])
 @pytest.mark.parametrize("d", [64, 128])
 def test_token_quad_layout_matches_a_lane_by_lane_construction(bits, d):
     # catches: a wrong slot, word, half-word or bit position of the token-quad form; tokens past the end not zero
@@ -511,17 +538,17 @@ def test_token_quad_layout_matches_a_lane_by_lane_construction(bits, d):
 
 def test_token_quad_class_buffer_holds_the_same_values_and_meta():
     # catches: the quad form losing or reordering meta, touching K, or changing the block size
-    w = workloads.small("quads", 2, 8, 2, [64 * 2 + 40, 130], 8, 32, mix=(0.2, 0.3, 0.5))
+    w = workloads.small("quads", 2, 8, 2, [64 * 2 + 40, 130], 8, 32, mix=(0.2, 0.2, 0.2, 0.4))
     ks, vs = _seqs(w)
     cache = O.reorder_quantize(ks, vs, workloads.chunk_bits(w), 8, 32)
-    for cls in range(3):
+    for cls in range(O.NUM_CLASSES):
         assert O.pack_class_buffer(cache, cls, "k", v_quads=True).tobytes() == O.pack_class_buffer(cache, cls, "k").tobytes()
         rows = O.pack_class_buffer(cache, cls, "v")
         quads = O.pack_class_buffer(cache, cls, "v", v_quads=True)
         assert rows.size == quads.size
         bb = O.block_bytes(cls, 128, 32)
         bits = O.CLASS_BITS[cls]
-        mb = 0 if cls == 2 else 4 * 128 // 32
+        mb = 0 if cls == O.FP16_CLASS else 4 * 128 // 32
         pos = 0
         for b in range(2):
             cc = cache.seqs[b][cls]
@@ -531,7 +558,7 @@ def test_token_quad_class_buffer_holds_the_same_values_and_meta():
             for h in range(2):
                 blk = quads[pos:pos + nblk * bb].reshape(nblk, bb)
                 vals, meta = O.unpack_quad_blocks(blk, cc.n_tokens, 128, bits, mb)
-                if cls == 2:
+                if cls == O.FP16_CLASS:
                     assert (vals == cc.v_raw[h].view(np.uint16)).all()
                 else:
                     assert (vals == cc.v_codes[h]).all()
@@ -561,7 +588,7 @@ def test_signed_zeros_do_not_reach_scale_or_zero():
     # catches: the sign of a zero extreme leaking into the stored scale or zero (it would depend on element order)
     for order in ([-0.0, 0.0], [0.0, -0.0], [-0.0, -0.0], [0.0, 0.0]):
         x = np.array([order * 16], dtype=np.float16)
-        for bits in (2, 4):
+        for bits in (2, 4, 8):
             codes, scale, zero = O.quantize_rows(x, bits, 32)
             assert scale.view(np.uint16).item() == 0 and zero.view(np.uint16).item() == 0 and not codes.any()
     # a group whose maximum is a zero and whose minimum is negative: range = -min exactly, whatever the zero's sign

@@ -15,7 +15,8 @@ Recipe (per config `c`, layer `l`, sequence `b`, head `h`):
   K[b,h] ~ N(0,1) [T_b, D] fp16; 4 channels per (layer, kv-head), drawn without
            replacement, are multiplied by 10 for every token (key outliers);
   V[b,h] ~ N(0,1) [T_b, D] fp16;   q[b,hq] ~ N(0,1) [D] fp16;
-  chunk bits: iid per chunk with the config's P(FP16, INT4, INT2), shared by
+  chunk bits: iid per chunk with the config's P(FP16, INT4, INT2) (test shapes may add an INT8
+           share: P(FP16, INT8, INT4, INT2)), shared by
            all layers and heads of a sequence (the bitwidth configuration comes
            from text chunks, Sec. III-B);  config 5 draws a Dirichlet(1,1,1)
            mix per sequence and forces sequence 0 to all-FP16, 1 to all-INT2.
@@ -47,7 +48,7 @@ class Workload:
     chunk_size: int
     group_size: int
     seq_lens: Tuple[int, ...]   # context tokens per sequence
-    mix: Tuple[float, float, float]  # P(FP16, INT4, INT2); ignored if dirichlet
+    mix: Tuple[float, ...]      # P(FP16, INT4, INT2), or P(FP16, INT8, INT4, INT2); ignored if dirichlet
     num_layers: int = 1
     dirichlet: bool = False
     seed_offset: int = 0
@@ -90,7 +91,7 @@ def small(name: str, batch: int, hq: int, hkv: int, seq_lens: Sequence[int], chu
 
 
 def chunk_bits(w: Workload) -> List[np.ndarray]:
-    """Per sequence: uint8 array [N_b] with values in {2, 4, 16}."""
+    """Per sequence: uint8 array [N_b] with values in {2, 4, 16} (and 8 where the mix has four entries)."""
     out = []
     for b, n in enumerate(w.num_chunks):
         r = _rng(w.config, w.seed_offset, b, _TAG_BITS)
@@ -104,7 +105,8 @@ def chunk_bits(w: Workload) -> List[np.ndarray]:
         else:
             p = np.asarray(w.mix, dtype=np.float64)
         p = p / p.sum()
-        lab = r.choice(np.array([16, 4, 2], dtype=np.uint8), size=n, p=p)
+        labels = [16, 4, 2] if len(p) == 3 else [16, 8, 4, 2]
+        lab = r.choice(np.array(labels, dtype=np.uint8), size=n, p=p)
         out.append(lab.astype(np.uint8))
     return out
 
