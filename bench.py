@@ -347,7 +347,7 @@ def main():
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.num_q_heads, "kv_heads": w.num_kv_heads,
                    "head_dim": w.head_dim, "context": list(w.seq_lens), "chunk_size": w.chunk_size,
                    "group_size": w.group_size,
-                   "class_tokens_int2_int4_fp16": d["class_tokens"],
+                   "class_tokens_int2_int4_int8_fp16": d["class_tokens"],
                    "decode_workgroups": d["workers"], "decode_calls_per_step": ntok, "cache_copies": head["cache_copies"],
                    "kernel_family": "one query head per wave on the vector ALU (no matrix instructions)"
                    if head["kernel"] == "decode_attention_kernel" else

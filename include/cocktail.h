@@ -3,14 +3,14 @@
  * (arXiv 2503.23294, Sec. III-C, Algorithm 1) for AMD MI355X (gfx950).
  *
  * The library covers the data-parallel hot path of the paper's second module.
- * Given the bitwidth (FP16 / INT4 / INT2) that the chunk-level quantization
+ * Given the bitwidth (FP16 / INT8 / INT4 / INT2) that the chunk-level quantization
  * search (Sec. III-B) chose for every context chunk, it
  *   1. reorders the KV chunks so that every bitwidth class is contiguous in
  *      memory (Alg. 1, prefill loop; Fig. 3),
- *   2. quantizes and packs the INT2 and INT4 classes (Alg. 1, `quant`),
- *   3. runs single-query decode attention over the three classes: logits of the
- *      INT2, INT4 and FP16 blocks, one softmax over their concatenation, three
- *      att x V products summed (Alg. 1, decode phase).  The concatenation is
+ *   2. quantizes and packs the INT2, INT4 and INT8 classes (Alg. 1, `quant`),
+ *   3. runs single-query decode attention over the classes: logits of the
+ *      INT2, INT4 (INT8) and FP16 blocks, one softmax over their concatenation, the
+ *      att x V products of the blocks summed (Alg. 1, decode phase).  The concatenation is
  *      never materialised: each worker keeps a partial softmax state
  *      (max, sum, weighted V sum) and the states are merged exactly, which
  *      gives the same result because the softmax-weighted sum does not depend
@@ -23,7 +23,8 @@
  *   - All functions return a cocktail_status; on failure a message is kept in
  *     thread-local storage (cocktail_last_error).  Arguments are validated on
  *     the host before anything is launched.
- *   - class index 0 = INT2, 1 = INT4, 2 = FP16 (the concatenation order of Alg. 1).
+ *   - class index 0 = INT2, 1 = INT4, 2 = INT8, 3 = FP16: the concatenation order of Alg. 1 (INT2, INT4,
+ *     FP16) with INT8, which Sec. I names as a further bitwidth, in its place by precision.
  *
  * Packed cache layout (an encoding defined by this library; the paper does not
  * fix one).  For each class c the K data and the V data live in one device
@@ -32,12 +33,12 @@
  * head, n_{b,c} being its token count in class c.  Inside a block:
  *   codes   the row of token i (i = 0..63) is cut into 16-byte pieces; piece p
  *           of token i is at byte (p*64 + i)*16.  Row size: D*bits/8 bytes for
- *           INT2/INT4, 2*D bytes (raw fp16, channel order) for FP16.
+ *           INT2/INT4/INT8, 2*D bytes (raw fp16, channel order) for FP16.
  *           A quantized row is a sequence of little-endian 32-bit words; word k
  *           covers the n = 32/bits channels k*n .. k*n+n-1, channel k*n+2f in
  *           bits [f*bits, f*bits+bits) and channel k*n+2f+1 in bits
  *           [16+f*bits, 16+f*bits+bits).
- *   meta    (INT2/INT4 only) after the codes, at byte 64*rowbytes: for token i
+ *   meta    (quantized classes only) after the codes, at byte 64*rowbytes: for token i
  *           and group g of G consecutive channels, 4 bytes at (i*(D/G)+g)*4 =
  *           fp16 scale, then fp16 zero.  Value of a code: zero + code*scale.
  *   Tokens past n_{b,c} in the last block of a head are zero bytes.
@@ -71,7 +72,7 @@
 extern "C" {
 #endif
 
-#define COCKTAIL_NUM_CLASSES 3
+#define COCKTAIL_NUM_CLASSES 4
 #define COCKTAIL_TOKENS_PER_BLOCK 64
 #define COCKTAIL_MAX_Q_PER_KV 8
 #define COCKTAIL_V_ROWS 0
@@ -116,7 +117,8 @@ typedef struct cocktail_sizes {
 } cocktail_sizes;
 
 /* The packed mixed-precision cache of one layer: the six lists of Alg. 1
- * (K_q2, K_q4, K_fp16, V_q2, V_q4, V_fp16) plus the plan that describes them. */
+ * (K_q2, K_q4, K_fp16, V_q2, V_q4, V_fp16), an INT8 pair between the INT4 and the FP16 ones, and the plan
+ * that describes them. */
 typedef struct cocktail_cache {
   void* k[COCKTAIL_NUM_CLASSES]; /* DEVICE, class_bytes[c] each, 256-byte aligned; may be NULL iff 0 bytes */
   void* v[COCKTAIL_NUM_CLASSES]; /* DEVICE, same sizes                                                     */
@@ -138,12 +140,12 @@ typedef struct cocktail_cache {
  * decode work over `num_workers` workgroups.
  *
  *   seq_lens     HOST [B]           context tokens T_b >= 0
- *   chunk_bits   HOST [sum_b N_b]   N_b = floor(T_b / C) values in {2, 4, 16}, sequence after sequence
+ *   chunk_bits   HOST [sum_b N_b]   N_b = floor(T_b / C) values in {2, 4, 8, 16}, sequence after sequence
  *   num_workers  workgroups for the decode kernel (> 0), normally
  *                cocktail_default_workers()
  *   sizes        HOST out, always written on success
  *   plan_host    HOST out, plan_capacity bytes, or NULL to query sizes only
- *   class_tokens HOST out [B][3] n_{b,c}, or NULL
+ *   class_tokens HOST out [B][COCKTAIL_NUM_CLASSES] n_{b,c}, or NULL
  *   perm         HOST out [sum_b N_b]: position j of sequence b's reordered chunk
  *                list holds original chunk perm[off_b + j] (the x_j of Eq. 5), or NULL
  *
@@ -179,7 +181,7 @@ int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_lens, const
 
 /*
  * Prefill side of Alg. 1: gather every chunk into its class (reorder), then
- * quantize and pack the INT2 and INT4 classes; FP16 chunks and the tail are
+ * quantize and pack the INT2, INT4 and INT8 classes; FP16 chunks and the tail are
  * copied.  One kernel launch handles K and V of all classes.
  *
  *   k_src, v_src  DEVICE fp16, 16-byte aligned, head_dim contiguous; strides in
@@ -228,7 +230,7 @@ int cocktail_reorder_quantize_paged(const cocktail_shape* shape, const cocktail_
 
 /*
  * Decode side of Alg. 1: out[b,h] = softmax(sm_scale * q[b,h] . K^_b^T) V^_b over
- * all tokens of the three classes of sequence b, K^/V^ being the dequantized
+ * all tokens of all classes of sequence b, K^/V^ being the dequantized
  * (or raw fp16) rows of kv head h / (Hq/Hkv).  Two launches: partial states per
  * worker, then the exact merge.  Workers that finish their own share early take
  * further pieces from a pool shared by a few neighbouring workers; the pools are
@@ -285,7 +287,7 @@ int cocktail_decode_attention_static(const cocktail_shape* shape, const void* q,
 /*
  * Diagnostic: waits for `stream`, then reads the status words the last decode call on `workspace` left
  * (the only entry point that synchronises and copies).  The softmax of Alg. 1's decode phase runs over the
- * concatenation of all three classes, i.e. over every token of the sequence exactly once; the status word
+ * concatenation of all classes, i.e. over every token of the sequence exactly once; the status word
  * of a (sequence, query head) is the number of tokens its partial states covered minus the sequence length.
  *
  *   workspace  DEVICE, the workspace of that call; NULL = the built-in one of cocktail_decode_attention_static
@@ -356,10 +358,10 @@ int cocktail_stream_read_probe(const void* buf, size_t bytes, void* sink, size_t
  * Diagnostic, not a step of the method.  The quantizer (top of this file) is defined by IEEE binary32
  * divisions; the kernel replaces them by shorter sequences that are exact on the operands that can
  * occur.  This call checks that claim on the device for every such operand: all floats in [0, 131008]
- * for (mx - mn) / 3 and / 15, and every positive finite fp16 value for 1 / scale.
+ * for (mx - mn) / 3, / 15 and / 255, and every positive finite fp16 value for 1 / scale.
  *
  *   mismatches  DEVICE uint64 [4] out, 16-byte aligned: operands on which the result differs from the
- *               division, for / 3, / 15, 1 / scale; [3] is zero.  All zero on a correct device.
+ *               division, for / 3, / 15, 1 / scale, / 255.  All zero on a correct device.
  *
  * Two kernel launches (about a millisecond).  Errors: EINVAL, EALIGN, EHIP.
  */

@@ -14,7 +14,7 @@ import torch  # noqa: F401  (must be imported before the library is loaded)
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("COCKTAIL_LIB", os.path.join(HERE, "libcocktail.so"))
 
-NUM_CLASSES = 3
+NUM_CLASSES = 4
 TOKENS_PER_BLOCK = 64
 MAX_Q_PER_KV = 8
 STATIC_WORKSPACE_BYTES = 16 << 20
@@ -29,8 +29,8 @@ class Shape(C.Structure):
 
 
 class Sizes(C.Structure):
-    _fields_ = [("total_chunks", C.c_int64), ("class_tokens", C.c_int64 * 3), ("class_blocks", C.c_int64 * 3),
-                ("class_bytes", C.c_int64 * 3), ("plan_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
+    _fields_ = [("total_chunks", C.c_int64), ("class_tokens", C.c_int64 * NUM_CLASSES),
+                ("class_blocks", C.c_int64 * NUM_CLASSES), ("class_bytes", C.c_int64 * NUM_CLASSES), ("plan_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
                 ("packed_bytes", C.c_int64), ("num_workers", C.c_int32), ("num_partials", C.c_int32),
                 ("num_segments", C.c_int32), ("append_capacity", C.c_int32), ("append_bytes", C.c_int64),
                 ("v_layout", C.c_int32), ("reserved", C.c_int32)]
@@ -41,7 +41,7 @@ class PlanOptions(C.Structure):
 
 
 class Cache(C.Structure):
-    _fields_ = [("k", C.c_void_p * 3), ("v", C.c_void_p * 3), ("plan_host", C.c_void_p), ("plan_dev", C.c_void_p),
+    _fields_ = [("k", C.c_void_p * NUM_CLASSES), ("v", C.c_void_p * NUM_CLASSES), ("plan_host", C.c_void_p), ("plan_dev", C.c_void_p),
                 ("k_app", C.c_void_p), ("v_app", C.c_void_p), ("num_appended", C.c_int32), ("reserved", C.c_int32)]
 
 

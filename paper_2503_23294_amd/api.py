@@ -28,7 +28,7 @@ class Plan:
     shape: Shape
     sizes: Sizes
     blob: np.ndarray            # uint8 [plan_bytes], host
-    class_tokens: np.ndarray    # int32 [B, 3]
+    class_tokens: np.ndarray    # int32 [B, 4]: INT2, INT4, INT8, FP16
     perm: np.ndarray            # int32 [total_chunks]
     seq_lens: np.ndarray
 
@@ -60,7 +60,7 @@ def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[in
     check(lib().cocktail_plan_ex(C.byref(shape), slp, cbp, num_workers, C.byref(opt), C.byref(sizes), None, 0, None,
                                  None))
     blob = np.zeros(int(sizes.plan_bytes), dtype=np.uint8)
-    ct = np.zeros((shape.batch, 3), dtype=np.int32)
+    ct = np.zeros((shape.batch, _lib.NUM_CLASSES), dtype=np.int32)
     perm = np.zeros(max(int(sizes.total_chunks), 1), dtype=np.int32)
     check(lib().cocktail_plan_ex(C.byref(shape), slp, cbp, num_workers, C.byref(opt), C.byref(sizes),
                                  blob.ctypes.data, blob.size, ct.ctypes.data_as(C.POINTER(C.c_int32)),
@@ -84,12 +84,12 @@ class PackedCache:
         self.plan_dev = torch.from_numpy(plan.blob).to(device)
         self.k: List[torch.Tensor] = []
         self.v: List[torch.Tensor] = []
-        for c in range(3):
+        for c in range(_lib.NUM_CLASSES):
             n = int(plan.sizes.class_bytes[c])
             self.k.append(torch.empty(n, dtype=torch.uint8, device=device))
             self.v.append(torch.empty(n, dtype=torch.uint8, device=device))
         self.desc = Cache()
-        for c in range(3):
+        for c in range(_lib.NUM_CLASSES):
             self.desc.k[c] = self.k[c].data_ptr() if self.k[c].numel() else None
             self.desc.v[c] = self.v[c].data_ptr() if self.v[c].numel() else None
         self.desc.plan_host = plan.blob.ctypes.data
@@ -251,7 +251,8 @@ def cocktail_chunk_bitwidths(query_emb: torch.Tensor, chunk_emb: torch.Tensor, n
 
 
 def cocktail_selftest_arithmetic(device: torch.device, stream: Optional[torch.cuda.Stream] = None) -> List[int]:
-    """Runs the exhaustive check of the quantizer's division shortcuts; returns the three mismatch counts."""
+    """Runs the exhaustive check of the quantizer's division shortcuts; returns the four mismatch counts
+    (/ 3, / 15, 1 / scale, / 255)."""
     out = torch.empty(4, dtype=torch.int64, device=device)
     check(lib().cocktail_selftest_arithmetic(out.data_ptr(), _stream_ptr(stream)))
-    return [int(x) for x in out.cpu().tolist()[:3]]
+    return [int(x) for x in out.cpu().tolist()]

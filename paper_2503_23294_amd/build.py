@@ -27,10 +27,28 @@ def hipcc() -> str:
 
 
 def build(verbose: bool = True, extra: list[str] | None = None, out: str = LIB) -> str:
-    cmd = [hipcc(), *FLAGS, *(extra or []), *[os.path.join(CSRC, s) for s in SOURCES], "-o", out]
+    """Compiles every source to an object file (in parallel, the sources are independent) and links them."""
+    from concurrent.futures import ThreadPoolExecutor
+    import hashlib
+    tag = hashlib.sha1((out + " ".join(extra or [])).encode()).hexdigest()[:10]
+    objdir = os.path.join(HERE, "_build", tag)
+    os.makedirs(objdir, exist_ok=True)
+    compile_flags = [f for f in FLAGS if f != "-shared"]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        cmd = [hipcc(), *compile_flags, *(extra or []), "-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1, 8)) as ex:
+        objs = list(ex.map(compile_one, SOURCES))
+    link = [hipcc(), "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", out]
     if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True)
+        print(" ".join(link), flush=True)
+    subprocess.run(link, check=True)
     return out
 
 

@@ -1,5 +1,5 @@
-// Decode side of Alg. 1 (Sec. III-C): single-query attention over the INT2, INT4
-// and FP16 classes of the packed cache.
+// Decode side of Alg. 1 (Sec. III-C): single-query attention over the INT2, INT4,
+// INT8 and FP16 classes of the packed cache.
 //
 // Design (gfx950, wave64):
 //  * The host planner puts all 64-token blocks of a layer into one global order and cuts it into
@@ -237,14 +237,16 @@ __device__ __forceinline__ void appended_tokens(int bh, float* red, int r, int l
     return;
   }
   Stream sm;
-  sm.init_run(2, n, bh * kp->app_blocks, kp->app_blocks,
+  sm.init_run(kFp16Class, n, bh * kp->app_blocks, kp->app_blocks,
               (bh / kp->num_kv_heads) * kp->num_q_heads + (bh % kp->num_kv_heads) * kp->rep, pid);
   Piece cur = sm.next(lane);
-  if (cur.nu > 0) run_class<HalfClass<G>, 2, G, AUX>(sm, cur, red, r, lane, true);
+  if (cur.nu > 0) run_class<HalfClass<G>, kFp16Class, G, AUX>(sm, cur, red, r, lane, true);
 }
 
-// One single-wave workgroup per worker (Hq = Hkv: the query head of a kv head is that head).
-template <int G, int AUX>
+// One single-wave workgroup per worker (Hq = Hkv: the query head of a kv head is that head).  INT8: the cache
+// has an INT8 class; caches without one run a kernel without that code (a third less of it to fetch and
+// to allocate registers for, worth 1.5 us on a 32K-token layer).
+template <int G, int AUX, bool INT8>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_attention_kernel(DecodeParams) {
   __shared__ float red[64 * 17];   // reduction tile of a flush
   const int lane = threadIdx.x;
@@ -264,8 +266,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
       run_class<QuantClass<2, G>, 0, G, AUX>(sm, cur, red, r, lane);
     } else if (cur.cls == 1) {
       run_class<QuantClass<4, G>, 1, G, AUX>(sm, cur, red, r, lane);
+    } else if (INT8 && cur.cls == 2) {
+      if constexpr (INT8) run_class<QuantClass<8, G>, 2, G, AUX>(sm, cur, red, r, lane);
     } else {
-      run_class<HalfClass<G>, 2, G, AUX>(sm, cur, red, r, lane);
+      run_class<HalfClass<G>, kFp16Class, G, AUX>(sm, cur, red, r, lane);
     }
   }
   // pool parts this worker never entered still own a partial slot: fill it with the neutral state
@@ -476,7 +480,7 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
   }
   p.bh_off = reinterpret_cast<const int32_t*>(pd + hd->off_bh_off);
   p.q = static_cast<const uint32_t*>(q);
-  for (int c = 0; c < 3; ++c) {
+  for (int c = 0; c < kNumClasses; ++c) {
     if (hd->class_bytes[c] > 0 && (!cache->k[c] || !cache->v[c]))
       return fail(COCKTAIL_EINVAL, "cache buffer of class %d is NULL", c);
     if ((reinterpret_cast<uintptr_t>(cache->k[c]) | reinterpret_cast<uintptr_t>(cache->v[c])) & 15)
@@ -509,16 +513,21 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
     const bool nt = nt_override >= 0 ? nt_override == 1
                                      : ((hd->rep == 1 || (quads && quad_waves(hd->rep) == 1)) &&
                                         hd->packed_bytes >= kNonTemporalMinBytes);
+    const bool int8 = hd->class_blocks[2] > 0;
     if (quads) {
-      const hipError_t e = launch_decode_quads(p, shape->group_size, nt, int(grid.x), st);
+      const hipError_t e = launch_decode_quads(p, shape->group_size, nt, int8, int(grid.x), st);
       if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_quads launch failed: %s", hipGetErrorString(e));
     } else {
       void (*kern)(DecodeParams) = nullptr;
+#define COCKTAIL_PICK(G)                                                                                              \
+  kern = int8 ? (nt ? decode_attention_kernel<G, kAuxNonTemporal, true> : decode_attention_kernel<G, kAuxDefault, true>) \
+              : (nt ? decode_attention_kernel<G, kAuxNonTemporal, false> : decode_attention_kernel<G, kAuxDefault, false>)
       switch (shape->group_size) {
-        case 32: kern = nt ? decode_attention_kernel<32, kAuxNonTemporal> : decode_attention_kernel<32, kAuxDefault>; break;
-        case 64: kern = nt ? decode_attention_kernel<64, kAuxNonTemporal> : decode_attention_kernel<64, kAuxDefault>; break;
-        default: kern = nt ? decode_attention_kernel<128, kAuxNonTemporal> : decode_attention_kernel<128, kAuxDefault>; break;
+        case 32: COCKTAIL_PICK(32); break;
+        case 64: COCKTAIL_PICK(64); break;
+        default: COCKTAIL_PICK(128); break;
       }
+#undef COCKTAIL_PICK
       hipLaunchKernelGGL(kern, grid, block, 0, st, p);
       const hipError_t e = hipGetLastError();
       if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_attention launch failed: %s", hipGetErrorString(e));

@@ -17,6 +17,7 @@ constexpr float kRescaleThreshold = 8.0f;   // log2 units
 constexpr float kTwo24 = 16777216.0f;
 constexpr int J2 = COCKTAIL_J2;    // INT2 units in flight per wave
 constexpr int J4 = COCKTAIL_J4;    // INT4 units in flight per wave
+constexpr int J8 = COCKTAIL_J8;    // INT8 units in flight per wave
 constexpr int J16 = COCKTAIL_J16;  // FP16 units in flight per wave
 
 struct DecodeParams {
@@ -28,8 +29,8 @@ struct DecodeParams {
   const int32_t* seq_len;   // [B] context tokens per sequence
   int32_t* status;          // [B*Hq] written by the merge: 0, or how far the tokens covered by the partials are off
   const uint32_t* q;        // fp16 [B][Hq][D] viewed as dwords
-  const char* k[3];
-  const char* v[3];
+  const char* k[kNumClasses];
+  const char* v[kNumClasses];
   const char* k_app;        // append buffers: [B*Hkv][app_blocks] FP16 blocks, or NULL
   const char* v_app;
   float* ws;                // [num_partials][rep][D + 4]
@@ -115,7 +116,7 @@ struct LaneState {
 // A word holds 32/BITS codes; even channels in the low half-word, odd ones in the high
 // half-word.  Masking field k of both half-words of `w` or `w >> 8` leaves two fp16
 // subnormals  code * 2^(BITS*k - 24)  for the channel pair (2f, 2f+1), f = 4*half + k
-// (INT2) or 2*half + k (INT4).
+// (INT2), 2*half + k (INT4) or half (INT8, one field per byte).
 template <int BITS, int G>
 struct QuantClass {
   static constexpr int PH = D * BITS / 256;         // 16-byte pieces per lane and unit
@@ -123,11 +124,11 @@ struct QuantClass {
   static constexpr int NGH = NG >= 2 ? NG / 2 : 1;  // groups a lane touches
   static constexpr int GL = G < DH ? G : DH;        // channels of a lane that share one group
   static constexpr int CPW = 32 / BITS;             // channels per word
-  static constexpr int NPOS = 8 / BITS;             // fields per byte: 4 (INT2) or 2 (INT4)
+  static constexpr int NPOS = 8 / BITS;             // fields per byte: 4 (INT2), 2 (INT4) or 1 (INT8)
   static constexpr int ROWB = D * BITS / 8;
   static constexpr int BLOCKB = kTB * (ROWB + 4 * NG);
-  static constexpr int J = BITS == 2 ? J2 : J4;
-  static constexpr uint32_t MASK0 = (BITS == 2) ? 0x00030003u : 0x000F000Fu;
+  static constexpr int J = BITS == 2 ? J2 : BITS == 4 ? J4 : J8;
+  static constexpr uint32_t MASK0 = (BITS == 2) ? 0x00030003u : (BITS == 4) ? 0x000F000Fu : 0x00FF00FFu;
 
   struct Stage {              // one lane's share of one unit of K or V
     u32x4 pc[PH];
@@ -290,7 +291,7 @@ struct Piece {
   int pid;         // partial id of that state (meaningful when fresh)
 };                 // the segment it lies in is the stream's current one (blk0, nblk, qrow there)
 
-__device__ __forceinline__ int iter_units(int cls) { return cls == 0 ? J2 : cls == 1 ? J4 : J16; }
+__device__ __forceinline__ int iter_units(int cls) { return cls == 0 ? J2 : cls == 1 ? J4 : cls == 2 ? J8 : J16; }
 
 // A ticket from the group's counter.  The value is only needed a few loop iterations later; it
 // travels through the vector memory pipeline like any load and is picked up with readfirstlane.
@@ -435,7 +436,7 @@ __device__ __forceinline__ void write_neutral(int slot, int r, int lane) {
 }
 
 // Launches the kernel for 2 to 8 query heads per kv head (decode_quads.hip): `grid` workgroups of one wave
-// (up to 4 heads) or two waves (5 to 8).
-hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, int grid, hipStream_t st);
+// (up to 4 heads) or two waves (5 to 8); int8: the cache has an INT8 class.
+hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, bool int8, int grid, hipStream_t st);
 
 }  // namespace cocktail

@@ -429,15 +429,15 @@ __device__ __forceinline__ void appended_tokens_quads(int bh, float* red, int r,
     return;
   }
   Stream sm;
-  sm.init_run(2, n, bh * kp->app_blocks, kp->app_blocks,
+  sm.init_run(kFp16Class, n, bh * kp->app_blocks, kp->app_blocks,
               (bh / kp->num_kv_heads) * kp->num_q_heads + (bh % kp->num_kv_heads) * kp->rep, pid);
   Piece cur = sm.next(lane);
-  if (cur.nu > 0) run_quads<QuadHalf<G>, 2, G, AUX>(sm, cur, red, r, lane, true);
+  if (cur.nu > 0) run_quads<QuadHalf<G>, kFp16Class, G, AUX>(sm, cur, red, r, lane, true);
 }
 
 // One workgroup per worker: one wave for 2 to 4 query heads per kv head, two waves (heads 0-3 and 4-7, both
 // walking the same blocks, so the second read of a line comes from the cache) for 5 to 8.
-template <int G, int AUX, int WAVES>
+template <int G, int AUX, int WAVES, bool INT8>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2))) void decode_quads_kernel(DecodeParams) {
   __shared__ __attribute__((aligned(16))) float red_all[WAVES * 64 * kRedStride];
   const int lane = threadIdx.x & 63;
@@ -458,8 +458,10 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
       run_quads<QuadQuant<2, G>, 0, G, AUX>(sm, cur, red, r, lane);
     } else if (cur.cls == 1) {
       run_quads<QuadQuant<4, G>, 1, G, AUX>(sm, cur, red, r, lane);
+    } else if (INT8 && cur.cls == 2) {
+      if constexpr (INT8) run_quads<QuadQuant<8, G>, 2, G, AUX>(sm, cur, red, r, lane);
     } else {
-      run_quads<QuadHalf<G>, 2, G, AUX>(sm, cur, red, r, lane);
+      run_quads<QuadHalf<G>, kFp16Class, G, AUX>(sm, cur, red, r, lane);
     }
   }
   for (int i = 0; i < sm.nps; ++i) {
@@ -478,18 +480,22 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2)))
 #endif
 }
 
-hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, int grid, hipStream_t st) {
+hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, bool int8, int grid, hipStream_t st) {
   const int waves = quad_waves(p.rep);
   void (*kern)(DecodeParams) = nullptr;
-#define COCKTAIL_PICK(G) \
-  kern = waves == 1 ? (non_temporal ? decode_quads_kernel<G, kAuxNonTemporal, 1> : decode_quads_kernel<G, kAuxDefault, 1>) \
-                    : (non_temporal ? decode_quads_kernel<G, kAuxNonTemporal, 2> : decode_quads_kernel<G, kAuxDefault, 2>)
+#define COCKTAIL_PICK2(G, I8) \
+  kern = waves == 1 ? (non_temporal ? decode_quads_kernel<G, kAuxNonTemporal, 1, I8> : decode_quads_kernel<G, kAuxDefault, 1, I8>) \
+                    : (non_temporal ? decode_quads_kernel<G, kAuxNonTemporal, 2, I8> : decode_quads_kernel<G, kAuxDefault, 2, I8>)
+#define COCKTAIL_PICK(G)           \
+  if (int8) COCKTAIL_PICK2(G, true); \
+  else COCKTAIL_PICK2(G, false)
   switch (group_size) {
     case 32: COCKTAIL_PICK(32); break;
     case 64: COCKTAIL_PICK(64); break;
     default: COCKTAIL_PICK(128); break;
   }
 #undef COCKTAIL_PICK
+#undef COCKTAIL_PICK2
   hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * waves), 0, st, p);
   return hipGetLastError();
 }

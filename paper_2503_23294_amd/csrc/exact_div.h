@@ -9,7 +9,7 @@
 
 namespace cocktail {
 
-// r / qmax for qmax in {3, 15} and 0 <= r <= 131008 (the largest difference of two fp16 values):
+// r / qmax for qmax in {3, 15, 255} and 0 <= r <= 131008 (the largest difference of two fp16 values):
 // multiply by the rounded reciprocal, then one correction step with the exact remainder.
 // The result goes through an empty asm statement: the quantizer rounds it to fp16 next, and without
 // the barrier the compiler merges the last fma with that conversion into one instruction that rounds

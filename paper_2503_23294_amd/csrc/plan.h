@@ -10,22 +10,27 @@
 namespace cocktail {
 
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
-constexpr uint32_t kPlanVersion = 11;
+constexpr uint32_t kPlanVersion = 12;
 constexpr int kTB = 64;                        // tokens per block
 constexpr int kUT = 32;                        // tokens per unit (half a block): what one wave handles at a time
-constexpr int kNumClasses = 3;
+constexpr int kNumClasses = 4;                 // INT2, INT4, INT8, FP16: the order of the concatenation
+constexpr int kFp16Class = kNumClasses - 1;
+constexpr int kClassBits[kNumClasses] = {2, 4, 8, 16};
 constexpr int kPartialFloats = 4;              // (m, l, tokens covered as int32, unused) in front of the D output values
-// Units one wave consumes per loop iteration in class INT2, INT4, FP16: the grain of the shared pools.
+// Units one wave consumes per loop iteration in class INT2, INT4, INT8, FP16: the grain of the shared pools.
 #ifndef COCKTAIL_J2
 #define COCKTAIL_J2 4
 #endif
 #ifndef COCKTAIL_J4
 #define COCKTAIL_J4 2
 #endif
+#ifndef COCKTAIL_J8
+#define COCKTAIL_J8 1
+#endif
 #ifndef COCKTAIL_J16
 #define COCKTAIL_J16 1
 #endif
-constexpr int kIterUnits[kNumClasses] = {COCKTAIL_J2, COCKTAIL_J4, COCKTAIL_J16};
+constexpr int kIterUnits[kNumClasses] = {COCKTAIL_J2, COCKTAIL_J4, COCKTAIL_J8, COCKTAIL_J16};
 constexpr int kMaxPoolSegments = 32;           // segments one pool may touch (a worker tracks them in a bit mask)
 constexpr int kCounterStride = 32;             // uint32 slots between two pool counters (one 128-byte line each)
 // Query heads per kv head for which a wave serves four of them at a time with matrix instructions and V is
@@ -40,7 +45,7 @@ struct Segment {
                              // (sequence, kv head, class) run; may exceed nblk * 64
   int32_t blk0;              // first block, index into the class buffer
   int32_t nblk;
-  int32_t gblk0;             // first block in the global order (group by group; inside a group FP16, INT2, INT4)
+  int32_t gblk0;             // first block in the global order
   int32_t pid0;              // partial id of the first worker whose own range touches this segment
 };
 
@@ -116,10 +121,10 @@ struct PlanHeader {
   int32_t off_cum_tokens;     // int64 [B+1]
   int32_t off_chunk_off;      // int32 [B+1]   prefix of N_b
   int32_t off_perm;           // int32 [total_chunks]  per-sequence chunk indices, gather form
-  int32_t off_class_tokens;   // int32 [B][3]
-  int32_t off_class_chunk0;   // int32 [B][3]  first position in perm_b of class c
-  int32_t off_blk_base;       // int32 [B+1][3] first block of sequence b in class buffer c
-  int32_t off_nblk;           // int32 [B][3]  blocks per head
+  int32_t off_class_tokens;   // int32 [B][4]
+  int32_t off_class_chunk0;   // int32 [B][4]  first position in perm_b of class c
+  int32_t off_blk_base;       // int32 [B+1][4] first block of sequence b in class buffer c
+  int32_t off_nblk;           // int32 [B][4]  blocks per head
   int32_t off_segments;       // Segment [num_segments]
   int32_t append_capacity;    // tokens per sequence the append buffers hold (0 = none)
   int32_t off_worker_rec;     // WorkerRec [num_workers]

@@ -41,9 +41,9 @@ int check_shape(const cocktail_shape* s) {
   return COCKTAIL_OK;
 }
 
-constexpr int64_t kCostWeightInt2 = 1150, kCostWeightInt4 = 1300, kCostWeightFp16 = 530;
+constexpr int64_t kCostWeight[kNumClasses] = {1150, 1300, 900, 530};
 // The same for the kernel that serves four query heads per wave: its arithmetic runs on the matrix unit.
-constexpr int64_t kQuadCostWeightInt2 = 1300, kQuadCostWeightInt4 = 1250, kQuadCostWeightFp16 = 450;
+constexpr int64_t kQuadCostWeight[kNumClasses] = {1300, 1250, 800, 450};
 // Workers per group.  Measured on MI355X: with one query head per kv head 4 to 8 are equal on long
 // ranges (8 a hair ahead at 128K), 5 to 6 clearly best on short ones (32K: 33.2 against 35.9 us); the
 // grouped-query kernel likes 4.
@@ -53,10 +53,11 @@ constexpr int kLongRangeBlocks = 24;   // average blocks per worker from which a
 constexpr int kPoolPercent = 25;
 constexpr int kPairMode = 0;
 constexpr int kLayout = 0;
-// Relative speed of a worker of class [self] whose SIMD mate works on class [mate] (INT2, INT4, FP16), traced on
-// MI355X at equal weighted cost: two bandwidth-bound or two ALU-bound waves on a SIMD get in each other's way,
-// an INT4 wave next to an FP16 wave runs well ahead.
-constexpr double kPairSpeed[3][3] = {{0.87, 1.0, 1.0}, {1.0, 1.17, 1.27}, {0.97, 1.06, 0.9}};
+// Relative speed of a worker of class [self] whose SIMD mate works on class [mate] (INT2, INT4, INT8, FP16), traced
+// on MI355X at equal weighted cost: two bandwidth-bound or two ALU-bound waves on a SIMD get in each other's way,
+// an INT4 wave next to an FP16 wave runs well ahead.  (INT8 was not traced: neutral.)
+constexpr double kPairSpeed[kNumClasses][kNumClasses] = {
+    {0.87, 1.0, 1.0, 1.0}, {1.0, 1.17, 1.0, 1.27}, {1.0, 1.0, 1.0, 1.0}, {0.97, 1.06, 1.0, 0.9}};
 // A group only gets a pool if its range holds at least this many blocks per worker.
 constexpr int kMinBlocksPerWorkerForPool = 4;
 // Groups with short ranges (below this many blocks per worker) put a larger share into the pool: there the
@@ -67,7 +68,7 @@ constexpr int kShortRangePoolPercent = 40;
 // The split parameters.  The defaults are what was measured best on MI355X; the environment variables
 // are tuning aids for experiments and are read once per cocktail_plan call.
 struct Tuning {
-  int64_t weight[3] = {kCostWeightInt2, kCostWeightInt4, kCostWeightFp16};   // COCKTAIL_COST_WEIGHTS="a,b,c"
+  int64_t weight[kNumClasses] = {kCostWeight[0], kCostWeight[1], kCostWeight[2], kCostWeight[3]};   // COCKTAIL_COST_WEIGHTS="int2,int4,int8,fp16" or "int2,int4,fp16"
   bool weight_set = false;
   int pool_percent = kPoolPercent;      // COCKTAIL_POOL_PERCENT   0..100
   bool pool_percent_set = false;        // the environment fixed the share for every group
@@ -81,9 +82,12 @@ struct Tuning {
 static Tuning read_tuning() {
   Tuning t;
   if (const char* e = std::getenv("COCKTAIL_COST_WEIGHTS")) {
-    long a = 0, b = 0, c = 0;
-    if (std::sscanf(e, "%ld,%ld,%ld", &a, &b, &c) == 3 && a > 0 && b > 0 && c > 0)
-      t.weight[0] = a, t.weight[1] = b, t.weight[2] = c, t.weight_set = true;
+    long a = 0, b = 0, c = 0, d = 0;
+    const int n = std::sscanf(e, "%ld,%ld,%ld,%ld", &a, &b, &c, &d);
+    if (n == 4 && a > 0 && b > 0 && c > 0 && d > 0)
+      t.weight[0] = a, t.weight[1] = b, t.weight[2] = c, t.weight[3] = d, t.weight_set = true;
+    else if (n == 3 && a > 0 && b > 0 && c > 0)
+      t.weight[0] = a, t.weight[1] = b, t.weight[3] = c, t.weight_set = true;
   }
   auto int_knob = [](const char* name, int lo, int hi, int& out) {
     if (const char* e = std::getenv(name)) {
@@ -199,43 +203,44 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   if (total_tokens >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "more than 2^31 tokens in one call");
   for (int64_t i = 0; i < total_chunks; ++i) {
     const uint8_t v = chunk_bits[i];
-    if (v != 2 && v != 4 && v != 16)
-      return fail(COCKTAIL_EINVAL, "chunk_bits[%lld] = %d is not one of 2, 4, 16", (long long)i, int(v));
+    if (v != 2 && v != 4 && v != 8 && v != 16)
+      return fail(COCKTAIL_EINVAL, "chunk_bits[%lld] = %d is not one of 2, 4, 8, 16", (long long)i, int(v));
   }
 
-  const int bits_of[3] = {2, 4, 16};
-  int32_t row_bytes[3], block_bytes[3], algo_row[3];
-  for (int c = 0; c < 3; ++c) {
-    const int meta = (c == 2) ? 0 : 4 * (D / G);
+  constexpr int NC = kNumClasses;
+  const int* bits_of = kClassBits;
+  int32_t row_bytes[NC], block_bytes[NC], algo_row[NC];
+  for (int c = 0; c < NC; ++c) {
+    const int meta = (c == kFp16Class) ? 0 : 4 * (D / G);
     row_bytes[c] = D * bits_of[c] / 8;
     block_bytes[c] = kTB * (row_bytes[c] + meta);
     algo_row[c] = row_bytes[c] + meta;
   }
 
-  // ---- Alg. 1 prefill loop: class lists in loop order, concatenated INT2 | INT4 | FP16 ----
-  std::vector<int32_t> v_perm(total_chunks), v_chunk_off(B + 1, 0), v_ct(3 * B), v_cc0(3 * B), v_nblk(3 * B),
-      v_blk_base(3 * (B + 1), 0);
+  // ---- Alg. 1 prefill loop: class lists in loop order, concatenated INT2 | INT4 | INT8 | FP16 ----
+  std::vector<int32_t> v_perm(total_chunks), v_chunk_off(B + 1, 0), v_ct(NC * B), v_cc0(NC * B), v_nblk(NC * B),
+      v_blk_base(NC * (B + 1), 0);
   std::vector<int64_t> v_cum(B + 1, 0);
-  int64_t class_tokens_tot[3] = {0, 0, 0};
+  int64_t class_tokens_tot[NC] = {};
   int64_t packed = 0;
   for (int b = 0; b < B; ++b) {
     const int n = seq_lens[b] / C;
     const uint8_t* bits = chunk_bits ? chunk_bits + v_chunk_off[b] : nullptr;
     int32_t* pb = v_perm.data() + v_chunk_off[b];
     int pos = 0;
-    for (int c = 0; c < 3; ++c) {
-      v_cc0[3 * b + c] = pos;
+    for (int c = 0; c < NC; ++c) {
+      v_cc0[NC * b + c] = pos;
       for (int i = 0; i < n; ++i)
         if (bits[i] == bits_of[c]) pb[pos++] = i;
-      int64_t ntok = int64_t(pos - v_cc0[3 * b + c]) * C;
-      if (c == 2) ntok += seq_lens[b] - n * C;  // Sec. III-A: the remainder stays FP16
-      v_ct[3 * b + c] = static_cast<int32_t>(ntok);
-      v_nblk[3 * b + c] = static_cast<int32_t>((ntok + kTB - 1) / kTB);
+      int64_t ntok = int64_t(pos - v_cc0[NC * b + c]) * C;
+      if (c == kFp16Class) ntok += seq_lens[b] - n * C;  // Sec. III-A: the remainder stays FP16
+      v_ct[NC * b + c] = static_cast<int32_t>(ntok);
+      v_nblk[NC * b + c] = static_cast<int32_t>((ntok + kTB - 1) / kTB);
       class_tokens_tot[c] += ntok;
       packed += 2 * int64_t(Hkv) * ntok * algo_row[c];
-      const int64_t nb = int64_t(v_blk_base[3 * b + c]) + int64_t(Hkv) * v_nblk[3 * b + c];
+      const int64_t nb = int64_t(v_blk_base[NC * b + c]) + int64_t(Hkv) * v_nblk[NC * b + c];
       if (nb >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "class %d needs more than 2^31 blocks", c);
-      v_blk_base[3 * (b + 1) + c] = static_cast<int32_t>(nb);
+      v_blk_base[NC * (b + 1) + c] = static_cast<int32_t>(nb);
     }
     v_chunk_off[b + 1] = v_chunk_off[b] + n;
     v_cum[b + 1] = v_cum[b] + seq_lens[b];
@@ -252,7 +257,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   // shared by those waves, so those shapes keep the purely static split
   const bool quads = uses_token_quads(rep);
   if (quads && !tune.weight_set)
-    tune.weight[0] = kQuadCostWeightInt2, tune.weight[1] = kQuadCostWeightInt4, tune.weight[2] = kQuadCostWeightFp16;
+    for (int c = 0; c < NC; ++c) tune.weight[c] = kQuadCostWeight[c];
   const int64_t* weight = tune.weight;
   if ((rep > 1 && !(quads && quad_waves(rep) == 1)) || reproducible) pool_percent = 0;
 
@@ -261,16 +266,17 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
     int b, h, cls, nb, ntok, blk0;
   };
   std::vector<Run> runs;
-  int64_t class_nblk[3] = {0, 0, 0};
-  for (int c = 0; c < 3; ++c)
+  int64_t class_nblk[NC] = {};
+  for (int c = 0; c < NC; ++c)
     for (int b = 0; b < B; ++b)
       for (int h = 0; h < Hkv; ++h) {
-        const int nb = v_nblk[3 * b + c];
+        const int nb = v_nblk[NC * b + c];
         if (nb == 0) continue;
-        runs.push_back({b, h, c, nb, v_ct[3 * b + c], v_blk_base[3 * b + c] + h * nb});
+        runs.push_back({b, h, c, nb, v_ct[NC * b + c], v_blk_base[NC * b + c] + h * nb});
         class_nblk[c] += nb;
       }
-  int64_t tot_blocks = class_nblk[0] + class_nblk[1] + class_nblk[2];
+  int64_t tot_blocks = 0;
+  for (int c = 0; c < NC; ++c) tot_blocks += class_nblk[c];
   if (tot_blocks >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "more than 2^31 blocks in one call");
   const int group_workers = tune.group_workers > 0 ? tune.group_workers
                             : quads                ? kQuadGroupWorkers
@@ -280,17 +286,17 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   // The workers form groups of `group_workers`; group j works on one stripe [cut[c][j], cut[c][j+1]) of
   // the blocks of every class c (blocks in (b, h, block) order).  A segment is the intersection of a
   // stripe with a run; the global order lists the groups one after the other.
-  //   layout 0: the class-major order INT2 | INT4 | FP16 is cut into NGR parts of equal cost, so a
+  //   layout 0: the class-major order INT2 | INT4 | INT8 | FP16 is cut into NGR parts of equal cost, so a
   //             group works on one class (two where it straddles a class boundary);
-  //   layout 1: every group receives the same share of every class (FP16 stripe, then INT2, then INT4).
+  //   layout 1: every group receives the same share of every class (FP16 stripe, then INT2, INT4, INT8).
   const int NGR = (P + group_workers - 1) / group_workers;
   const bool pair_speed_on = tune.pair_speed;
   const int layout = tune.layout;
-  const int class_order[3] = {layout ? 2 : 0, layout ? 0 : 1, layout ? 1 : 2};
-  std::vector<int64_t> cut[3];
+  const int class_order[NC] = {layout ? 3 : 0, layout ? 0 : 1, layout ? 1 : 2, layout ? 2 : 3};
+  std::vector<int64_t> cut[NC];
   {
-    int64_t per[3], tot = 0, start[3];
-    for (int c = 0; c < 3; ++c) {
+    int64_t per[NC], tot = 0, start[NC];
+    for (int c = 0; c < NC; ++c) {
       per[c] = 2 * int64_t(block_bytes[c]) * weight[c];
       start[c] = tot;
       tot += class_nblk[c] * per[c];
@@ -315,12 +321,12 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
       for (int w = 0; w < P; ++w) {
         const int j = w / group_workers, k = (j + 1) * group_workers <= P ? group_workers : P - j * group_workers;
         const double x = double(tot) * (gfrac[j] + (w - j * group_workers + 0.5) / k * (gfrac[j + 1] - gfrac[j]));
-        wclass[w] = x < double(start[1]) ? 0 : (x < double(start[2]) ? 1 : 2);
+        wclass[w] = x < double(start[1]) ? 0 : x < double(start[2]) ? 1 : x < double(start[3]) ? 2 : 3;
       }
       for (int w = 0; w < P; ++w) wcap[w] = kPairSpeed[wclass[w]][wclass[(w + P / 2) % P]];
     }
     for (int j = 0; j <= NGR; ++j) {
-      for (int c = 0; c < 3; ++c) {
+      for (int c = 0; c < NC; ++c) {
         if (layout) {
           const int w_lo = j * group_workers < P ? j * group_workers : P;
           cut[c][j] = class_nblk[c] * w_lo / P;
@@ -331,20 +337,20 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
         }
       }
     }
-    for (int c = 0; c < 3; ++c) cut[c][0] = 0, cut[c][NGR] = class_nblk[c];
+    for (int c = 0; c < NC; ++c) cut[c][0] = 0, cut[c][NGR] = class_nblk[c];
   }
   std::vector<Segment> segs;
   std::vector<int64_t> seg_cost0;   // cumulative cost (weighted bytes of K+V) at the start of each segment
   std::vector<int32_t> group_g0(NGR + 1, 0), group_s0(NGR + 1, 0);
   int64_t gblk = 0, cost = 0;
   {
-    std::vector<Run> by_class[3];
+    std::vector<Run> by_class[NC];
     for (const Run& r : runs) by_class[r.cls].push_back(r);
-    size_t cur_run[3] = {0, 0, 0};      // run holding the next block of each class
-    int64_t run_first[3] = {0, 0, 0};   // class-local index of that run's first block
+    size_t cur_run[NC] = {};      // run holding the next block of each class
+    int64_t run_first[NC] = {};   // class-local index of that run's first block
     for (int j = 0; j < NGR; ++j) {
       group_g0[j] = static_cast<int32_t>(gblk), group_s0[j] = static_cast<int32_t>(segs.size());
-      for (int ci = 0; ci < 3; ++ci) {
+      for (int ci = 0; ci < NC; ++ci) {
         const int c = class_order[ci];
         int64_t lo = cut[c][j];
         const int64_t hi = cut[c][j + 1];
@@ -536,15 +542,15 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   // ---- reorder+quantize records: one per block of the class buffers ----
   std::vector<RQItem> rq_items;
   rq_items.reserve(tot_blocks);
-  for (int c = 0; c < 3; ++c)
+  for (int c = 0; c < NC; ++c)
     for (int b = 0; b < B; ++b) {
-      const int nb = v_nblk[3 * b + c], ntok = v_ct[3 * b + c];
+      const int nb = v_nblk[NC * b + c], ntok = v_ct[NC * b + c];
       if (nb == 0) continue;
       const int n = seq_lens[b] / C;
       const int32_t* pb = v_perm.data() + v_chunk_off[b];
-      const int cc0 = v_cc0[3 * b + c];
+      const int cc0 = v_cc0[NC * b + c];
       const int tail = seq_lens[b] - n * C;
-      const int chunk_tokens = c == 2 ? ntok - tail : ntok;
+      const int chunk_tokens = c == kFp16Class ? ntok - tail : ntok;
       auto src_token = [&](int r) {   // source token of row r of the class (Alg. 1 order; tail after the FP16 chunks)
         if (r < chunk_tokens) return pb[cc0 + r / C] * C + r % C;
         return n * C + (r - chunk_tokens);
@@ -582,8 +588,8 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   hd.total_gblocks = static_cast<int32_t>(gblk);
   hd.v_layout = quads ? 1 : 0;
   hd.total_chunks = total_chunks, hd.total_tokens = total_tokens, hd.packed_bytes = packed;
-  for (int c = 0; c < 3; ++c) {
-    hd.class_blocks[c] = v_blk_base[3 * B + c];
+  for (int c = 0; c < NC; ++c) {
+    hd.class_blocks[c] = v_blk_base[NC * B + c];
     hd.class_bytes[c] = hd.class_blocks[c] * block_bytes[c];
     hd.block_bytes[c] = block_bytes[c];
     hd.row_bytes[c] = row_bytes[c];
@@ -602,10 +608,10 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   place(hd.off_cum_tokens, 8 * int64_t(B + 1));
   place(hd.off_chunk_off, 4 * int64_t(B + 1));
   place(hd.off_perm, 4 * total_chunks);
-  place(hd.off_class_tokens, 12 * int64_t(B));
-  place(hd.off_class_chunk0, 12 * int64_t(B));
-  place(hd.off_blk_base, 12 * int64_t(B + 1));
-  place(hd.off_nblk, 12 * int64_t(B));
+  place(hd.off_class_tokens, 4 * NC * int64_t(B));
+  place(hd.off_class_chunk0, 4 * NC * int64_t(B));
+  place(hd.off_blk_base, 4 * NC * int64_t(B + 1));
+  place(hd.off_nblk, 4 * NC * int64_t(B));
   place(hd.off_segments, int64_t(sizeof(Segment)) * S);
   place(hd.off_bh_off, 4 * int64_t(BH + 1));
   place(hd.off_worker_rec, int64_t(sizeof(WorkerRec)) * P);
@@ -619,7 +625,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
 
   std::memset(sizes, 0, sizeof(*sizes));
   sizes->total_chunks = total_chunks;
-  for (int c = 0; c < 3; ++c) {
+  for (int c = 0; c < NC; ++c) {
     sizes->class_tokens[c] = class_tokens_tot[c];
     sizes->class_blocks[c] = hd.class_blocks[c];
     sizes->class_bytes[c] = hd.class_bytes[c];
@@ -649,10 +655,10 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
     put(hd.off_cum_tokens, v_cum.data(), 8 * size_t(B + 1));
     put(hd.off_chunk_off, v_chunk_off.data(), 4 * size_t(B + 1));
     put(hd.off_perm, v_perm.data(), 4 * size_t(total_chunks));
-    put(hd.off_class_tokens, v_ct.data(), 12 * size_t(B));
-    put(hd.off_class_chunk0, v_cc0.data(), 12 * size_t(B));
-    put(hd.off_blk_base, v_blk_base.data(), 12 * size_t(B + 1));
-    put(hd.off_nblk, v_nblk.data(), 12 * size_t(B));
+    put(hd.off_class_tokens, v_ct.data(), 4 * NC * size_t(B));
+    put(hd.off_class_chunk0, v_cc0.data(), 4 * NC * size_t(B));
+    put(hd.off_blk_base, v_blk_base.data(), 4 * NC * size_t(B + 1));
+    put(hd.off_nblk, v_nblk.data(), 4 * NC * size_t(B));
     put(hd.off_segments, segs.data(), sizeof(Segment) * size_t(S));
     put(hd.off_bh_off, bh_off.data(), 4 * bh_off.size());
     std::vector<WorkerRec> recs(P);

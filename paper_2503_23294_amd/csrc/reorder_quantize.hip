@@ -22,7 +22,7 @@ struct RQParams {
   const void* plan;
   const RQItem* items;     // one record per block, in launch order
   const _Float16* src[2];  // K, V
-  char* dst[2][3];         // [K|V][class]
+  char* dst[2][kNumClasses];   // [K|V][class]
   int64_t stride_b, stride_h, stride_t;
   int32_t ragged;
   int32_t v_quads;         // V blocks in the token-quad form
@@ -31,7 +31,7 @@ struct RQParams {
   int64_t stride_page;
   int32_t page_size, table_stride, num_pages;
   int32_t page_shift;      // log2(page_size) if it is a power of two, else -1
-  int32_t cls_end0, cls_end1, cls_end2;  // prefix sums of class_blocks
+  int32_t cls_first[kNumClasses];        // index of the first record of every class (prefix sums of class_blocks)
 };
 
 // min (or max) of v and a neighbour lane's v in one instruction: the neighbour's value arrives as a
@@ -133,12 +133,15 @@ __device__ __forceinline__ void quantize_rows(LoadRow load_row, char* lds, int r
   const int qh = seg >> 3, qj = seg & 3, qe0 = 8 * ((seg >> 2) & 1);
   const bool writes_meta = (seg & (LPG - 1)) == 0;
   char* const meta0 = lds + meta_base + (row * NG + seg / LPG) * 4;
-  // row form: INT4 has one word per lane; INT2 one word per lane pair, written by the even lane
-  const int word = BITS == 4 ? seg : seg >> 1;
+  // row form: INT8 has two words per lane, INT4 one; INT2 one word per lane pair, written by the even lane
+  const int word = BITS == 8 ? 2 * seg : BITS == 4 ? seg : seg >> 1;
   char* const row0 = lds + ((word >> 2) * kTB + row) * 16 + (word & 3) * 4;
   // token quads: one half-word per 16 / BITS channels
-  char* const quad0 = lds + quad_halfword_offset(BITS == 4 ? 2 : 1, 16 / BITS, row, qh, qj, qe0);
-  char* const quad1 = lds + quad_halfword_offset(2, 4, row, qh, qj, qe0 + 4);   // INT4: channels 4..7
+  constexpr int QPH = BITS / 2;   // 16-byte pieces per 64-channel half of a row
+  char* const quad0 = lds + quad_halfword_offset(QPH, 16 / BITS, row, qh, qj, qe0);
+  char* const quad1 = lds + quad_halfword_offset(QPH, 16 / BITS, row, qh, qj, qe0 + (BITS == 8 ? 2 : 4));   // INT4: channels 4..7; INT8: 2, 3
+  char* const quad2 = lds + quad_halfword_offset(QPH, 16 / BITS, row, qh, qj, qe0 + 4);   // INT8: channels 4, 5
+  char* const quad3 = lds + quad_halfword_offset(QPH, 16 / BITS, row, qh, qj, qe0 + 6);   // INT8: channels 6, 7
 #pragma unroll
   for (int pass = 0; pass < 4; ++pass) {
     const u32x4 raw = load_row(pass);
@@ -155,13 +158,24 @@ __device__ __forceinline__ void quantize_rows(LoadRow load_row, char* lds, int r
     }
     if (quads) {
       // a half-word holds consecutive channels of one token, lowest channel in the lowest bits
-      if constexpr (BITS == 4) {
+      if constexpr (BITS == 8) {
+        *reinterpret_cast<uint16_t*>(quad0 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[1], 256.0f, c[0])));
+        *reinterpret_cast<uint16_t*>(quad1 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[3], 256.0f, c[2])));
+        *reinterpret_cast<uint16_t*>(quad2 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[5], 256.0f, c[4])));
+        *reinterpret_cast<uint16_t*>(quad3 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[7], 256.0f, c[6])));
+      } else if constexpr (BITS == 4) {
         *reinterpret_cast<uint16_t*>(quad0 + pass * 256) = uint16_t(static_cast<uint32_t>(pack4<4>(c[0], c[1], c[2], c[3])));
         *reinterpret_cast<uint16_t*>(quad1 + pass * 256) = uint16_t(static_cast<uint32_t>(pack4<4>(c[4], c[5], c[6], c[7])));
       } else {
         const float lo = pack4<2>(c[0], c[1], c[2], c[3]), hi = pack4<2>(c[4], c[5], c[6], c[7]);
         *reinterpret_cast<uint16_t*>(quad0 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(hi, 256.0f, lo)));
       }
+    } else if constexpr (BITS == 8) {
+      // row form, four channels per word: (c0, c2) in the low half-word, (c1, c3) in the high one
+      u32x2 w;
+      w.x = static_cast<uint32_t>(__builtin_fmaf(c[2], 256.0f, c[0])) | (static_cast<uint32_t>(__builtin_fmaf(c[3], 256.0f, c[1])) << 16);
+      w.y = static_cast<uint32_t>(__builtin_fmaf(c[6], 256.0f, c[4])) | (static_cast<uint32_t>(__builtin_fmaf(c[7], 256.0f, c[5])) << 16);
+      *reinterpret_cast<u32x2*>(row0 + pass * 256) = w;
     } else {
       // row form: even channels in the low half-word, odd ones in the high half-word
       const uint32_t even = static_cast<uint32_t>(pack4<BITS>(c[0], c[2], c[4], c[6]));
@@ -216,17 +230,17 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
     const int32_t* chunk_off = plan_array<int32_t>(p.plan, hd->off_chunk_off);
     N = chunk_off[b + 1] - chunk_off[b];
     perm = plan_array<int32_t>(p.plan, hd->off_perm) + chunk_off[b];
-    cc0 = plan_array<int32_t>(p.plan, hd->off_class_chunk0)[3 * b + cls];
-    const int ntok = plan_array<int32_t>(p.plan, hd->off_class_tokens)[3 * b + cls];
+    cc0 = plan_array<int32_t>(p.plan, hd->off_class_chunk0)[kNumClasses * b + cls];
+    const int ntok = plan_array<int32_t>(p.plan, hd->off_class_tokens)[kNumClasses * b + cls];
     const int T = plan_array<int32_t>(p.plan, hd->off_seq_len)[b];
-    chunk_tokens = (cls == 2) ? ntok - (T - N * C) : ntok;   // tokens of this class that come from chunks
+    chunk_tokens = (cls == kFp16Class) ? ntok - (T - N * C) : ntok;   // tokens of this class that come from chunks
   }
 
   const int tid = threadIdx.x;
   const int seg = tid & 15;        // 8 channels seg*8 .. seg*8+7
   const int row = tid >> 4;        // this thread's rows of the block: row, row + 16, row + 32, row + 48
   const bool quads = which == 1 && p.v_quads != 0;   // token-quad form of V
-  const int row_bytes = (cls == 0) ? D / 4 : (cls == 1) ? D / 2 : 2 * D;
+  const int row_bytes = D * kClassBits[cls] / 8;
 
   // row `pass * 16 + row` of the block, 8 channels of it (zeros past the last valid row).  Consecutive
   // source rows (almost every block): one pointer per thread and a fixed step per pass.
@@ -285,7 +299,7 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   // Token quads: the thread's channels are those of lane qj of a quad in the 64-channel half qh, its e-th
   // channels for e = qe0 .. qe0+7.
   const int qh = seg >> 3, qj = seg & 3, qe0 = 8 * ((seg >> 2) & 1);
-  if (cls == 2) {
+  if (cls == kFp16Class) {
 #pragma unroll
     for (int pass = 0; pass < 4; ++pass) {
       const int i = pass * 16 + row;
@@ -301,14 +315,15 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
     }
   } else if (cls == 0) {
     quantize_rows<2, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
-  } else {
+  } else if (cls == 1) {
     quantize_rows<4, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
+  } else {
+    quantize_rows<8, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
   }
   __syncthreads();
   constexpr int NGc = D / G;
-  const int bb = kTB * (row_bytes + (cls == 2 ? 0 : 4 * NGc));
-  const int first = cls == 0 ? 0 : cls == 1 ? p.cls_end0 : p.cls_end1;   // first record of this class
-  char* dst = p.dst[which][cls] + int64_t(int(blockIdx.x) - first) * bb;
+  const int bb = kTB * (row_bytes + (cls == kFp16Class ? 0 : 4 * NGc));
+  char* dst = p.dst[which][cls] + int64_t(int(blockIdx.x) - p.cls_first[cls]) * bb;
   for (int o = tid * 16; o < bb; o += 256 * 16)
     RQ_STORE(*reinterpret_cast<const u32x4*>(lds + o), reinterpret_cast<u32x4*>(dst + o));
 }
@@ -322,12 +337,15 @@ __global__ __launch_bounds__(256) void fill_zero_kernel(u32x4* __restrict__ p, s
 
 // Exhaustive check of exact_div.h against the IEEE divisions, over every operand the quantizer can see.
 __global__ __launch_bounds__(256) void selftest_div_kernel(unsigned long long* __restrict__ bad) {
-  unsigned long long n3 = 0, n15 = 0, nr = 0;
+  unsigned long long n3 = 0, n15 = 0, n255 = 0, nr = 0;
   const uint64_t stride = uint64_t(gridDim.x) * 256;
   // every non-negative float up to 131008 = 0x47FFE000
   for (uint64_t i = uint64_t(blockIdx.x) * 256 + threadIdx.x; i <= 0x47FFE000ull; i += stride) {
     const float r = __builtin_bit_cast(float, uint32_t(i));
     const float a3 = r / 3.0f, b3 = div_by_qmax<3>(r), a15 = r / 15.0f, b15 = div_by_qmax<15>(r);
+    const float a255 = r / 255.0f, b255 = div_by_qmax<255>(r);
+    n255 += __builtin_bit_cast(uint32_t, a255) != __builtin_bit_cast(uint32_t, b255) ||
+            __builtin_bit_cast(uint16_t, static_cast<_Float16>(a255)) != __builtin_bit_cast(uint16_t, static_cast<_Float16>(b255));
     // the binary32 quotient and the fp16 scale made from it, as the quantizer makes it
     n3 += __builtin_bit_cast(uint32_t, a3) != __builtin_bit_cast(uint32_t, b3) ||
           __builtin_bit_cast(uint16_t, static_cast<_Float16>(a3)) != __builtin_bit_cast(uint16_t, static_cast<_Float16>(b3));
@@ -342,6 +360,7 @@ __global__ __launch_bounds__(256) void selftest_div_kernel(unsigned long long* _
   if (n3) atomicAdd(bad + 0, n3);
   if (n15) atomicAdd(bad + 1, n15);
   if (nr) atomicAdd(bad + 2, nr);
+  if (n255) atomicAdd(bad + 3, n255);
 }
 
 }  // namespace cocktail
@@ -371,7 +390,7 @@ int launch_reorder_quantize(const cocktail_shape* shape, const cocktail_cache* c
   p.plan = cache->plan_dev;
   p.items = reinterpret_cast<const RQItem*>(static_cast<const char*>(cache->plan_dev) + hd->off_rq_items);
   int64_t tot = 0;
-  for (int c = 0; c < 3; ++c) {
+  for (int c = 0; c < kNumClasses; ++c) {
     if (hd->class_bytes[c] > 0 && (!cache->k[c] || !cache->v[c]))
       return fail(COCKTAIL_EINVAL, "cache buffer of class %d is NULL but %lld bytes are needed", c,
                   (long long)hd->class_bytes[c]);
@@ -379,13 +398,11 @@ int launch_reorder_quantize(const cocktail_shape* shape, const cocktail_cache* c
       return fail(COCKTAIL_EALIGN, "cache buffers must be 16-byte aligned");
     p.dst[0][c] = static_cast<char*>(cache->k[c]);
     p.dst[1][c] = static_cast<char*>(cache->v[c]);
+    p.cls_first[c] = static_cast<int32_t>(tot);
     tot += hd->class_blocks[c];
   }
   if (tot >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "too many blocks for one launch");
   p.v_quads = hd->v_layout;
-  p.cls_end0 = static_cast<int32_t>(hd->class_blocks[0]);
-  p.cls_end1 = p.cls_end0 + static_cast<int32_t>(hd->class_blocks[1]);
-  p.cls_end2 = static_cast<int32_t>(tot);
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (hd->append_capacity > 0) {
     if (!cache->k_app || !cache->v_app) return fail(COCKTAIL_EINVAL, "the plan has append buffers but k_app or v_app is NULL");

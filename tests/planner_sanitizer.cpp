@@ -35,7 +35,7 @@ static const T* view(const std::vector<char>& blob, int64_t off, int64_t count) 
 static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& lens, const std::vector<uint8_t>& bits,
                        int workers, const cocktail_plan_options& opt, std::mt19937_64& rng) {
   cocktail_sizes sz;
-  std::vector<int32_t> ct(3 * sh.batch), perm(bits.size() + 1);
+  std::vector<int32_t> ct(kNumClasses * sh.batch), perm(bits.size() + 1);
   int rc = cocktail_plan_ex(&sh, lens.data(), bits.empty() ? nullptr : bits.data(), workers, &opt, &sz, nullptr, 0,
                             nullptr, nullptr);
   REQUIRE(rc == COCKTAIL_OK);
@@ -61,11 +61,11 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   const uint32_t* counters = view<uint32_t>(blob, hd.off_counters, int64_t(NG) * kCounterStride);
   const int32_t* chunk_off = view<int32_t>(blob, hd.off_chunk_off, B + 1);
   const int32_t* pperm = view<int32_t>(blob, hd.off_perm, hd.total_chunks);
-  const int32_t* cc0 = view<int32_t>(blob, hd.off_class_chunk0, 3 * B);
-  const int32_t* ctok = view<int32_t>(blob, hd.off_class_tokens, 3 * B);
+  const int32_t* cc0 = view<int32_t>(blob, hd.off_class_chunk0, kNumClasses * B);
+  const int32_t* ctok = view<int32_t>(blob, hd.off_class_tokens, kNumClasses * B);
   const int32_t* seq_len = view<int32_t>(blob, hd.off_seq_len, B);
   int64_t nblocks = 0;
-  for (int c = 0; c < 3; ++c) nblocks += hd.class_blocks[c];
+  for (int c = 0; c < kNumClasses; ++c) nblocks += hd.class_blocks[c];
   const RQItem* items = view<RQItem>(blob, hd.off_rq_items, nblocks);
   for (int64_t i = 0; i < int64_t(NG) * kCounterStride; ++i) REQUIRE(counters[i] == 0);
   REQUIRE(hd.off_counters % 128 == 0);
@@ -80,26 +80,26 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
       const int i = pperm[chunk_off[b] + j];
       REQUIRE(i >= 0 && i < n && !seen[i]);
       seen[i] = 1;
-      const int v = bits[chunk_off[b] + i], cls = v == 2 ? 0 : v == 4 ? 1 : 2;
+      const int v = bits[chunk_off[b] + i], cls = v == 2 ? 0 : v == 4 ? 1 : v == 8 ? 2 : 3;
       REQUIRE(cls > prev_cls || (cls == prev_cls && i > prev_idx));
       prev_cls = cls, prev_idx = i;
       REQUIRE(perm[chunk_off[b] + j] == i);
     }
     int64_t tot = 0;
-    for (int c = 0; c < 3; ++c) {
-      tot += ctok[3 * b + c];
-      REQUIRE(ct[3 * b + c] == ctok[3 * b + c]);
+    for (int c = 0; c < kNumClasses; ++c) {
+      tot += ctok[kNumClasses * b + c];
+      REQUIRE(ct[kNumClasses * b + c] == ctok[kNumClasses * b + c]);
     }
     REQUIRE(tot == lens[b]);
   }
 
   // segments tile every class buffer exactly once and are listed in global order
-  std::vector<std::vector<uint8_t>> phys(3);
-  for (int c = 0; c < 3; ++c) phys[c].assign(hd.class_blocks[c], 0);
+  std::vector<std::vector<uint8_t>> phys(kNumClasses);
+  for (int c = 0; c < kNumClasses; ++c) phys[c].assign(hd.class_blocks[c], 0);
   int64_t g = 0;
   for (int s = 0; s < S; ++s) {
     const Segment& sg = segs[s];
-    REQUIRE(sg.cls >= 0 && sg.cls < 3 && sg.b >= 0 && sg.b < B && sg.h >= 0 && sg.h < Hkv);
+    REQUIRE(sg.cls >= 0 && sg.cls < kNumClasses && sg.b >= 0 && sg.b < B && sg.h >= 0 && sg.h < Hkv);
     REQUIRE(sg.gblk0 == g && sg.nblk > 0 && int64_t(sg.nblk - 1) * kTB < sg.ntok);
     REQUIRE(sg.blk0 >= 0 && int64_t(sg.blk0) + sg.nblk <= hd.class_blocks[sg.cls]);
     for (int i = 0; i < sg.nblk; ++i) REQUIRE(phys[sg.cls][sg.blk0 + i]++ == 0);
@@ -191,13 +191,13 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
 
   // reorder+quantize records: every block of every class buffer, its rows inside the source
   int64_t idx = 0;
-  for (int c = 0; c < 3; ++c)
+  for (int c = 0; c < kNumClasses; ++c)
     for (int64_t i = 0; i < hd.class_blocks[c]; ++i, ++idx) {
       const RQItem& it = items[idx];
       const int cls = it.cls_nvalid & 0xff, nvalid = it.cls_nvalid >> 8;
       REQUIRE(cls == c && nvalid >= 1 && nvalid <= kTB && it.b >= 0 && it.b < B && it.h >= 0 && it.h < Hkv);
       const int T = lens[it.b], N = T / C;
-      const int ntok = ctok[3 * it.b + c], chunk_tokens = c == 2 ? ntok - (T - N * C) : ntok;
+      const int ntok = ctok[kNumClasses * it.b + c], chunk_tokens = c == kFp16Class ? ntok - (T - N * C) : ntok;
       REQUIRE(int64_t(it.j) * kTB + nvalid <= ntok);
       if (it.t0 >= 0) {
         REQUIRE(it.t0 + nvalid <= T);
@@ -206,8 +206,8 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
           int t;
           if (r < chunk_tokens) {
             const int slot = r / C;
-            REQUIRE(cc0[3 * it.b + c] + slot < N);
-            t = pperm[chunk_off[it.b] + cc0[3 * it.b + c] + slot] * C + (r - slot * C);
+            REQUIRE(cc0[kNumClasses * it.b + c] + slot < N);
+            t = pperm[chunk_off[it.b] + cc0[kNumClasses * it.b + c] + slot] * C + (r - slot * C);
           } else {
             t = N * C + (r - chunk_tokens);
           }
@@ -221,7 +221,7 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   int64_t v = -1;
   REQUIRE(cocktail_plan_field(blob.data(), "num_partials", 0, &v) == COCKTAIL_OK && v == hd.num_partials);
   REQUIRE(cocktail_plan_field(blob.data(), "class_blocks", 2, &v) == COCKTAIL_OK && v == hd.class_blocks[2]);
-  REQUIRE(cocktail_plan_field(blob.data(), "class_blocks", 3, &v) == COCKTAIL_EINVAL);
+  REQUIRE(cocktail_plan_field(blob.data(), "class_blocks", kNumClasses, &v) == COCKTAIL_EINVAL);
   REQUIRE(cocktail_plan_field(blob.data(), "no_such_field", 0, &v) == COCKTAIL_EINVAL);
 }
 
@@ -241,12 +241,12 @@ int main(int argc, char** argv) {
     std::vector<int32_t> lens(sh.batch);
     std::vector<uint8_t> bits;
     const int scale = pick({70, 700, 7000, 40000});
-    const int mix = int(rng() % 5);   // 0..2: a single class, 3, 4: mixed
+    const int mix = int(rng() % 7);   // 0..3: a single class, 4..6: mixed
     for (int b = 0; b < sh.batch; ++b) {
       lens[b] = (rng() % 5 == 0) ? int(rng() % sh.chunk_size) : int(rng() % scale);
       for (int i = 0; i < lens[b] / sh.chunk_size; ++i) {
-        const int c = mix < 3 ? mix : int(rng() % 3);
-        bits.push_back(c == 0 ? 2 : c == 1 ? 4 : 16);
+        const int c = mix < 4 ? mix : int(rng() % 4);
+        bits.push_back(uint8_t(kClassBits[c]));
       }
     }
     const int workers = pick({1, 2, 3, 5, 8, 16, 33, 64, 200, 2048});

@@ -68,7 +68,7 @@ class Case:
         self.vbuf = [t.cpu().numpy() for t in self.cache.v]
         ct = self.plan.class_tokens.astype(np.int64)
         self.nblk = (ct + 63) // 64
-        self.blk_base = np.zeros((w.batch + 1, 3), dtype=np.int64)
+        self.blk_base = np.zeros((w.batch + 1, O.NUM_CLASSES), dtype=np.int64)
         self.blk_base[1:] = np.cumsum(self.nblk * w.num_kv_heads, axis=0)
 
     def check_plan(self):
@@ -85,7 +85,7 @@ class Case:
         w = self.w
         kh, vh = workloads.kv_head(w, self.layer, b, h)
         oc = O.reorder_quantize([kh[None]], [vh[None]], [self.bits[b]], w.chunk_size, w.group_size)
-        for c in range(3):
+        for c in range(O.NUM_CLASSES):
             bb = O.block_bytes(c, w.head_dim, w.group_size)
             lo = (self.blk_base[b, c] + h * self.nblk[b, c]) * bb
             hi = lo + self.nblk[b, c] * bb
@@ -139,12 +139,13 @@ def test_config1_all_heads(workers):
 @pytest.mark.parametrize("rep", [1, 2, 3, 4, 5, 8])
 def test_group_sizes_and_gqa(group, rep):
     w = workloads.small(f"g{group}_r{rep}", 2, 2 * rep, 2, [64 * 5 + 32 * 3 + 7, 32 * 9], 32, group,
-                        mix=(0.25, 0.35, 0.4), seed_offset=group + rep)
+                        mix=(0.2, 0.25, 0.25, 0.3), seed_offset=group + rep)
     _announce(w.name)
     Case(w, workers=5).check_all()
 
 
-@pytest.mark.parametrize("mix", [(1, 0, 0), (0, 1, 0), (0, 0, 1), (0.5, 0, 0.5)])
+@pytest.mark.parametrize("mix", [(1, 0, 0), (0, 1, 0), (0, 0, 1), (0.5, 0, 0.5), (0, 1, 0, 0), (0.3, 0.3, 0, 0.4),
+                                 (0, 0.5, 0.5, 0), (0.25, 0.25, 0.25, 0.25)])
 def test_single_class_and_missing_class(mix):
     w = workloads.small("mix" + "".join(str(int(10 * m)) for m in mix), 1, 2, 2, [8 * 40 + 3], 8, 32, mix=mix,
                         seed_offset=11)
@@ -213,7 +214,7 @@ def test_paged_source(page_size, head_major, rep):
     vs = [O.gather_pages(pools[1], table[b], w.seq_lens[b]) for b in range(w.batch)]
     oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
     v_quads = int(plan.sizes.v_layout) == 1
-    for c in range(3):
+    for c in range(O.NUM_CLASSES):
         assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k")), f"K class {c}"
         assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads)), f"V class {c}"
     q = workloads.query(w, 0)
@@ -459,7 +460,7 @@ def test_reproducible_plan_gives_bitwise_identical_results(rep):
 
 def test_quantizer_division_shortcuts_are_exact_on_every_operand():
     """The kernel's replacements for (mx - mn) / qmax and 1 / scale against the IEEE divisions, exhaustively."""
-    assert ck.cocktail_selftest_arithmetic(_dev()) == [0, 0, 0]
+    assert ck.cocktail_selftest_arithmetic(_dev()) == [0, 0, 0, 0]
 
 
 def test_runs_on_a_side_stream():
@@ -592,7 +593,7 @@ def test_value_ranges_from_tiny_to_near_the_fp16_limit(rep, kscale, vscale):
     torch.cuda.synchronize()
     oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
     v_quads = int(plan.sizes.v_layout) == 1
-    for c in range(3):
+    for c in range(O.NUM_CLASSES):
         assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k"))
         assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads))
     ref, rl = O.decode_attention(q, oc)
@@ -675,7 +676,7 @@ def test_quantizer_corner_groups_are_bit_exact(rep):
     torch.cuda.synchronize()
     oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
     v_quads = int(plan.sizes.v_layout) == 1
-    for c in range(3):
+    for c in range(O.NUM_CLASSES):
         assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k")), f"K class {c}"
         assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads)), f"V class {c}"
 
@@ -691,9 +692,11 @@ def _random_case(seed):
     lens = [int(x) for x in rng.integers(0, 2500, size=batch)]
     if rng.random() < 0.3:
         lens[int(rng.integers(0, batch))] = int(rng.integers(0, chunk))      # a tail-only (or empty) sequence
-    mix = rng.dirichlet([1.0, 1.0, 1.0])
+    mix = rng.dirichlet([1.0, 1.0, 1.0, 1.0])                                 # FP16, INT8, INT4, INT2
     if rng.random() < 0.25:
-        mix = np.eye(3)[int(rng.integers(0, 3))]                              # a single class
+        mix = np.eye(4)[int(rng.integers(0, 4))]                              # a single class
+    elif rng.random() < 0.3:
+        mix[int(rng.integers(0, 4))] = 0.0                                    # an empty class
     workers = int(rng.choice([1, 2, 5, 8, 16, 33, 64, 200]))
     w = workloads.small(f"fuzz{seed}", batch, hkv * rep, hkv, lens, chunk, group, mix=tuple(float(x) for x in mix),
                         seed_offset=9000 + seed)

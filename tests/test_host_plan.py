@@ -39,7 +39,7 @@ def _parse(plan):
     h = {"rep": f("rep"), "workers": f("num_workers"), "segments": f("num_segments"), "partials": f("num_partials"),
          "gblocks": f("total_gblocks"), "v_layout": f("v_layout"), "plan_bytes": f("plan_bytes"),
          "groups": f("num_groups"), "pool_segs": f("num_pool_segs"), "ws_status_off": f("ws_status_off"),
-         "block_bytes": [f("block_bytes", c) for c in range(3)]}
+         "block_bytes": [f("block_bytes", c) for c in range(_lib.NUM_CLASSES)]}
     h["off"] = {k: f("off_" + k) for k in ("segments", "worker_rec", "group_rec", "pool_seg", "counters", "bh_off")}
     assert f("sizeof_segment") == 32 and f("sizeof_worker_rec") == 64 and f("sizeof_group_rec") == 32
     assert f("sizeof_pool_seg") == 32
@@ -47,7 +47,7 @@ def _parse(plan):
 
 
 def _consts(plan):
-    return ([ck.cocktail_plan_field(plan, "iter_units", c) for c in range(3)],
+    return ([ck.cocktail_plan_field(plan, "iter_units", c) for c in range(_lib.NUM_CLASSES)],
             ck.cocktail_plan_field(plan, "counter_stride_bytes") // 4, ck.cocktail_plan_field(plan, "partial_header_floats"))
 
 
@@ -72,7 +72,7 @@ def _check_work_split(plan, w, workers, seed=0):
     assert (counters == 0).all() and h["off"]["counters"] % 128 == 0
     assert h["gblocks"] == sum(plan.sizes.class_blocks)
     # segments tile the class buffers: every physical block of every (class, b, h) exactly once
-    phys = [np.zeros(int(plan.sizes.class_blocks[c]), dtype=np.int32) for c in range(3)]
+    phys = [np.zeros(int(plan.sizes.class_blocks[c]), dtype=np.int32) for c in range(_lib.NUM_CLASSES)]
     g = 0
     for b_, h_, cls, ntok, blk0, nblk, gblk0, spid in segs:
         assert gblk0 == g and nblk > 0 and (nblk - 1) * 64 < ntok
@@ -177,7 +177,7 @@ def test_planner_matches_oracle_and_splits_work_exactly_once(cfg, workers):
         packed += O.packed_bytes(sp.class_tokens, w.num_kv_heads, w.head_dim, w.group_size)
         pos += n
     assert plan.sizes.packed_bytes == packed
-    for c in range(3):
+    for c in range(_lib.NUM_CLASSES):
         blocks = sum(((int(plan.class_tokens[b, c]) + 63) // 64) * w.num_kv_heads for b in range(w.batch))
         assert plan.sizes.class_blocks[c] == blocks
         assert plan.sizes.class_bytes[c] == blocks * O.block_bytes(c, w.head_dim, w.group_size)
@@ -217,8 +217,8 @@ def test_work_split_of_random_small_shapes(seed):
 def test_plan_handles_empty_sequences_and_tail_only():
     sh = ck.make_shape(3, 2, 2, 128, 16, 32)
     plan = ck.cocktail_plan(sh, [0, 5, 16], [4], 8)
-    assert plan.class_tokens.tolist() == [[0, 0, 0], [0, 0, 5], [0, 16, 0]]
-    assert list(plan.sizes.class_blocks) == [0, 2, 2] and plan.sizes.num_partials >= 4
+    assert plan.class_tokens.tolist() == [[0, 0, 0, 0], [0, 0, 0, 5], [0, 16, 0, 0]]
+    assert list(plan.sizes.class_blocks) == [0, 2, 0, 2] and plan.sizes.num_partials >= 4
 
 
 @pytest.mark.parametrize("kwargs,code", [
