@@ -42,6 +42,7 @@
  *           and group g of G consecutive channels, 4 bytes at (i*(D/G)+g)*4 =
  *           fp16 scale, then fp16 zero.  Value of a code: zero + code*scale.
  *   Tokens past n_{b,c} in the last block of a head are zero bytes.
+ *   (At head_dim 64 a row is half as long, everything else is the same; group_size is then 32 or 64.)
  *   V in token quads (cocktail_sizes::v_layout == COCKTAIL_V_TOKEN_QUADS; chosen
  *   when 2 <= Hq/Hkv <= 8, where a wave serves four query heads of a kv head
  *   with matrix instructions and needs four tokens of a channel side by side):
@@ -50,7 +51,7 @@
  *   token i of the block and channel c are found at
  *     h = c / 64, j = (c % 32) / 8, e = 8 * ((c % 64) / 32) + c % 8,
  *     slot sl = 4 * (i / 4) + j, word w = 2 * (e / n) + (i % 4) / 2,
- *     piece (D*bits/1024) * h + w / 4, 32-bit word w % 4 of the piece, low (i even)
+ *     piece (bits / 2) * h + w / 4 (a 64-channel half of a row is bits / 2 pieces), 32-bit word w % 4 of the piece, low (i even)
  *     or high (i odd) half-word, bits [(e % n) * bits, +bits).
  *   K always uses the row form.
  *
@@ -93,7 +94,7 @@ typedef struct cocktail_shape {
   int32_t batch;        /* B  sequences                                        */
   int32_t num_q_heads;  /* Hq query heads, a multiple of num_kv_heads          */
   int32_t num_kv_heads; /* Hkv                                                 */
-  int32_t head_dim;     /* D, a multiple of 64 (kernels: 128)                  */
+  int32_t head_dim;     /* D, a multiple of 64 (kernels: 64 and 128)           */
   int32_t chunk_size;   /* C tokens per context chunk (Sec. III-A)             */
   int32_t group_size;   /* G in {32, 64, 128}: channels per scale/zero pair    */
 } cocktail_shape;
@@ -191,7 +192,7 @@ int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_lens, const
  *                 plan_host/plan_dev must come from cocktail_plan for this shape
  *   stream        hipStream_t (NULL = default stream)
  *
- * Inputs must be finite.  Errors: EINVAL, EUNSUPPORTED (head_dim != 128),
+ * Inputs must be finite.  Errors: EINVAL, EUNSUPPORTED (head_dim other than 64 or 128),
  * EALIGN, EHIP.  Nothing is launched when an error is returned.
  */
 int cocktail_reorder_quantize(const cocktail_shape* shape, const void* k_src, const void* v_src,
@@ -259,7 +260,7 @@ int cocktail_reorder_quantize_paged(const cocktail_shape* shape, const cocktail_
  *              then one status word per (sequence, query head)).  Calls that share a
  *              workspace must not overlap in time.
  *
- * The packed K/V data is not modified.  Errors: EINVAL, EUNSUPPORTED (head_dim != 128,
+ * The packed K/V data is not modified.  Errors: EINVAL, EUNSUPPORTED (head_dim other than 64 or 128,
  * Hq/Hkv > COCKTAIL_MAX_Q_PER_KV), EALIGN, ENOSPACE, EHIP.
  */
 int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,

@@ -9,7 +9,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcocktail.so")
-SOURCES = ["plan.hip", "reorder_quantize.hip", "decode_attention.hip", "decode_quads.hip", "append.hip", "chunk_search.hip", "stream_probe.hip"]
+SOURCES = ["decode_quads.hip", "decode_quads_d64.hip", "decode_attention.hip", "decode_heads_d64.hip", "plan.hip", "reorder_quantize.hip",
+           "append.hip", "chunk_search.hip", "stream_probe.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
     "-fhip-fp32-correctly-rounded-divide-sqrt",

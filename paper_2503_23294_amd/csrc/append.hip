@@ -13,15 +13,15 @@ namespace cocktail {
 __global__ __launch_bounds__(256) void append_fp16_kernel(const u32x4* __restrict__ k_new,
                                                            const u32x4* __restrict__ v_new, char* __restrict__ k_app,
                                                            char* __restrict__ v_app, int position, int app_blocks,
-                                                           int num_bh, int v_quads) {
-  constexpr int kPieces = 2 * 128 / 16;        // 16-byte pieces of one fp16 row
+                                                           int num_bh, int v_quads, int head_dim) {
+  const int kPieces = 2 * head_dim / 16;       // 16-byte pieces of one fp16 row
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= num_bh * kPieces) return;
   const int bh = idx / kPieces, p = idx % kPieces;
   const u32x4* src = blockIdx.y ? v_new : k_new;
   char* dst = blockIdx.y ? v_app : k_app;
   const size_t block = size_t(bh) * app_blocks + position / kTB;
-  char* blk = dst + block * (kTB * 2 * 128);
+  char* blk = dst + block * size_t(kTB * 2 * head_dim);
   const u32x4 v = src[idx];
   if (blockIdx.y && v_quads) {
     // the piece is channels 8p .. 8p+7 of the token: lane j = p % 4 of its quad, channels e = 8 ((p / 4) % 2) + x
@@ -52,7 +52,8 @@ extern "C" int cocktail_append_fp16(const cocktail_shape* shape, const void* k_n
       hd->chunk_size != shape->chunk_size || hd->group_size != shape->group_size ||
       hd->num_q_heads != shape->num_q_heads)
     return fail(COCKTAIL_EINVAL, "plan was made for a different shape");
-  if (shape->head_dim != 128) return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
+  if (shape->head_dim != 64 && shape->head_dim != 128)
+    return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 64 and 128, got %d", shape->head_dim);
   if (hd->append_capacity <= 0) return fail(COCKTAIL_EINVAL, "the plan was made without append buffers");
   if (position < 0 || position >= hd->append_capacity)
     return fail(COCKTAIL_EINVAL, "position %d outside the append capacity %d", position, hd->append_capacity);
@@ -62,11 +63,11 @@ extern "C" int cocktail_append_fp16(const cocktail_shape* shape, const void* k_n
        reinterpret_cast<uintptr_t>(cache->k_app) | reinterpret_cast<uintptr_t>(cache->v_app)) & 15)
     return fail(COCKTAIL_EALIGN, "k_new, v_new and the append buffers must be 16-byte aligned");
   const int num_bh = hd->batch * hd->num_kv_heads;
-  const dim3 grid((num_bh * 16 + 255) / 256, 2, 1);
+  const dim3 grid((num_bh * (shape->head_dim / 8) + 255) / 256, 2, 1);
   hipLaunchKernelGGL(append_fp16_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
                      static_cast<char*>(cache->k_app), static_cast<char*>(cache->v_app), position, hd->append_blocks,
-                     num_bh, hd->v_layout);
+                     num_bh, hd->v_layout, shape->head_dim);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(COCKTAIL_EHIP, "append launch failed: %s", hipGetErrorString(e));
   return COCKTAIL_OK;

@@ -1,36 +1,10 @@
 // Decode side of Alg. 1 (Sec. III-C): single-query attention over the INT2, INT4,
 // INT8 and FP16 classes of the packed cache.
 //
-// Design (gfx950, wave64):
-//  * The host planner puts all 64-token blocks of a layer into one global order and cuts it into
-//    groups of a few workers.  A worker (workgroup) streams its own block range and then takes
-//    pieces of the group's shared pool through an atomic ticket counter, so that the workers of a
-//    group finish together; it emits one partial softmax state per (sequence, kv head) segment it
-//    touches.
-//  * Inside a wave a token is owned by a PAIR of lanes: lane l works on token
-//    l % 32 of a 32-token unit and on channels [64*(l/32), 64*(l/32)+64).  The block
-//    layout stores the j-th 16-byte piece of all 64 tokens contiguously, so each
-//    half-wave reads one contiguous 512-byte run per load instruction, and the q.k
-//    dot product needs a single cross-lane add per token.  A lane keeps 64 output
-//    accumulators and its half of the query in registers; the kernel stays below
-//    256 VGPRs so that two waves share every SIMD and one wave's loads hide behind
-//    the other's arithmetic.
-//  * Codes are expanded without any conversion: a code field masked out of a
-//    half-word IS an fp16 subnormal of value code * 2^(pos-24), which v_dot2_f32_f16
-//    and v_fma_mix_f32 consume exactly; the power of two is folded into per-group
-//    factors.  Dequantisation is folded too:
-//      q.k^      = sum_g scale_g * (q.code)_g + zero_g * sum(q_g)
-//      sum p v^  = sum_t (p_t scale_tg) code_t + sum_t p_t zero_tg
-//  * Loads go through buffer resources (one VGPR of address per lane) and are
-//    software pipelined by hand: J register stages of K units and J of V units are
-//    refilled one loop iteration ahead of the arithmetic, with the units of whatever
-//    piece comes next (same segment, next segment, or a pool piece).
-//  * Softmax is online per lane pair: logits of J units, one lazy rescale when the
-//    reference maximum grows by more than 2^8, then the V pass.  (m, l, o[D])
-//    partials go to the workspace and a second small kernel merges them exactly
-//    (the softmax-weighted sum does not depend on how tokens are grouped, Eq. 4-5).
-//  * This kernel serves shapes with one query head per kv head; grouped-query shapes run on the
-//    kernel of decode_quads.hip, which shares the pieces, pools and register stages with this one.
+// This file holds the exact merge of the partial softmax states and the host side of the decode entry points;
+// the partial-state kernels are templates (decode_heads_impl.h: one query head per kv head, vector ALU;
+// decode_quads_impl.h: grouped-query shapes, 4x4x4 matrix instructions) instantiated per head_dim in their
+// own translation units.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -38,263 +12,18 @@
 #include <mutex>
 #include <vector>
 
-#include "decode_common.h"
+#include "decode_heads_impl.h"
 
 namespace cocktail {
 
-// One lazy-rescale step of a lane's online softmax followed by p_j = 2^(s_j - m).
-template <int NGH, int J>
-__device__ __forceinline__ void softmax_step(const float (&s)[J], float (&p)[J], LaneState<NGH>& st) {
-  float smax = s[0];
-#pragma unroll
-  for (int jj = 1; jj < J; ++jj) smax = fmaxf(smax, s[jj]);
-  // the reference maximum only moves when it is exceeded by more than 2^8, and then for the whole
-  // wave at once (to the largest logit any lane has seen): the lanes share one reference, so the
-  // number of rescales per state is that of one running maximum, not of 64 independent ones
-  const bool grow = smax > st.m + kRescaleThreshold;
-  if (__builtin_expect(__builtin_amdgcn_ballot_w64(grow) != 0, 0)) {
-    float mnew = fmaxf(smax, st.m);
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) mnew = fmaxf(mnew, __shfl_xor(mnew, o));
-    const float alpha = __builtin_amdgcn_exp2f(st.m - mnew);
-    st.m = mnew;
-    st.l *= alpha;
-#pragma unroll
-    for (int d = 0; d < DH; ++d) st.acc[d] *= alpha;
-#pragma unroll
-    for (int g = 0; g < NGH; ++g) st.zacc[g] *= alpha;
-  }
-#pragma unroll
-  for (int jj = 0; jj < J; ++jj) {
-    p[jj] = __builtin_amdgcn_exp2f(s[jj] - st.m);
-    st.l += p[jj];
-  }
-}
-
-// Writes this wave's partial state `pid`: (m, l, o[D]) reduced over its lanes, and the number of tokens it covers.
-template <int NGH, int GL>
-__device__ __forceinline__ void flush_partial(const LaneState<NGH>& st, float* red, int pid, int r, int lane, int tokens) {
-  kparams_t prm = kparams();
-  const int rep = prm->rep;
-  float mw = st.m;
-#pragma unroll
-  for (int o = 16; o > 0; o >>= 1) mw = fmaxf(mw, __shfl_xor(mw, o));
-  const float f = __builtin_amdgcn_exp2f(st.m - mw);
-  float lw = st.l * f;
-#pragma unroll
-  for (int o = 16; o > 0; o >>= 1) lw += __shfl_xor(lw, o);
-  float* out = prm->ws + (int64_t(pid) * rep + r) * (D + kPartialFloats);
-  if (lane == 0) {
-    out[0] = mw;
-    out[1] = lw;
-    out[2] = __int_as_float(tokens);
-  }
-  float(*tile)[17] = reinterpret_cast<float(*)[17]>(red + r * 64 * 17);
-#pragma unroll
-  for (int ch = 0; ch < DH / 16; ++ch) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-#pragma unroll
-    for (int c = 0; c < 16; ++c) {
-      const int d = ch * 16 + c;
-      tile[lane][c] = (st.acc[d] + st.zacc[d / GL]) * f;
-    }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    // lane (c, quarter) adds 16 rows; quarters 0,1 hold channel half 0 and quarters 2,3 half 1
-    const int c = lane & 15, quarter = lane >> 4;
-    float sum = 0.f;
-#pragma unroll
-    for (int row = 0; row < 16; ++row) sum += tile[quarter * 16 + row][c];
-    sum += __shfl_xor(sum, 16);
-    if ((quarter & 1) == 0) out[kPartialFloats + (quarter >> 1) * DH + ch * 16 + c] = sum;
-  }
-}
-
-// Zeroes the partial state and loads this lane's half of the query row `qrow`.
-template <int NGH, int GL>
-__device__ __forceinline__ void begin_state(int qrow, int h, LaneState<NGH>& st, uint32_t (&q)[DH / 2],
-                                            float (&qsum)[NGH]) {
-#pragma unroll
-  for (int i = 0; i < DH; ++i) st.acc[i] = 0.f;
-#pragma unroll
-  for (int gq = 0; gq < NGH; ++gq) st.zacc[gq] = 0.f;
-  st.m = kNegBig;
-  st.l = 0.f;
-  const u32x4* qp = reinterpret_cast<const u32x4*>(kparams()->q + int64_t(qrow) * (D / 2) + h * (DH / 2));
-#pragma unroll
-  for (int i = 0; i < DH / 8; ++i) {
-    const u32x4 v = qp[i];
-    q[4 * i] = v.x, q[4 * i + 1] = v.y, q[4 * i + 2] = v.z, q[4 * i + 3] = v.w;
-  }
-#pragma unroll
-  for (int gq = 0; gq < NGH; ++gq) {
-    float a = 0.f;
-#pragma unroll
-    for (int i = 0; i < GL / 2; ++i) a = dot2(q[gq * (GL / 2) + i], 0x3C003C00u, a);   // (1.0, 1.0)
-    qsum[gq] = a;
-  }
-}
-
-// Consumes the stream while its pieces belong to class CID, starting with `cur` (whose loads have
-// not been issued yet); returns with `cur` = the first piece of another class, or the end piece.
-//
-// J register stages hold the K units and J the V units of the piece being worked on; each stage is
-// refilled with the corresponding unit of the NEXT piece as soon as it has been consumed, so the
-// loads of a piece are in flight during the arithmetic of the piece before it, across segment and
-// pool boundaries alike.  A piece with fewer than J units leaves stages unused, and after the last
-// piece of the class nothing is left to fetch: those refills address the first unit past the segment,
-// which the buffer resource answers with zeros without touching memory, so the loop body has no
-// branches around the loads (the zeros are masked like padding).  The accumulators live and die inside this function, one
-// instance per class.
-template <class CLS, int CID, int G, int AUX>
-__device__ __forceinline__ void run_class(Stream& sm, Piece& cur, float* red, int r, int lane, bool app = false) {
-  constexpr int NG = D / G;
-  constexpr int NGH = NG >= 2 ? NG / 2 : 1;
-  constexpr int GL = G < DH ? G : DH;
-  constexpr int J = CLS::J;
-  static_assert(J == kIterUnits[CID], "the planner cuts pool pieces to the kernel's iteration size");
-  const int t = lane & 31, h = lane >> 5;
-  const uint32_t vc = CLS::code_voff(t, h), vm = CLS::meta_voff(t, h);
-  const char* const kbase = uni(app ? kparams()->k_app : kparams()->k[CID]);   // app: the append buffers
-  const char* const vbase = uni(app ? kparams()->v_app : kparams()->v[CID]);
-  const float scale_log2 = kparams()->scale_log2;
-  LaneState<NGH> st;
-  uint32_t q[DH / 2];
-  float qsum[NGH];
-  typename CLS::Stage ks[J], vs[J];
-  int pid = cur.pid;
-  // `cur` is the piece the stream produced last, so the stream's segment fields describe it
-  rsrc_t krs = make_rsrc(kbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
-  rsrc_t vrs = make_rsrc(vbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
-  int ru = cur.us, rn = cur.nu;   // the piece the stages are (re)filled with
-  int roob = 2 * sm.nblk;         // first unit past its segment: a load from there is out of range and costs nothing
-#pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(ks[jj], krs, jj < rn ? ru + jj : roob, vc, vm);
-#pragma unroll
-  for (int jj = 0; jj < J; ++jj) CLS::template load<AUX>(vs[jj], vrs, jj < rn ? ru + jj : roob, vc, vm);
-  sched_fence();
-  begin_state<NGH, GL>(sm.qrow + r, h, st, q, qsum);   // the query arrives while the first units are on their way
-  int valid = cur.valid;
-  int covered = 0;   // tokens the current partial state covers (the merge checks the total per sequence)
-  Piece nxt = sm.next(lane);
-#pragma unroll 1
-  while (true) {
-    const bool more = nxt.nu > 0 && nxt.cls == CID;
-    if (more) {
-      krs = make_rsrc(kbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
-      vrs = make_rsrc(vbase + int64_t(sm.blk0) * CLS::BLOCKB, uint32_t(sm.nblk) * CLS::BLOCKB);
-      ru = nxt.us, rn = nxt.nu, roob = 2 * sm.nblk;
-    } else {
-      rn = 0;   // nothing follows in this class: every refill goes out of range
-    }
-    covered += valid;
-    float s[J], p[J];
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      s[jj] = CLS::half_logit(ks[jj], q, qsum);
-      sched_fence();
-      CLS::template load<AUX>(ks[jj], krs, jj < rn ? ru + jj : roob, vc, vm);
-      sched_fence();
-    }
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      const float full = (s[jj] + __shfl_xor(s[jj], 32)) * scale_log2;   // both halves of the token
-      s[jj] = (jj * UT + t < valid) ? full : -INFINITY;
-    }
-    softmax_step<NGH, J>(s, p, st);
-#pragma unroll
-    for (int jj = 0; jj < J; ++jj) {
-      CLS::accumulate(vs[jj], p[jj], st);
-      sched_fence();
-      CLS::template load<AUX>(vs[jj], vrs, jj < rn ? ru + jj : roob, vc, vm);
-      sched_fence();
-    }
-    if (!more || nxt.fresh) flush_partial<NGH, GL>(st, red, pid, r, lane, covered);
-    if (!more) break;
-    if (nxt.fresh) {
-      pid = nxt.pid;
-      covered = 0;
-      begin_state<NGH, GL>(sm.qrow + r, h, st, q, qsum);
-    }
-    valid = nxt.valid;
-    nxt = sm.next(lane);
-  }
-  cur = nxt;
-}
-
-// Workgroups behind the regular workers: workgroup num_workers + bh attends to the tokens appended to
-// (sequence, kv head) bh during decoding (Sec. III-A), an FP16 run of num_appended tokens in the
-// append buffers, and writes the last partial of bh's range.
-template <int G, int AUX>
-__device__ __forceinline__ void appended_tokens(int bh, float* red, int r, int lane) {
-  kparams_t kp = kparams();
-  const int n = kp->num_appended;
-  const int pid = uni(kp->bh_off[bh + 1]) - 1;
-  if (n <= 0) {
-    write_neutral(pid, r, lane);
-    return;
-  }
-  Stream sm;
-  sm.init_run(kFp16Class, n, bh * kp->app_blocks, kp->app_blocks,
-              (bh / kp->num_kv_heads) * kp->num_q_heads + (bh % kp->num_kv_heads) * kp->rep, pid);
-  Piece cur = sm.next(lane);
-  if (cur.nu > 0) run_class<HalfClass<G>, kFp16Class, G, AUX>(sm, cur, red, r, lane, true);
-}
-
-// One single-wave workgroup per worker (Hq = Hkv: the query head of a kv head is that head).  INT8: the cache
-// has an INT8 class; caches without one run a kernel without that code (a third less of it to fetch and
-// to allocate registers for, worth 1.5 us on a 32K-token layer).
-template <int G, int AUX, bool INT8>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void decode_attention_kernel(DecodeParams) {
-  __shared__ float red[64 * 17];   // reduction tile of a flush
-  const int lane = threadIdx.x;
-  constexpr int r = 0;             // query head inside the kv head's group
-#ifdef COCKTAIL_TRACE
-  const uint64_t t_start = __builtin_amdgcn_s_memrealtime();
-#endif
-  if (int(blockIdx.x) >= kparams()->num_workers) {
-    appended_tokens<G, AUX>(int(blockIdx.x) - kparams()->num_workers, red, r, lane);
-    return;
-  }
-  Stream sm;
-  sm.init(load_record(kparams()->recs + blockIdx.x));
-  Piece cur = sm.next(lane);
-  while (cur.nu > 0) {
-    if (cur.cls == 0) {
-      run_class<QuantClass<2, G>, 0, G, AUX>(sm, cur, red, r, lane);
-    } else if (cur.cls == 1) {
-      run_class<QuantClass<4, G>, 1, G, AUX>(sm, cur, red, r, lane);
-    } else if (INT8 && cur.cls == 2) {
-      if constexpr (INT8) run_class<QuantClass<8, G>, 2, G, AUX>(sm, cur, red, r, lane);
-    } else {
-      run_class<HalfClass<G>, kFp16Class, G, AUX>(sm, cur, red, r, lane);
-    }
-  }
-  // pool parts this worker never entered still own a partial slot: fill it with the neutral state
-  for (int i = 0; i < sm.nps; ++i) {
-    if ((sm.used >> i) & 1u) continue;
-    const PoolSeg ps = load_record(kparams()->psegs + sm.pseg0 + i);
-    if (sm.rank < ps.nslots) write_neutral(ps.slot0 + sm.rank, r, lane);
-  }
-#ifdef COCKTAIL_TRACE
-  if (threadIdx.x == 0) {
-    uint64_t* tr = kparams()->trace + blockIdx.x * 4;
-    tr[0] = t_start;
-    tr[1] = __builtin_amdgcn_s_memrealtime();
-    tr[2] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));    // HW_ID
-    tr[3] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));   // XCC_ID
-  }
-#endif
-}
+template hipError_t launch_decode_heads<128>(const DecodeParams&, int, bool, bool, int, hipStream_t);
 
 // Exact merge of the partial states of one (sequence, query head):
 //   M = max m_i,  L = sum l_i 2^(m_i - M),  out = sum o_i 2^(m_i - M) / L,  lse = ln2 (M + log2 L).
-// The partials of a (sequence, kv head) are a dense block of the workspace.  512 threads: 32 channel
-// quads x 16 slices of the block; a slice loads eight partials at a time (128 in flight per workgroup,
-// usually the whole block in one round) and folds them with a running maximum, then the sixteen
-// slice states are folded through shared memory.  A (sequence, query head) without any partial
+// The partials of a (sequence, kv head) are a dense block of the workspace.  HD / 4 channel quads x 16
+// slices of the block (512 threads at head_dim 128); a slice loads eight partials at a time (128 in flight
+// per workgroup, usually the whole block in one round) and folds them with a running maximum, then the
+// sixteen slice states are folded through shared memory.  A (sequence, query head) without any partial
 // (empty sequence) gets zeros and lse = -inf.
 // Every partial also says how many tokens it covers.  Their sum has to be the token count of the
 // sequence: the softmax over the concatenation of Alg. 1 attends to every token exactly once.  If it is
@@ -302,7 +31,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2))) void de
 // damaged plan), the row is not a result: out and lse are set to NaN and the difference goes to the
 // status array.
 constexpr int kMergeSlices = 16;
-__global__ __launch_bounds__(32 * kMergeSlices) void decode_merge_kernel(DecodeParams prm) {
+template <int D>
+__global__ __launch_bounds__(D / 4 * kMergeSlices) void decode_merge_kernel(DecodeParams prm) {
+  constexpr int QUADS = D / 4;
   __shared__ float sm_m[kMergeSlices];
   __shared__ float sm_l[kMergeSlices];
   __shared__ int sm_c[kMergeSlices];
@@ -319,10 +50,10 @@ __global__ __launch_bounds__(32 * kMergeSlices) void decode_merge_kernel(DecodeP
   const int tid = threadIdx.x;
   // every worker has drawn its last ticket: put the counters back to zero for the next call
   if (blockIdx.x == 0)
-    for (int i = tid; i < prm.num_groups; i += 32 * kMergeSlices) prm.counters[i * kCounterStride] = 0u;
+    for (int i = tid; i < prm.num_groups; i += QUADS * kMergeSlices) prm.counters[i * kCounterStride] = 0u;
   constexpr int STRIDE = D + kPartialFloats;
   constexpr int U = 8;   // partials in flight per thread
-  const int quad = tid & 31, slice = tid >> 5;
+  const int quad = tid % QUADS, slice = tid / QUADS;
   const float* base = prm.ws + (int64_t(lo) * rep + r) * STRIDE;
   float m = -INFINITY, l = 0.f, o0 = 0.f, o1 = 0.f, o2 = 0.f, o3 = 0.f;
   int covered = 0;
@@ -447,8 +178,8 @@ int check_plan_matches(const cocktail_shape* shape, const cocktail_cache* cache,
 // Validates the arguments and enqueues the two kernels; `workspace` holds at least hd->workspace_bytes.
 int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void* q, const cocktail_cache* cache,
                    float sm_scale, void* out, float* lse, void* workspace, void* stream) {
-  if (shape->head_dim != D)
-    return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
+  if (shape->head_dim != 64 && shape->head_dim != 128)
+    return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 64 and 128, got %d", shape->head_dim);
   if (hd->rep > COCKTAIL_MAX_Q_PER_KV)
     return fail(COCKTAIL_EUNSUPPORTED, "Hq/Hkv = %d exceeds %d", hd->rep, COCKTAIL_MAX_Q_PER_KV);
   static_assert(COCKTAIL_MAX_Q_PER_KV == kQuadMaxRep, "every ratio above 1 runs on the token-quad kernel");
@@ -514,26 +245,17 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
                                      : ((hd->rep == 1 || (quads && quad_waves(hd->rep) == 1)) &&
                                         hd->packed_bytes >= kNonTemporalMinBytes);
     const bool int8 = hd->class_blocks[2] > 0;
-    if (quads) {
-      const hipError_t e = launch_decode_quads(p, shape->group_size, nt, int8, int(grid.x), st);
-      if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_quads launch failed: %s", hipGetErrorString(e));
-    } else {
-      void (*kern)(DecodeParams) = nullptr;
-#define COCKTAIL_PICK(G)                                                                                              \
-  kern = int8 ? (nt ? decode_attention_kernel<G, kAuxNonTemporal, true> : decode_attention_kernel<G, kAuxDefault, true>) \
-              : (nt ? decode_attention_kernel<G, kAuxNonTemporal, false> : decode_attention_kernel<G, kAuxDefault, false>)
-      switch (shape->group_size) {
-        case 32: COCKTAIL_PICK(32); break;
-        case 64: COCKTAIL_PICK(64); break;
-        default: COCKTAIL_PICK(128); break;
-      }
-#undef COCKTAIL_PICK
-      hipLaunchKernelGGL(kern, grid, block, 0, st, p);
-      const hipError_t e = hipGetLastError();
-      if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode_attention launch failed: %s", hipGetErrorString(e));
-    }
+    const bool d64 = shape->head_dim == 64;
+    const hipError_t e = quads ? (d64 ? launch_decode_quads<64>(p, shape->group_size, nt, int8, int(grid.x), st)
+                                      : launch_decode_quads<128>(p, shape->group_size, nt, int8, int(grid.x), st))
+                               : (d64 ? launch_decode_heads<64>(p, shape->group_size, nt, int8, int(grid.x), st)
+                                      : launch_decode_heads<128>(p, shape->group_size, nt, int8, int(grid.x), st));
+    if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode launch failed: %s", hipGetErrorString(e));
   }
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(shape->batch * shape->num_q_heads), dim3(32 * kMergeSlices), 0, st, p);
+  if (shape->head_dim == 64)
+    hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(shape->batch * shape->num_q_heads), dim3(16 * kMergeSlices), 0, st, p);
+  else
+    hipLaunchKernelGGL(decode_merge_kernel<128>, dim3(shape->batch * shape->num_q_heads), dim3(32 * kMergeSlices), 0, st, p);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess)
     return fail(COCKTAIL_EHIP, "decode_merge launch failed: %s (the ticket counters in plan_dev were not reset: upload the plan again)",

@@ -9,9 +9,17 @@
 namespace cocktail {
 
 
-constexpr int D = 128;
-constexpr int DH = D / 2;                   // channels per lane
-constexpr int UT = 32;                      // tokens per unit (half a block)
+constexpr int DH = 64;                      // channels per lane, for every head_dim
+// Geometry of a wave for head_dim HD (64 or 128).  A lane always works on 64 channels of one token; a token
+// is owned by HD / 64 lanes, so a wave handles 64 tokens at a time at head_dim 64 (a whole block) and 32 at
+// head_dim 128 (half a block, each lane pair splitting the channels).
+template <int HD>
+struct Geo {
+  static_assert(HD == 64 || HD == 128, "kernels are built for head_dim 64 and 128");
+  static constexpr int LPT = HD / DH;         // lanes per token
+  static constexpr int UT = 64 / LPT;         // tokens per unit: what one wave handles at a time
+  static constexpr int UPB = kTB / UT;        // units per 64-token block
+};
 constexpr float kNegBig = -1.0e30f;
 constexpr float kRescaleThreshold = 8.0f;   // log2 units
 constexpr float kTwo24 = 16777216.0f;
@@ -28,13 +36,13 @@ struct DecodeParams {
   const int32_t* bh_off;    // [B*Hkv + 1] (sequence, kv head) owns the partial ids bh_off[bh] .. bh_off[bh+1]-1
   const int32_t* seq_len;   // [B] context tokens per sequence
   int32_t* status;          // [B*Hq] written by the merge: 0, or how far the tokens covered by the partials are off
-  const uint32_t* q;        // fp16 [B][Hq][D] viewed as dwords
+  const uint32_t* q;        // fp16 [B][Hq][head_dim] viewed as dwords
   const char* k[kNumClasses];
   const char* v[kNumClasses];
   const char* k_app;        // append buffers: [B*Hkv][app_blocks] FP16 blocks, or NULL
   const char* v_app;
-  float* ws;                // [num_partials][rep][D + 4]
-  _Float16* out;            // [B][Hq][D]
+  float* ws;                // [num_partials][rep][head_dim + 4]
+  _Float16* out;            // [B][Hq][head_dim]
   float* lse;               // [B][Hq] or NULL
   float scale_log2;         // sm_scale * log2(e)
   int32_t rep, num_q_heads, num_kv_heads, num_groups;
@@ -117,15 +125,16 @@ struct LaneState {
 // half-word.  Masking field k of both half-words of `w` or `w >> 8` leaves two fp16
 // subnormals  code * 2^(BITS*k - 24)  for the channel pair (2f, 2f+1), f = 4*half + k
 // (INT2), 2*half + k (INT4) or half (INT8, one field per byte).
-template <int BITS, int G>
+template <int HD, int BITS, int G>
 struct QuantClass {
-  static constexpr int PH = D * BITS / 256;         // 16-byte pieces per lane and unit
-  static constexpr int NG = D / G;
-  static constexpr int NGH = NG >= 2 ? NG / 2 : 1;  // groups a lane touches
+  static constexpr int UT = Geo<HD>::UT, UPB = Geo<HD>::UPB;
+  static constexpr int PH = DH * BITS / 128;        // 16-byte pieces per lane and unit
+  static constexpr int NG = HD / G;
+  static constexpr int NGH = G < DH ? DH / G : 1;   // groups a lane touches
   static constexpr int GL = G < DH ? G : DH;        // channels of a lane that share one group
   static constexpr int CPW = 32 / BITS;             // channels per word
   static constexpr int NPOS = 8 / BITS;             // fields per byte: 4 (INT2), 2 (INT4) or 1 (INT8)
-  static constexpr int ROWB = D * BITS / 8;
+  static constexpr int ROWB = HD * BITS / 8;
   static constexpr int BLOCKB = kTB * (ROWB + 4 * NG);
   static constexpr int J = BITS == 2 ? J2 : BITS == 4 ? J4 : J8;
   static constexpr uint32_t MASK0 = (BITS == 2) ? 0x00030003u : (BITS == 4) ? 0x000F000Fu : 0x00FF00FFu;
@@ -138,14 +147,14 @@ struct QuantClass {
   // per-lane byte offsets of the code pieces and of the scale/zero pairs inside a unit
   __device__ static __forceinline__ uint32_t code_voff(int t, int h) { return (PH * h * kTB + t) * 16u; }
   __device__ static __forceinline__ uint32_t meta_voff(int t, int h) {
-    return NG >= 2 ? (t * NG + h * NGH) * 4u : t * 4u;
+    return (t * NG + (h * DH) / G) * 4u;   // the lane's first group
   }
 
-  // unit u of the run = tokens [32u, 32u+32): block u/2, first or second half of its token slots
+  // unit u of the run = tokens [UT u, UT u + UT): block u / UPB, and which part of its token slots
   template <int AUX>
   __device__ static __forceinline__ void load(Stage& s, rsrc_t rs, int u, uint32_t vc, uint32_t vm) {
-    const uint32_t boff = uint32_t(u >> 1) * BLOCKB;
-    const uint32_t sub = uint32_t(u & 1);
+    const uint32_t boff = uint32_t(u / UPB) * BLOCKB;
+    const uint32_t sub = uint32_t(u % UPB);
 #pragma unroll
     for (int p = 0; p < PH; ++p) s.pc[p] = load16<AUX>(rs, vc, boff + sub * (UT * 16) + p * (kTB * 16));
     const uint32_t moff = boff + kTB * ROWB + sub * (UT * 4 * NG);
@@ -231,12 +240,13 @@ struct QuantClass {
 };
 
 // ---------------------------------------------------------------------- FP16 class
-template <int G>
+template <int HD, int G>
 struct HalfClass {
+  static constexpr int UT = Geo<HD>::UT, UPB = Geo<HD>::UPB;
   static constexpr int PH = 8;
-  static constexpr int NG = D / G;
-  static constexpr int NGH = NG >= 2 ? NG / 2 : 1;
-  static constexpr int BLOCKB = kTB * 2 * D;
+  static constexpr int NG = HD / G;
+  static constexpr int NGH = G < DH ? DH / G : 1;
+  static constexpr int BLOCKB = kTB * 2 * HD;
   static constexpr int J = J16;
 
   struct Stage {
@@ -247,7 +257,7 @@ struct HalfClass {
 
   template <int AUX>
   __device__ static __forceinline__ void load(Stage& s, rsrc_t rs, int u, uint32_t vc, uint32_t) {
-    const uint32_t boff = uint32_t(u >> 1) * BLOCKB + uint32_t(u & 1) * (UT * 16);
+    const uint32_t boff = uint32_t(u / UPB) * BLOCKB + uint32_t(u % UPB) * (UT * 16);
 #pragma unroll
     for (int p = 0; p < PH; ++p) s.pc[p] = load16<AUX>(rs, vc, boff + p * (kTB * 16));
   }
@@ -306,8 +316,10 @@ __device__ __forceinline__ uint32_t request_ticket(int counter, int lane) {
 // Yields the pieces of one worker: first its own block range front to back, then pieces of the
 // group's pool, one ticket each, until the tickets run out.  Segments are visited in ascending
 // order, so every segment is entered at most once.
+template <int HD>
 struct Stream {
-  int u, u1;          // own range: cursor and end in global units (two per block)
+  static constexpr int UT = Geo<HD>::UT, UPB = Geo<HD>::UPB;
+  int u, u1;          // own range: cursor and end in global units (UPB per block)
   int s;              // index of the current segment; the fields below describe it
   int cls, ntok, blk0, nblk, gu0, qrow;   // gu0: first global unit of the segment
   int pid;            // partial id of this worker's own piece of the current segment
@@ -322,13 +334,13 @@ struct Stream {
   __device__ __forceinline__ void enter(const Segment& g, int index) {
     kparams_t kp = kparams();
     s = index;
-    cls = uni(g.cls), ntok = uni(g.ntok), blk0 = uni(g.blk0), nblk = uni(g.nblk), gu0 = 2 * uni(g.gblk0);
+    cls = uni(g.cls), ntok = uni(g.ntok), blk0 = uni(g.blk0), nblk = uni(g.nblk), gu0 = UPB * uni(g.gblk0);
     pid = uni(g.pid0);   // whoever enters a segment from its start is its first visitor
     qrow = uni(g.b) * kp->num_q_heads + uni(g.h) * kp->rep;
   }
 
   __device__ __forceinline__ void init(const WorkerRec& rec) {
-    u = 2 * uni(rec.g0), u1 = 2 * uni(rec.g1);
+    u = UPB * uni(rec.g0), u1 = UPB * uni(rec.g1);
     enter(rec.first, uni(rec.seg0));
     pid = uni(rec.pid0);   // the first segment is usually entered somewhere in the middle
     if (u >= u1) s = -1;   // no own range: `first` describes nothing, the first pool piece enters its segment
@@ -374,9 +386,9 @@ struct Stream {
         phase = 1;
       }
       if (u < u1) {
-        if (u >= gu0 + 2 * nblk) enter(load_record(kparams()->segs + s + 1), s + 1);
+        if (u >= gu0 + UPB * nblk) enter(load_record(kparams()->segs + s + 1), s + 1);
         const int us = u - gu0;
-        const int nu = min(iter_units(cls), min(u1 - gu0, 2 * nblk) - us);
+        const int nu = min(iter_units(cls), min(u1 - gu0, UPB * nblk) - us);
         if (nu <= 0) {   // cannot happen with a plan written by cocktail_plan; guarantees termination
           phase = 3;
           return d;
@@ -427,16 +439,21 @@ struct Stream {
 };
 
 // The neutral partial state (weight zero in the merge) for a slot nobody had tokens for.
+template <int HD>
 __device__ __forceinline__ void write_neutral(int slot, int r, int lane) {
   kparams_t kp = kparams();
-  float* out = kp->ws + (int64_t(slot) * kp->rep + r) * (D + kPartialFloats);
+  float* out = kp->ws + (int64_t(slot) * kp->rep + r) * (HD + kPartialFloats);
   if (lane == 0) out[0] = kNegBig, out[1] = 0.f, out[2] = 0.f;   // covers no tokens
-  out[kPartialFloats + lane] = 0.f;
-  out[kPartialFloats + 64 + lane] = 0.f;
+#pragma unroll
+  for (int i = 0; i < HD / 64; ++i) out[kPartialFloats + 64 * i + lane] = 0.f;
 }
 
-// Launches the kernel for 2 to 8 query heads per kv head (decode_quads.hip): `grid` workgroups of one wave
-// (up to 4 heads) or two waves (5 to 8); int8: the cache has an INT8 class.
+// Launch the partial-state kernels for head_dim HD (one translation unit per head_dim and kernel family):
+// one query head per wave on the vector ALU; 2 to 8 query heads per kv head on matrix instructions, `grid`
+// workgroups of one wave (up to 4 heads) or two waves (5 to 8).  int8: the cache has an INT8 class.
+template <int HD>
+hipError_t launch_decode_heads(const DecodeParams& p, int group_size, bool non_temporal, bool int8, int grid, hipStream_t st);
+template <int HD>
 hipError_t launch_decode_quads(const DecodeParams& p, int group_size, bool non_temporal, bool int8, int grid, hipStream_t st);
 
 }  // namespace cocktail

@@ -12,7 +12,6 @@ namespace cocktail {
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
 constexpr uint32_t kPlanVersion = 12;
 constexpr int kTB = 64;                        // tokens per block
-constexpr int kUT = 32;                        // tokens per unit (half a block): what one wave handles at a time
 constexpr int kNumClasses = 4;                 // INT2, INT4, INT8, FP16: the order of the concatenation
 constexpr int kFp16Class = kNumClasses - 1;
 constexpr int kClassBits[kNumClasses] = {2, 4, 8, 16};
@@ -78,7 +77,8 @@ static_assert(sizeof(GroupRec) == 32, "GroupRec layout");
 // stands for units [unit0 + (t - gran0) * J, + J) of the segment, J = kIterUnits[class].
 struct PoolSeg {
   int32_t seg;               // segment index
-  int32_t unit0;             // first unit, counted from the start of the segment
+  int32_t unit0;             // first unit, counted from the start of the segment (a unit = what a wave handles at a
+                             // time: 32 tokens at head_dim 128, 64 at head_dim 64)
   int32_t nunits;
   int32_t gran0;             // first ticket of this part
   int32_t slot0;             // partial id of rank 0; rank r < nslots of the group writes slot0 + r
@@ -144,7 +144,7 @@ struct PlanHeader {
 
 // Token-quad form of a V block: byte offset, inside the block, of the half-word that holds token i
 // (0..63) of lane j's channels e .. e + per - 1 in the 64-channel half h, where per = 16 / bits values
-// fill a half-word and ph = pieces of 16 bytes per half (D * bits / 1024).  Channel of (h, j, e):
+// fill a half-word and ph = pieces of 16 bytes per 64-channel half of a row (bits / 2).  Channel of (h, j, e):
 // 64 h + 32 (e / 8) + 8 j + e % 8.
 __host__ __device__ inline uint32_t quad_halfword_offset(int ph, int per, int i, int h, int j, int e) {
   const int w = 2 * (e / per) + ((i & 3) >> 1);

@@ -186,6 +186,9 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   const int B = shape->batch, Hkv = shape->num_kv_heads, D = shape->head_dim, C = shape->chunk_size,
             G = shape->group_size;
   const int P = num_workers;
+  // a wave handles 64 tokens at a time at head_dim 64 and 32 at head_dim 128 (a lane works on 64 channels):
+  // the units the pool tickets count in
+  const int units_per_block = D == 64 ? 1 : 2;
 
   int64_t total_chunks = 0, total_tokens = 0;
   for (int b = 0; b < B; ++b) {
@@ -445,8 +448,8 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
           PoolSeg ps;
           std::memset(&ps, 0, sizeof(ps));
           ps.seg = s;
-          ps.unit0 = 2 * (lo - segs[s].gblk0);
-          ps.nunits = 2 * (hi - lo);
+          ps.unit0 = units_per_block * (lo - segs[s].gblk0);
+          ps.nunits = units_per_block * (hi - lo);
           ps.gran0 = gran;
           const int J = kIterUnits[segs[s].cls];
           gran += (ps.nunits + J - 1) / J;

@@ -123,13 +123,17 @@ __device__ __forceinline__ float pack4(float a, float b, float c, float d) {
   return __builtin_fmaf(__builtin_fmaf(__builtin_fmaf(d, S, c), S, b), S, a);
 }
 
-// Quantizes this thread's four rows (8 channels each) and writes codes and scale/zero pairs into the block
-// image in shared memory (row form, or token quads for V where the cache stores V that way).
-template <int BITS, int G, class LoadRow>
+// Quantizes this thread's rows (8 channels each; four rows at head_dim 128, two at head_dim 64) and writes codes
+// and scale/zero pairs into the block image in shared memory (row form, or token quads for V where the cache
+// stores V that way).
+template <int D, int BITS, int G, class LoadRow>
 __device__ __forceinline__ void quantize_rows(LoadRow load_row, char* lds, int row, int seg, bool quads,
                                               int meta_base) {
   constexpr int LPG = G / 8;   // lanes per group
-  constexpr int NG = 128 / G;
+  constexpr int NG = D / G;
+  constexpr int RPP = 256 / (D / 8);    // rows per pass: the workgroup's 256 threads cover D / 8 lanes per row
+  constexpr int PASSES = kTB / RPP;
+  constexpr int PSTEP = RPP * 16;       // bytes between a thread's rows inside one 16-byte-piece plane
   const int qh = seg >> 3, qj = seg & 3, qe0 = 8 * ((seg >> 2) & 1);
   const bool writes_meta = (seg & (LPG - 1)) == 0;
   char* const meta0 = lds + meta_base + (row * NG + seg / LPG) * 4;
@@ -143,7 +147,7 @@ __device__ __forceinline__ void quantize_rows(LoadRow load_row, char* lds, int r
   char* const quad2 = lds + quad_halfword_offset(QPH, 16 / BITS, row, qh, qj, qe0 + 4);   // INT8: channels 4, 5
   char* const quad3 = lds + quad_halfword_offset(QPH, 16 / BITS, row, qh, qj, qe0 + 6);   // INT8: channels 6, 7
 #pragma unroll
-  for (int pass = 0; pass < 4; ++pass) {
+  for (int pass = 0; pass < PASSES; ++pass) {
     const u32x4 raw = load_row(pass);
     float mn, mx;
     group_min_max<LPG>(raw, mn, mx);
@@ -154,39 +158,39 @@ __device__ __forceinline__ void quantize_rows(LoadRow load_row, char* lds, int r
       h2 m;
       m.x = scale_h;
       m.y = static_cast<_Float16>(mn);
-      *reinterpret_cast<uint32_t*>(meta0 + pass * (16 * NG * 4)) = as_u32(m);
+      *reinterpret_cast<uint32_t*>(meta0 + pass * (RPP * NG * 4)) = as_u32(m);
     }
     if (quads) {
       // a half-word holds consecutive channels of one token, lowest channel in the lowest bits
       if constexpr (BITS == 8) {
-        *reinterpret_cast<uint16_t*>(quad0 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[1], 256.0f, c[0])));
-        *reinterpret_cast<uint16_t*>(quad1 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[3], 256.0f, c[2])));
-        *reinterpret_cast<uint16_t*>(quad2 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[5], 256.0f, c[4])));
-        *reinterpret_cast<uint16_t*>(quad3 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[7], 256.0f, c[6])));
+        *reinterpret_cast<uint16_t*>(quad0 + pass * PSTEP) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[1], 256.0f, c[0])));
+        *reinterpret_cast<uint16_t*>(quad1 + pass * PSTEP) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[3], 256.0f, c[2])));
+        *reinterpret_cast<uint16_t*>(quad2 + pass * PSTEP) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[5], 256.0f, c[4])));
+        *reinterpret_cast<uint16_t*>(quad3 + pass * PSTEP) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(c[7], 256.0f, c[6])));
       } else if constexpr (BITS == 4) {
-        *reinterpret_cast<uint16_t*>(quad0 + pass * 256) = uint16_t(static_cast<uint32_t>(pack4<4>(c[0], c[1], c[2], c[3])));
-        *reinterpret_cast<uint16_t*>(quad1 + pass * 256) = uint16_t(static_cast<uint32_t>(pack4<4>(c[4], c[5], c[6], c[7])));
+        *reinterpret_cast<uint16_t*>(quad0 + pass * PSTEP) = uint16_t(static_cast<uint32_t>(pack4<4>(c[0], c[1], c[2], c[3])));
+        *reinterpret_cast<uint16_t*>(quad1 + pass * PSTEP) = uint16_t(static_cast<uint32_t>(pack4<4>(c[4], c[5], c[6], c[7])));
       } else {
         const float lo = pack4<2>(c[0], c[1], c[2], c[3]), hi = pack4<2>(c[4], c[5], c[6], c[7]);
-        *reinterpret_cast<uint16_t*>(quad0 + pass * 256) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(hi, 256.0f, lo)));
+        *reinterpret_cast<uint16_t*>(quad0 + pass * PSTEP) = uint16_t(static_cast<uint32_t>(__builtin_fmaf(hi, 256.0f, lo)));
       }
     } else if constexpr (BITS == 8) {
       // row form, four channels per word: (c0, c2) in the low half-word, (c1, c3) in the high one
       u32x2 w;
       w.x = static_cast<uint32_t>(__builtin_fmaf(c[2], 256.0f, c[0])) | (static_cast<uint32_t>(__builtin_fmaf(c[3], 256.0f, c[1])) << 16);
       w.y = static_cast<uint32_t>(__builtin_fmaf(c[6], 256.0f, c[4])) | (static_cast<uint32_t>(__builtin_fmaf(c[7], 256.0f, c[5])) << 16);
-      *reinterpret_cast<u32x2*>(row0 + pass * 256) = w;
+      *reinterpret_cast<u32x2*>(row0 + pass * PSTEP) = w;
     } else {
       // row form: even channels in the low half-word, odd ones in the high half-word
       const uint32_t even = static_cast<uint32_t>(pack4<BITS>(c[0], c[2], c[4], c[6]));
       const uint32_t odd = static_cast<uint32_t>(pack4<BITS>(c[1], c[3], c[5], c[7]));
       const uint32_t mine = even | (odd << 16);
       if constexpr (BITS == 4) {
-        *reinterpret_cast<uint32_t*>(row0 + pass * 256) = mine;   // word = 8 channels
+        *reinterpret_cast<uint32_t*>(row0 + pass * PSTEP) = mine;   // word = 8 channels
       } else {
         // word = 16 channels = two lanes: fields 0..3 of both half-words from the even lane, 4..7 from the odd one
         const uint32_t other = __shfl_xor(mine, 1);
-        if ((seg & 1) == 0) *reinterpret_cast<uint32_t*>(row0 + pass * 256) = mine | (other << 8);
+        if ((seg & 1) == 0) *reinterpret_cast<uint32_t*>(row0 + pass * PSTEP) = mine | (other << 8);
       }
     }
   }
@@ -194,7 +198,11 @@ __device__ __forceinline__ void quantize_rows(LoadRow load_row, char* lds, int r
 
 template <int D, int G, bool PAGED>
 __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
-  static_assert(D == 128, "one 16-lane row of 8 channels per lane");
+  static_assert(D == 64 || D == 128, "a row is 8 or 16 lanes of 8 channels");
+  static_assert(D % G == 0, "a group lies inside a row");
+  constexpr int SEGS = D / 8;           // lanes per row
+  constexpr int RPP = 256 / SEGS;       // rows per pass
+  constexpr int PASSES = kTB / RPP;
   __shared__ __attribute__((aligned(16))) char lds[kTB * 2 * D];
 
   const int which = blockIdx.y;  // 0 = K, 1 = V
@@ -237,15 +245,15 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   }
 
   const int tid = threadIdx.x;
-  const int seg = tid & 15;        // 8 channels seg*8 .. seg*8+7
-  const int row = tid >> 4;        // this thread's rows of the block: row, row + 16, row + 32, row + 48
+  const int seg = tid % SEGS;      // 8 channels seg*8 .. seg*8+7
+  const int row = tid / SEGS;      // this thread's rows of the block: row, row + RPP, ...
   const bool quads = which == 1 && p.v_quads != 0;   // token-quad form of V
   const int row_bytes = D * kClassBits[cls] / 8;
 
   // row `pass * 16 + row` of the block, 8 channels of it (zeros past the last valid row).  Consecutive
   // source rows (almost every block): one pointer per thread and a fixed step per pass.
   const _Float16* const row_ptr = src + int64_t(row) * p.stride_t + seg * 8;
-  const int64_t pass_step = 16 * p.stride_t;
+  const int64_t pass_step = RPP * p.stride_t;
   // source token of row i of the block when the rows are looked up one by one
   auto token_of = [&](int i) {
     if (t0 >= 0) return t0 + i;
@@ -258,12 +266,12 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   };
   // paged source, rows one by one: the page ids of this thread's four rows are fetched up front, so that
   // the four row loads do not each wait for a table look-up first (-1: not a page of the pool)
-  int row_page[4] = {0, 0, 0, 0};
+  int row_page[PASSES] = {};
   if constexpr (PAGED) {
     if (per_row) {
 #pragma unroll
-      for (int pass = 0; pass < 4; ++pass) {
-        const int i = pass * 16 + row;
+      for (int pass = 0; pass < PASSES; ++pass) {
+        const int i = pass * RPP + row;
         int page = -1;
         if (i < nvalid) {
           const int t = token_of(i);
@@ -275,7 +283,7 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
     }
   }
   auto load_row = [&](int pass) {
-    const int i = pass * 16 + row;
+    const int i = pass * RPP + row;
     u32x4 v = {0u, 0u, 0u, 0u};
     if (i < nvalid) {
       const _Float16* ptr = row_ptr + pass * pass_step;
@@ -301,8 +309,8 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
   const int qh = seg >> 3, qj = seg & 3, qe0 = 8 * ((seg >> 2) & 1);
   if (cls == kFp16Class) {
 #pragma unroll
-    for (int pass = 0; pass < 4; ++pass) {
-      const int i = pass * 16 + row;
+    for (int pass = 0; pass < PASSES; ++pass) {
+      const int i = pass * RPP + row;
       const u32x4 raw = load_row(pass);
       if (quads) {
 #pragma unroll
@@ -314,11 +322,11 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
       }
     }
   } else if (cls == 0) {
-    quantize_rows<2, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
+    quantize_rows<D, 2, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
   } else if (cls == 1) {
-    quantize_rows<4, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
+    quantize_rows<D, 4, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
   } else {
-    quantize_rows<8, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
+    quantize_rows<D, 8, G>(load_row, lds, row, seg, quads, kTB * row_bytes);
   }
   __syncthreads();
   constexpr int NGc = D / G;
@@ -408,20 +416,25 @@ int launch_reorder_quantize(const cocktail_shape* shape, const cocktail_cache* c
     if (!cache->k_app || !cache->v_app) return fail(COCKTAIL_EINVAL, "the plan has append buffers but k_app or v_app is NULL");
     if ((reinterpret_cast<uintptr_t>(cache->k_app) | reinterpret_cast<uintptr_t>(cache->v_app)) & 15)
       return fail(COCKTAIL_EALIGN, "append buffers must be 16-byte aligned");
-    const size_t n16 = size_t(hd->batch) * hd->num_kv_heads * hd->append_blocks * (kTB * 2 * 128 / 16);
+    const size_t n16 = size_t(hd->batch) * hd->num_kv_heads * hd->append_blocks * (kTB * 2 * shape->head_dim / 16);
     const unsigned blocks = static_cast<unsigned>(n16 / 256 < 4096 ? (n16 + 255) / 256 : 4096);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, static_cast<u32x4*>(cache->k_app), n16);
     hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks), dim3(256), 0, st, static_cast<u32x4*>(cache->v_app), n16);
   }
   if (tot == 0) return COCKTAIL_OK;
   const dim3 grid(static_cast<unsigned>(tot), 2, 1), block(256, 1, 1);
-#define COCKTAIL_RQ_LAUNCH(G)                                                                      \
-  if (paged) hipLaunchKernelGGL((reorder_quantize_kernel<128, G, true>), grid, block, 0, st, p);  \
-  else hipLaunchKernelGGL((reorder_quantize_kernel<128, G, false>), grid, block, 0, st, p)
-  switch (shape->group_size) {
-    case 32: COCKTAIL_RQ_LAUNCH(32); break;
-    case 64: COCKTAIL_RQ_LAUNCH(64); break;
-    default: COCKTAIL_RQ_LAUNCH(128); break;
+#define COCKTAIL_RQ_LAUNCH(D, G)                                                                 \
+  if (paged) hipLaunchKernelGGL((reorder_quantize_kernel<D, G, true>), grid, block, 0, st, p);  \
+  else hipLaunchKernelGGL((reorder_quantize_kernel<D, G, false>), grid, block, 0, st, p)
+  if (shape->head_dim == 64) {
+    if (shape->group_size == 32) COCKTAIL_RQ_LAUNCH(64, 32);
+    else COCKTAIL_RQ_LAUNCH(64, 64);
+  } else {
+    switch (shape->group_size) {
+      case 32: COCKTAIL_RQ_LAUNCH(128, 32); break;
+      case 64: COCKTAIL_RQ_LAUNCH(128, 64); break;
+      default: COCKTAIL_RQ_LAUNCH(128, 128); break;
+    }
   }
 #undef COCKTAIL_RQ_LAUNCH
   const hipError_t e = hipGetLastError();
@@ -439,7 +452,8 @@ int plan_of(const cocktail_shape* shape, const cocktail_cache* cache, const Plan
       hd->chunk_size != shape->chunk_size || hd->group_size != shape->group_size ||
       hd->num_q_heads != shape->num_q_heads)
     return fail(COCKTAIL_EINVAL, "plan was made for a different shape");
-  if (shape->head_dim != 128) return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 128, got %d", shape->head_dim);
+  if (shape->head_dim != 64 && shape->head_dim != 128)
+    return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 64 and 128, got %d", shape->head_dim);
   *out = hd;
   return COCKTAIL_OK;
 }

@@ -52,6 +52,7 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   const PlanHeader& hd = *view<PlanHeader>(blob, 0, 1);
   REQUIRE(hd.magic == kPlanMagic && hd.plan_bytes == int64_t(blob.size()));
   const int B = sh.batch, Hkv = sh.num_kv_heads, C = sh.chunk_size, P = workers;
+  const int UPB = sh.head_dim == 64 ? 1 : 2;   // units (what a wave handles at a time) per 64-token block
   const int S = hd.num_segments, NG = hd.num_groups, NPS = hd.num_pool_segs, BH = B * Hkv;
   const Segment* segs = view<Segment>(blob, hd.off_segments, S);
   const WorkerRec* recs = view<WorkerRec>(blob, hd.off_worker_rec, P);
@@ -108,7 +109,7 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   REQUIRE(g == hd.total_gblocks && g == nblocks);
 
   // the walk of every worker: own range, then the pool tickets of its group (handed out at random)
-  std::vector<uint8_t> unit_seen(2 * g, 0);
+  std::vector<uint8_t> unit_seen(UPB * g, 0);
   std::vector<uint8_t> pid_seen(hd.num_partials, 0);
   auto claim_pid = [&](int pid, const Segment& sg) {
     REQUIRE(pid >= 0 && pid < hd.num_partials && !pid_seen[pid]);
@@ -131,25 +132,25 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
       const WorkerRec& rc_ = recs[w];
       const int rank = rc_.rank_nps & 0xffff;
       REQUIRE(rank < gr.nworkers && (rc_.rank_nps >> 16) == gr.nps && rc_.ngran == gr.ngran && rc_.pseg0 == gr.pseg0);
-      int u = 2 * rc_.g0, u1 = 2 * rc_.g1, s = rc_.seg0, pid = rc_.pid0, last_seg = -1;
+      int u = UPB * rc_.g0, u1 = UPB * rc_.g1, s = rc_.seg0, pid = rc_.pid0, last_seg = -1;
       REQUIRE(rc_.g0 <= rc_.g1 && rc_.g1 <= g);
       if (u < u1) {
         REQUIRE(s >= 0 && s < S && std::memcmp(&rc_.first, &segs[s], sizeof(Segment)) == 0);
       }
       while (u < u1) {
         REQUIRE(s < S);
-        if (u >= 2 * (segs[s].gblk0 + segs[s].nblk)) {
+        if (u >= UPB * (segs[s].gblk0 + segs[s].nblk)) {
           ++s;
           REQUIRE(s < S);
           pid = segs[s].pid0;
           continue;
         }
-        REQUIRE(u >= 2 * segs[s].gblk0);
+        REQUIRE(u >= UPB * segs[s].gblk0);
         if (s != last_seg) {
           claim_pid(pid, segs[s]);
           last_seg = s;
         }
-        const int end = std::min(u1, 2 * (segs[s].gblk0 + segs[s].nblk));
+        const int end = std::min(u1, UPB * (segs[s].gblk0 + segs[s].nblk));
         const int nu = std::min(kIterUnits[segs[s].cls], end - u);
         REQUIRE(nu > 0);
         for (int i = 0; i < nu; ++i) REQUIRE(unit_seen[u + i]++ == 0);
@@ -166,21 +167,21 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
         const Segment& sg = segs[ps.seg];
         const int J = kIterUnits[sg.cls];
         const int us = ps.unit0 + (t - ps.gran0) * J, nu = std::min(J, ps.unit0 + ps.nunits - us);
-        REQUIRE(nu > 0 && us >= 0 && us + nu <= 2 * sg.nblk);
+        REQUIRE(nu > 0 && us >= 0 && us + nu <= UPB * sg.nblk);
         if (ps.seg != last_seg) {
           REQUIRE(rank < ps.nslots);
           claim_pid(ps.slot0 + rank, sg);
           used |= 1u << pi;
           last_seg = ps.seg;
         }
-        for (int i = 0; i < nu; ++i) REQUIRE(unit_seen[2 * sg.gblk0 + us + i]++ == 0);
+        for (int i = 0; i < nu; ++i) REQUIRE(unit_seen[UPB * sg.gblk0 + us + i]++ == 0);
       }
       for (int i = 0; i < gr.nps; ++i)   // slots the worker fills with the neutral state
         if (!((used >> i) & 1u) && rank < psegs[gr.pseg0 + i].nslots)
           claim_pid(psegs[gr.pseg0 + i].slot0 + rank, segs[psegs[gr.pseg0 + i].seg]);
     }
   }
-  for (int64_t i = 0; i < 2 * g; ++i) REQUIRE(unit_seen[i] == 1);
+  for (int64_t i = 0; i < UPB * g; ++i) REQUIRE(unit_seen[i] == 1);
   if (opt.append_capacity > 0)   // the last partial of every (sequence, kv head) belongs to the appended tokens
     for (int bh = 0; bh < BH; ++bh) {
       REQUIRE(bh_off[bh + 1] - 1 >= bh_off[bh] && !pid_seen[bh_off[bh + 1] - 1]);
@@ -235,8 +236,8 @@ int main(int argc, char** argv) {
     sh.batch = 1 + int(rng() % 6);
     sh.num_kv_heads = 1 + int(rng() % 4);
     sh.num_q_heads = sh.num_kv_heads * pick({1, 1, 2, 3, 4, 5, 8});
-    sh.head_dim = 128;
-    sh.group_size = pick({32, 64, 128});
+    sh.head_dim = pick({64, 128, 128});
+    sh.group_size = sh.head_dim == 64 ? pick({32, 64}) : pick({32, 64, 128});
     sh.chunk_size = pick({1, 8, 17, 32, 64, 100, 256, 1000});
     std::vector<int32_t> lens(sh.batch);
     std::vector<uint8_t> bits;

@@ -144,6 +144,27 @@ def test_group_sizes_and_gqa(group, rep):
     Case(w, workers=5).check_all()
 
 
+@pytest.mark.parametrize("group", [32, 64])
+@pytest.mark.parametrize("rep", [1, 2, 3, 4, 5, 8])
+def test_head_dim_64(group, rep):
+    """head_dim 64: a lane still works on 64 channels, so a wave takes 64 tokens at a time instead of 32."""
+    w = workloads.small(f"d64_g{group}_r{rep}", 2, 2 * rep, 2, [64 * 5 + 32 * 3 + 7, 64 * 9 + 1], 32, group,
+                        mix=(0.2, 0.25, 0.25, 0.3), head_dim=64, seed_offset=64 + group + rep)
+    _announce(w.name)
+    Case(w, workers=5).check_all()
+
+
+@pytest.mark.parametrize("rep,workers", [(1, 24), (4, 7)])
+def test_head_dim_64_long_sequences_with_pools(rep, workers):
+    w = workloads.small(f"d64pools_r{rep}", 3, 2 * rep, 2, [6000, 2500, 9000], 64, 32, mix=(0.2, 0.2, 0.2, 0.4),
+                        head_dim=64, seed_offset=164 + rep)
+    _announce(w.name)
+    c = Case(w, workers=workers)
+    assert _counters(c)[1] > 0, "this shape is meant to exercise the pools"
+    c.check_all()
+    ck.cocktail_decode_check(c.cache)
+
+
 @pytest.mark.parametrize("mix", [(1, 0, 0), (0, 1, 0), (0, 0, 1), (0.5, 0, 0.5), (0, 1, 0, 0), (0.3, 0.3, 0, 0.4),
                                  (0, 0.5, 0.5, 0), (0.25, 0.25, 0.25, 0.25)])
 def test_single_class_and_missing_class(mix):
@@ -174,12 +195,13 @@ def test_strided_padded_source():
     Case(w, workers=4, strided_pad=8).check_all()
 
 
-@pytest.mark.parametrize("page_size,head_major,rep", [(16, True, 1), (64, False, 1), (128, True, 4), (5, True, 1), (256, False, 2)])
-def test_paged_source(page_size, head_major, rep):
+@pytest.mark.parametrize("page_size,head_major,rep,head_dim", [(16, True, 1, 128), (64, False, 1, 128), (128, True, 4, 128),
+                                                               (5, True, 1, 128), (256, False, 2, 128), (16, True, 4, 64)])
+def test_paged_source(page_size, head_major, rep, head_dim):
     """Reorder+quantize straight from a paged KV cache with a shuffled page table: the packed cache must be the
     one the oracle makes from the gathered K and V, byte for byte."""
     w = workloads.small(f"paged{page_size}", 3, 2 * rep, 2, [64 * 9 + 21, 0, 700], 32, 32, mix=(0.2, 0.4, 0.4),
-                        seed_offset=600 + page_size)
+                        head_dim=head_dim, seed_offset=600 + page_size)
     _announce(f"{w.name} head_major={head_major} rep={rep}")
     dev = _dev()
     shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
@@ -339,11 +361,12 @@ def test_planner_tuning_knobs_keep_parity(env, monkeypatch):
     Case(w, workers=16).check_all()
 
 
-@pytest.mark.parametrize("rep,capacity,steps", [(1, 70, 70), (4, 130, 37), (2, 1, 1), (8, 66, 66), (6, 5, 3)])
-def test_appended_decode_tokens(rep, capacity, steps):
+@pytest.mark.parametrize("rep,capacity,steps,head_dim", [(1, 70, 70, 128), (4, 130, 37, 128), (2, 1, 1, 128), (8, 66, 66, 128),
+                                                         (6, 5, 3, 128), (1, 70, 70, 64), (4, 130, 67, 64)])
+def test_appended_decode_tokens(rep, capacity, steps, head_dim):
     """Sec. III-A: generated tokens are appended in FP16; every decode step attends to all of them."""
-    w = workloads.small(f"append_r{rep}", 2, 2 * rep, 2, [64 * 9 + 5, 300], 64, 32, mix=(0.2, 0.4, 0.4),
-                        seed_offset=60 + rep)
+    w = workloads.small(f"append_r{rep}_d{head_dim}", 2, 2 * rep, 2, [64 * 9 + 5, 300], 64, 32, mix=(0.2, 0.4, 0.4),
+                        head_dim=head_dim, seed_offset=60 + rep)
     _announce(w.name)
     dev = _dev()
     shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
@@ -687,7 +710,8 @@ def _random_case(seed):
     rep = int(rng.choice([1, 1, 2, 3, 4, 4, 5, 6, 8]))
     hkv = int(rng.integers(1, 4))
     batch = int(rng.integers(1, 5))
-    group = int(rng.choice([32, 64, 128]))
+    head_dim = int(rng.choice([64, 128, 128]))
+    group = int(rng.choice([32, 64, 128] if head_dim == 128 else [32, 64]))
     chunk = int(rng.choice([8, 32, 64, 100, 256]))
     lens = [int(x) for x in rng.integers(0, 2500, size=batch)]
     if rng.random() < 0.3:
@@ -699,13 +723,13 @@ def _random_case(seed):
         mix[int(rng.integers(0, 4))] = 0.0                                    # an empty class
     workers = int(rng.choice([1, 2, 5, 8, 16, 33, 64, 200]))
     w = workloads.small(f"fuzz{seed}", batch, hkv * rep, hkv, lens, chunk, group, mix=tuple(float(x) for x in mix),
-                        seed_offset=9000 + seed)
+                        head_dim=head_dim, seed_offset=9000 + seed)
     return w, workers
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(32))
 def test_random_shapes(seed):
     w, workers = _random_case(seed)
-    _announce(f"{w.name}: B={w.batch} Hq={w.num_q_heads} Hkv={w.num_kv_heads} G={w.group_size} C={w.chunk_size} "
+    _announce(f"{w.name}: B={w.batch} Hq={w.num_q_heads} Hkv={w.num_kv_heads} D={w.head_dim} G={w.group_size} C={w.chunk_size} "
               f"T={list(w.seq_lens)} mix={[round(m, 2) for m in w.mix]} workers={workers}")
     Case(w, workers=workers).check_all()

@@ -274,10 +274,11 @@ def test_gpu_entry_points_validate_on_host_before_launching():
     assert L.cocktail_decode_attention(C.byref(sh), None, C.byref(cache), 0.0, 16, None, 16, 0, None) == _lib.EINVAL
     assert L.cocktail_decode_attention(C.byref(sh), 16, C.byref(cache), 0.0, 16, None, 16, 0, None) == _lib.ENOSPACE
     assert L.cocktail_decode_attention(C.byref(sh), 16, C.byref(cache), 0.0, 24, None, 16, 1 << 20, None) == _lib.EALIGN
-    sh64 = ck.make_shape(1, 2, 2, 64, 8, 32)
-    p64 = ck.cocktail_plan(sh64, [16], [2, 4], 4)
-    cache.plan_host = p64.blob.ctypes.data
-    assert L.cocktail_decode_attention(C.byref(sh64), 16, C.byref(cache), 0.0, 16, None, 16, 1 << 20, None) == _lib.EUNSUPPORTED
+    sh192 = ck.make_shape(1, 2, 2, 192, 8, 32)        # the planner takes any multiple of 64, the kernels 64 and 128
+    p192 = ck.cocktail_plan(sh192, [16], [2, 4], 4)
+    cache.plan_host = p192.blob.ctypes.data
+    assert L.cocktail_decode_attention(C.byref(sh192), 16, C.byref(cache), 0.0, 16, None, 16, 1 << 20, None) == _lib.EUNSUPPORTED
+    assert L.cocktail_reorder_quantize(C.byref(sh192), 16, 16, 0, 0, 0, 192, C.byref(cache), None) == _lib.EUNSUPPORTED
     sh16 = ck.make_shape(1, 16, 1, 128, 8, 32)
     p16 = ck.cocktail_plan(sh16, [16], [2, 4], 4)
     cache.plan_host = p16.blob.ctypes.data
