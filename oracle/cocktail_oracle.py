@@ -333,12 +333,15 @@ def gather_pages(pages: np.ndarray, table_row: Sequence[int], seq_len: int) -> n
     return out
 
 
-def append_tokens(cache: OracleCache, k_new: np.ndarray, v_new: np.ndarray) -> None:
+def append_tokens(cache: OracleCache, k_new: np.ndarray, v_new: np.ndarray, active: Sequence[bool] = None) -> None:
     """Sec. III-A: one generated token per sequence joins the cache in FP16, behind everything else.
 
-    k_new, v_new: fp16 [B, Hkv, D].
+    k_new, v_new: fp16 [B, Hkv, D].  active: which sequences generated a token in this step (all by default);
+    the rows of the others are ignored, so sequences may stop generating at different steps.
     """
     for b in range(len(cache.seqs)):
+        if active is not None and not active[b]:
+            continue
         cache.app_k[b] = np.concatenate([cache.app_k[b], k_new[b][:, None, :].astype(np.float16)], axis=1)
         cache.app_v[b] = np.concatenate([cache.app_v[b], v_new[b][:, None, :].astype(np.float16)], axis=1)
 

@@ -598,6 +598,33 @@ def test_signed_zeros_do_not_reach_scale_or_zero():
         assert float(scale[0, 0]) == 1.0 and float(zero[0, 0]) == -3.0 and codes[0, :3].tolist() == [0, 3, 2]
 
 
+def test_sequences_that_stop_generating_at_different_steps_equal_single_sequence_runs():
+    # catches: a skipped sequence still receiving a row, rows of one sequence landing in another, a step miscounted
+    w = workloads.small("raggedgen", 3, 4, 2, [70, 33, 120], 16, 32, mix=(0.2, 0.4, 0.4), seed_offset=29)
+    ks, vs = _seqs(w)
+    bits = workloads.chunk_bits(w)
+    q = workloads.query(w, 0)
+    cache = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    singles = [O.reorder_quantize([ks[b]], [vs[b]], [bits[b]], w.chunk_size, w.group_size) for b in range(3)]
+    stops = [2, 0, 5]                                     # sequence 1 generates nothing, 0 stops after 2 tokens
+    for step in range(5):
+        kn, vn = _new_tokens(w, 100 + step)
+        active = [step < stops[b] for b in range(3)]
+        O.append_tokens(cache, kn, vn, active)
+        for b in range(3):
+            if active[b]:
+                O.append_tokens(singles[b], kn[b:b + 1], vn[b:b + 1])
+    assert [cache.app_k[b].shape[1] for b in range(3)] == stops
+    out, lse = O.decode_attention(q, cache)
+    for b in range(3):
+        o1, l1 = O.decode_attention(q[b:b + 1], singles[b])
+        np.testing.assert_array_equal(out[b], o1[0])
+        np.testing.assert_array_equal(lse[b], l1[0])
+        # and the single-sequence run is textbook attention over context + its own appended rows (all-FP16 check is
+        # test_appended_tokens_all_fp16_equal_textbook_attention_over_the_concatenation)
+    assert O.pack_append_buffer(cache, "k", 8).size == 3 * 2 * 64 * 256
+
+
 def test_page_gather_by_hand_and_round_trip():
     """gather_pages against a table typed out by hand, and as the inverse of a scatter into shuffled pages."""
     # 3 pages of 2 tokens, 1 head, D = 1: page p, slot s holds the value 10 p + s
