@@ -129,8 +129,12 @@ typedef struct cocktail_cache {
                                     (see cocktail_decode_attention)                                        */
   void* k_app;                   /* DEVICE append_bytes each, 256-byte aligned: K/V rows of the tokens     */
   void* v_app;                   /*        generated during decoding; NULL iff append_capacity == 0         */
-  int32_t num_appended;          /* tokens appended so far to every sequence, 0 .. append_capacity         */
+  int32_t num_appended;          /* tokens appended so far to every sequence, 0 .. append_capacity (batches
+                                    that generate in lockstep); 0 if appended_dev is used                  */
   int32_t reserved;
+  int32_t* appended_dev;         /* DEVICE int32 [B], or NULL: tokens appended so far per sequence, for batches
+                                    whose sequences stop generating at different steps; read by
+                                    cocktail_decode_attention, advanced by cocktail_append_fp16_ragged      */
 } cocktail_cache;
 
 /*
@@ -249,7 +253,8 @@ int cocktail_reorder_quantize_paged(const cocktail_shape* shape, const cocktail_
  * cocktail_plan_options::reproducible).  Shapes with Hq = Hkv run one query head per wave on the vector
  * ALU; 2 <= Hq/Hkv <= 8 run four query heads per wave on 4x4x4 matrix instructions (V in token quads).
  *
- *   cache      num_appended tokens of the append buffers are attended to after the context
+ *   cache      the appended tokens (num_appended of every sequence, or appended_dev[b] of sequence b) are
+ *              attended to after the context
  *   q          DEVICE fp16 [B][Hq][D], 16-byte aligned
  *   sm_scale   softmax scale; <= 0 selects 1/sqrt(D)
  *   out        DEVICE fp16 [B][Hq][D]; a sequence with no tokens yields zeros
@@ -312,6 +317,24 @@ int cocktail_decode_check(const cocktail_shape* shape, const cocktail_cache* cac
  */
 int cocktail_append_fp16(const cocktail_shape* shape, const void* k_new, const void* v_new,
                          const cocktail_cache* cache, int32_t position, void* stream);
+
+/*
+ * Sec. III-A for a batch whose sequences generate (and stop) independently: for every sequence b with
+ * active_dev[b] != 0 the K/V rows of its new token are stored as appended token cache->appended_dev[b] of that
+ * sequence, then appended_dev[b] is advanced by one; the rows of the other sequences are ignored.  A sequence
+ * whose append buffer is full (appended_dev[b] == append_capacity) is left as it is.  The following
+ * cocktail_decode_attention calls attend to the context and to the first appended_dev[b] appended tokens of
+ * every sequence.  Counts and flags live on the device, so a decode loop needs no host round trip.
+ *
+ *   k_new, v_new  DEVICE fp16 [B][Hkv][D], 16-byte aligned
+ *   cache         appended_dev must not be NULL (zero it before the first token; cocktail_reorder_quantize
+ *                 does not touch it)
+ *   active_dev    DEVICE uint8 [B], or NULL = every sequence
+ *
+ * Two kernel launches (store, then advance the counts).  Errors: EINVAL, EUNSUPPORTED, EALIGN, EHIP.
+ */
+int cocktail_append_fp16_ragged(const cocktail_shape* shape, const void* k_new, const void* v_new,
+                                const cocktail_cache* cache, const uint8_t* active_dev, void* stream);
 
 /*
  * Chunk-level quantization search (Sec. III-B): scores[i] = cosine similarity of sequence b's query

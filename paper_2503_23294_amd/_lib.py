@@ -42,7 +42,8 @@ class PlanOptions(C.Structure):
 
 class Cache(C.Structure):
     _fields_ = [("k", C.c_void_p * NUM_CLASSES), ("v", C.c_void_p * NUM_CLASSES), ("plan_host", C.c_void_p), ("plan_dev", C.c_void_p),
-                ("k_app", C.c_void_p), ("v_app", C.c_void_p), ("num_appended", C.c_int32), ("reserved", C.c_int32)]
+                ("k_app", C.c_void_p), ("v_app", C.c_void_p), ("num_appended", C.c_int32), ("reserved", C.c_int32),
+                ("appended_dev", C.c_void_p)]
 
 
 class PagedSource(C.Structure):
@@ -60,6 +61,8 @@ EXPORTS = {
                                    C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "cocktail_append_fp16": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.POINTER(Cache), C.c_int32,
                                        C.c_void_p]),
+    "cocktail_append_fp16_ragged": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.POINTER(Cache), C.c_void_p,
+                                              C.c_void_p]),
     "cocktail_chunk_bitwidths": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "cocktail_reorder_quantize": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,

@@ -100,6 +100,10 @@ class PackedCache:
         self.desc.k_app = self.k_app.data_ptr() if nb else None
         self.desc.v_app = self.v_app.data_ptr() if nb else None
         self.desc.num_appended = 0
+        # per-sequence counts of appended tokens, used once cocktail_append_fp16_ragged is called (NULL before:
+        # lockstep batches count in desc.num_appended)
+        self.appended = torch.zeros(plan.shape.batch, dtype=torch.int32, device=device) if nb else None
+        self.desc.appended_dev = None
         self.workspace = torch.empty(int(plan.sizes.workspace_bytes), dtype=torch.uint8, device=device)
 
 
@@ -172,6 +176,28 @@ def cocktail_append_fp16(cache: PackedCache, k_new: torch.Tensor, v_new: torch.T
     check(lib().cocktail_append_fp16(C.byref(sh), k_new.data_ptr(), v_new.data_ptr(), C.byref(cache.desc), pos,
                                      _stream_ptr(stream)))
     cache.desc.num_appended = max(int(cache.desc.num_appended), pos + 1)
+
+
+def cocktail_append_fp16_ragged(cache: PackedCache, k_new: torch.Tensor, v_new: torch.Tensor,
+                                active: Optional[torch.Tensor] = None,
+                                stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Stores one generated token for every sequence with active[b] != 0 (device uint8 [B]; None = all) behind
+    what that sequence has appended so far and advances its count (cache.appended, on the device)."""
+    sh = cache.plan.shape
+    for t in (k_new, v_new):
+        if t.dtype != torch.float16 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError("k_new and v_new must be contiguous float16 device tensors")
+        if tuple(t.shape) != (sh.batch, sh.num_kv_heads, sh.head_dim):
+            raise ValueError("k_new and v_new must have shape [B, Hkv, D]")
+    if active is not None and (active.dtype != torch.uint8 or not active.is_cuda or tuple(active.shape) != (sh.batch,)):
+        raise TypeError("active must be a uint8 device tensor [B]")
+    if cache.appended is None:
+        raise ValueError("the plan was made without append buffers")
+    if int(cache.desc.num_appended) != 0:
+        raise ValueError("this cache counts appended tokens in lockstep (cocktail_append_fp16); do not mix the two")
+    cache.desc.appended_dev = cache.appended.data_ptr()
+    check(lib().cocktail_append_fp16_ragged(C.byref(sh), k_new.data_ptr(), v_new.data_ptr(), C.byref(cache.desc),
+                                            active.data_ptr() if active is not None else None, _stream_ptr(stream)))
 
 
 def cocktail_decode_attention(cache: PackedCache, q: torch.Tensor, sm_scale: float = 0.0,

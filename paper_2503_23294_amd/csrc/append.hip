@@ -13,11 +13,21 @@ namespace cocktail {
 __global__ __launch_bounds__(256) void append_fp16_kernel(const u32x4* __restrict__ k_new,
                                                            const u32x4* __restrict__ v_new, char* __restrict__ k_app,
                                                            char* __restrict__ v_app, int position, int app_blocks,
-                                                           int num_bh, int v_quads, int head_dim) {
+                                                           int num_bh, int v_quads, int head_dim,
+                                                           const int32_t* __restrict__ appended,
+                                                           const uint8_t* __restrict__ active, int num_kv_heads,
+                                                           int capacity) {
   const int kPieces = 2 * head_dim / 16;       // 16-byte pieces of one fp16 row
   const int idx = blockIdx.x * 256 + threadIdx.x;
   if (idx >= num_bh * kPieces) return;
   const int bh = idx / kPieces, p = idx % kPieces;
+  if (appended) {
+    // per-sequence positions: the token goes behind what the sequence has appended so far
+    const int b = bh / num_kv_heads;
+    if (active && !active[b]) return;
+    position = appended[b];
+    if (position < 0 || position >= capacity) return;   // the append buffer of this sequence is full
+  }
   const u32x4* src = blockIdx.y ? v_new : k_new;
   char* dst = blockIdx.y ? v_app : k_app;
   const size_t block = size_t(bh) * app_blocks + position / kTB;
@@ -37,12 +47,23 @@ __global__ __launch_bounds__(256) void append_fp16_kernel(const u32x4* __restric
   *reinterpret_cast<u32x4*>(blk + (size_t(p) * kTB + position % kTB) * 16) = v;
 }
 
+// After the rows are stored: appended[b] += 1 for every active sequence that had room.
+__global__ __launch_bounds__(256) void advance_appended_kernel(int32_t* __restrict__ appended,
+                                                                const uint8_t* __restrict__ active, int batch, int capacity) {
+  for (int b = blockIdx.x * 256 + threadIdx.x; b < batch; b += gridDim.x * 256) {
+    const int n = appended[b];
+    if ((!active || active[b]) && n >= 0 && n < capacity) appended[b] = n + 1;
+  }
+}
+
 }  // namespace cocktail
 
 using namespace cocktail;
 
-extern "C" int cocktail_append_fp16(const cocktail_shape* shape, const void* k_new, const void* v_new,
-                                    const cocktail_cache* cache, int32_t position, void* stream) {
+namespace {
+
+int check_append(const cocktail_shape* shape, const void* k_new, const void* v_new, const cocktail_cache* cache,
+                 const PlanHeader** out) {
   if (int rc = check_shape(shape)) return rc;
   if (!cache || !cache->plan_host) return fail(COCKTAIL_EINVAL, "cache or its plan is NULL");
   const PlanHeader* hd = static_cast<const PlanHeader*>(cache->plan_host);
@@ -55,19 +76,50 @@ extern "C" int cocktail_append_fp16(const cocktail_shape* shape, const void* k_n
   if (shape->head_dim != 64 && shape->head_dim != 128)
     return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 64 and 128, got %d", shape->head_dim);
   if (hd->append_capacity <= 0) return fail(COCKTAIL_EINVAL, "the plan was made without append buffers");
-  if (position < 0 || position >= hd->append_capacity)
-    return fail(COCKTAIL_EINVAL, "position %d outside the append capacity %d", position, hd->append_capacity);
   if (!k_new || !v_new || !cache->k_app || !cache->v_app)
     return fail(COCKTAIL_EINVAL, "k_new, v_new and the append buffers must not be NULL");
   if ((reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new) |
        reinterpret_cast<uintptr_t>(cache->k_app) | reinterpret_cast<uintptr_t>(cache->v_app)) & 15)
     return fail(COCKTAIL_EALIGN, "k_new, v_new and the append buffers must be 16-byte aligned");
+  *out = hd;
+  return COCKTAIL_OK;
+}
+
+}  // namespace
+
+extern "C" int cocktail_append_fp16_ragged(const cocktail_shape* shape, const void* k_new, const void* v_new,
+                                           const cocktail_cache* cache, const uint8_t* active_dev, void* stream) {
+  const PlanHeader* hd = nullptr;
+  if (int rc = check_append(shape, k_new, v_new, cache, &hd)) return rc;
+  if (!cache->appended_dev) return fail(COCKTAIL_EINVAL, "appended_dev is NULL: the per-sequence counts live there");
+  if (reinterpret_cast<uintptr_t>(cache->appended_dev) & 3) return fail(COCKTAIL_EALIGN, "appended_dev must be 4-byte aligned");
+  const int num_bh = hd->batch * hd->num_kv_heads;
+  const dim3 grid((num_bh * (shape->head_dim / 8) + 255) / 256, 2, 1);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(append_fp16_kernel, grid, dim3(256), 0, st, static_cast<const u32x4*>(k_new),
+                     static_cast<const u32x4*>(v_new), static_cast<char*>(cache->k_app), static_cast<char*>(cache->v_app), 0,
+                     hd->append_blocks, num_bh, hd->v_layout, shape->head_dim, cache->appended_dev, active_dev,
+                     hd->num_kv_heads, hd->append_capacity);
+  hipLaunchKernelGGL(advance_appended_kernel, dim3((hd->batch + 255) / 256 < 64 ? (hd->batch + 255) / 256 : 64), dim3(256), 0, st,
+                     cache->appended_dev, active_dev, hd->batch, hd->append_capacity);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(COCKTAIL_EHIP, "append launch failed: %s", hipGetErrorString(e));
+  return COCKTAIL_OK;
+}
+
+extern "C" int cocktail_append_fp16(const cocktail_shape* shape, const void* k_new, const void* v_new,
+                                    const cocktail_cache* cache, int32_t position, void* stream) {
+  const PlanHeader* hd = nullptr;
+  if (int rc = check_append(shape, k_new, v_new, cache, &hd)) return rc;
+  if (position < 0 || position >= hd->append_capacity)
+    return fail(COCKTAIL_EINVAL, "position %d outside the append capacity %d", position, hd->append_capacity);
   const int num_bh = hd->batch * hd->num_kv_heads;
   const dim3 grid((num_bh * (shape->head_dim / 8) + 255) / 256, 2, 1);
   hipLaunchKernelGGL(append_fp16_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(k_new), static_cast<const u32x4*>(v_new),
                      static_cast<char*>(cache->k_app), static_cast<char*>(cache->v_app), position, hd->append_blocks,
-                     num_bh, hd->v_layout, shape->head_dim);
+                     num_bh, hd->v_layout, shape->head_dim, static_cast<const int32_t*>(nullptr),
+                     static_cast<const uint8_t*>(nullptr), hd->num_kv_heads, hd->append_capacity);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(COCKTAIL_EHIP, "append launch failed: %s", hipGetErrorString(e));
   return COCKTAIL_OK;

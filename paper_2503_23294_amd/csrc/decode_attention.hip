@@ -46,7 +46,8 @@ __global__ __launch_bounds__(D / 4 * kMergeSlices) void decode_merge_kernel(Deco
   const int r = hq % rep;
   const int lo = prm.bh_off[bh];
   const int n = prm.bh_off[bh + 1] - lo;
-  const int expected = prm.seq_len[b] + prm.num_appended;
+  const int appended = prm.appended ? prm.appended[b] : prm.num_appended;
+  const int expected = prm.seq_len[b] + min(max(appended, 0), prm.app_capacity);
   const int tid = threadIdx.x;
   // every worker has drawn its last ticket: put the counters back to zero for the next call
   if (blockIdx.x == 0)
@@ -198,16 +199,22 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
   p.num_workers = hd->num_workers;
   p.k_app = p.v_app = nullptr;
   p.num_appended = 0, p.app_blocks = hd->append_blocks;
+  p.appended = nullptr, p.app_capacity = hd->append_capacity, p.app_slices = hd->append_slices;
   if (hd->append_capacity > 0) {
     if (!cache->k_app || !cache->v_app) return fail(COCKTAIL_EINVAL, "the plan has append buffers but k_app or v_app is NULL");
     if ((reinterpret_cast<uintptr_t>(cache->k_app) | reinterpret_cast<uintptr_t>(cache->v_app)) & 15)
       return fail(COCKTAIL_EALIGN, "append buffers must be 16-byte aligned");
     if (cache->num_appended < 0 || cache->num_appended > hd->append_capacity)
       return fail(COCKTAIL_EINVAL, "num_appended %d outside [0, %d]", cache->num_appended, hd->append_capacity);
+    if (cache->appended_dev && (reinterpret_cast<uintptr_t>(cache->appended_dev) & 3))
+      return fail(COCKTAIL_EALIGN, "appended_dev must be 4-byte aligned");
+    if (cache->appended_dev && cache->num_appended != 0)
+      return fail(COCKTAIL_EINVAL, "num_appended must be 0 when appended_dev holds the per-sequence counts");
     p.k_app = static_cast<const char*>(cache->k_app), p.v_app = static_cast<const char*>(cache->v_app);
     p.num_appended = cache->num_appended;
-  } else if (cache->num_appended != 0) {
-    return fail(COCKTAIL_EINVAL, "num_appended is %d but the plan was made without append buffers", cache->num_appended);
+    p.appended = cache->appended_dev;
+  } else if (cache->num_appended != 0 || cache->appended_dev) {
+    return fail(COCKTAIL_EINVAL, "num_appended / appended_dev are set but the plan was made without append buffers");
   }
   p.bh_off = reinterpret_cast<const int32_t*>(pd + hd->off_bh_off);
   p.q = static_cast<const uint32_t*>(q);
@@ -231,10 +238,10 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
   p.trace = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + ((hd->workspace_bytes + 255) & ~int64_t(255)));
 #endif
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int app_groups = hd->append_capacity > 0 ? hd->batch * hd->num_kv_heads : 0;
+  const int app_groups = hd->batch * hd->num_kv_heads * hd->append_slices;   // 0 without append buffers
   if (hd->total_gblocks > 0 || app_groups > 0) {
     const bool quads = hd->v_layout == COCKTAIL_V_TOKEN_QUADS;
-    const dim3 grid(hd->num_workers + app_groups, 1, 1), block(64, 1, 1);
+    const dim3 grid(hd->num_workers + app_groups, 1, 1);
     // non-temporal K/V loads when nothing is read twice: one wave per workgroup, and a cache large enough
     // that it cannot stay in the memory-side cache from one call to the next
     static const int nt_override = [] {   // tuning aid, read once: COCKTAIL_NON_TEMPORAL=0 | 1

@@ -46,8 +46,10 @@ struct DecodeParams {
   float* lse;               // [B][Hq] or NULL
   float scale_log2;         // sm_scale * log2(e)
   int32_t rep, num_q_heads, num_kv_heads, num_groups;
-  int32_t num_workers;      // workgroups behind these serve the appended tokens, one per (sequence, kv head)
-  int32_t num_appended, app_blocks;
+  int32_t num_workers;      // workgroups behind these serve the appended tokens, app_slices per (sequence, kv head)
+  int32_t num_appended, app_blocks;   // tokens appended to every sequence (used if `appended` is NULL), blocks per (b, kv head)
+  const int32_t* appended;  // [B] tokens appended per sequence, or NULL
+  int32_t app_capacity, app_slices;   // tokens per sequence the append buffers hold; workgroups per (b, kv head) for them
 #ifdef COCKTAIL_TRACE
   uint64_t* trace;          // [num_workers][4]: start, end (100 MHz ticks), hw id, xcc id
 #endif
@@ -437,6 +439,32 @@ struct Stream {
     return d;
   }
 };
+
+// Tokens appended to sequence b so far (never more than the append buffers hold).
+__device__ __forceinline__ int appended_count(int b) {
+  kparams_t kp = kparams();
+  const int n = kp->appended ? kp->appended[b] : kp->num_appended;
+  return min(max(n, 0), kp->app_capacity);
+}
+
+// The part of an append run that workgroup `idx` behind the regular workers attends to.
+struct AppendSlice {
+  int bh, tokens, first_block, blocks, qrow, pid;
+};
+__device__ __forceinline__ AppendSlice append_slice(int idx) {
+  kparams_t kp = kparams();
+  AppendSlice a;
+  const int slices = kp->app_slices, sl = idx % slices;
+  a.bh = idx / slices;
+  const int b = a.bh / kp->num_kv_heads;
+  const int first = sl * kAppendSliceBlocks;
+  a.tokens = uni(min(max(appended_count(b) - first * kTB, 0), kAppendSliceBlocks * kTB));
+  a.blocks = min(kAppendSliceBlocks, kp->app_blocks - first);
+  a.first_block = a.bh * kp->app_blocks + first;
+  a.qrow = b * kp->num_q_heads + (a.bh % kp->num_kv_heads) * kp->rep;
+  a.pid = uni(kp->bh_off[a.bh + 1]) - slices + sl;
+  return a;
+}
 
 // The neutral partial state (weight zero in the merge) for a slot nobody had tokens for.
 template <int HD>

@@ -229,21 +229,18 @@ __device__ __forceinline__ void run_class(Stream<HD>& sm, Piece& cur, float* red
   cur = nxt;
 }
 
-// Workgroups behind the regular workers: workgroup num_workers + bh attends to the tokens appended to
-// (sequence, kv head) bh during decoding (Sec. III-A), an FP16 run of num_appended tokens in the
-// append buffers, and writes the last partial of bh's range.
+// Workgroups behind the regular workers attend to the tokens appended during decoding (Sec. III-A): FP16 runs in
+// the append buffers, one workgroup per slice of a (sequence, kv head)'s run, each writing one of the last
+// partials of that head's range.
 template <int HD, int G, int AUX>
-__device__ __forceinline__ void appended_tokens(int bh, float* red, int r, int lane) {
-  kparams_t kp = kparams();
-  const int n = kp->num_appended;
-  const int pid = uni(kp->bh_off[bh + 1]) - 1;
-  if (n <= 0) {
-    write_neutral<HD>(pid, r, lane);
+__device__ __forceinline__ void appended_tokens(int idx, float* red, int r, int lane) {
+  const AppendSlice a = append_slice(idx);
+  if (a.tokens <= 0) {
+    write_neutral<HD>(a.pid, r, lane);
     return;
   }
   Stream<HD> sm;
-  sm.init_run(kFp16Class, n, bh * kp->app_blocks, kp->app_blocks,
-              (bh / kp->num_kv_heads) * kp->num_q_heads + (bh % kp->num_kv_heads) * kp->rep, pid);
+  sm.init_run(kFp16Class, a.tokens, a.first_block, a.blocks, a.qrow, a.pid);
   Piece cur = sm.next(lane);
   if (cur.nu > 0) run_class<HD, HalfClass<HD, G>, kFp16Class, G, AUX>(sm, cur, red, r, lane, true);
 }

@@ -433,17 +433,14 @@ __device__ __forceinline__ void write_neutral_heads(int slot, int r, int lane) {
 }
 
 template <int HD, int G, int AUX>
-__device__ __forceinline__ void appended_tokens_quads(int bh, float* red, int r, int lane) {
-  kparams_t kp = kparams();
-  const int n = kp->num_appended;
-  const int pid = uni(kp->bh_off[bh + 1]) - 1;
-  if (n <= 0) {
-    write_neutral_heads<HD>(pid, r, lane);
+__device__ __forceinline__ void appended_tokens_quads(int idx, float* red, int r, int lane) {
+  const AppendSlice a = append_slice(idx);
+  if (a.tokens <= 0) {
+    write_neutral_heads<HD>(a.pid, r, lane);
     return;
   }
   Stream<HD> sm;
-  sm.init_run(kFp16Class, n, bh * kp->app_blocks, kp->app_blocks,
-              (bh / kp->num_kv_heads) * kp->num_q_heads + (bh % kp->num_kv_heads) * kp->rep, pid);
+  sm.init_run(kFp16Class, a.tokens, a.first_block, a.blocks, a.qrow, a.pid);
   Piece cur = sm.next(lane);
   if (cur.nu > 0) run_quads<HD, QuadHalf<HD, G>, kFp16Class, G, AUX>(sm, cur, red, r, lane, true);
 }

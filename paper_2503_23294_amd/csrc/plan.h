@@ -10,7 +10,7 @@
 namespace cocktail {
 
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
-constexpr uint32_t kPlanVersion = 12;
+constexpr uint32_t kPlanVersion = 13;
 constexpr int kTB = 64;                        // tokens per block
 constexpr int kNumClasses = 4;                 // INT2, INT4, INT8, FP16: the order of the concatenation
 constexpr int kFp16Class = kNumClasses - 1;
@@ -31,6 +31,9 @@ constexpr int kPartialFloats = 4;              // (m, l, tokens covered as int32
 #endif
 constexpr int kIterUnits[kNumClasses] = {COCKTAIL_J2, COCKTAIL_J4, COCKTAIL_J8, COCKTAIL_J16};
 constexpr int kMaxPoolSegments = 32;           // segments one pool may touch (a worker tracks them in a bit mask)
+// The appended tokens of a (sequence, kv head) are attended to by one extra workgroup per this many 64-token
+// blocks of append capacity (one partial state each), so a long generation does not hang on a single wave.
+constexpr int kAppendSliceBlocks = 8;
 constexpr int kCounterStride = 32;             // uint32 slots between two pool counters (one 128-byte line each)
 // Query heads per kv head for which a wave serves four of them at a time with matrix instructions and V is
 // stored in token quads: 2 to 4 heads take one wave per workgroup, 5 to 8 two waves (one per head quad).
@@ -134,9 +137,9 @@ struct PlanHeader {
   int32_t num_groups, num_pool_segs;
   int32_t append_blocks;      // blocks per (sequence, kv head) in the append buffers
   int32_t off_bh_off;         // int32 [B*Hkv + 1] prefix: (b, kv head) owns partial ids bh_off[bh] .. bh_off[bh+1]-1;
-                              // with append buffers the last id of each range is that of the appended tokens
+                              // with append buffers the last append_slices ids of each range are those of the appended tokens
   int32_t off_rq_items;       // RQItem [sum of class_blocks]
-  int32_t pad0;
+  int32_t append_slices;      // workgroups (and partial ids) per (sequence, kv head) for the appended tokens
   int64_t ws_status_off;      // byte offset, inside the decode workspace, of int32 [B * Hq]: per (sequence, query
                               // head) tokens covered by the last call's partial states minus tokens of the sequence
                               // (0 = every token was attended to exactly once)

@@ -146,7 +146,7 @@ extern "C" int cocktail_plan_field(const void* plan_host, const char* name, int3
   COCKTAIL_FIELD(off_nblk) COCKTAIL_FIELD(off_segments) COCKTAIL_FIELD(append_capacity)
   COCKTAIL_FIELD(off_worker_rec) COCKTAIL_FIELD(off_group_rec) COCKTAIL_FIELD(off_pool_seg)
   COCKTAIL_FIELD(off_counters) COCKTAIL_FIELD(num_groups) COCKTAIL_FIELD(num_pool_segs)
-  COCKTAIL_FIELD(append_blocks) COCKTAIL_FIELD(off_bh_off) COCKTAIL_FIELD(off_rq_items)
+  COCKTAIL_FIELD(append_blocks) COCKTAIL_FIELD(append_slices) COCKTAIL_FIELD(off_bh_off) COCKTAIL_FIELD(off_rq_items)
   COCKTAIL_FIELD(ws_status_off)
 #undef COCKTAIL_FIELD
 #undef COCKTAIL_ARRAY
@@ -514,8 +514,10 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
       ps.nslots = n;
       bh_off[bh_of(segs[ps.seg]) + 1] += n;
     }
-  if (append_capacity > 0)   // one more partial per (b, kv head): the appended tokens; it is the last of its range
-    for (int i = 0; i < BH; ++i) ++bh_off[i + 1];
+  // the appended tokens: one more partial per slice of the append buffer of a (b, kv head), at the end of its range
+  const int append_blocks = (append_capacity + kTB - 1) / kTB;
+  const int append_slices = (append_blocks + kAppendSliceBlocks - 1) / kAppendSliceBlocks;
+  for (int i = 0; i < BH; ++i) bh_off[i + 1] += append_slices;
   for (int i = 0; i < BH; ++i) bh_off[i + 1] += bh_off[i];
   const int32_t npart = bh_off[BH];
   {
@@ -587,7 +589,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   hd.chunk_size = C, hd.group_size = G, hd.rep = rep;
   hd.num_workers = P, hd.num_segments = S, hd.num_partials = npart;
   hd.num_groups = NG, hd.num_pool_segs = NPS;
-  hd.append_capacity = append_capacity, hd.append_blocks = (append_capacity + kTB - 1) / kTB;
+  hd.append_capacity = append_capacity, hd.append_blocks = append_blocks, hd.append_slices = append_slices;
   hd.total_gblocks = static_cast<int32_t>(gblk);
   hd.v_layout = quads ? 1 : 0;
   hd.total_chunks = total_chunks, hd.total_tokens = total_tokens, hd.packed_bytes = packed;

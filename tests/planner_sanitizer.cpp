@@ -182,10 +182,12 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
     }
   }
   for (int64_t i = 0; i < UPB * g; ++i) REQUIRE(unit_seen[i] == 1);
-  if (opt.append_capacity > 0)   // the last partial of every (sequence, kv head) belongs to the appended tokens
-    for (int bh = 0; bh < BH; ++bh) {
-      REQUIRE(bh_off[bh + 1] - 1 >= bh_off[bh] && !pid_seen[bh_off[bh + 1] - 1]);
-      pid_seen[bh_off[bh + 1] - 1] = 1;
+  // the last partials of every (sequence, kv head) belong to the appended tokens, one per slice of the append buffer
+  REQUIRE(hd.append_slices == (hd.append_blocks + kAppendSliceBlocks - 1) / kAppendSliceBlocks);
+  for (int bh = 0; bh < BH; ++bh)
+    for (int sl = 1; sl <= hd.append_slices; ++sl) {
+      REQUIRE(bh_off[bh + 1] - sl >= bh_off[bh] && !pid_seen[bh_off[bh + 1] - sl]);
+      pid_seen[bh_off[bh + 1] - sl] = 1;
     }
   for (int i = 0; i < hd.num_partials; ++i) REQUIRE(pid_seen[i] == 1);
   REQUIRE(bh_off[0] == 0 && bh_off[BH] == hd.num_partials);
@@ -253,7 +255,7 @@ int main(int argc, char** argv) {
     const int workers = pick({1, 2, 3, 5, 8, 16, 33, 64, 200, 2048});
     cocktail_plan_options opt;
     std::memset(&opt, 0, sizeof(opt));
-    opt.append_capacity = pick({0, 0, 1, 64, 130});
+    opt.append_capacity = pick({0, 0, 1, 64, 130, 1500});
     opt.reproducible = int(rng() % 4 == 0);
     check_plan(sh, lens, bits, workers, opt, rng);
   }

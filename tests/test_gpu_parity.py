@@ -412,6 +412,62 @@ def test_appended_decode_tokens(rep, capacity, steps, head_dim):
             ck.cocktail_append_fp16(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
 
 
+@pytest.mark.parametrize("rep,head_dim,stops", [(1, 128, [40, 0, 700]), (4, 128, [3, 130, 66]), (4, 64, [700, 1, 64]),
+                                                (8, 128, [5, 70, 0])])
+def test_sequences_that_stop_generating_at_different_steps(rep, head_dim, stops):
+    """Sec. III-A in a batch whose sequences generate independently: per-sequence counts on the device, a step
+    appends a token to the active sequences only; long runs of appended tokens are shared by several workgroups."""
+    w = workloads.small(f"raggedgen_r{rep}_d{head_dim}", 3, 2 * rep, 2, [64 * 9 + 5, 300, 1000], 64, 32,
+                        mix=(0.2, 0.4, 0.4), head_dim=head_dim, seed_offset=260 + rep)
+    _announce(f"{w.name} stops={stops}")
+    dev = _dev()
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = workloads.chunk_bits(w)
+    capacity = max(stops)
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), 12, append_capacity=capacity)
+    assert ck.cocktail_plan_field(plan, "append_slices") == -(-(-(-capacity // 64)) // 8)
+    cache = ck.PackedCache(plan, dev)
+    k, v = workloads.kv_flat(w, 0)
+    ck.cocktail_reorder_quantize(cache, torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev), ragged=True)
+    ks, vs = [], []
+    for b in range(w.batch):
+        kh, vh = zip(*[workloads.kv_head(w, 0, b, h) for h in range(w.num_kv_heads)])
+        ks.append(np.stack(kh)), vs.append(np.stack(vh))
+    oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    q = workloads.query(w, 0)
+    q_dev = torch.from_numpy(q).to(dev)
+    rng = np.random.default_rng([workloads.BASE_SEED, 4343, rep])
+
+    def compare():
+        out, lse = ck.cocktail_decode_attention(cache, q_dev)
+        ck.cocktail_decode_check(cache)
+        ref, rl = O.decode_attention(q, oc)
+        got = out.cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref).max(axis=2) / np.abs(ref).max(axis=2)
+        assert err.max() <= TOL, f"appended {cache.appended.tolist()}: max rel err {err.max():.3e}"
+        assert np.abs(lse.cpu().numpy() - rl).max() <= 1e-4 * max(1.0, np.abs(rl).max())
+
+    for step in range(capacity + 2):                        # two steps past the end: nobody is active, nothing changes
+        active = np.array([step < s for s in stops], dtype=np.uint8)
+        kn = rng.standard_normal((w.batch, w.num_kv_heads, w.head_dim), dtype=np.float32).astype(np.float16)
+        vn = rng.standard_normal((w.batch, w.num_kv_heads, w.head_dim), dtype=np.float32).astype(np.float16)
+        kn[:, :, 3] *= np.float16(6.0)
+        ck.cocktail_append_fp16_ragged(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev),
+                                       torch.from_numpy(active).to(dev))
+        O.append_tokens(oc, kn, vn, active)
+        if step in (0, 1, 2, 63, 64, 65, 129, 511, 512, capacity - 1, capacity + 1):
+            compare()
+    assert cache.appended.cpu().tolist() == stops
+    v_quads = 2 <= rep <= 8
+    for which, buf in (("k", cache.k_app), ("v", cache.v_app)):      # append buffers bit-exact, unused rows zero
+        assert np.array_equal(buf.cpu().numpy(), O.pack_append_buffer(oc, which, capacity, v_quads=v_quads))
+    # a full sequence stays as it is when it is asked to take another token
+    ck.cocktail_append_fp16_ragged(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
+    torch.cuda.synchronize()
+    full = [min(s + 1, capacity) for s in stops]
+    assert cache.appended.cpu().tolist() == full
+
+
 @pytest.mark.parametrize("alpha,beta", [(0.6, 0.1), (0.0, 0.0), (0.3, 0.5), (1.0, 1.0)])
 def test_chunk_level_quantization_search(alpha, beta):
     """Sec. III-B: scores and bitwidths of every chunk, bit for bit (the arithmetic is fixed on both sides)."""
