@@ -90,7 +90,7 @@ def measured_traffic(workload_name):
     return None, None
 
 
-def run_config(cfg, steps, warmup, ntok, workers_arg, decode_only, cpu_heads, calibrate_copy=False):
+def run_config(cfg, steps, warmup, ntok, workers_arg, decode_only, cpu_heads, calibrate_copy=False, vector_alu_only=False):
     """Times one benchmark configuration; returns (entry for the `configs` array, details for the headline)."""
     import torch
     import paper_2503_23294_amd as ck
@@ -100,8 +100,8 @@ def run_config(cfg, steps, warmup, ntok, workers_arg, decode_only, cpu_heads, ca
     w = workloads.config(cfg)
     shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
     bits = workloads.chunk_bits(w)
-    workers = workers_arg or ck.cocktail_default_workers(shape)
-    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), workers)
+    workers = workers_arg or ck.cocktail_default_workers(shape, vector_alu_only)
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), workers, vector_alu_only=vector_alu_only)
     packed = int(plan.sizes.packed_bytes)
     # enough cache copies that a call never finds its data in the 256 MB last-level cache
     ncopies = min(max(2, -(-MIN_ROTATION_BYTES // max(packed, 1))), 64)
@@ -186,6 +186,8 @@ def run_config(cfg, steps, warmup, ntok, workers_arg, decode_only, cpu_heads, ca
         "reorder_quantize_bytes": rq_bytes,
         "reorder_quantize_gbps": None if decode_only else rq_bytes / (float(rq_us.mean()) * 1e-6) / 1e9,
         "kernel": "decode_quads_kernel" if int(plan.sizes.v_layout) == 1 else "decode_attention_kernel",
+        "kernel_family": "four query heads per wave on 4x4x4 matrix instructions" if int(plan.sizes.v_layout) == 1
+                         else "one query head per wave on the vector ALU (no matrix instructions)",
         "cache_copies": ncopies, "distinct_layers": len(src), "steps": steps, "decode_calls_per_step": ntok,
     }
     base = None
@@ -311,6 +313,8 @@ def main():
     ap.add_argument("--tokens-per-step", type=int, default=128, help="decode calls per step (output tokens per request)")
     ap.add_argument("--other-configs", type=int, default=1,
                     help="1 = also run a short pass over the other four configurations (the `configs` array)")
+    ap.add_argument("--vector-alu-only", action="store_true",
+                    help="plan grouped-query shapes for the kernel without matrix instructions (one query head per wave)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device copy, the known-size kernel that scales the HBM traffic counters")
     args = ap.parse_args()
@@ -323,7 +327,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     ntok = max(1, args.tokens_per_step)
     head, d = run_config(args.config, args.steps, args.warmup, ntok, args.workers, args.decode_only, args.cpu_heads,
-                         args.calibrate_copy)
+                         args.calibrate_copy, args.vector_alu_only)
     w, plan = d["w"], d["plan"]
     stream_gbps = stream_read_ceiling(d["decode_bytes"])
     traffic, traffic_source = measured_traffic(w.name)
@@ -335,6 +339,12 @@ def main():
                 continue
             entry, _ = run_config(cfg, steps=6, warmup=2, ntok=64, workers_arg=args.workers, decode_only=False, cpu_heads=2)
             entry["frac_of_stream_read"] = entry["gbps"] / stream_gbps
+            if entry["kernel"] == "decode_quads_kernel":
+                # the same shape on the kernel without matrix instructions (one query head per wave), for reference
+                alt, _ = run_config(cfg, steps=3, warmup=1, ntok=32, workers_arg=args.workers, decode_only=True, cpu_heads=1,
+                                    vector_alu_only=True)
+                entry["vector_alu_only"] = {"decode_us": alt["decode_us"], "frac_of_hbm_peak": alt["frac_of_hbm_peak"],
+                                            "parity_max_rel_err": alt["parity_max_rel_err"]}
             configs.append(entry)
         configs.sort(key=lambda e: e["workload"])
     head["frac_of_stream_read"] = gbps / stream_gbps

@@ -44,7 +44,7 @@
  *   Tokens past n_{b,c} in the last block of a head are zero bytes.
  *   (At head_dim 64 a row is half as long, everything else is the same; group_size is then 32 or 64.)
  *   V in token quads (cocktail_sizes::v_layout == COCKTAIL_V_TOKEN_QUADS; chosen
- *   when 2 <= Hq/Hkv <= 8, where a wave serves four query heads of a kv head
+ *   wherever the matrix kernel runs (Hq/Hkv >= 2 unless the plan is vector-ALU-only or Hq/Hkv > 8 is prime), where a wave serves four query heads of a kv head
  *   with matrix instructions and needs four tokens of a channel side by side):
  *   same block size, piece addressing and meta as above, but the 16-byte piece at
  *   slot sl no longer holds one token.  With n = 16/bits values per half-word,
@@ -75,7 +75,7 @@ extern "C" {
 
 #define COCKTAIL_NUM_CLASSES 4
 #define COCKTAIL_TOKENS_PER_BLOCK 64
-#define COCKTAIL_MAX_Q_PER_KV 8
+#define COCKTAIL_MAX_Q_PER_KV 64
 #define COCKTAIL_V_ROWS 0
 #define COCKTAIL_V_TOKEN_QUADS 1
 
@@ -171,7 +171,10 @@ typedef struct cocktail_plan_options {
                               (b, h, block).                                                                  */
   int32_t reproducible;    /* != 0: purely static split of the decode work (no shared pools): calls on the same
                               inputs then agree bit for bit, at some cost in speed                            */
-  int32_t reserved[6];     /* must be zero                                                                    */
+  int32_t vector_alu_only; /* != 0: grouped-query shapes are planned for the kernel that runs one query head per wave
+                              on the vector ALU alone (no matrix instructions, V in token rows); every query head
+                              then reads the blocks of its kv head by itself                                    */
+  int32_t reserved[5];     /* must be zero                                                                    */
 } cocktail_plan_options;
 
 /* cocktail_plan with options (NULL = defaults = cocktail_plan). */
@@ -251,7 +254,10 @@ int cocktail_reorder_quantize_paged(const cocktail_shape* shape, const cocktail_
  * two calls on the same inputs agree to fp32 summation order, not bit for bit
  * (shapes with Hq/Hkv > 4 use no pools and are reproducible bit for bit, and so is any plan made with
  * cocktail_plan_options::reproducible).  Shapes with Hq = Hkv run one query head per wave on the vector
- * ALU; 2 <= Hq/Hkv <= 8 run four query heads per wave on 4x4x4 matrix instructions (V in token quads).
+ * ALU; 2 <= Hq/Hkv <= 8 run four query heads per wave on 4x4x4 matrix instructions (V in token quads), unless
+ * the plan asks for the vector ALU only; for larger ratios (up to COCKTAIL_MAX_Q_PER_KV) the query heads of a kv
+ * head are cut into equal sets of up to 8 that each read the kv head's blocks (one head per wave if no such set size
+ * divides the ratio).
  *
  *   cache      the appended tokens (num_appended of every sequence, or appended_dev[b] of sequence b) are
  *              attended to after the context
@@ -359,8 +365,8 @@ int cocktail_chunk_bitwidths(int32_t batch, int32_t embed_dim, int32_t total_chu
 
 /*
  * Number of decode workgroups that fills the current HIP device for this shape
- * (compute units x resident waves per unit / waves per workgroup; a workgroup is one wave up to
- * Hq/Hkv = 4 and two waves up to 8).  Needs a GPU: EHIP otherwise.
+ * (compute units x resident waves per unit / waves per workgroup; a workgroup is two waves for
+ * 5 <= Hq/Hkv <= 8 and one wave otherwise).  Needs a GPU: EHIP otherwise.
  */
 int cocktail_default_workers(const cocktail_shape* shape, int32_t* num_workers);
 

@@ -16,7 +16,7 @@ LIB_PATH = os.environ.get("COCKTAIL_LIB", os.path.join(HERE, "libcocktail.so"))
 
 NUM_CLASSES = 4
 TOKENS_PER_BLOCK = 64
-MAX_Q_PER_KV = 8
+MAX_Q_PER_KV = 64
 STATIC_WORKSPACE_BYTES = 16 << 20
 
 OK, EINVAL, EUNSUPPORTED, EALIGN, ENOSPACE, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
@@ -37,7 +37,8 @@ class Sizes(C.Structure):
 
 
 class PlanOptions(C.Structure):
-    _fields_ = [("append_capacity", C.c_int32), ("reproducible", C.c_int32), ("reserved", C.c_int32 * 6)]
+    _fields_ = [("append_capacity", C.c_int32), ("reproducible", C.c_int32), ("vector_alu_only", C.c_int32),
+                ("reserved", C.c_int32 * 5)]
 
 
 class Cache(C.Structure):

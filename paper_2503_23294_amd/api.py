@@ -33,18 +33,23 @@ class Plan:
     seq_lens: np.ndarray
 
 
-def cocktail_default_workers(shape: Shape) -> int:
+def cocktail_default_workers(shape: Shape, vector_alu_only: bool = False) -> int:
+    """Decode workgroups that fill the GPU for this shape (vector_alu_only: for a plan made with that option,
+    where every workgroup is one wave whatever Hq/Hkv is)."""
     n = C.c_int32(0)
+    if vector_alu_only:
+        shape = Shape(shape.batch, shape.num_q_heads, shape.num_q_heads, shape.head_dim, shape.chunk_size, shape.group_size)
     check(lib().cocktail_default_workers(C.byref(shape), C.byref(n)))
     return int(n.value)
 
 
 def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[int], num_workers: int,
-                  append_capacity: int = 0, reproducible: bool = False) -> Plan:
+                  append_capacity: int = 0, reproducible: bool = False, vector_alu_only: bool = False) -> Plan:
     """Host-only: Alg. 1's prefill partition plus cache layout and decode work split (cocktail_plan_ex).
 
     append_capacity > 0 reserves room for that many generated tokens per sequence; reproducible=True
-    asks for a purely static decode split (bitwise identical results from call to call).
+    asks for a purely static decode split (bitwise identical results from call to call); vector_alu_only=True
+    plans grouped-query shapes for the kernel without matrix instructions (one query head per wave).
     """
     sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
     cb = np.ascontiguousarray(np.asarray(chunk_bits, dtype=np.uint8).reshape(-1))
@@ -56,7 +61,7 @@ def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[in
     sizes = Sizes()
     slp = sl.ctypes.data_as(C.POINTER(C.c_int32))
     cbp = cb.ctypes.data_as(C.POINTER(C.c_uint8)) if cb.size else None
-    opt = _lib.PlanOptions(int(append_capacity), int(bool(reproducible)))
+    opt = _lib.PlanOptions(int(append_capacity), int(bool(reproducible)), int(bool(vector_alu_only)))
     check(lib().cocktail_plan_ex(C.byref(shape), slp, cbp, num_workers, C.byref(opt), C.byref(sizes), None, 0, None,
                                  None))
     blob = np.zeros(int(sizes.plan_bytes), dtype=np.uint8)

@@ -124,8 +124,8 @@ extern "C" int cocktail_default_workers(const cocktail_shape* shape, int32_t* nu
   }
   const int rep = shape->num_q_heads / shape->num_kv_heads;
   const int waves_per_cu = 8;   // two waves per SIMD at <= 256 VGPRs
-  int per_cu = waves_per_cu / (uses_token_quads(rep) ? quad_waves(rep) : rep);   // waves per workgroup
-  if (per_cu < 1) per_cu = 1;
+  const int wrep = work_rep_of(rep, false);
+  const int per_cu = waves_per_cu / (uses_token_quads(wrep) ? quad_waves(wrep) : 1);   // by waves per workgroup
   *num_workers = prop.multiProcessorCount * per_cu;
   return COCKTAIL_OK;
 }
@@ -183,7 +183,6 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
     return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 64 and 128, got %d", shape->head_dim);
   if (hd->rep > COCKTAIL_MAX_Q_PER_KV)
     return fail(COCKTAIL_EUNSUPPORTED, "Hq/Hkv = %d exceeds %d", hd->rep, COCKTAIL_MAX_Q_PER_KV);
-  static_assert(COCKTAIL_MAX_Q_PER_KV == kQuadMaxRep, "every ratio above 1 runs on the token-quad kernel");
   if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(out) | reinterpret_cast<uintptr_t>(workspace) |
        reinterpret_cast<uintptr_t>(cache->plan_dev)) & 15)
     return fail(COCKTAIL_EALIGN, "q, out, workspace and plan_dev must be 16-byte aligned");
@@ -232,13 +231,14 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
   p.lse = lse;
   if (!(sm_scale > 0.f)) sm_scale = 1.0f / std::sqrt(static_cast<float>(shape->head_dim));
   p.scale_log2 = sm_scale * 1.4426950408889634f;
-  p.rep = hd->rep, p.num_q_heads = hd->num_q_heads, p.num_kv_heads = hd->num_kv_heads;
+  p.rep = hd->work_rep, p.num_q_heads = hd->num_q_heads, p.num_kv_heads = hd->work_heads;
+  p.kv_share = hd->work_heads / hd->num_kv_heads;
 #ifdef COCKTAIL_TRACE
   // debugging builds only: the caller provides 32 bytes per worker behind the regular workspace
   p.trace = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + ((hd->workspace_bytes + 255) & ~int64_t(255)));
 #endif
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int app_groups = hd->batch * hd->num_kv_heads * hd->append_slices;   // 0 without append buffers
+  const int app_groups = hd->batch * hd->work_heads * hd->append_slices;   // 0 without append buffers
   if (hd->total_gblocks > 0 || app_groups > 0) {
     const bool quads = hd->v_layout == COCKTAIL_V_TOKEN_QUADS;
     const dim3 grid(hd->num_workers + app_groups, 1, 1);
@@ -249,8 +249,9 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
       return e ? (std::atoi(e) != 0 ? 1 : 0) : -1;
     }();
     const bool nt = nt_override >= 0 ? nt_override == 1
-                                     : ((hd->rep == 1 || (quads && quad_waves(hd->rep) == 1)) &&
-                                        hd->packed_bytes >= kNonTemporalMinBytes);
+                                     : ((hd->rep == 1 || (quads && quad_waves(hd->work_rep) == 1 && hd->work_rep == hd->rep)) &&
+                                        hd->packed_bytes >= kNonTemporalMinBytes);   // rep > 1 without quads: the query
+                                                                                     // heads of a kv head re-read its lines
     const bool int8 = hd->class_blocks[2] > 0;
     const bool d64 = shape->head_dim == 64;
     const hipError_t e = quads ? (d64 ? launch_decode_quads<64>(p, shape->group_size, nt, int8, int(grid.x), st)

@@ -45,7 +45,8 @@ struct DecodeParams {
   _Float16* out;            // [B][Hq][head_dim]
   float* lse;               // [B][Hq] or NULL
   float scale_log2;         // sm_scale * log2(e)
-  int32_t rep, num_q_heads, num_kv_heads, num_groups;
+  int32_t rep, num_q_heads, num_kv_heads, num_groups;   // rep, num_kv_heads: of the work split (PlanHeader::work_rep, work_heads)
+  int32_t kv_share;         // work heads that share one kv head of the cache (1, or Hq / Hkv with one wave per query head)
   int32_t num_workers;      // workgroups behind these serve the appended tokens, app_slices per (sequence, kv head)
   int32_t num_appended, app_blocks;   // tokens appended to every sequence (used if `appended` is NULL), blocks per (b, kv head)
   const int32_t* appended;  // [B] tokens appended per sequence, or NULL
@@ -460,7 +461,8 @@ __device__ __forceinline__ AppendSlice append_slice(int idx) {
   const int first = sl * kAppendSliceBlocks;
   a.tokens = uni(min(max(appended_count(b) - first * kTB, 0), kAppendSliceBlocks * kTB));
   a.blocks = min(kAppendSliceBlocks, kp->app_blocks - first);
-  a.first_block = a.bh * kp->app_blocks + first;
+  // the append buffers are laid out by (sequence, kv head of the cache)
+  a.first_block = (b * (kp->num_kv_heads / kp->kv_share) + (a.bh % kp->num_kv_heads) / kp->kv_share) * kp->app_blocks + first;
   a.qrow = b * kp->num_q_heads + (a.bh % kp->num_kv_heads) * kp->rep;
   a.pid = uni(kp->bh_off[a.bh + 1]) - slices + sl;
   return a;

@@ -10,7 +10,7 @@
 namespace cocktail {
 
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
-constexpr uint32_t kPlanVersion = 13;
+constexpr uint32_t kPlanVersion = 14;
 constexpr int kTB = 64;                        // tokens per block
 constexpr int kNumClasses = 4;                 // INT2, INT4, INT8, FP16: the order of the concatenation
 constexpr int kFp16Class = kNumClasses - 1;
@@ -40,6 +40,17 @@ constexpr int kCounterStride = 32;             // uint32 slots between two pool 
 constexpr int kQuadMinRep = 2, kQuadMaxRep = 8;
 __host__ __device__ inline bool uses_token_quads(int rep) { return rep >= kQuadMinRep && rep <= kQuadMaxRep; }
 __host__ __device__ inline int quad_waves(int rep) { return (rep + 3) / 4; }
+// Query heads one workgroup serves when rep = Hq / Hkv heads share a kv head: all of them up to kQuadMaxRep; beyond
+// that the heads of a kv head are cut into equal sets (the largest divisor of rep that the matrix kernel takes),
+// each walking the kv head's blocks by itself; 1 (a wave per query head, vector ALU) if there is no such divisor
+// or the plan asks for it.
+__host__ __device__ inline int work_rep_of(int rep, bool vector_alu_only) {
+  if (vector_alu_only || rep <= 1) return 1;
+  if (rep <= kQuadMaxRep) return rep;
+  for (int d = kQuadMaxRep; d >= kQuadMinRep; --d)
+    if (rep % d == 0) return d;
+  return 1;
+}
 
 // One contiguous run of blocks of one (sequence, kv head, class): the part of it that one group works on.
 struct Segment {
@@ -107,6 +118,10 @@ struct PlanHeader {
   uint32_t magic, version;
   int32_t batch, num_q_heads, num_kv_heads, head_dim, chunk_size, group_size;
   int32_t rep;               // Hq / Hkv
+  int32_t work_heads;        // heads of the decode work split: Hkv, or Hq where every query head is served by a wave
+                             // of its own (vector-ALU-only plans, and Hq / Hkv beyond what the matrix kernel takes):
+                             // Segment::h and the (sequence, head) ranges of partial ids count in these
+  int32_t work_rep;          // query heads one workgroup serves: Hq / work_heads
   int32_t num_workers, num_segments, num_partials;
   int32_t total_gblocks;
   int32_t v_layout;          // 0: V blocks hold token rows like K; 1: token quads (2 to 8 query heads per kv head)

@@ -137,7 +137,7 @@ extern "C" int cocktail_plan_field(const void* plan_host, const char* name, int3
   }
   COCKTAIL_FIELD(magic) COCKTAIL_FIELD(version) COCKTAIL_FIELD(batch) COCKTAIL_FIELD(num_q_heads)
   COCKTAIL_FIELD(num_kv_heads) COCKTAIL_FIELD(head_dim) COCKTAIL_FIELD(chunk_size) COCKTAIL_FIELD(group_size)
-  COCKTAIL_FIELD(rep) COCKTAIL_FIELD(num_workers) COCKTAIL_FIELD(num_segments) COCKTAIL_FIELD(num_partials)
+  COCKTAIL_FIELD(rep) COCKTAIL_FIELD(work_heads) COCKTAIL_FIELD(work_rep) COCKTAIL_FIELD(num_workers) COCKTAIL_FIELD(num_segments) COCKTAIL_FIELD(num_partials)
   COCKTAIL_FIELD(total_gblocks) COCKTAIL_FIELD(v_layout) COCKTAIL_FIELD(total_chunks) COCKTAIL_FIELD(total_tokens)
   COCKTAIL_ARRAY(class_blocks) COCKTAIL_ARRAY(class_bytes) COCKTAIL_ARRAY(block_bytes) COCKTAIL_ARRAY(row_bytes)
   COCKTAIL_FIELD(workspace_bytes) COCKTAIL_FIELD(plan_bytes) COCKTAIL_FIELD(packed_bytes)
@@ -175,6 +175,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   if (int rc = check_shape(shape)) return rc;
   const int32_t append_capacity = options ? options->append_capacity : 0;
   const bool reproducible = options && options->reproducible != 0;
+  const bool vector_alu_only = options && options->vector_alu_only != 0;
   if (options)
     for (int32_t v : options->reserved)
       if (v != 0) return fail(COCKTAIL_EINVAL, "cocktail_plan_options::reserved must be zero");
@@ -258,11 +259,17 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   // 2 to 4 query heads per kv head are served by one wave (token-quad form of V); beyond that the query
   // heads run as two or more waves of one workgroup on the same blocks, where a pool would need a ticket
   // shared by those waves, so those shapes keep the purely static split
-  const bool quads = uses_token_quads(rep);
+  // Up to eight query heads of a kv head are served by one workgroup.  Where more of them share a kv head they are
+  // cut into equal sets, and with one wave per query head (the vector-ALU kernel, on request) every head is a set
+  // of its own: each set walks the blocks of its kv head as if they were its own.
+  const int wrep = work_rep_of(rep, vector_alu_only);   // query heads a workgroup serves
+  const int Hw = shape->num_q_heads / wrep;             // heads of the decode work split
+  const int share = rep / wrep;                         // work heads that walk the blocks of one kv head
+  const bool quads = uses_token_quads(wrep);
   if (quads && !tune.weight_set)
     for (int c = 0; c < NC; ++c) tune.weight[c] = kQuadCostWeight[c];
   const int64_t* weight = tune.weight;
-  if ((rep > 1 && !(quads && quad_waves(rep) == 1)) || reproducible) pool_percent = 0;
+  if ((wrep > 1 && !(quads && quad_waves(wrep) == 1)) || reproducible) pool_percent = 0;
 
   // ---- physical runs of the class buffers: (class, b, h) order, each a contiguous run of blocks ----
   struct Run {
@@ -272,10 +279,10 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   int64_t class_nblk[NC] = {};
   for (int c = 0; c < NC; ++c)
     for (int b = 0; b < B; ++b)
-      for (int h = 0; h < Hkv; ++h) {
+      for (int h = 0; h < Hw; ++h) {
         const int nb = v_nblk[NC * b + c];
         if (nb == 0) continue;
-        runs.push_back({b, h, c, nb, v_ct[NC * b + c], v_blk_base[NC * b + c] + h * nb});
+        runs.push_back({b, h, c, nb, v_ct[NC * b + c], v_blk_base[NC * b + c] + (h / share) * nb});
         class_nblk[c] += nb;
       }
   int64_t tot_blocks = 0;
@@ -309,7 +316,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
     // if the workgroups fill the chip twice (workgroup i and i + P/2 share a SIMD), a few rounds that
     // scale every worker's share by the measured relative speed of its class next to its mate's class.
     std::vector<double> wcap(P, 1.0), gfrac(NGR + 1, 0.0);
-    const bool pair_speed = pair_speed_on && !layout && rep == 1 && P % 2 == 0 && P >= 2 * group_workers;
+    const bool pair_speed = pair_speed_on && !layout && wrep == 1 && P % 2 == 0 && P >= 2 * group_workers;
     for (int round = 0; round < (pair_speed ? 4 : 1); ++round) {
       double total_cap = 0.0;
       for (int w = 0; w < P; ++w) total_cap += wcap[w];
@@ -487,8 +494,8 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   // ids of a (b, kv head) are contiguous, so the merge reads one dense block of the workspace.  A worker
   // enters every segment but its first one at the segment's start, i.e. as its first visitor; so the
   // id of its first piece is stored with the worker and the id of the first visitor with the segment.
-  const int BH = B * Hkv;
-  auto bh_of = [&](const Segment& sg) { return sg.b * Hkv + sg.h; };
+  const int BH = B * Hw;
+  auto bh_of = [&](const Segment& sg) { return sg.b * Hw + sg.h; };
   std::vector<int32_t> own_cnt(S, 0), bh_off(BH + 1, 0);
   for (int w = 0; w < P; ++w) {
     int sidx = items[w].seg0;
@@ -586,7 +593,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   std::memset(&hd, 0, sizeof(hd));
   hd.magic = kPlanMagic, hd.version = kPlanVersion;
   hd.batch = B, hd.num_q_heads = shape->num_q_heads, hd.num_kv_heads = Hkv, hd.head_dim = D;
-  hd.chunk_size = C, hd.group_size = G, hd.rep = rep;
+  hd.chunk_size = C, hd.group_size = G, hd.rep = rep, hd.work_heads = Hw, hd.work_rep = wrep;
   hd.num_workers = P, hd.num_segments = S, hd.num_partials = npart;
   hd.num_groups = NG, hd.num_pool_segs = NPS;
   hd.append_capacity = append_capacity, hd.append_blocks = append_blocks, hd.append_slices = append_slices;
@@ -600,7 +607,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
     hd.row_bytes[c] = row_bytes[c];
   }
   // decode workspace: the partial states, then one status word per (sequence, query head)
-  hd.ws_status_off = align16(int64_t(npart > 0 ? npart : 1) * hd.rep * (D + kPartialFloats) * int64_t(sizeof(float)));
+  hd.ws_status_off = align16(int64_t(npart > 0 ? npart : 1) * wrep * (D + kPartialFloats) * int64_t(sizeof(float)));
   hd.workspace_bytes = hd.ws_status_off + align16(int64_t(sizeof(int32_t)) * B * shape->num_q_heads);
   int64_t off = align16(sizeof(PlanHeader));
   bool too_large = false;
@@ -641,7 +648,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   sizes->num_workers = P, sizes->num_partials = npart, sizes->num_segments = S;
   sizes->append_capacity = append_capacity;
   sizes->v_layout = hd.v_layout, sizes->reserved = 0;
-  sizes->append_bytes = int64_t(BH) * hd.append_blocks * kTB * 2 * D;
+  sizes->append_bytes = int64_t(B) * Hkv * hd.append_blocks * kTB * 2 * D;
 
   if (class_tokens) std::memcpy(class_tokens, v_ct.data(), sizeof(int32_t) * v_ct.size());
   if (perm && total_chunks) std::memcpy(perm, v_perm.data(), sizeof(int32_t) * v_perm.size());

@@ -53,7 +53,10 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   REQUIRE(hd.magic == kPlanMagic && hd.plan_bytes == int64_t(blob.size()));
   const int B = sh.batch, Hkv = sh.num_kv_heads, C = sh.chunk_size, P = workers;
   const int UPB = sh.head_dim == 64 ? 1 : 2;   // units (what a wave handles at a time) per 64-token block
-  const int S = hd.num_segments, NG = hd.num_groups, NPS = hd.num_pool_segs, BH = B * Hkv;
+  const int Hw = hd.work_heads;   // heads of the decode work split: Hkv, or Hq with one wave per query head
+  REQUIRE(hd.work_rep >= 1 && hd.work_rep <= 8 && Hw * hd.work_rep == sh.num_q_heads && Hw % Hkv == 0);
+  const int share = Hw / Hkv;
+  const int S = hd.num_segments, NG = hd.num_groups, NPS = hd.num_pool_segs, BH = B * Hw;
   const Segment* segs = view<Segment>(blob, hd.off_segments, S);
   const WorkerRec* recs = view<WorkerRec>(blob, hd.off_worker_rec, P);
   const GroupRec* groups = view<GroupRec>(blob, hd.off_group_rec, NG);
@@ -100,13 +103,15 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   int64_t g = 0;
   for (int s = 0; s < S; ++s) {
     const Segment& sg = segs[s];
-    REQUIRE(sg.cls >= 0 && sg.cls < kNumClasses && sg.b >= 0 && sg.b < B && sg.h >= 0 && sg.h < Hkv);
+    REQUIRE(sg.cls >= 0 && sg.cls < kNumClasses && sg.b >= 0 && sg.b < B && sg.h >= 0 && sg.h < Hw);
     REQUIRE(sg.gblk0 == g && sg.nblk > 0 && int64_t(sg.nblk - 1) * kTB < sg.ntok);
     REQUIRE(sg.blk0 >= 0 && int64_t(sg.blk0) + sg.nblk <= hd.class_blocks[sg.cls]);
-    for (int i = 0; i < sg.nblk; ++i) REQUIRE(phys[sg.cls][sg.blk0 + i]++ == 0);
+    for (int i = 0; i < sg.nblk; ++i) REQUIRE(phys[sg.cls][sg.blk0 + i]++ < share);
     g += sg.nblk;
   }
-  REQUIRE(g == hd.total_gblocks && g == nblocks);
+  REQUIRE(g == hd.total_gblocks && g == nblocks * share);
+  for (int c = 0; c < kNumClasses; ++c)
+    for (uint8_t n : phys[c]) REQUIRE(n == share);   // every block once per work head of its kv head
 
   // the walk of every worker: own range, then the pool tickets of its group (handed out at random)
   std::vector<uint8_t> unit_seen(UPB * g, 0);
@@ -114,7 +119,7 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   auto claim_pid = [&](int pid, const Segment& sg) {
     REQUIRE(pid >= 0 && pid < hd.num_partials && !pid_seen[pid]);
     pid_seen[pid] = 1;
-    const int bh = sg.b * Hkv + sg.h;
+    const int bh = sg.b * Hw + sg.h;
     REQUIRE(bh_off[bh] <= pid && pid < bh_off[bh + 1]);
   };
   std::vector<std::vector<int>> members(NG);
@@ -237,7 +242,7 @@ int main(int argc, char** argv) {
     cocktail_shape sh;
     sh.batch = 1 + int(rng() % 6);
     sh.num_kv_heads = 1 + int(rng() % 4);
-    sh.num_q_heads = sh.num_kv_heads * pick({1, 1, 2, 3, 4, 5, 8});
+    sh.num_q_heads = sh.num_kv_heads * pick({1, 1, 2, 3, 4, 5, 8, 11, 12, 16});
     sh.head_dim = pick({64, 128, 128});
     sh.group_size = sh.head_dim == 64 ? pick({32, 64}) : pick({32, 64, 128});
     sh.chunk_size = pick({1, 8, 17, 32, 64, 100, 256, 1000});
@@ -257,6 +262,7 @@ int main(int argc, char** argv) {
     std::memset(&opt, 0, sizeof(opt));
     opt.append_capacity = pick({0, 0, 1, 64, 130, 1500});
     opt.reproducible = int(rng() % 4 == 0);
+    opt.vector_alu_only = int(rng() % 5 == 0);
     check_plan(sh, lens, bits, workers, opt, rng);
   }
   // extremes: the longest sequence the planner accepts, and one it has to refuse

@@ -24,15 +24,15 @@ def _dev():
 class Case:
     """Runs plan -> reorder_quantize -> decode_attention on the GPU for one workload layer."""
 
-    def __init__(self, w, layer=0, workers=None, sm_scale=0.0, strided_pad=0):
+    def __init__(self, w, layer=0, workers=None, sm_scale=0.0, strided_pad=0, vector_alu_only=False):
         self.w, self.layer = w, layer
         dev = _dev()
         self.shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
         self.bits = workloads.chunk_bits(w)
         flat_bits = np.concatenate(self.bits) if self.bits else np.zeros(0, np.uint8)
         if workers is None:
-            workers = ck.cocktail_default_workers(self.shape)
-        self.plan = ck.cocktail_plan(self.shape, w.seq_lens, flat_bits, workers)
+            workers = ck.cocktail_default_workers(self.shape, vector_alu_only)
+        self.plan = ck.cocktail_plan(self.shape, w.seq_lens, flat_bits, workers, vector_alu_only=vector_alu_only)
         self.cache = ck.PackedCache(self.plan, dev)
         for t in self.cache.k + self.cache.v:
             t.fill_(0xAB)                       # the library must overwrite padding too
@@ -61,9 +61,10 @@ class Case:
         torch.cuda.synchronize()
         self.out = self.out_dev.cpu().numpy()
         self.lse = self.lse_dev.cpu().numpy()
-        # V is stored in token quads where 2 to 8 query heads share a kv head
+        # V is stored in token quads where 2 to 8 query heads share a kv head (unless the plan keeps to the vector ALU)
         self.v_quads = int(self.plan.sizes.v_layout) == 1
-        assert self.v_quads == (2 <= w.num_q_heads // w.num_kv_heads <= 8)
+        rep = w.num_q_heads // w.num_kv_heads
+        assert self.v_quads == (rep >= 2 and not vector_alu_only and rep not in (11, 13))
         self.kbuf = [t.cpu().numpy() for t in self.cache.k]
         self.vbuf = [t.cpu().numpy() for t in self.cache.v]
         ct = self.plan.class_tokens.astype(np.int64)
@@ -136,7 +137,7 @@ def test_config1_all_heads(workers):
 
 
 @pytest.mark.parametrize("group", [32, 64, 128])
-@pytest.mark.parametrize("rep", [1, 2, 3, 4, 5, 8])
+@pytest.mark.parametrize("rep", [1, 2, 3, 4, 5, 6, 7, 8, 11, 12, 16])
 def test_group_sizes_and_gqa(group, rep):
     w = workloads.small(f"g{group}_r{rep}", 2, 2 * rep, 2, [64 * 5 + 32 * 3 + 7, 32 * 9], 32, group,
                         mix=(0.2, 0.25, 0.25, 0.3), seed_offset=group + rep)
@@ -144,8 +145,23 @@ def test_group_sizes_and_gqa(group, rep):
     Case(w, workers=5).check_all()
 
 
+@pytest.mark.parametrize("rep,head_dim,workers", [(2, 128, 5), (4, 128, 16), (8, 128, 7), (4, 64, 9), (16, 64, 12)])
+def test_grouped_queries_on_the_vector_alu_only(rep, head_dim, workers):
+    """A plan made with vector_alu_only runs grouped-query shapes on the kernel without matrix instructions: one
+    query head per wave, V in token rows, pools as with one head per kv head.  Same cache bytes for K, same answers."""
+    w = workloads.small(f"valu_r{rep}_d{head_dim}", 3, 2 * rep, 2, [3000, 700, 64 * 5 + 9], 64, 32,
+                        mix=(0.2, 0.2, 0.2, 0.4), head_dim=head_dim, seed_offset=700 + rep)
+    _announce(w.name)
+    c = Case(w, workers=workers, vector_alu_only=True)
+    assert ck.cocktail_plan_field(c.plan, "work_heads") == w.num_q_heads and ck.cocktail_plan_field(c.plan, "work_rep") == 1
+    c.check_all()
+    ck.cocktail_decode_check(c.cache)
+    ref = Case(w, workers=workers)                           # the default plan (matrix instructions up to ratio 8)
+    assert (c.out.astype(np.float32) - ref.out.astype(np.float32)).__abs__().max() <= 2e-3 * np.abs(ref.out.astype(np.float32)).max()
+
+
 @pytest.mark.parametrize("group", [32, 64])
-@pytest.mark.parametrize("rep", [1, 2, 3, 4, 5, 8])
+@pytest.mark.parametrize("rep", [1, 2, 3, 4, 5, 8, 12])
 def test_head_dim_64(group, rep):
     """head_dim 64: a lane still works on 64 channels, so a wave takes 64 tokens at a time instead of 32."""
     w = workloads.small(f"d64_g{group}_r{rep}", 2, 2 * rep, 2, [64 * 5 + 32 * 3 + 7, 64 * 9 + 1], 32, group,
@@ -362,7 +378,7 @@ def test_planner_tuning_knobs_keep_parity(env, monkeypatch):
 
 
 @pytest.mark.parametrize("rep,capacity,steps,head_dim", [(1, 70, 70, 128), (4, 130, 37, 128), (2, 1, 1, 128), (8, 66, 66, 128),
-                                                         (6, 5, 3, 128), (1, 70, 70, 64), (4, 130, 67, 64)])
+                                                         (6, 5, 3, 128), (1, 70, 70, 64), (4, 130, 67, 64), (16, 70, 66, 128)])
 def test_appended_decode_tokens(rep, capacity, steps, head_dim):
     """Sec. III-A: generated tokens are appended in FP16; every decode step attends to all of them."""
     w = workloads.small(f"append_r{rep}_d{head_dim}", 2, 2 * rep, 2, [64 * 9 + 5, 300], 64, 32, mix=(0.2, 0.4, 0.4),
@@ -406,7 +422,7 @@ def test_appended_decode_tokens(rep, capacity, steps, head_dim):
     torch.cuda.synchronize()
     assert cache.desc.num_appended == steps
     for which, buf in (("k", cache.k_app), ("v", cache.v_app)):      # append buffers bit-exact, unused rows zero
-        assert np.array_equal(buf.cpu().numpy(), O.pack_append_buffer(oc, which, capacity, v_quads=2 <= rep <= 8))
+        assert np.array_equal(buf.cpu().numpy(), O.pack_append_buffer(oc, which, capacity, v_quads=rep >= 2))
     if steps == capacity:
         with pytest.raises(ck.CocktailError):
             ck.cocktail_append_fp16(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
@@ -458,7 +474,7 @@ def test_sequences_that_stop_generating_at_different_steps(rep, head_dim, stops)
         if step in (0, 1, 2, 63, 64, 65, 129, 511, 512, capacity - 1, capacity + 1):
             compare()
     assert cache.appended.cpu().tolist() == stops
-    v_quads = 2 <= rep <= 8
+    v_quads = rep >= 2
     for which, buf in (("k", cache.k_app), ("v", cache.v_app)):      # append buffers bit-exact, unused rows zero
         assert np.array_equal(buf.cpu().numpy(), O.pack_append_buffer(oc, which, capacity, v_quads=v_quads))
     # a full sequence stays as it is when it is asked to take another token
@@ -648,12 +664,15 @@ def test_config5_ragged_dirichlet():
 
 
 @pytest.mark.parametrize("rep", [1, 4, 8])
-@pytest.mark.parametrize("kscale,vscale", [(1.0, 2.0e4), (1.0, 1.0e-3), (6.0, 1.0), (0.02, 3.0e-3), (3.0, 5.0e-5)])
-def test_value_ranges_from_tiny_to_near_the_fp16_limit(rep, kscale, vscale):
-    """V from fp16-subnormal magnitudes to values near 65504, peaked and flat softmax: same tolerance."""
+@pytest.mark.parametrize("kscale,vscale,qscale", [(1.0, 2.0e4, 1.0), (1.0, 1.0e-3, 1.0), (6.0, 1.0, 1.0), (0.02, 3.0e-3, 1.0),
+                                                  (3.0, 5.0e-5, 1.0), (1.0, 2.0e4, 0.01), (1.0, 1.0, 1.0e-3), (0.1, 6.0e3, 0.05)])
+def test_value_ranges_from_tiny_to_near_the_fp16_limit(rep, kscale, vscale, qscale):
+    """V from fp16-subnormal magnitudes to values near 65504, peaked and flat softmax (a small query makes every
+    token weigh the same, so the roundings of the weights that the matrix kernel feeds to its instructions in
+    fp16 add up over all tokens instead of a few): same tolerance."""
     w = workloads.small(f"range_r{rep}", 2, 2 * rep, 2, [64 * 7 + 9, 64 * 3], 64, 32, mix=(0.2, 0.4, 0.4),
                         seed_offset=300 + rep)
-    _announce(f"{w.name} k x{kscale} v x{vscale}")
+    _announce(f"{w.name} k x{kscale} v x{vscale} q x{qscale}")
     dev = _dev()
     shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
     bits = workloads.chunk_bits(w)
@@ -667,7 +686,7 @@ def test_value_ranges_from_tiny_to_near_the_fp16_limit(rep, kscale, vscale):
     k_flat = np.concatenate([x.reshape(-1, w.head_dim) for x in ks])      # ragged: per sequence [Hkv][T_b] rows
     v_flat = np.concatenate([x.reshape(-1, w.head_dim) for x in vs])
     ck.cocktail_reorder_quantize(cache, torch.from_numpy(k_flat).to(dev), torch.from_numpy(v_flat).to(dev), ragged=True)
-    q = workloads.query(w, 0)
+    q = (workloads.query(w, 0).astype(np.float32) * qscale).astype(np.float16)
     out, lse = ck.cocktail_decode_attention(cache, torch.from_numpy(q).to(dev))
     torch.cuda.synchronize()
     oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
@@ -763,7 +782,7 @@ def test_quantizer_corner_groups_are_bit_exact(rep):
 def _random_case(seed):
     """A random small workload: any supported head ratio, group size, chunk size, batch, lengths, mix, workers."""
     rng = np.random.default_rng(9000 + seed)
-    rep = int(rng.choice([1, 1, 2, 3, 4, 4, 5, 6, 8]))
+    rep = int(rng.choice([1, 1, 2, 3, 4, 4, 5, 6, 8, 12, 16]))
     hkv = int(rng.integers(1, 4))
     batch = int(rng.integers(1, 5))
     head_dim = int(rng.choice([64, 128, 128]))

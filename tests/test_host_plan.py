@@ -38,6 +38,7 @@ def _parse(plan):
     f = lambda name, i=0: ck.cocktail_plan_field(plan, name, i)
     h = {"rep": f("rep"), "workers": f("num_workers"), "segments": f("num_segments"), "partials": f("num_partials"),
          "gblocks": f("total_gblocks"), "v_layout": f("v_layout"), "plan_bytes": f("plan_bytes"),
+         "work_heads": f("work_heads"), "work_rep": f("work_rep"),
          "groups": f("num_groups"), "pool_segs": f("num_pool_segs"), "ws_status_off": f("ws_status_off"),
          "block_bytes": [f("block_bytes", c) for c in range(_lib.NUM_CLASSES)]}
     h["off"] = {k: f("off_" + k) for k in ("segments", "worker_rec", "group_rec", "pool_seg", "counters", "bh_off")}
@@ -63,22 +64,23 @@ def _check_work_split(plan, w, workers, seed=0):
     assert h["plan_bytes"] == plan.blob.size and h["workers"] == workers
     S, P, NG, NPS = h["segments"], workers, h["groups"], h["pool_segs"]
     segs = _arr(plan.blob, h["off"]["segments"], np.int32, 8 * S).reshape(S, 8)
-    BH = w.batch * w.num_kv_heads
+    BH = w.batch * h["work_heads"]
     bh_off = _arr(plan.blob, h["off"]["bh_off"], np.int32, BH + 1)
     recs = _arr(plan.blob, h["off"]["worker_rec"], np.int32, 16 * P).reshape(P, 16)
     groups = _arr(plan.blob, h["off"]["group_rec"], np.int32, 8 * NG).reshape(NG, 8)
     psegs = _arr(plan.blob, h["off"]["pool_seg"], np.int32, 8 * NPS).reshape(NPS, 8)
     counters = _arr(plan.blob, h["off"]["counters"], np.uint32, COUNTER_STRIDE * NG)
     assert (counters == 0).all() and h["off"]["counters"] % 128 == 0
-    assert h["gblocks"] == sum(plan.sizes.class_blocks)
-    # segments tile the class buffers: every physical block of every (class, b, h) exactly once
+    share = h["work_heads"] // w.num_kv_heads              # work heads that walk the blocks of one kv head
+    assert h["gblocks"] == sum(plan.sizes.class_blocks) * share
+    # segments tile the class buffers: every physical block of every (class, b, h) exactly once per work head
     phys = [np.zeros(int(plan.sizes.class_blocks[c]), dtype=np.int32) for c in range(_lib.NUM_CLASSES)]
     g = 0
     for b_, h_, cls, ntok, blk0, nblk, gblk0, spid in segs:
         assert gblk0 == g and nblk > 0 and (nblk - 1) * 64 < ntok
         phys[cls][blk0:blk0 + nblk] += 1
         g += nblk
-    assert all((x == 1).all() for x in phys)
+    assert all((x == share).all() for x in phys)
 
     rng = np.random.default_rng(seed)
     seen = np.zeros(2 * h["gblocks"], dtype=np.int32)       # per unit
@@ -94,8 +96,8 @@ def _check_work_split(plan, w, workers, seed=0):
         assert len(ws) == nworkers and [int(recs[x, 13]) & 0xffff for x in ws] == list(range(nworkers))
         assert all(recs[x, 13] >> 16 == nps and recs[x, 14] == ngran and recs[x, 15] == pseg0 for x in ws)
         assert 0 <= nps <= 32 and counter == gi
-        if w.num_q_heads // w.num_kv_heads > 4:
-            assert ngran == 0                                # one wave per query head: static split only
+        if h["work_rep"] > 4:
+            assert ngran == 0                                # two waves on the same blocks: static split only
         # tickets are handed out in ascending order to whichever worker asks next
         hand = sorted(rng.integers(0, nworkers, size=ngran).tolist()) if ngran else []
         tickets = {r: [] for r in range(nworkers)}
@@ -114,7 +116,7 @@ def _check_work_split(plan, w, workers, seed=0):
             u, u1 = 2 * g0, 2 * g1
             while u < u1:                                    # own range
                 b_, h_, cls, ntok, blk0, nblk, gblk0, spid = segs[s]
-                bh = b_ * w.num_kv_heads + h_
+                bh = b_ * h["work_heads"] + h_
                 if u >= 2 * (gblk0 + nblk):
                     s += 1
                     pid = segs[s, 7]                         # enters the next segment as its first visitor
@@ -133,7 +135,7 @@ def _check_work_split(plan, w, workers, seed=0):
                 pi = max(i for i in range(nps) if psegs[pseg0 + i, 3] <= t)
                 seg, unit0, nunits, gran0, slot0 = psegs[pseg0 + pi, :5]
                 b_, h_, cls, ntok, blk0, nblk, gblk0, spid = segs[seg]
-                bh = b_ * w.num_kv_heads + h_
+                bh = b_ * h["work_heads"] + h_
                 J = ITER_UNITS[cls]
                 us = unit0 + (t - gran0) * J
                 nu = min(J, unit0 + nunits - us)
@@ -151,14 +153,14 @@ def _check_work_split(plan, w, workers, seed=0):
                 if pi not in used and r < psegs[pseg0 + pi, 5]:
                     seg, slot0 = psegs[pseg0 + pi, 0], psegs[pseg0 + pi, 4]
                     assert slot0 + r not in pid_owner
-                    pid_owner[slot0 + r] = (segs[seg, 2], segs[seg, 0] * w.num_kv_heads + segs[seg, 1], 1)
+                    pid_owner[slot0 + r] = (segs[seg, 2], segs[seg, 0] * h["work_heads"] + segs[seg, 1], 1)
     assert (seen == 1).all()
     assert sorted(pid_owner) == list(range(h["partials"])) and h["partials"] == plan.sizes.num_partials
     assert bh_off[0] == 0 and bh_off[BH] == h["partials"] and (np.diff(bh_off) >= 0).all()
     for bh in range(BH):
         assert all(pid_owner[p][1] == bh for p in range(bh_off[bh], bh_off[bh + 1]))
     # workspace: the partial states (header + head_dim floats each), then one status word per (sequence, query head)
-    assert h["ws_status_off"] == max(h["partials"], 1) * h["rep"] * (w.head_dim + header_floats) * 4
+    assert h["ws_status_off"] == max(h["partials"], 1) * h["work_rep"] * (w.head_dim + header_floats) * 4
     assert plan.sizes.workspace_bytes == h["ws_status_off"] + (4 * w.batch * w.num_q_heads + 15) // 16 * 16
     return h, cost, pool_cost
 
@@ -279,10 +281,10 @@ def test_gpu_entry_points_validate_on_host_before_launching():
     cache.plan_host = p192.blob.ctypes.data
     assert L.cocktail_decode_attention(C.byref(sh192), 16, C.byref(cache), 0.0, 16, None, 16, 1 << 20, None) == _lib.EUNSUPPORTED
     assert L.cocktail_reorder_quantize(C.byref(sh192), 16, 16, 0, 0, 0, 192, C.byref(cache), None) == _lib.EUNSUPPORTED
-    sh16 = ck.make_shape(1, 16, 1, 128, 8, 32)
-    p16 = ck.cocktail_plan(sh16, [16], [2, 4], 4)
-    cache.plan_host = p16.blob.ctypes.data
-    assert L.cocktail_decode_attention(C.byref(sh16), 16, C.byref(cache), 0.0, 16, None, 16, 1 << 20, None) == _lib.EUNSUPPORTED
+    sh_wide = ck.make_shape(1, 128, 1, 128, 8, 32)        # 128 query heads on one kv head: beyond COCKTAIL_MAX_Q_PER_KV
+    p_wide = ck.cocktail_plan(sh_wide, [16], [2, 4], 4)
+    cache.plan_host = p_wide.blob.ctypes.data
+    assert L.cocktail_decode_attention(C.byref(sh_wide), 16, C.byref(cache), 0.0, 16, None, 16, 1 << 20, None) == _lib.EUNSUPPORTED
     n = C.c_size_t(0)
     assert L.cocktail_stream_read_probe(None, 1 << 30, 16, C.byref(n), None) == _lib.EINVAL
     assert L.cocktail_stream_read_probe(8, 1 << 30, 16, C.byref(n), None) == _lib.EALIGN
@@ -387,14 +389,20 @@ def test_chunk_bitwidths_validates_on_host():
     assert L.cocktail_selftest_arithmetic(4, None) == _lib.EALIGN
 
 
-@pytest.mark.parametrize("rep,quads", [(1, False), (2, True), (3, True), (4, True), (5, True), (8, True)])
-def test_v_layout_follows_the_query_to_kv_head_ratio(rep, quads):
-    """Token quads where a wave serves four query heads of a kv head (ratios 2 to 8); one-wave workgroups get pools."""
+@pytest.mark.parametrize("rep,quads,valu", [(1, False, False), (2, True, False), (3, True, False), (4, True, False), (5, True, False),
+                                            (8, True, False), (12, True, False), (16, True, False), (11, False, False), (4, False, True), (8, False, True)])
+def test_v_layout_follows_the_query_to_kv_head_ratio(rep, quads, valu):
+    """Token quads where a wave serves four query heads of a kv head (ratios 2 to 8); one-wave workgroups get pools.
+    Vector-ALU-only plans and ratios beyond 8 run one query head per wave: token rows, a work head per query head."""
     shape = ck.make_shape(2, 2 * rep, 2, 128, 64, 32)
     bits = np.array([2, 4, 16, 2] * 16 + [4, 2] * 16, dtype=np.uint8)
-    plan = ck.cocktail_plan(shape, [64 * 64, 32 * 64], bits, 16)
+    plan = ck.cocktail_plan(shape, [64 * 64, 32 * 64], bits, 16, vector_alu_only=valu)
     assert int(plan.sizes.v_layout) == int(quads)
     h = _parse(plan)
     assert h["rep"] == rep and h["v_layout"] == int(quads)
+    work_rep = {12: 6, 16: 8}.get(rep, rep) if quads else 1      # sets of query heads that read a kv head's blocks together
+    assert h["work_heads"] == 2 * rep // work_rep and h["work_rep"] == work_rep
     groups = _arr(plan.blob, h["off"]["group_rec"], np.int32, 8 * h["groups"]).reshape(-1, 8)
-    assert (groups[:, 0] > 0).any() == (rep <= 4)
+    assert (groups[:, 0] > 0).any() == (h["work_rep"] <= 4)
+    w = workloads.small("vl", 2, 2 * rep, 2, [64 * 64, 32 * 64], 64, 32)
+    _check_work_split(plan, w, 16)
