@@ -125,7 +125,9 @@ extern "C" int cocktail_default_workers(const cocktail_shape* shape, int32_t* nu
   const int rep = shape->num_q_heads / shape->num_kv_heads;
   const int waves_per_cu = 8;   // two waves per SIMD at <= 256 VGPRs
   const int wrep = work_rep_of(rep, false);
-  const int per_cu = waves_per_cu / (uses_token_quads(wrep) ? quad_waves(wrep) : 1);   // by waves per workgroup
+  // one-wave workgroups: eight per compute unit; two-wave workgroups (which share their K/V units through 32 KB
+  // of shared memory each): four
+  const int per_cu = uses_token_quads(wrep) ? waves_per_cu / quad_waves(wrep) : waves_per_cu;
   *num_workers = prop.multiProcessorCount * per_cu;
   return COCKTAIL_OK;
 }

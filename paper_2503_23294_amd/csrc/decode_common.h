@@ -78,6 +78,7 @@ __device__ __forceinline__ rsrc_t make_rsrc(const char* base, uint32_t bytes) {
 // MI355X is worth 10 % of HBM throughput); workgroups of two waves, whose waves re-read each other's lines
 // from the L2, and small caches that stay resident between calls use the default policy.
 constexpr int kAuxDefault = 0, kAuxNonTemporal = 2;
+typedef __attribute__((address_space(3))) char* lds_ptr_t;   // a wave-uniform address in shared memory
 constexpr int64_t kNonTemporalMinBytes = int64_t(64) << 20;   // packed K+V bytes of one call
 template <int AUX>
 __device__ __forceinline__ u32x4 load16(rsrc_t rs, uint32_t voff, uint32_t soff) {
@@ -167,6 +168,28 @@ struct QuantClass {
     } else {
       s.meta[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, vm, moff, AUX);
     }
+  }
+
+  // The same unit fetched into shared memory instead (workgroups whose waves share their K/V units): the
+  // image is what the lanes of one wave would hold in registers, piece p of lane l at p*1024 + l*16 and
+  // scale/zero dword g of lane l at PH*1024 + g*256 + l*4; the loads write it without passing through registers.
+  static constexpr int LDS_UNIT = PH * 1024 + NGH * 256;
+  template <int AUX>
+  __device__ static __forceinline__ void load_lds(lds_ptr_t dst, rsrc_t rs, int u, uint32_t vc, uint32_t vm) {
+    const uint32_t boff = uint32_t(u / UPB) * BLOCKB;
+    const uint32_t sub = uint32_t(u % UPB);
+#pragma unroll
+    for (int p = 0; p < PH; ++p)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst + p * 1024, 16, vc, boff + sub * (UT * 16) + p * (kTB * 16), 0, AUX);
+    const uint32_t moff = boff + kTB * ROWB + sub * (UT * 4 * NG);
+#pragma unroll
+    for (int g = 0; g < NGH; ++g) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst + PH * 1024 + g * 256, 4, vm + g * 4, moff, 0, AUX);
+  }
+  __device__ static __forceinline__ void read_lds(Stage& s, const char* src, int lane) {
+#pragma unroll
+    for (int p = 0; p < PH; ++p) s.pc[p] = *reinterpret_cast<const u32x4*>(src + p * 1024 + lane * 16);
+#pragma unroll
+    for (int g = 0; g < NGH; ++g) s.meta[g] = *reinterpret_cast<const uint32_t*>(src + PH * 1024 + g * 256 + lane * 4);
   }
 
   // this lane's half of q.k^ (natural units, before the softmax scale)
@@ -263,6 +286,18 @@ struct HalfClass {
     const uint32_t boff = uint32_t(u / UPB) * BLOCKB + uint32_t(u % UPB) * (UT * 16);
 #pragma unroll
     for (int p = 0; p < PH; ++p) s.pc[p] = load16<AUX>(rs, vc, boff + p * (kTB * 16));
+  }
+
+  static constexpr int LDS_UNIT = PH * 1024;   // see QuantClass::load_lds
+  template <int AUX>
+  __device__ static __forceinline__ void load_lds(lds_ptr_t dst, rsrc_t rs, int u, uint32_t vc, uint32_t) {
+    const uint32_t boff = uint32_t(u / UPB) * BLOCKB + uint32_t(u % UPB) * (UT * 16);
+#pragma unroll
+    for (int p = 0; p < PH; ++p) __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, dst + p * 1024, 16, vc, boff + p * (kTB * 16), 0, AUX);
+  }
+  __device__ static __forceinline__ void read_lds(Stage& s, const char* src, int lane) {
+#pragma unroll
+    for (int p = 0; p < PH; ++p) s.pc[p] = *reinterpret_cast<const u32x4*>(src + p * 1024 + lane * 16);
   }
 
   __device__ static __forceinline__ float half_logit(const Stage& s, const uint32_t (&q)[DH / 2],

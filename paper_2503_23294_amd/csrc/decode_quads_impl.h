@@ -38,6 +38,7 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr float kTopExp = 15.0f;     // p * scale stays below 2^kTopExp (fp16 holds up to 2^16 - 32)
 constexpr float kHeadroom = 4.0f;    // log2 units left to grow into when the reference is moved
+#define COCKTAIL_ARG(...) __VA_ARGS__   // a template-id with commas as one macro argument
 constexpr int kRedStride = 36;      // floats per lane in the reduction tile (32 + padding, 16-byte aligned rows)
 
 __device__ __forceinline__ f4 mfma4(u32x2 a, u32x2 b, f4 c) {
@@ -425,6 +426,143 @@ __device__ __forceinline__ void run_quads(Stream<HD>& sm, Piece& cur, float* red
   cur = nxt;
 }
 
+// Bytes of one stage buffer in shared memory: the K (or V) units of one loop iteration, the largest class counts.
+constexpr int kStageBytes = 8 * 1024;
+static_assert(J2 * (1024 + 512) <= kStageBytes && J4 * (2048 + 512) <= kStageBytes && J8 * (4096 + 512) <= kStageBytes &&
+              J16 * 8192 <= kStageBytes, "a stage buffer holds the units of one iteration of every class");
+
+// run_quads for workgroups of two waves (5 to 8 query heads of a kv head): both waves work on the same pieces,
+// wave r for heads 4r .. 4r+3.  The K and V units are fetched once per workgroup, straight into shared memory
+// (wave 0 fetches the K units of a piece, wave 1 its V units), into one of kStageSets sets of buffers; each wave
+// reads its lanes' share from there, so nothing is fetched twice.  A second stream object runs kStageSets - 1
+// pieces ahead of the one that drives the arithmetic and says what to fetch.  One workgroup barrier per iteration:
+// after it the piece of this iteration is complete in its set and nobody reads the set of the piece before any
+// more, so the next piece to fetch is sent there.  Both waves run the same scalar code on the same plan records
+// (these workgroups take no pool tickets), hence the same sequence of barriers.  The reduction tile of a flush
+// lives in the set that has just been used up, one wave after the other.
+// Measured on MI355X (4 x 128K tokens, 64 query / 8 kv heads, 780 MB packed): two sets (32 KB of shared memory,
+// four workgroups per compute unit) 200 us; three sets (48 KB, three workgroups) 242 us; both waves fetching
+// everything for themselves into registers 210 us.  What counts is the number of resident waves: a wave's own
+// instruction stream, not the bytes in flight, limits how fast a workgroup gets through its blocks.
+#ifndef COCKTAIL_STAGE_SETS
+#define COCKTAIL_STAGE_SETS 2
+#endif
+constexpr int kStageSets = COCKTAIL_STAGE_SETS;   // 2 or 3
+constexpr int kAhead = kStageSets - 1;            // pieces that are fetched ahead of the one being worked on
+// s_waitcnt vmcnt(NEWER): until all but the newest NEWER vector-memory operations of this wave are complete.
+// Only vmcnt is waited for; the other counters get their maximum (expcnt 7, lgkmcnt 15).
+template <int NEWER>
+__device__ __forceinline__ void wait_all_but() {
+  static_assert(NEWER >= 0 && NEWER < 16, "the low four bits of the count");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | NEWER);
+}
+template <int HD, class CLS, int CID, int G, int AUX>
+__device__ __forceinline__ void run_quads_shared(Stream<HD>& sm, Piece& cur, char* stage, int r, int lane, bool app = false) {
+  constexpr int NGH = CLS::NGH;
+  constexpr int GL = G < DH ? G : DH;
+  constexpr int J = CLS::J;
+  constexpr int UT = Geo<HD>::UT, UPB = Geo<HD>::UPB;
+  constexpr int UB = CLS::LDS_UNIT;
+  constexpr int NI = J * (UB / 1024 + (UB % 1024) / 256);   // load instructions one wave issues per piece
+  static_assert(J == kIterUnits[CID], "the planner cuts pool pieces to the kernel's iteration size");
+  static_assert(J * UB <= kStageBytes, "stage buffer too small");
+  const int t = lane % UT, h = lane / UT;
+  const uint32_t vc = CLS::code_voff(t, h), vm = CLS::meta_voff(t, h);
+  const char* const kbase = uni(app ? kparams()->k_app : kparams()->k[CID]);
+  const char* const vbase = uni(app ? kparams()->v_app : kparams()->v[CID]);
+  const float scale_log2 = kparams()->scale_log2;
+  u32x2 ident;   // column j of the 4x4 identity, j = lane % 4
+  ident.x = (lane & 2) ? 0u : ((lane & 1) ? 0x3C000000u : 0x00003C00u);
+  ident.y = (lane & 2) ? ((lane & 1) ? 0x3C000000u : 0x00003C00u) : 0u;
+  QuadState<NGH> st;
+  u32x2 qa[16];
+  f4 qs[NGH];
+  int pid = cur.pid;
+  // this wave fetches K (r = 0) or V (r = 1); buffer of (set, tensor x) at stage + (2 set + x) kStageBytes
+  const char* const mybase = r == 0 ? kbase : vbase;
+  auto fetch = [&](int set, const Stream<HD>& from, int ru, int rn) {   // `from` describes the segment of the piece
+    const rsrc_t rs = make_rsrc(mybase + int64_t(from.blk0) * CLS::BLOCKB, uint32_t(from.nblk) * CLS::BLOCKB);
+    lds_ptr_t dst = (lds_ptr_t)(stage + (2 * set + r) * kStageBytes);   // generic to shared: a C-style cast
+    const int roob = UPB * from.nblk;
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) CLS::template load_lds<AUX>(dst + jj * UB, rs, jj < rn ? ru + jj : roob, vc, vm);
+  };
+  __syncthreads();   // the other wave may still be reading the buffers for the class that came before
+  fetch(0, sm, cur.us, cur.nu);
+  Stream<HD> ahead = sm;                     // the stream that says what to fetch: it runs ahead of `sm`
+  Piece far;
+  bool far_ok = true;
+  if constexpr (kAhead == 2) {
+    far = ahead.next(lane);                  // the piece after `cur`
+    far_ok = far.nu > 0 && far.cls == CID;
+    if (far_ok) fetch(1, ahead, far.us, far.nu);
+  }
+  begin_quads<HD, CLS, NGH, GL>(sm.qrow, h, r, lane, st, qa, qs);
+  int valid = cur.valid;
+  int covered = 0;   // tokens the current partial states cover
+  int set = 0;
+  Piece nxt = sm.next(lane);
+#pragma unroll 1
+  while (true) {
+    const bool more = nxt.nu > 0 && nxt.cls == CID;
+    // the piece to fetch now: kAhead pieces after the current one
+    if (far_ok) {
+      far = ahead.next(lane);
+      far_ok = far.nu > 0 && far.cls == CID;
+    }
+    // this wave's fetches of the current piece have landed (with three sets those of the next one may still be on
+    // their way: loads complete in order, and they are the newest NI of them)
+    if (kAhead == 2 && more) wait_all_but<NI>();
+    else wait_all_but<0>();
+    __syncthreads();                 // ... and so have the other wave's; both are done with the set used before
+    if (far_ok) fetch(set == 0 ? kStageSets - 1 : set - 1, ahead, far.us, far.nu);
+    covered += valid;
+    const char* const kst = stage + (2 * set) * kStageBytes;
+    const char* const vst = kst + kStageBytes;
+    f4 s[J], p[J];
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      typename CLS::Stage ks;
+      CLS::read_lds(ks, kst + jj * UB, lane);
+      s[jj] = CLS::logits(ks, qa, qs);
+    }
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      f4 full = s[jj];
+      if constexpr (HD == 128) full += shfl_xor4(s[jj], 32);   // both halves of the token
+      full *= scale_log2;
+      s[jj] = (jj * UT + t < valid) ? full : splat(-INFINITY);
+    }
+    typename CLS::Stage vs[J];
+    float ev[J];
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) {
+      CLS::read_lds(vs[jj], vst + jj * UB, lane);
+      ev[jj] = CLS::scale_exponent(vs[jj]);
+    }
+    softmax_quads<NGH, J>(s, ev, p, st);
+#pragma unroll
+    for (int jj = 0; jj < J; ++jj) CLS::accumulate(vs[jj], p[jj], st, ident);
+    if (!more || nxt.fresh) {
+      // the set of this iteration is used up: it serves as the reduction tile, for one wave after the other
+      float* tile = reinterpret_cast<float*>(stage + (2 * set) * kStageBytes);
+      if (r == 0) flush_quads<HD, CLS, NGH, GL>(st, tile, pid, r, lane, covered);
+      __syncthreads();
+      if (r == 1) flush_quads<HD, CLS, NGH, GL>(st, tile, pid, r, lane, covered);
+    }
+    if (!more) break;
+    if (nxt.fresh) {
+      pid = nxt.pid;
+      covered = 0;
+      begin_quads<HD, CLS, NGH, GL>(sm.qrow, h, r, lane, st, qa, qs);
+    }
+    valid = nxt.valid;
+    nxt = sm.next(lane);
+    set = set == kStageSets - 1 ? 0 : set + 1;
+  }
+  cur = nxt;
+}
+
 // The neutral partial state for this wave's heads of a slot nobody had tokens for.
 template <int HD>
 __device__ __forceinline__ void write_neutral_heads(int slot, int r, int lane) {
@@ -432,8 +570,8 @@ __device__ __forceinline__ void write_neutral_heads(int slot, int r, int lane) {
   for (int i = 4 * r; i < rep && i < 4 * r + 4; ++i) write_neutral<HD>(slot, i, lane);
 }
 
-template <int HD, int G, int AUX>
-__device__ __forceinline__ void appended_tokens_quads(int idx, float* red, int r, int lane) {
+template <int HD, int G, int AUX, int WAVES>
+__device__ __forceinline__ void appended_tokens_quads(int idx, float* red, char* stage, int r, int lane) {
   const AppendSlice a = append_slice(idx);
   if (a.tokens <= 0) {
     write_neutral_heads<HD>(a.pid, r, lane);
@@ -442,37 +580,53 @@ __device__ __forceinline__ void appended_tokens_quads(int idx, float* red, int r
   Stream<HD> sm;
   sm.init_run(kFp16Class, a.tokens, a.first_block, a.blocks, a.qrow, a.pid);
   Piece cur = sm.next(lane);
-  if (cur.nu > 0) run_quads<HD, QuadHalf<HD, G>, kFp16Class, G, AUX>(sm, cur, red, r, lane, true);
+  if (cur.nu > 0) {
+    if constexpr (WAVES == 2) run_quads_shared<HD, QuadHalf<HD, G>, kFp16Class, G, AUX>(sm, cur, stage, r, lane, true);
+    else run_quads<HD, QuadHalf<HD, G>, kFp16Class, G, AUX>(sm, cur, red, r, lane, true);
+  }
 }
 
 // One workgroup per worker: one wave for 2 to 4 query heads per kv head, two waves (heads 0-3 and 4-7, both
-// walking the same blocks, so the second read of a line comes from the cache) for 5 to 8.
+// working on the same blocks, which they fetch once into shared memory: run_quads_shared) for 5 to 8.
 template <int HD, int G, int AUX, int WAVES, bool INT8>
 __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(2))) void decode_quads_kernel(DecodeParams) {
-  __shared__ __attribute__((aligned(16))) float red_all[WAVES * 64 * kRedStride];
+  // one-wave workgroups: the reduction tile of a flush; two-wave workgroups: three sets of a K and a V buffer,
+  // in which the tile finds its place too
+  __shared__ __attribute__((aligned(16))) float red_all[WAVES == 2 ? 4 : 64 * kRedStride];
+  __shared__ __attribute__((aligned(16))) char stage[WAVES == 2 ? kStageSets * 2 * kStageBytes : 16];
+  static_assert(64 * kRedStride * sizeof(float) <= 2 * kStageBytes, "a set of stage buffers holds a reduction tile");
   const int lane = threadIdx.x & 63;
   const int r = WAVES == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  float* red = red_all + r * 64 * kRedStride;
+  float* red = red_all;   // (not used by two-wave workgroups)
 #ifdef COCKTAIL_TRACE
   const uint64_t t_start = __builtin_amdgcn_s_memrealtime();
 #endif
   if (int(blockIdx.x) >= kparams()->num_workers) {
-    appended_tokens_quads<HD, G, AUX>(int(blockIdx.x) - kparams()->num_workers, red, r, lane);
+    appended_tokens_quads<HD, G, AUX, WAVES>(int(blockIdx.x) - kparams()->num_workers, red, stage, r, lane);
     return;
   }
   Stream<HD> sm;
   sm.init(load_record(kparams()->recs + blockIdx.x));
+  // the two waves of a workgroup have to walk the same pieces (they meet at barriers): they take no pool tickets;
+  // the planner gives such workgroups no pools (a plan that did would lose tokens, which the merge reports)
+  if constexpr (WAVES == 2) sm.ngran = 0, sm.nps = 0;
   Piece cur = sm.next(lane);
   while (cur.nu > 0) {
+#define COCKTAIL_RUN(CLS, CID)                                                                              \
+  if constexpr (WAVES == 2) run_quads_shared<HD, CLS, CID, G, AUX>(sm, cur, stage, r, lane);              \
+  else run_quads<HD, CLS, CID, G, AUX>(sm, cur, red, r, lane)
     if (cur.cls == 0) {
-      run_quads<HD, QuadQuant<HD, 2, G>, 0, G, AUX>(sm, cur, red, r, lane);
+      COCKTAIL_RUN(COCKTAIL_ARG(QuadQuant<HD, 2, G>), 0);
     } else if (cur.cls == 1) {
-      run_quads<HD, QuadQuant<HD, 4, G>, 1, G, AUX>(sm, cur, red, r, lane);
+      COCKTAIL_RUN(COCKTAIL_ARG(QuadQuant<HD, 4, G>), 1);
     } else if (INT8 && cur.cls == 2) {
-      if constexpr (INT8) run_quads<HD, QuadQuant<HD, 8, G>, 2, G, AUX>(sm, cur, red, r, lane);
+      if constexpr (INT8) {
+        COCKTAIL_RUN(COCKTAIL_ARG(QuadQuant<HD, 8, G>), 2);
+      }
     } else {
-      run_quads<HD, QuadHalf<HD, G>, kFp16Class, G, AUX>(sm, cur, red, r, lane);
+      COCKTAIL_RUN(COCKTAIL_ARG(QuadHalf<HD, G>), kFp16Class);
     }
+#undef COCKTAIL_RUN
   }
   for (int i = 0; i < sm.nps; ++i) {
     if ((sm.used >> i) & 1u) continue;
