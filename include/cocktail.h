@@ -146,8 +146,10 @@ typedef struct cocktail_cache {
  *
  *   seq_lens     HOST [B]           context tokens T_b >= 0
  *   chunk_bits   HOST [sum_b N_b]   N_b = floor(T_b / C) values in {2, 4, 8, 16}, sequence after sequence
- *   num_workers  workgroups for the decode kernel (> 0), normally
- *                cocktail_default_workers()
+ *   num_workers  most workgroups the decode kernel may be launched with (> 0), normally
+ *                cocktail_default_workers(); a plan never has more workers than 32-token
+ *                (head_dim 64: 64-token) units of work, rounded up to a multiple of 64:
+ *                sizes->num_workers says how many it has
  *   sizes        HOST out, always written on success
  *   plan_host    HOST out, plan_capacity bytes, or NULL to query sizes only
  *   class_tokens HOST out [B][COCKTAIL_NUM_CLASSES] n_{b,c}, or NULL

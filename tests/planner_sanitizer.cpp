@@ -51,7 +51,8 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   REQUIRE(rc == COCKTAIL_OK);
   const PlanHeader& hd = *view<PlanHeader>(blob, 0, 1);
   REQUIRE(hd.magic == kPlanMagic && hd.plan_bytes == int64_t(blob.size()));
-  const int B = sh.batch, Hkv = sh.num_kv_heads, C = sh.chunk_size, P = workers;
+  const int B = sh.batch, Hkv = sh.num_kv_heads, C = sh.chunk_size, P = hd.num_workers;
+  REQUIRE(P >= 1 && P <= workers && P == sz.num_workers && (P == workers || P % 64 == 0));   // the request is an upper bound
   const int UPB = sh.head_dim == 64 ? 1 : 2;   // units (what a wave handles at a time) per 64-token block
   const int Hw = hd.work_heads;   // heads of the decode work split: Hkv, or Hq with one wave per query head
   REQUIRE(hd.work_rep >= 1 && hd.work_rep <= 8 && Hw * hd.work_rep == sh.num_q_heads && Hw % Hkv == 0);
