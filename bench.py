@@ -186,7 +186,9 @@ def run_config(cfg, steps, warmup, ntok, workers_arg, decode_only, cpu_heads, ca
         "reorder_quantize_bytes": rq_bytes,
         "reorder_quantize_gbps": None if decode_only else rq_bytes / (float(rq_us.mean()) * 1e-6) / 1e9,
         "kernel": "decode_quads_kernel" if int(plan.sizes.v_layout) == 1 else "decode_attention_kernel",
-        "kernel_family": "four query heads per wave on 4x4x4 matrix instructions" if int(plan.sizes.v_layout) == 1
+        "kernel_family": ("four query heads per wave on 4x4x4 matrix instructions"
+                          + (", two waves per workgroup sharing their K/V units through shared memory"
+                             if w.num_q_heads // w.num_kv_heads > 4 else "")) if int(plan.sizes.v_layout) == 1
                          else "one query head per wave on the vector ALU (no matrix instructions)",
         "cache_copies": ncopies, "distinct_layers": len(src), "steps": steps, "decode_calls_per_step": ntok,
     }
@@ -306,7 +308,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=4, help="workload: benchmark configuration 1..5 (headline: 4)")
+    ap.add_argument("--config", type=int, default=4, help="workload: benchmark configuration 1..5 (headline: 4); 6 = extra shape with 8 query heads per kv head")
     ap.add_argument("--workers", type=int, default=0, help="decode workgroups (0 = library default)")
     ap.add_argument("--cpu-heads", type=int, default=32, help="kv heads the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--decode-only", action="store_true", help="steps run decode attention only (for profiling)")

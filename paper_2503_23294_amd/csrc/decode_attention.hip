@@ -244,16 +244,17 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
   if (hd->total_gblocks > 0 || app_groups > 0) {
     const bool quads = hd->v_layout == COCKTAIL_V_TOKEN_QUADS;
     const dim3 grid(hd->num_workers + app_groups, 1, 1);
-    // non-temporal K/V loads when nothing is read twice: one wave per workgroup, and a cache large enough
-    // that it cannot stay in the memory-side cache from one call to the next
+    // non-temporal K/V loads when nothing is read twice (one workgroup per kv head's blocks: the vector-ALU kernel
+    // with one query head per kv head, the matrix kernel with all query heads of a kv head in one workgroup) and the
+    // cache is large enough that it cannot stay in the memory-side cache from one call to the next
     static const int nt_override = [] {   // tuning aid, read once: COCKTAIL_NON_TEMPORAL=0 | 1
       const char* e = std::getenv("COCKTAIL_NON_TEMPORAL");
       return e ? (std::atoi(e) != 0 ? 1 : 0) : -1;
     }();
+    // (several work heads per kv head - one wave per query head of a grouped-query shape, or sets of eight at
+    // ratios above eight - read the same lines from different workgroups: default policy, the L2 serves the repeats)
     const bool nt = nt_override >= 0 ? nt_override == 1
-                                     : ((hd->rep == 1 || (quads && quad_waves(hd->work_rep) == 1 && hd->work_rep == hd->rep)) &&
-                                        hd->packed_bytes >= kNonTemporalMinBytes);   // rep > 1 without quads: the query
-                                                                                     // heads of a kv head re-read its lines
+                                     : (hd->work_rep == hd->rep && hd->packed_bytes >= kNonTemporalMinBytes);
     const bool int8 = hd->class_blocks[2] > 0;
     const bool d64 = shape->head_dim == 64;
     const hipError_t e = quads ? (d64 ? launch_decode_quads<64>(p, shape->group_size, nt, int8, int(grid.x), st)

@@ -75,8 +75,8 @@ __device__ __forceinline__ rsrc_t make_rsrc(const char* base, uint32_t bytes) {
 }
 // Cache policy of the K/V loads.  Every byte of a large cache is read exactly once per call, so the loads
 // are marked non-temporal (they do not displace anything in the L2 and the memory-side cache, which on
-// MI355X is worth 10 % of HBM throughput); workgroups of two waves, whose waves re-read each other's lines
-// from the L2, and small caches that stay resident between calls use the default policy.
+// MI355X is worth 10 % of HBM throughput); shapes in which several workgroups walk the blocks of one kv head,
+// and small caches that stay resident between calls, use the default policy.
 constexpr int kAuxDefault = 0, kAuxNonTemporal = 2;
 typedef __attribute__((address_space(3))) char* lds_ptr_t;   // a wave-uniform address in shared memory
 constexpr int64_t kNonTemporalMinBytes = int64_t(64) << 20;   // packed K+V bytes of one call

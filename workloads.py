@@ -63,7 +63,7 @@ def _rng(*key: int) -> np.random.Generator:
 
 
 def config(n: int) -> Workload:
-    """The five benchmark configurations (1-based)."""
+    """The five benchmark configurations (1-based), and extra shapes for profiling from 6 on."""
     if n == 1:
         return Workload("cfg1_2k_8h", 1, 1, 8, 8, 128, 128, 32, (2048,), (0.1, 0.3, 0.6))
     if n == 2:
@@ -80,6 +80,10 @@ def config(n: int) -> Workload:
         lens = tuple(int(x) * 256 for x in r.integers(8192 // 256, 131072 // 256 + 1, size=8))
         return Workload("cfg5_ragged_gqa_b8", 5, 8, 32, 8, 128, 256, 32, lens,
                         (1 / 3, 1 / 3, 1 / 3), dirichlet=True)
+    if n == 6:
+        # not one of the benchmark's five: a Llama-3-70B-shaped layer (8 query heads per kv head), the shape the
+        # two-wave grouped-query kernel is profiled on
+        return Workload("x6_gqa_64q_8kv_128k_b4", 6, 4, 64, 8, 128, 256, 32, (131072,) * 4, (0.15, 0.35, 0.5))
     raise ValueError(f"unknown config {n}")
 
 
