@@ -3,7 +3,9 @@
 Needs a build of the library with per-worker time stamps, made on the build machine with
     python -m paper_2503_23294_amd.build --out paper_2503_23294_amd/libcocktail_trace.so -DCOCKTAIL_TRACE
 and is then run on the GPU as
-    python -m paper_2503_23294_amd.worker_trace --config 2
+    COCKTAIL_LIB=paper_2503_23294_amd/libcocktail_trace.so python -m paper_2503_23294_amd.worker_trace --config 2
+(the package loads the library named by COCKTAIL_LIB when it is imported, which `python -m` does before this
+module runs, so the variable has to be set by the caller)
 It prints the start and end times of the workers (microseconds from the first start), per bitwidth class and
 per group of workers that share a pool, next to the time a plain stream read of the packed bytes would take:
 the split of a call into start-up, streaming and the tail between the first and the last worker to finish.
@@ -25,8 +27,10 @@ def main():
     args = ap.parse_args()
     if not os.path.exists(TRACE_LIB):
         sys.exit(f"{TRACE_LIB} is missing; build it first (see the module docstring)")
-    os.environ["COCKTAIL_LIB"] = TRACE_LIB          # read by _lib when the package is imported
     sys.path.insert(0, os.path.dirname(HERE))
+    from paper_2503_23294_amd import _lib
+    if os.path.abspath(_lib.LIB_PATH) != TRACE_LIB:
+        sys.exit(f"the package loaded {_lib.LIB_PATH}; run with COCKTAIL_LIB={TRACE_LIB} (see the module docstring)")
     import numpy as np
     import torch
     import paper_2503_23294_amd as ck
@@ -37,6 +41,7 @@ def main():
     shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
     workers = args.workers or ck.cocktail_default_workers(shape)
     plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(workloads.chunk_bits(w)), workers)
+    workers = int(plan.sizes.num_workers)   # a short context gets fewer workers than asked for
     tokens, hkv = sum(w.seq_lens), w.num_kv_heads
     # timing only: Gaussian noise of the right shape stands in for the workload's K, V and q
     k = torch.randn(hkv * tokens * w.head_dim, device=dev, dtype=torch.float16)
@@ -65,7 +70,7 @@ def main():
     print(f"  start  min/median/max {st.min():.2f} / {np.median(st):.2f} / {st.max():.2f} us")
     print(f"  end    min/p10/median/p90/max {en.min():.1f} / {np.percentile(en, 10):.1f} / {np.median(en):.1f} / "
           f"{np.percentile(en, 90):.1f} / {en.max():.1f} us   (workers without an own range: {int((own_blocks == 0).sum())})")
-    for c, name in enumerate(("INT2", "INT4", "FP16")):
+    for c, name in enumerate(("INT2", "INT4", "INT8", "FP16")):
         m = (cls == c) & (own_blocks > 0)
         if m.any():
             print(f"  {name}: {int(m.sum())} workers, {np.median(own_blocks[m]):.0f} own blocks each, end min/median/max "
