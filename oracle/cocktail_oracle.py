@@ -23,6 +23,8 @@ What it computes, in the paper's order:
   append_tokens   Sec. III-A: the K/V rows of tokens generated during decoding are
                   kept in FP16 after the context; attention then runs over the
                   three context blocks followed by those rows.
+  fold_appended   Sec. III-A: those rows become context (the FP16 list grows at
+                  its end; a chunk they complete is an FP16 chunk).
   pack_* / unpack_*   the byte layout of the packed cache (an encoding this
                   build defines; the paper is silent on it).  V has a second form,
                   "token quads" (pack_quad_blocks), for grouped-query shapes.
@@ -33,7 +35,7 @@ torch's scaled_dot_product_attention; invariance to the chunk permutation
 scalar-loop brute force on tiny inputs; partial-softmax merge identity; pack
 round trips; the KV-size figure of Sec. I; appended tokens equal textbook
 attention over the concatenation and behave exactly like the FP16 remainder of a
-longer context; the similarity scores equal scikit-learn's cosine_similarity,
+longer context, and folding them in gives the cache of that longer context; the similarity scores equal scikit-learn's cosine_similarity,
 and the thresholds a worked example, their limiting cases and their monotonicity
 in alpha and beta.  No function here is unpinned.
 """
@@ -292,6 +294,8 @@ class OracleCache:
     seqs: List[List[ClassCache]]         # [B][NUM_CLASSES]
     app_k: List[np.ndarray] = None       # [B] fp16 [Hkv, n_app, D]: rows appended during decoding
     app_v: List[np.ndarray] = None
+    seq_lens: List[int] = None           # [B] context tokens T_b
+    bits: List[np.ndarray] = None        # [B] uint8 [N_b]: the bitwidth of every chunk
 
 
 def reorder_quantize(k_seqs: Sequence[np.ndarray], v_seqs: Sequence[np.ndarray],
@@ -319,7 +323,8 @@ def reorder_quantize(k_seqs: Sequence[np.ndarray], v_seqs: Sequence[np.ndarray],
         plans.append(sp)
         seqs.append(ccs)
     empty = [np.zeros((hkv, 0, d), dtype=np.float16) for _ in plans]
-    return OracleCache(d, group, chunk_size, hkv, plans, seqs, empty, [e.copy() for e in empty])
+    return OracleCache(d, group, chunk_size, hkv, plans, seqs, empty, [e.copy() for e in empty],
+                       [int(k.shape[1]) for k in k_seqs], [np.asarray(x, dtype=np.uint8).copy() for x in bits_seqs])
 
 
 def gather_pages(pages: np.ndarray, table_row: Sequence[int], seq_len: int) -> np.ndarray:
@@ -344,6 +349,28 @@ def append_tokens(cache: OracleCache, k_new: np.ndarray, v_new: np.ndarray, acti
             continue
         cache.app_k[b] = np.concatenate([cache.app_k[b], k_new[b][:, None, :].astype(np.float16)], axis=1)
         cache.app_v[b] = np.concatenate([cache.app_v[b], v_new[b][:, None, :].astype(np.float16)], axis=1)
+
+
+def fold_appended(cache: OracleCache) -> None:
+    """Sec. III-A: the rows appended during decoding become context.  T_b grows by their number; they stay FP16
+    and stay where they are in the order of the tokens, behind the remainder of the context, so the FP16 list of
+    Alg. 1 simply grows at its end; a chunk that they complete is an FP16 chunk (bitwidth 16).  Afterwards nothing
+    is appended any more, and the cache is the one reorder_quantize builds from the longer context."""
+    for b, ccs in enumerate(cache.seqs):
+        n = cache.app_k[b].shape[1]
+        if n == 0:
+            continue
+        fp = ccs[FP16_CLASS]
+        fp.k_raw = np.concatenate([fp.k_raw, cache.app_k[b]], axis=1)
+        fp.v_raw = np.concatenate([fp.v_raw, cache.app_v[b]], axis=1)
+        fp.n_tokens += n
+        t = cache.seq_lens[b] + n
+        completed = t // cache.chunk_size - cache.bits[b].size
+        cache.bits[b] = np.concatenate([cache.bits[b], np.full(completed, 16, dtype=np.uint8)])
+        cache.seq_lens[b] = t
+        cache.plans[b] = plan_sequence(t, cache.chunk_size, cache.bits[b])
+        cache.app_k[b] = cache.app_k[b][:, :0, :]
+        cache.app_v[b] = cache.app_v[b][:, :0, :]
 
 
 def pack_append_buffer(cache: OracleCache, which: str, capacity: int, v_quads: bool = False) -> np.ndarray:
@@ -386,21 +413,30 @@ def _values_and_meta(cc: ClassCache, h: int):
     return cc.v_codes[h].astype(np.uint16), np.ascontiguousarray(meta).view(np.uint8).reshape(cc.n_tokens, -1)
 
 
-def pack_class_buffer(cache: OracleCache, cls: int, which: str, v_quads: bool = False) -> np.ndarray:
+def pack_class_buffer(cache: OracleCache, cls: int, which: str, v_quads: bool = False,
+                      reserve: Sequence[int] = None) -> np.ndarray:
     """Bytes of the K (or V) device buffer of one class: blocks ordered by (sequence, kv head, block).
-    v_quads: V is stored in the token-quad form (pack_quad_blocks); K is not affected."""
+    v_quads: V is stored in the token-quad form (pack_quad_blocks); K is not affected.
+    reserve: the FP16 runs of sequence b are laid out with room for reserve[b] more tokens (a cache that appended
+    rows are folded into later): every (sequence, kv head) run of the FP16 class is followed by zero blocks up to
+    ceil((n + reserve[b]) / 64) blocks."""
     parts = []
-    for ccs in cache.seqs:
+    bb = block_bytes(cls, cache.head_dim, cache.group)
+    for b, ccs in enumerate(cache.seqs):
         cc = ccs[cls]
-        if cc.n_tokens == 0:
-            continue
+        room = reserve[b] if (reserve is not None and cls == FP16_CLASS) else 0
+        nblk = (cc.n_tokens + TOKENS_PER_BLOCK - 1) // TOKENS_PER_BLOCK
+        spare = (cc.n_tokens + room + TOKENS_PER_BLOCK - 1) // TOKENS_PER_BLOCK - nblk
         for h in range(cache.num_kv_heads):
-            if v_quads and which == "v":
-                vals, meta = _values_and_meta(cc, h)
-                parts.append(pack_quad_blocks(vals, cc.bits, meta).reshape(-1))
-                continue
-            rows, meta = _rows_and_meta(cc, which, h)
-            parts.append(_pack_head_blocks(rows, meta).reshape(-1))
+            if cc.n_tokens:
+                if v_quads and which == "v":
+                    vals, meta = _values_and_meta(cc, h)
+                    parts.append(pack_quad_blocks(vals, cc.bits, meta).reshape(-1))
+                else:
+                    rows, meta = _rows_and_meta(cc, which, h)
+                    parts.append(_pack_head_blocks(rows, meta).reshape(-1))
+            if spare:
+                parts.append(np.zeros(spare * bb, dtype=np.uint8))
     if not parts:
         return np.zeros(0, dtype=np.uint8)
     return np.concatenate(parts)

@@ -625,6 +625,103 @@ def test_sequences_that_stop_generating_at_different_steps_equal_single_sequence
     assert O.pack_append_buffer(cache, "k", 8).size == 3 * 2 * 64 * 256
 
 
+def test_folding_appended_tokens_gives_the_cache_of_the_longer_context():
+    """Sec. III-A: context + appended rows, folded, is exactly what reorder_quantize builds from the longer
+    context whose completed chunks are FP16 chunks: plans, every class array, the byte images and the attention.
+    Catches: rows folded in front of the remainder, a completed chunk given another bitwidth, rows of one
+    sequence folded into another, rows left in the append list."""
+    chunk = 16
+    w = workloads.small("fold", 3, 4, 2, [70, 33, 125], chunk, 32, mix=(0.25, 0.35, 0.4), seed_offset=31)
+    ks, vs = _seqs(w)
+    bits = workloads.chunk_bits(w)
+    grow = [21, 0, 40]                                    # 70 + 21 = 91 completes chunk 4; 125 + 40 completes 3 chunks
+    cache = O.reorder_quantize(ks, vs, bits, chunk, 32)
+    new_k = [np.zeros((2, 0, 128), np.float16) for _ in range(3)]
+    new_v = [np.zeros((2, 0, 128), np.float16) for _ in range(3)]
+    for step in range(max(grow)):
+        kn, vn = _new_tokens(w, 300 + step)
+        active = [step < grow[b] for b in range(3)]
+        O.append_tokens(cache, kn, vn, active)
+        for b in range(3):
+            if active[b]:
+                new_k[b] = np.concatenate([new_k[b], kn[b][:, None, :]], axis=1)
+                new_v[b] = np.concatenate([new_v[b], vn[b][:, None, :]], axis=1)
+    q = workloads.query(w, 0)
+    before, lse_before = O.decode_attention(q, cache)
+    O.fold_appended(cache)
+    long_k = [np.concatenate([ks[b], new_k[b]], axis=1) for b in range(3)]
+    long_v = [np.concatenate([vs[b], new_v[b]], axis=1) for b in range(3)]
+    long_bits = [np.concatenate([bits[b], np.full((w.seq_lens[b] + grow[b]) // chunk - len(bits[b]), 16, np.uint8)])
+                 for b in range(3)]
+    assert [len(x) for x in long_bits] == [5, 2, 10]
+    fresh = O.reorder_quantize(long_k, long_v, long_bits, chunk, 32)
+    assert cache.seq_lens == fresh.seq_lens == [91, 33, 165]
+    for b in range(3):
+        assert cache.app_k[b].shape[1] == 0 and cache.app_v[b].shape[1] == 0
+        assert np.array_equal(cache.bits[b], fresh.bits[b])
+        assert np.array_equal(cache.plans[b].perm, fresh.plans[b].perm)
+        assert cache.plans[b].class_chunks == fresh.plans[b].class_chunks
+        assert cache.plans[b].class_tokens == fresh.plans[b].class_tokens and cache.plans[b].tail == fresh.plans[b].tail
+        for c in range(O.NUM_CLASSES):
+            a, f = cache.seqs[b][c], fresh.seqs[b][c]
+            assert a.n_tokens == f.n_tokens
+            for name in ("k_codes", "k_scale", "k_zero", "v_codes", "v_scale", "v_zero", "k_raw", "v_raw"):
+                x, y = getattr(a, name), getattr(f, name)
+                assert (x is None) == (y is None)
+                if x is not None:
+                    assert np.array_equal(np.ascontiguousarray(x).view(np.uint8), np.ascontiguousarray(y).view(np.uint8)), name
+    for c in range(O.NUM_CLASSES):
+        for which in ("k", "v"):
+            for quads in (False, True):
+                assert np.array_equal(O.pack_class_buffer(cache, c, which, quads), O.pack_class_buffer(fresh, c, which, quads))
+    after, lse_after = O.decode_attention(q, cache)
+    fr, lse_fr = O.decode_attention(q, fresh)
+    np.testing.assert_array_equal(after, fr)
+    np.testing.assert_allclose(after, before, rtol=0, atol=1e-13)      # folding does not change the attention
+    np.testing.assert_allclose(lse_after, lse_before, rtol=0, atol=1e-13)
+    # the appended rows sit behind the old remainder: the last rows of the FP16 list are the new tokens
+    for b in (0, 2):
+        assert np.array_equal(cache.seqs[b][O.FP16_CLASS].k_raw[:, -grow[b]:], new_k[b])
+
+
+def test_fp16_runs_with_room_to_grow_are_the_runs_followed_by_zero_blocks():
+    """pack_class_buffer(reserve=...): the layout a cache has when appended rows are to be folded into it later.
+    Catches: room counted in blocks instead of tokens, room given to another class, a run without tokens that gets
+    no room, spare blocks in front of the run."""
+    w = workloads.small("reserve", 3, 2, 2, [64 + 10, 8, 200], 8, 32, mix=(0.3, 0.3, 0.4), seed_offset=37)
+    ks, vs = _seqs(w)
+    bits = [x.copy() for x in workloads.chunk_bits(w)]
+    bits[1][:] = 2                                        # sequence 1: no FP16 tokens at all (8 tokens = one INT2 chunk)
+    bits[0][:] = 2
+    bits[0][0] = 16                                       # sequence 0: one FP16 chunk + the 2-token remainder
+    cache = O.reorder_quantize(ks, vs, bits, 8, 32)
+    assert cache.seqs[1][O.FP16_CLASS].n_tokens == 0 and cache.seqs[0][O.FP16_CLASS].n_tokens == 10
+    bb = 64 * 256
+    # 10 tokens + room for 50 still fit the run's one block; + 60 need a second one
+    for reserve, spare0 in (([50, 70, 0], 0), ([60, 1, 5], 1)):
+        for which, quads in (("k", False), ("v", False), ("v", True)):
+            plain = O.pack_class_buffer(cache, O.FP16_CLASS, which, quads)
+            roomy = O.pack_class_buffer(cache, O.FP16_CLASS, which, quads, reserve=reserve)
+            pos_p = pos_r = 0
+            for b in range(3):
+                n = cache.seqs[b][O.FP16_CLASS].n_tokens
+                used = -(-n // 64)
+                total = -(-(n + reserve[b]) // 64)
+                if b == 0:
+                    assert total - used == spare0
+                for h in range(2):
+                    assert np.array_equal(roomy[pos_r:pos_r + used * bb], plain[pos_p:pos_p + used * bb])
+                    assert not roomy[pos_r + used * bb:pos_r + total * bb].any()
+                    pos_p += used * bb
+                    pos_r += total * bb
+            assert pos_p == plain.size and pos_r == roomy.size
+            # other classes take no room
+            assert np.array_equal(O.pack_class_buffer(cache, 0, which, quads, reserve=reserve),
+                                  O.pack_class_buffer(cache, 0, which, quads))
+    # sequence 1 has no FP16 tokens: room for 70 is two blocks per head, room for 1 is one
+    assert O.pack_class_buffer(cache, O.FP16_CLASS, "k", reserve=[0, 70, 0]).size - O.pack_class_buffer(cache, O.FP16_CLASS, "k").size == 2 * 2 * bb
+
+
 def test_page_gather_by_hand_and_round_trip():
     """gather_pages against a table typed out by hand, and as the inverse of a scatter into shuffled pages."""
     # 3 pages of 2 tokens, 1 head, D = 1: page p, slot s holds the value 10 p + s
