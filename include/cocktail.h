@@ -176,7 +176,14 @@ typedef struct cocktail_plan_options {
   int32_t vector_alu_only; /* != 0: grouped-query shapes are planned for the kernel that runs one query head per wave
                               on the vector ALU alone (no matrix instructions, V in token rows); every query head
                               then reads the blocks of its kv head by itself                                    */
-  int32_t reserved[5];     /* must be zero                                                                    */
+  int32_t reserved0;       /* must be zero                                                                    */
+  const int32_t* max_seq_lens; /* HOST [B] or NULL: the context length every sequence may reach when generated tokens
+                              are folded into the packed cache (cocktail_fold_appended; Sec. III-A: they stay FP16).
+                              The FP16 run of every (sequence, kv head) is laid out with room for
+                              max_seq_lens[b] - seq_lens[b] more tokens (zero blocks after reorder+quantize), so a
+                              plan for a longer context with the same max_seq_lens has the same cache layout.
+                              max_seq_lens[b] >= seq_lens[b].                                                   */
+  int32_t reserved[2];     /* must be zero                                                                    */
 } cocktail_plan_options;
 
 /* cocktail_plan with options (NULL = defaults = cocktail_plan). */
@@ -343,6 +350,32 @@ int cocktail_append_fp16(const cocktail_shape* shape, const void* k_new, const v
  */
 int cocktail_append_fp16_ragged(const cocktail_shape* shape, const void* k_new, const void* v_new,
                                 const cocktail_cache* cache, const uint8_t* active_dev, void* stream);
+
+/*
+ * Sec. III-A, for long generations: the tokens appended so far become context.  Their K/V rows move from the
+ * append buffers into the packed cache, behind the FP16 rows of their (sequence, kv head) (they stay FP16 and keep
+ * their place in the order of the tokens: the FP16 list of Alg. 1 grows at its end, nothing is quantized again), so
+ * that the decode work split of a new plan covers them like any other token instead of leaving them to the few
+ * workgroups that serve the append buffers.
+ *
+ *   cache          the cache as it is: plan_host / plan_dev = the plan in use (made with append buffers and with
+ *                  cocktail_plan_options::max_seq_lens), class and append buffers, appended_dev or num_appended
+ *   new_plan_host  HOST plan of the longer contexts: seq_lens[b] + (tokens appended to sequence b), chunk_bits
+ *                  extended by 16 for every chunk the new tokens complete, the same shape and the same
+ *                  max_seq_lens, hence the same cache layout (checked)
+ *   new_plan_dev   DEVICE copy of new_plan_host, 16-byte aligned, complete before this call runs on `stream`
+ *
+ * Every sequence is folded completely: new seq_lens[b] - old seq_lens[b] has to be the number of tokens appended
+ * to sequence b (checked against num_appended for batches in lockstep; with appended_dev the counts live on the
+ * device and are the caller's to match).  Afterwards the caller switches cache->plan_host and cache->plan_dev to
+ * the new plan and sets num_appended = 0; appended_dev is cleared by this call.  The workspace of the new plan may
+ * be larger than the old one's.
+ *
+ * One or two kernel launches.  Errors: EINVAL (plans that differ in more than FP16 tokens at the end, counts out of
+ * range, NULL), EUNSUPPORTED, EALIGN, EHIP.
+ */
+int cocktail_fold_appended(const cocktail_shape* shape, const cocktail_cache* cache, const void* new_plan_host,
+                           const void* new_plan_dev, void* stream);
 
 /*
  * Chunk-level quantization search (Sec. III-B): scores[i] = cosine similarity of sequence b's query

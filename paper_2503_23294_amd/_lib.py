@@ -38,7 +38,7 @@ class Sizes(C.Structure):
 
 class PlanOptions(C.Structure):
     _fields_ = [("append_capacity", C.c_int32), ("reproducible", C.c_int32), ("vector_alu_only", C.c_int32),
-                ("reserved", C.c_int32 * 5)]
+                ("reserved0", C.c_int32), ("max_seq_lens", C.POINTER(C.c_int32)), ("reserved", C.c_int32 * 2)]
 
 
 class Cache(C.Structure):
@@ -64,6 +64,7 @@ EXPORTS = {
                                        C.c_void_p]),
     "cocktail_append_fp16_ragged": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.POINTER(Cache), C.c_void_p,
                                               C.c_void_p]),
+    "cocktail_fold_appended": (C.c_int, [C.POINTER(Shape), C.POINTER(Cache), C.c_void_p, C.c_void_p, C.c_void_p]),
     "cocktail_chunk_bitwidths": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "cocktail_reorder_quantize": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.c_void_p, C.c_int32, C.c_int64,

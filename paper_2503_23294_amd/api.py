@@ -44,12 +44,14 @@ def cocktail_default_workers(shape: Shape, vector_alu_only: bool = False) -> int
 
 
 def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[int], num_workers: int,
-                  append_capacity: int = 0, reproducible: bool = False, vector_alu_only: bool = False) -> Plan:
+                  append_capacity: int = 0, reproducible: bool = False, vector_alu_only: bool = False,
+                  max_seq_lens: Optional[Sequence[int]] = None) -> Plan:
     """Host-only: Alg. 1's prefill partition plus cache layout and decode work split (cocktail_plan_ex).
 
     append_capacity > 0 reserves room for that many generated tokens per sequence; reproducible=True
     asks for a purely static decode split (bitwise identical results from call to call); vector_alu_only=True
-    plans grouped-query shapes for the kernel without matrix instructions (one query head per wave).
+    plans grouped-query shapes for the kernel without matrix instructions (one query head per wave);
+    max_seq_lens lays the FP16 runs out with room to grow to those context lengths (cocktail_fold_appended).
     """
     sl = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int32))
     cb = np.ascontiguousarray(np.asarray(chunk_bits, dtype=np.uint8).reshape(-1))
@@ -62,6 +64,11 @@ def cocktail_plan(shape: Shape, seq_lens: Sequence[int], chunk_bits: Sequence[in
     slp = sl.ctypes.data_as(C.POINTER(C.c_int32))
     cbp = cb.ctypes.data_as(C.POINTER(C.c_uint8)) if cb.size else None
     opt = _lib.PlanOptions(int(append_capacity), int(bool(reproducible)), int(bool(vector_alu_only)))
+    if max_seq_lens is not None:
+        ml = np.ascontiguousarray(np.asarray(max_seq_lens, dtype=np.int32))
+        if ml.shape != (shape.batch,):
+            raise ValueError("max_seq_lens must have one entry per sequence")
+        opt.max_seq_lens = ml.ctypes.data_as(C.POINTER(C.c_int32))   # `ml` stays alive until both calls below return
     check(lib().cocktail_plan_ex(C.byref(shape), slp, cbp, num_workers, C.byref(opt), C.byref(sizes), None, 0, None,
                                  None))
     blob = np.zeros(int(sizes.plan_bytes), dtype=np.uint8)
@@ -203,6 +210,26 @@ def cocktail_append_fp16_ragged(cache: PackedCache, k_new: torch.Tensor, v_new: 
     cache.desc.appended_dev = cache.appended.data_ptr()
     check(lib().cocktail_append_fp16_ragged(C.byref(sh), k_new.data_ptr(), v_new.data_ptr(), C.byref(cache.desc),
                                             active.data_ptr() if active is not None else None, _stream_ptr(stream)))
+
+
+def cocktail_fold_appended(cache: PackedCache, new_plan: Plan, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Moves the appended tokens of every sequence into the packed cache (they become context) and switches the
+    cache to `new_plan`, the plan of the longer contexts made with the same max_seq_lens."""
+    sh = cache.plan.shape
+    s = stream if stream is not None else torch.cuda.current_stream()
+    with torch.cuda.stream(s):
+        new_dev = torch.from_numpy(new_plan.blob).to(cache.device)       # stream-ordered before the fold
+        check(lib().cocktail_fold_appended(C.byref(sh), C.byref(cache.desc), new_plan.blob.ctypes.data, new_dev.data_ptr(),
+                                           _stream_ptr(s)))
+        old_dev = cache.plan_dev
+        old_dev.record_stream(s)
+        if int(new_plan.sizes.workspace_bytes) > cache.workspace.numel():
+            cache.workspace.record_stream(s)
+            cache.workspace = torch.empty(int(new_plan.sizes.workspace_bytes), dtype=torch.uint8, device=cache.device)
+    cache.plan, cache.plan_dev = new_plan, new_dev
+    cache.desc.plan_host = new_plan.blob.ctypes.data
+    cache.desc.plan_dev = new_dev.data_ptr()
+    cache.desc.num_appended = 0
 
 
 def cocktail_decode_attention(cache: PackedCache, q: torch.Tensor, sm_scale: float = 0.0,

@@ -10,7 +10,7 @@
 namespace cocktail {
 
 constexpr uint32_t kPlanMagic = 0x434b544cu;  // "CKTL"
-constexpr uint32_t kPlanVersion = 14;
+constexpr uint32_t kPlanVersion = 15;
 constexpr int kTB = 64;                        // tokens per block
 constexpr int kNumClasses = 4;                 // INT2, INT4, INT8, FP16: the order of the concatenation
 constexpr int kFp16Class = kNumClasses - 1;
@@ -142,7 +142,9 @@ struct PlanHeader {
   int32_t off_class_tokens;   // int32 [B][4]
   int32_t off_class_chunk0;   // int32 [B][4]  first position in perm_b of class c
   int32_t off_blk_base;       // int32 [B+1][4] first block of sequence b in class buffer c
-  int32_t off_nblk;           // int32 [B][4]  blocks per head
+  int32_t off_nblk;           // int32 [B][4]  blocks per head that hold tokens
+  int32_t off_run_blocks;     // int32 [B][4]  blocks per head the run is laid out with (>= the above: FP16 runs with
+                              //               room for tokens that are folded in later)
   int32_t off_segments;       // Segment [num_segments]
   int32_t append_capacity;    // tokens per sequence the append buffers hold (0 = none)
   int32_t off_worker_rec;     // WorkerRec [num_workers]

@@ -143,7 +143,7 @@ extern "C" int cocktail_plan_field(const void* plan_host, const char* name, int3
   COCKTAIL_FIELD(workspace_bytes) COCKTAIL_FIELD(plan_bytes) COCKTAIL_FIELD(packed_bytes)
   COCKTAIL_FIELD(off_seq_len) COCKTAIL_FIELD(off_cum_tokens) COCKTAIL_FIELD(off_chunk_off) COCKTAIL_FIELD(off_perm)
   COCKTAIL_FIELD(off_class_tokens) COCKTAIL_FIELD(off_class_chunk0) COCKTAIL_FIELD(off_blk_base)
-  COCKTAIL_FIELD(off_nblk) COCKTAIL_FIELD(off_segments) COCKTAIL_FIELD(append_capacity)
+  COCKTAIL_FIELD(off_nblk) COCKTAIL_FIELD(off_run_blocks) COCKTAIL_FIELD(off_segments) COCKTAIL_FIELD(append_capacity)
   COCKTAIL_FIELD(off_worker_rec) COCKTAIL_FIELD(off_group_rec) COCKTAIL_FIELD(off_pool_seg)
   COCKTAIL_FIELD(off_counters) COCKTAIL_FIELD(num_groups) COCKTAIL_FIELD(num_pool_segs)
   COCKTAIL_FIELD(append_blocks) COCKTAIL_FIELD(append_slices) COCKTAIL_FIELD(off_bh_off) COCKTAIL_FIELD(off_rq_items)
@@ -176,9 +176,12 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   const int32_t append_capacity = options ? options->append_capacity : 0;
   const bool reproducible = options && options->reproducible != 0;
   const bool vector_alu_only = options && options->vector_alu_only != 0;
-  if (options)
+  const int32_t* max_seq_lens = options ? options->max_seq_lens : nullptr;
+  if (options) {
+    if (options->reserved0 != 0) return fail(COCKTAIL_EINVAL, "cocktail_plan_options::reserved must be zero");
     for (int32_t v : options->reserved)
       if (v != 0) return fail(COCKTAIL_EINVAL, "cocktail_plan_options::reserved must be zero");
+  }
   if (append_capacity < 0 || append_capacity > (1 << 24) - kTB)   // an append run stays below 4 GiB, like a context run
     return fail(COCKTAIL_EINVAL, "append_capacity %d out of range [0, 2^24 - 64]", append_capacity);
   if (!seq_lens || !sizes) return fail(COCKTAIL_EINVAL, "seq_lens and sizes must not be NULL");
@@ -193,11 +196,14 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   int64_t total_chunks = 0, total_tokens = 0;
   for (int b = 0; b < B; ++b) {
     if (seq_lens[b] < 0) return fail(COCKTAIL_EINVAL, "seq_lens[%d] = %d is negative", b, seq_lens[b]);
+    if (max_seq_lens && max_seq_lens[b] < seq_lens[b])
+      return fail(COCKTAIL_EINVAL, "max_seq_lens[%d] = %d is below seq_lens[%d] = %d", b, max_seq_lens[b], b, seq_lens[b]);
     // the kernels address the blocks of one (b, h, class) run with 32-bit byte offsets and describe it by a
     // buffer resource with a 32-bit size: an all-FP16 run of T tokens has ceil(T / 64) * 64 * 2 D bytes
-    if ((int64_t(seq_lens[b]) + kTB - 1) / kTB * kTB * 2 * D >= (int64_t(1) << 32))
-      return fail(COCKTAIL_EUNSUPPORTED, "seq_lens[%d] = %d: one (sequence, kv head) run in FP16 would reach 4 GiB "
-                  "(at most %lld tokens per sequence at head_dim %d)", b, seq_lens[b],
+    const int32_t longest = max_seq_lens ? max_seq_lens[b] : seq_lens[b];   // what the sequence may grow to
+    if ((int64_t(longest) + kTB - 1) / kTB * kTB * 2 * D >= (int64_t(1) << 32))
+      return fail(COCKTAIL_EUNSUPPORTED, "sequence %d with %d tokens: one (sequence, kv head) run in FP16 would reach 4 GiB "
+                  "(at most %lld tokens per sequence at head_dim %d)", b, longest,
                   (long long)(((int64_t(1) << 32) / (2 * D) - 1) / kTB * kTB), D);
     total_chunks += seq_lens[b] / C;
     total_tokens += seq_lens[b];
@@ -221,8 +227,10 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   }
 
   // ---- Alg. 1 prefill loop: class lists in loop order, concatenated INT2 | INT4 | INT8 | FP16 ----
+  // v_nblk: blocks per head that hold tokens; v_cap: blocks per head the run is laid out with (more than v_nblk
+  // only for FP16 runs with room to grow, cocktail_plan_options::max_seq_lens)
   std::vector<int32_t> v_perm(total_chunks), v_chunk_off(B + 1, 0), v_ct(NC * B), v_cc0(NC * B), v_nblk(NC * B),
-      v_blk_base(NC * (B + 1), 0);
+      v_cap(NC * B), v_blk_base(NC * (B + 1), 0);
   std::vector<int64_t> v_cum(B + 1, 0);
   int64_t class_tokens_tot[NC] = {};
   int64_t packed = 0;
@@ -239,9 +247,11 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
       if (c == kFp16Class) ntok += seq_lens[b] - n * C;  // Sec. III-A: the remainder stays FP16
       v_ct[NC * b + c] = static_cast<int32_t>(ntok);
       v_nblk[NC * b + c] = static_cast<int32_t>((ntok + kTB - 1) / kTB);
+      const int64_t room = (c == kFp16Class && max_seq_lens) ? int64_t(max_seq_lens[b]) - seq_lens[b] : 0;
+      v_cap[NC * b + c] = static_cast<int32_t>((ntok + room + kTB - 1) / kTB);
       class_tokens_tot[c] += ntok;
       packed += 2 * int64_t(Hkv) * ntok * algo_row[c];
-      const int64_t nb = int64_t(v_blk_base[NC * b + c]) + int64_t(Hkv) * v_nblk[NC * b + c];
+      const int64_t nb = int64_t(v_blk_base[NC * b + c]) + int64_t(Hkv) * v_cap[NC * b + c];
       if (nb >= (int64_t(1) << 31)) return fail(COCKTAIL_EINVAL, "class %d needs more than 2^31 blocks", c);
       v_blk_base[NC * (b + 1) + c] = static_cast<int32_t>(nb);
     }
@@ -281,7 +291,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
       for (int h = 0; h < Hw; ++h) {
         const int nb = v_nblk[NC * b + c];
         if (nb == 0) continue;
-        runs.push_back({b, h, c, nb, v_ct[NC * b + c], v_blk_base[NC * b + c] + (h / share) * nb});
+        runs.push_back({b, h, c, nb, v_ct[NC * b + c], v_blk_base[NC * b + c] + (h / share) * v_cap[NC * b + c]});
         class_nblk[c] += nb;
       }
   int64_t tot_blocks = 0;
@@ -556,11 +566,12 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   }
 
   // ---- reorder+quantize records: one per block of the class buffers ----
+  // (blocks of an FP16 run that are only room to grow get a record without valid rows: they are written as zeros)
   std::vector<RQItem> rq_items;
-  rq_items.reserve(tot_blocks);
+  rq_items.reserve(v_blk_base[NC * B + 0] + v_blk_base[NC * B + 1] + v_blk_base[NC * B + 2] + v_blk_base[NC * B + 3]);
   for (int c = 0; c < NC; ++c)
     for (int b = 0; b < B; ++b) {
-      const int nb = v_nblk[NC * b + c], ntok = v_ct[NC * b + c];
+      const int nb = v_cap[NC * b + c], ntok = v_ct[NC * b + c];
       if (nb == 0) continue;
       const int n = seq_lens[b] / C;
       const int32_t* pb = v_perm.data() + v_chunk_off[b];
@@ -576,12 +587,13 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
         RQItem& it = head_items[j];
         std::memset(&it, 0, sizeof(it));
         const int r0 = j * kTB;
-        const int nvalid = ntok - r0 < kTB ? ntok - r0 : kTB;
+        const int nvalid = ntok - r0 < kTB ? (ntok > r0 ? ntok - r0 : 0) : kTB;
+        it.b = b, it.j = j;
+        it.cls_nvalid = c | (nvalid << 8);
+        if (nvalid == 0) continue;   // room to grow: t0 = 0, nothing is read
         const int t0 = src_token(r0);
         // rows are consecutive tokens iff the last one is (chunks keep their order, so tokens in between are too)
         it.t0 = src_token(r0 + nvalid - 1) == t0 + nvalid - 1 ? t0 : -1;
-        it.b = b, it.j = j;
-        it.cls_nvalid = c | (nvalid << 8);
       }
       for (int h = 0; h < Hkv; ++h)
         for (int j = 0; j < nb; ++j) {
@@ -628,6 +640,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
   place(hd.off_class_chunk0, 4 * NC * int64_t(B));
   place(hd.off_blk_base, 4 * NC * int64_t(B + 1));
   place(hd.off_nblk, 4 * NC * int64_t(B));
+  place(hd.off_run_blocks, 4 * NC * int64_t(B));
   place(hd.off_segments, int64_t(sizeof(Segment)) * S);
   place(hd.off_bh_off, 4 * int64_t(BH + 1));
   place(hd.off_worker_rec, int64_t(sizeof(WorkerRec)) * P);
@@ -675,6 +688,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
     put(hd.off_class_chunk0, v_cc0.data(), 4 * NC * size_t(B));
     put(hd.off_blk_base, v_blk_base.data(), 4 * NC * size_t(B + 1));
     put(hd.off_nblk, v_nblk.data(), 4 * NC * size_t(B));
+    put(hd.off_run_blocks, v_cap.data(), 4 * NC * size_t(B));
     put(hd.off_segments, segs.data(), sizeof(Segment) * size_t(S));
     put(hd.off_bh_off, bh_off.data(), 4 * bh_off.size());
     std::vector<WorkerRec> recs(P);

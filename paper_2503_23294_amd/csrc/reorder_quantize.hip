@@ -217,7 +217,7 @@ __global__ __launch_bounds__(256) void reorder_quantize_kernel(RQParams p) {
     src = p.src[which] + h * p.stride_h;     // the head inside a page; page and slot are added per block or per row
     const int last = t0 + (item.cls_nvalid >> 8) - 1;
     const int pg = t0 < 0 ? 0 : p.page_shift >= 0 ? t0 >> p.page_shift : t0 / p.page_size;
-    if (t0 >= 0 && (p.page_shift >= 0 ? last >> p.page_shift : last / p.page_size) == pg) {
+    if (t0 >= 0 && nvalid > 0 && (p.page_shift >= 0 ? last >> p.page_shift : last / p.page_size) == pg) {
       // the whole block lies inside one page: consecutive rows again
       const int page = p.page_table[int64_t(b) * p.table_stride + pg];
       if (uint32_t(page) < uint32_t(p.num_pages)) src += int64_t(page) * p.stride_page + int64_t(t0 - pg * p.page_size) * p.stride_t;

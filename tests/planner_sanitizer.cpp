@@ -69,9 +69,23 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
   const int32_t* cc0 = view<int32_t>(blob, hd.off_class_chunk0, kNumClasses * B);
   const int32_t* ctok = view<int32_t>(blob, hd.off_class_tokens, kNumClasses * B);
   const int32_t* seq_len = view<int32_t>(blob, hd.off_seq_len, B);
-  int64_t nblocks = 0;
-  for (int c = 0; c < kNumClasses; ++c) nblocks += hd.class_blocks[c];
-  const RQItem* items = view<RQItem>(blob, hd.off_rq_items, nblocks);
+  // layout: blocks per head that hold tokens, blocks per head the run is laid out with, first block per sequence
+  const int32_t* used_blk = view<int32_t>(blob, hd.off_nblk, kNumClasses * B);
+  const int32_t* run_blk = view<int32_t>(blob, hd.off_run_blocks, kNumClasses * B);
+  const int32_t* base_blk = view<int32_t>(blob, hd.off_blk_base, kNumClasses * (B + 1));
+  int64_t nblocks = 0, nrecords = 0;   // blocks with tokens (the decode work); blocks of the buffers (one record each)
+  for (int c = 0; c < kNumClasses; ++c) {
+    nrecords += hd.class_blocks[c];
+    REQUIRE(base_blk[c] == 0 && base_blk[kNumClasses * B + c] == hd.class_blocks[c] && sz.class_blocks[c] == hd.class_blocks[c]);
+    for (int b = 0; b < B; ++b) {
+      const int64_t n = ctok[kNumClasses * b + c];
+      const int64_t room = (c == kFp16Class && opt.max_seq_lens) ? opt.max_seq_lens[b] - lens[b] : 0;
+      REQUIRE(used_blk[kNumClasses * b + c] == (n + kTB - 1) / kTB && run_blk[kNumClasses * b + c] == (n + room + kTB - 1) / kTB);
+      REQUIRE(base_blk[kNumClasses * (b + 1) + c] - base_blk[kNumClasses * b + c] == int64_t(Hkv) * run_blk[kNumClasses * b + c]);
+      nblocks += int64_t(Hkv) * used_blk[kNumClasses * b + c];
+    }
+  }
+  const RQItem* items = view<RQItem>(blob, hd.off_rq_items, nrecords);
   for (int64_t i = 0; i < int64_t(NG) * kCounterStride; ++i) REQUIRE(counters[i] == 0);
   REQUIRE(hd.off_counters % 128 == 0);
 
@@ -111,8 +125,15 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
     g += sg.nblk;
   }
   REQUIRE(g == hd.total_gblocks && g == nblocks * share);
-  for (int c = 0; c < kNumClasses; ++c)
-    for (uint8_t n : phys[c]) REQUIRE(n == share);   // every block once per work head of its kv head
+  // every block that holds tokens once per work head of its kv head; blocks that are only room to grow never
+  for (int c = 0; c < kNumClasses; ++c) {
+    std::vector<uint8_t> want(hd.class_blocks[c], 0);
+    for (int b = 0; b < B; ++b)
+      for (int h = 0; h < Hkv; ++h)
+        for (int i = 0; i < used_blk[kNumClasses * b + c]; ++i)
+          want[base_blk[kNumClasses * b + c] + int64_t(h) * run_blk[kNumClasses * b + c] + i] = uint8_t(share);
+    REQUIRE(phys[c] == want);
+  }
 
   // the walk of every worker: own range, then the pool tickets of its group (handed out at random)
   std::vector<uint8_t> unit_seen(UPB * g, 0);
@@ -204,10 +225,17 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
     for (int64_t i = 0; i < hd.class_blocks[c]; ++i, ++idx) {
       const RQItem& it = items[idx];
       const int cls = it.cls_nvalid & 0xff, nvalid = it.cls_nvalid >> 8;
-      REQUIRE(cls == c && nvalid >= 1 && nvalid <= kTB && it.b >= 0 && it.b < B && it.h >= 0 && it.h < Hkv);
+      REQUIRE(cls == c && nvalid >= 0 && nvalid <= kTB && it.b >= 0 && it.b < B && it.h >= 0 && it.h < Hkv);
       const int T = lens[it.b], N = T / C;
       const int ntok = ctok[kNumClasses * it.b + c], chunk_tokens = c == kFp16Class ? ntok - (T - N * C) : ntok;
-      REQUIRE(int64_t(it.j) * kTB + nvalid <= ntok);
+      // record i describes block i of the class buffer: block j of the run of (b, h)
+      REQUIRE(i == base_blk[kNumClasses * it.b + c] + int64_t(it.h) * run_blk[kNumClasses * it.b + c] + it.j);
+      REQUIRE(it.j >= 0 && it.j < run_blk[kNumClasses * it.b + c]);
+      REQUIRE(nvalid == std::max<int64_t>(0, std::min<int64_t>(kTB, ntok - int64_t(it.j) * kTB)));
+      if (nvalid == 0) {   // room to grow: written as zeros, nothing is read
+        REQUIRE(c == kFp16Class && it.t0 == 0);
+        continue;
+      }
       if (it.t0 >= 0) {
         REQUIRE(it.t0 + nvalid <= T);
       } else {
@@ -224,7 +252,7 @@ static void check_plan(const cocktail_shape& sh, const std::vector<int32_t>& len
         }
       }
     }
-  REQUIRE(idx == nblocks);
+  REQUIRE(idx == nrecords);
 
   // the debugging accessor agrees with the header
   int64_t v = -1;
@@ -264,6 +292,11 @@ int main(int argc, char** argv) {
     opt.append_capacity = pick({0, 0, 1, 64, 130, 1500});
     opt.reproducible = int(rng() % 4 == 0);
     opt.vector_alu_only = int(rng() % 5 == 0);
+    std::vector<int32_t> most(lens);
+    if (rng() % 3 == 0) {   // FP16 runs with room to grow
+      for (int b = 0; b < sh.batch; ++b) most[b] += pick({0, 1, 63, 64, 65, 1000});
+      opt.max_seq_lens = most.data();
+    }
     check_plan(sh, lens, bits, workers, opt, rng);
   }
   // extremes: the longest sequence the planner accepts, and one it has to refuse

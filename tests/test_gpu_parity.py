@@ -484,6 +484,99 @@ def test_sequences_that_stop_generating_at_different_steps(rep, head_dim, stops)
     assert cache.appended.cpu().tolist() == full
 
 
+@pytest.mark.parametrize("rep,head_dim,ragged", [(1, 128, True), (4, 128, True), (4, 64, False), (8, 128, True), (1, 64, False)])
+def test_folding_appended_tokens_into_the_packed_cache(rep, head_dim, ragged):
+    """Sec. III-A over a long generation: the appended tokens become context.  After every fold the class buffers
+    are, byte for byte, those of a cache built from the longer context (FP16 runs laid out with room to grow), the
+    append counts are back to zero, and attention agrees with the oracle before and after."""
+    w = workloads.small(f"fold_r{rep}_d{head_dim}", 3, 2 * rep, 2, [64 * 5 + 37, 40, 700], 32, 32,
+                        mix=(0.2, 0.4, 0.4), head_dim=head_dim, seed_offset=290 + rep)
+    _announce(f"{w.name} ragged={ragged}")
+    dev = _dev()
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = [x.copy() for x in workloads.chunk_bits(w)]
+    lens = list(w.seq_lens)
+    most = [lens[0] + 400, lens[1] + 400, lens[2] + 400]
+    capacity = 200
+    plan = ck.cocktail_plan(shape, lens, np.concatenate(bits), 12, append_capacity=capacity, max_seq_lens=most)
+    cache = ck.PackedCache(plan, dev)
+    for t in cache.k + cache.v:
+        t.fill_(0xAB)                                       # room to grow has to be written too (as zeros)
+    k, v = workloads.kv_flat(w, 0)
+    ck.cocktail_reorder_quantize(cache, torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev), ragged=True)
+    ks, vs = [], []
+    for b in range(w.batch):
+        kh, vh = zip(*[workloads.kv_head(w, 0, b, h) for h in range(w.num_kv_heads)])
+        ks.append(np.stack(kh)), vs.append(np.stack(vh))
+    oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    q = workloads.query(w, 0)
+    q_dev = torch.from_numpy(q).to(dev)
+    rng = np.random.default_rng([workloads.BASE_SEED, 4747, rep, head_dim])
+    v_quads = int(plan.sizes.v_layout) == 1
+
+    def compare(what):
+        out, lse = ck.cocktail_decode_attention(cache, q_dev)
+        ck.cocktail_decode_check(cache)
+        ref, rl = O.decode_attention(q, oc)
+        got = out.cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref).max(axis=2) / np.abs(ref).max(axis=2)
+        assert err.max() <= TOL, f"{what}: max rel err {err.max():.3e}"
+        assert np.abs(lse.cpu().numpy() - rl).max() <= 1e-4 * max(1.0, np.abs(rl).max())
+
+    def compare_bytes(what):
+        reserve = [most[b] - oc.seq_lens[b] for b in range(w.batch)]
+        for c in range(O.NUM_CLASSES):
+            for which, bufs in (("k", cache.k), ("v", cache.v)):
+                ref = O.pack_class_buffer(oc, c, which, v_quads=v_quads, reserve=reserve)
+                got = bufs[c].cpu().numpy()
+                assert ref.size == got.size, f"{what}: class {c} {which}: {got.size} bytes, {ref.size} expected"
+                if not np.array_equal(ref, got):
+                    bad = np.flatnonzero(ref != got)
+                    bb = O.block_bytes(c, w.head_dim, w.group_size)
+                    raise AssertionError(f"{what}: class {c} {which}: {bad.size} bytes differ, first in block {bad[0] // bb} "
+                                         f"at offset {bad[0] % bb}")
+
+    compare_bytes("after reorder+quantize")
+    compare("before any token")
+    # three rounds: generate (sequences stop at different steps when ragged), decode, fold, decode
+    for rnd, steps in enumerate(([90, 0, 200], [64, 7, 1], [0, 0, 0])):
+        if not ragged:
+            steps = [max(steps)] * 3
+        for step in range(max(steps)):
+            active = np.array([step < n for n in steps], dtype=np.uint8)
+            kn = rng.standard_normal((w.batch, w.num_kv_heads, w.head_dim), dtype=np.float32).astype(np.float16)
+            vn = rng.standard_normal((w.batch, w.num_kv_heads, w.head_dim), dtype=np.float32).astype(np.float16)
+            if ragged:
+                ck.cocktail_append_fp16_ragged(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev),
+                                               torch.from_numpy(active).to(dev))
+            else:
+                ck.cocktail_append_fp16(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev), step)
+            O.append_tokens(oc, kn, vn, active)
+        compare(f"round {rnd}, {steps} tokens appended")
+        lens = [lens[b] + steps[b] for b in range(w.batch)]
+        bits = [np.concatenate([bits[b], np.full(lens[b] // w.chunk_size - len(bits[b]), 16, np.uint8)]) for b in range(w.batch)]
+        longer = ck.cocktail_plan(shape, lens, np.concatenate(bits), 12, append_capacity=capacity, max_seq_lens=most)
+        assert [int(x) for x in longer.sizes.class_bytes] == [int(x) for x in plan.sizes.class_bytes]
+        ck.cocktail_fold_appended(cache, longer)
+        O.fold_appended(oc)
+        assert oc.seq_lens == lens and all(np.array_equal(oc.bits[b], bits[b]) for b in range(w.batch))
+        torch.cuda.synchronize()
+        if ragged:
+            assert cache.appended.cpu().tolist() == [0, 0, 0]
+        assert int(cache.desc.num_appended) == 0
+        compare_bytes(f"after fold {rnd}")
+        compare(f"after fold {rnd}")
+    # generation goes on after a fold: the append buffers start from their first row again
+    kn = rng.standard_normal((w.batch, w.num_kv_heads, w.head_dim), dtype=np.float32).astype(np.float16)
+    vn = rng.standard_normal((w.batch, w.num_kv_heads, w.head_dim), dtype=np.float32).astype(np.float16)
+    if ragged:
+        ck.cocktail_append_fp16_ragged(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev))
+    else:
+        ck.cocktail_append_fp16(cache, torch.from_numpy(kn).to(dev), torch.from_numpy(vn).to(dev), 0)
+    O.append_tokens(oc, kn, vn)
+    compare("one more token after the last fold")
+
+
 @pytest.mark.parametrize("alpha,beta", [(0.6, 0.1), (0.0, 0.0), (0.3, 0.5), (1.0, 1.0)])
 def test_chunk_level_quantization_search(alpha, beta):
     """Sec. III-B: scores and bitwidths of every chunk, bit for bit (the arithmetic is fixed on both sides)."""

@@ -63,7 +63,14 @@ def _check_work_split(plan, w, workers, seed=0):
     ITER_UNITS, COUNTER_STRIDE, header_floats = _consts(plan)
     # the requested number of workers is an upper bound: never more workers than units of work (multiples of 64)
     share = h["work_heads"] // w.num_kv_heads
-    units = sum(plan.sizes.class_blocks) * share * (1 if w.head_dim == 64 else 2)
+    nc = _lib.NUM_CLASSES
+    f = ck.cocktail_plan_field
+    # blocks per head that hold tokens, blocks per head the run is laid out with (room to grow), first block per sequence
+    used_blk = _arr(plan.blob, f(plan, "off_nblk"), np.int32, nc * w.batch).reshape(w.batch, nc)
+    run_blk = _arr(plan.blob, f(plan, "off_run_blocks"), np.int32, nc * w.batch).reshape(w.batch, nc)
+    base_blk = _arr(plan.blob, f(plan, "off_blk_base"), np.int32, nc * (w.batch + 1)).reshape(w.batch + 1, nc)
+    work_blocks = int(used_blk.sum()) * w.num_kv_heads
+    units = work_blocks * share * (1 if w.head_dim == 64 else 2)
     assert h["plan_bytes"] == plan.blob.size
     assert h["workers"] == plan.sizes.num_workers == min(workers, max((units + 63) // 64 * 64, 64))
     workers = h["workers"]
@@ -77,7 +84,7 @@ def _check_work_split(plan, w, workers, seed=0):
     counters = _arr(plan.blob, h["off"]["counters"], np.uint32, COUNTER_STRIDE * NG)
     assert (counters == 0).all() and h["off"]["counters"] % 128 == 0
     share = h["work_heads"] // w.num_kv_heads              # work heads that walk the blocks of one kv head
-    assert h["gblocks"] == sum(plan.sizes.class_blocks) * share
+    assert h["gblocks"] == work_blocks * share
     # segments tile the class buffers: every physical block of every (class, b, h) exactly once per work head
     phys = [np.zeros(int(plan.sizes.class_blocks[c]), dtype=np.int32) for c in range(_lib.NUM_CLASSES)]
     g = 0
@@ -85,7 +92,13 @@ def _check_work_split(plan, w, workers, seed=0):
         assert gblk0 == g and nblk > 0 and (nblk - 1) * 64 < ntok
         phys[cls][blk0:blk0 + nblk] += 1
         g += nblk
-    assert all((x == share).all() for x in phys)
+    for c in range(nc):
+        want = np.zeros_like(phys[c])
+        for b_ in range(w.batch):
+            for h_ in range(w.num_kv_heads):
+                first = base_blk[b_, c] + h_ * run_blk[b_, c]
+                want[first:first + used_blk[b_, c]] = share       # blocks that are only room to grow belong to nobody
+        assert np.array_equal(phys[c], want)
 
     rng = np.random.default_rng(seed)
     seen = np.zeros(2 * h["gblocks"], dtype=np.int32)       # per unit
@@ -346,9 +359,13 @@ def test_append_capacity_sizes_and_validation():
     bp = bits.ctypes.data_as(C.POINTER(C.c_uint8))
     bad = _lib.PlanOptions(-1, 0)
     assert L.cocktail_plan_ex(C.byref(sh), lp, bp, 4, C.byref(bad), C.byref(sizes), None, 0, None, None) == _lib.EINVAL
-    bad = _lib.PlanOptions(0, 0)
-    bad.reserved[2] = 1
-    assert L.cocktail_plan_ex(C.byref(sh), lp, bp, 4, C.byref(bad), C.byref(sizes), None, 0, None, None) == _lib.EINVAL
+    for field in (0, 1, "reserved0"):
+        bad = _lib.PlanOptions(0, 0)
+        if field == "reserved0":
+            bad.reserved0 = 1
+        else:
+            bad.reserved[field] = 1
+        assert L.cocktail_plan_ex(C.byref(sh), lp, bp, 4, C.byref(bad), C.byref(sizes), None, 0, None, None) == _lib.EINVAL
     assert L.cocktail_plan_ex(C.byref(sh), lp, bp, 4, None, C.byref(sizes), None, 0, None, None) == _lib.OK
     w4 = workloads.config(4)
     sh4 = ck.make_shape(w4.batch, w4.num_q_heads, w4.num_kv_heads, w4.head_dim, w4.chunk_size, w4.group_size)
@@ -411,3 +428,100 @@ def test_v_layout_follows_the_query_to_kv_head_ratio(rep, quads, valu):
     assert (groups[:, 0] > 0).any() == (h["work_rep"] <= 4)
     w = workloads.small("vl", 2, 2 * rep, 2, [64 * 64, 32 * 64], 64, 32)
     _check_work_split(plan, w, 16)
+
+
+def test_room_to_grow_keeps_the_cache_layout_from_plan_to_plan():
+    """cocktail_plan_options::max_seq_lens: FP16 runs are laid out for the length a sequence may reach, so the plan
+    of a longer context (more FP16 tokens at the end, Sec. III-A) describes the same buffers."""
+    w = workloads.small("grow", 3, 4, 2, [300, 64, 1000], 32, 32, mix=(0.2, 0.4, 0.4), seed_offset=41)
+    sh = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = workloads.chunk_bits(w)
+    flat = np.concatenate(bits)
+    most = [300 + 500, 64, 1000 + 70]
+    plain = ck.cocktail_plan(sh, w.seq_lens, flat, 64, append_capacity=512)
+    p0 = ck.cocktail_plan(sh, w.seq_lens, flat, 64, append_capacity=512, max_seq_lens=most)
+    nc = _lib.NUM_CLASSES
+    f = ck.cocktail_plan_field
+
+    def layout(plan):
+        base = _arr(plan.blob, f(plan, "off_blk_base"), np.int32, nc * (w.batch + 1)).reshape(w.batch + 1, nc)
+        run = _arr(plan.blob, f(plan, "off_run_blocks"), np.int32, nc * w.batch).reshape(w.batch, nc)
+        used = _arr(plan.blob, f(plan, "off_nblk"), np.int32, nc * w.batch).reshape(w.batch, nc)
+        return base, run, used
+
+    base, run, used = layout(p0)
+    base_plain, run_plain, used_plain = layout(plain)
+    assert np.array_equal(used, used_plain) and np.array_equal(run_plain, used_plain)      # without room: run = used blocks
+    assert np.array_equal(run[:, :3], used[:, :3])                                          # only FP16 runs get room
+    for b in range(w.batch):
+        n16 = int(p0.class_tokens[b, 3])
+        assert run[b, 3] == -(-(n16 + most[b] - w.seq_lens[b]) // 64)
+    assert np.array_equal(np.diff(base, axis=0), run * w.num_kv_heads)
+    assert [int(x) for x in p0.sizes.class_blocks] == [int(x) for x in base[-1]]
+    assert int(p0.sizes.packed_bytes) == int(plain.sizes.packed_bytes)                      # algorithmic bytes: tokens only
+    # (the replay of the work split does not know the partial ids of the append workgroups: plans without them)
+    _check_work_split(ck.cocktail_plan(sh, w.seq_lens, flat, 64, max_seq_lens=most), w, 64)
+    # a later plan: sequence 0 grew by 200 tokens (6 chunks completed, all FP16), sequence 2 by 70
+    longer = [500, 64, 1070]
+    bits1 = [np.concatenate([bits[b], np.full(longer[b] // 32 - len(bits[b]), 16, np.uint8)]) for b in range(3)]
+    p1 = ck.cocktail_plan(sh, longer, np.concatenate(bits1), 64, append_capacity=512, max_seq_lens=most)
+    base1, run1, used1 = layout(p1)
+    assert np.array_equal(base1, base) and np.array_equal(run1, run)
+    assert [int(x) for x in p1.sizes.class_bytes] == [int(x) for x in p0.sizes.class_bytes]
+    assert np.array_equal(p1.class_tokens[:, :3], p0.class_tokens[:, :3])
+    assert (p1.class_tokens[:, 3] - p0.class_tokens[:, 3]).tolist() == [200, 0, 70]
+    _check_work_split(ck.cocktail_plan(sh, longer, np.concatenate(bits1), 64, max_seq_lens=most),
+                      w.__class__(**{**w.__dict__, "seq_lens": tuple(longer)}), 64)
+    # validation
+    with pytest.raises(ck.CocktailError, match="below seq_lens"):
+        ck.cocktail_plan(sh, w.seq_lens, flat, 64, max_seq_lens=[299, 64, 1000])
+    with pytest.raises(ValueError):
+        ck.cocktail_plan(sh, w.seq_lens, flat, 64, max_seq_lens=[300, 64])
+
+
+def test_fold_rejects_plans_that_do_not_belong_together():
+    """Host-side checks of cocktail_fold_appended (no kernel is launched on any of these paths)."""
+    w = workloads.small("foldv", 2, 2, 2, [100, 40], 16, 32, mix=(0.2, 0.4, 0.4), seed_offset=43)
+    sh = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = [np.array([4, 2, 2, 16, 2, 2], np.uint8), np.array([2, 16], np.uint8)]   # 16 INT4 tokens: one more chunk fits its block
+    most = [200, 140]
+    L = _lib.lib()
+
+    def plan(lens, bit_lists, **kw):
+        return ck.cocktail_plan(sh, lens, np.concatenate(bit_lists), 16, **kw)
+
+    def grown(lens):
+        return [np.concatenate([bits[b], np.full(lens[b] // 16 - len(bits[b]), 16, np.uint8)]) for b in range(2)]
+
+    p0 = plan(w.seq_lens, bits, append_capacity=64, max_seq_lens=most)
+    good = plan([110, 50], grown([110, 50]), append_capacity=64, max_seq_lens=most)
+    desc = _lib.Cache()
+    desc.plan_host = p0.blob.ctypes.data
+    fake = 1 << 20                               # never dereferenced: every call below fails validation first
+    desc.plan_dev = fake
+    desc.k_app = desc.v_app = fake
+    desc.k[3] = desc.v[3] = fake
+    desc.num_appended = 10
+
+    def fold(new_plan, new_dev=fake):
+        return L.cocktail_fold_appended(C.byref(sh), C.byref(desc), new_plan.blob.ctypes.data if new_plan else None, new_dev, None)
+
+    assert fold(None) == _lib.EINVAL
+    assert fold(good, None) == _lib.EINVAL
+    assert fold(good, fake + 4) == _lib.EALIGN
+    # a different layout (planned without room to grow), fewer tokens than before, more than the append buffers hold
+    assert fold(plan([110, 50], grown([110, 50]), append_capacity=64)) == _lib.EINVAL
+    assert b"lays the cache out differently" in L.cocktail_last_error()
+    assert fold(plan([90, 40], [bits[0][:5], bits[1]], append_capacity=64, max_seq_lens=most)) == _lib.EINVAL
+    assert fold(plan([180, 50], grown([180, 50]), append_capacity=64, max_seq_lens=most)) == _lib.EINVAL
+    assert b"append buffers hold" in L.cocktail_last_error()
+    # a completed chunk that is not FP16: the new plan differs in more than FP16 tokens at the end
+    wrong = grown([116, 50])
+    wrong[0][-1] = 4
+    assert fold(plan([116, 50], wrong, append_capacity=64, max_seq_lens=most)) == _lib.EINVAL
+    assert b"more than FP16 tokens" in L.cocktail_last_error()
+    # lockstep counting: every sequence must have grown by num_appended
+    assert fold(plan([110, 45], grown([110, 45]), append_capacity=64, max_seq_lens=most)) == _lib.EINVAL
+    # a plan without append buffers cannot be folded from
+    desc.plan_host = plan(w.seq_lens, bits, max_seq_lens=most).blob.ctypes.data
+    assert fold(good) == _lib.EINVAL
