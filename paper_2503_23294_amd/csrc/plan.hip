@@ -77,6 +77,8 @@ struct Tuning {
   int layout = kLayout;                 // COCKTAIL_LAYOUT         0 | 1
   int pair_mode = kPairMode;            // COCKTAIL_PAIR_MODE      0 | 2 | 3
   int min_pool_blocks = kMinBlocksPerWorkerForPool;   // COCKTAIL_MIN_POOL_BLOCKS  1..4096
+  double pair_table[kNumClasses][kNumClasses];        // COCKTAIL_PAIR_TABLE="16 numbers, row = own class": replaces
+  bool pair_table_set = false;                        // kPairSpeed, and switches the correction on for the matrix kernel too
 };
 
 static Tuning read_tuning() {
@@ -95,6 +97,27 @@ static Tuning read_tuning() {
       if (v >= lo && v <= hi) out = v;
     }
   };
+  for (int a = 0; a < kNumClasses; ++a)
+    for (int b = 0; b < kNumClasses; ++b) t.pair_table[a][b] = kPairSpeed[a][b];
+  if (const char* e = std::getenv("COCKTAIL_PAIR_TABLE")) {
+    double v[16];
+    int n = 0;
+    const char* q = e;
+    while (n < 16) {
+      char* end = nullptr;
+      const double x = std::strtod(q, &end);
+      if (end == q) break;
+      v[n++] = x;
+      q = end;
+      while (*q == ',' || *q == ' ') ++q;
+    }
+    bool ok = n == 16;
+    for (int i = 0; ok && i < 16; ++i) ok = v[i] > 0.25 && v[i] < 4.0;
+    if (ok) {
+      for (int i = 0; i < 16; ++i) t.pair_table[i / 4][i % 4] = v[i];
+      t.pair_table_set = true;
+    }
+  }
   int ps = 1;
   int_knob("COCKTAIL_POOL_PERCENT", 0, 100, t.pool_percent);
   t.pool_percent_set = std::getenv("COCKTAIL_POOL_PERCENT") != nullptr;
@@ -330,7 +353,8 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
     // if the workgroups fill the chip twice (workgroup i and i + P/2 share a SIMD), a few rounds that
     // scale every worker's share by the measured relative speed of its class next to its mate's class.
     std::vector<double> wcap(P, 1.0), gfrac(NGR + 1, 0.0);
-    const bool pair_speed = pair_speed_on && !layout && wrep == 1 && P % 2 == 0 && P >= 2 * group_workers;
+    const bool pair_speed = pair_speed_on && !layout && P % 2 == 0 && P >= 2 * group_workers &&
+                            (wrep == 1 || (tune.pair_table_set && quads && quad_waves(wrep) == 1));
     for (int round = 0; round < (pair_speed ? 4 : 1); ++round) {
       double total_cap = 0.0;
       for (int w = 0; w < P; ++w) total_cap += wcap[w];
@@ -347,7 +371,7 @@ extern "C" int cocktail_plan_ex(const cocktail_shape* shape, const int32_t* seq_
         const double x = double(tot) * (gfrac[j] + (w - j * group_workers + 0.5) / k * (gfrac[j + 1] - gfrac[j]));
         wclass[w] = x < double(start[1]) ? 0 : x < double(start[2]) ? 1 : x < double(start[3]) ? 2 : 3;
       }
-      for (int w = 0; w < P; ++w) wcap[w] = kPairSpeed[wclass[w]][wclass[(w + P / 2) % P]];
+      for (int w = 0; w < P; ++w) wcap[w] = tune.pair_table[wclass[w]][wclass[(w + P / 2) % P]];
     }
     for (int j = 0; j <= NGR; ++j) {
       for (int c = 0; c < NC; ++c) {

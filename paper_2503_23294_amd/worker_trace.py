@@ -75,6 +75,18 @@ def main():
         if m.any():
             print(f"  {name}: {int(m.sum())} workers, {np.median(own_blocks[m]):.0f} own blocks each, end min/median/max "
                   f"{en[m].min():.1f} / {np.median(en[m]):.1f} / {en[m].max():.1f} us")
+    # duration by own class and by the class of the SIMD mate (workgroup i shares a SIMD with workgroup i + P/2)
+    if workers % 2 == 0:
+        mate = np.roll(cls, -workers // 2)
+        names = ("INT2", "INT4", "INT8", "FP16")
+        print("  own ranges: worker end (median us) by own class (rows) and SIMD mate's class (columns), workers counted")
+        for c in range(4):
+            cells = []
+            for m in range(4):
+                sel = (cls == c) & (mate == m) & (own_blocks > 0)
+                cells.append(f"{names[m]} {np.median(en[sel]):6.1f} ({int(sel.sum()):4d})" if sel.any() else f"{names[m]}      - (   0)")
+            if ((cls == c) & (own_blocks > 0)).any():
+                print(f"    {names[c]}: " + "   ".join(cells))
     ng = int(group.max()) + 1
     gend = np.array([en[group == g].max() for g in range(ng)])
     gfirst = np.array([en[group == g].min() for g in range(ng)])
