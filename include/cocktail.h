@@ -18,8 +18,9 @@
  *
  * Conventions
  *   - Every pointer is marked HOST or DEVICE.  The library never allocates,
- *     frees or copies device memory and never synchronises the device; the two
- *     GPU entry points only enqueue kernels on the caller's stream.
+ *     frees or copies device memory and never synchronises the device (the one
+ *     exception, cocktail_decode_check, says so); the GPU entry points only
+ *     enqueue kernels on the caller's stream.
  *   - All functions return a cocktail_status; on failure a message is kept in
  *     thread-local storage (cocktail_last_error).  Arguments are validated on
  *     the host before anything is launched.
@@ -30,7 +31,9 @@
  * fix one).  For each class c the K data and the V data live in one device
  * buffer each.  A buffer is a sequence of 64-token blocks ordered by
  * (sequence b, kv head h, block j); sequence b owns ceil(n_{b,c}/64) blocks per
- * head, n_{b,c} being its token count in class c.  Inside a block:
+ * head, n_{b,c} being its token count in class c (the FP16 runs of a plan made with
+ * cocktail_plan_options::max_seq_lens own more: room for the tokens that may be folded in later, zero blocks
+ * until then).  Inside a block:
  *   codes   the row of token i (i = 0..63) is cut into 16-byte pieces; piece p
  *           of token i is at byte (p*64 + i)*16.  Row size: D*bits/8 bytes for
  *           INT2/INT4/INT8, 2*D bytes (raw fp16, channel order) for FP16.
