@@ -308,7 +308,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=4, help="workload: benchmark configuration 1..5 (headline: 4); 6 = extra shape with 8 query heads per kv head")
+    ap.add_argument("--config", type=int, default=4, help="workload: benchmark configuration 1..5 (headline: 4); 6..9 = extra shapes (8 query heads per kv head; head_dim 64; INT8 mixes)")
     ap.add_argument("--workers", type=int, default=0, help="decode workgroups (0 = library default)")
     ap.add_argument("--cpu-heads", type=int, default=32, help="kv heads the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--decode-only", action="store_true", help="steps run decode attention only (for profiling)")

@@ -41,9 +41,9 @@ int check_shape(const cocktail_shape* s) {
   return COCKTAIL_OK;
 }
 
-constexpr int64_t kCostWeight[kNumClasses] = {1150, 1300, 900, 530};
+constexpr int64_t kCostWeight[kNumClasses] = {1150, 1300, 1100, 530};
 // The same for the kernel that serves four query heads per wave: its arithmetic runs on the matrix unit.
-constexpr int64_t kQuadCostWeight[kNumClasses] = {1300, 1250, 800, 450};
+constexpr int64_t kQuadCostWeight[kNumClasses] = {1300, 1250, 950, 450};
 // Workers per group.  Measured on MI355X: with one query head per kv head 4 to 8 are equal on long
 // ranges (8 a hair ahead at 128K), 5 to 6 clearly best on short ones (32K: 33.2 against 35.9 us); the
 // grouped-query kernel likes 4.

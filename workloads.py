@@ -84,6 +84,15 @@ def config(n: int) -> Workload:
         # not one of the benchmark's five: a Llama-3-70B-shaped layer (8 query heads per kv head), the shape the
         # two-wave grouped-query kernel is profiled on
         return Workload("x6_gqa_64q_8kv_128k_b4", 6, 4, 64, 8, 128, 256, 32, (131072,) * 4, (0.15, 0.35, 0.5))
+    if n == 7:
+        # extra: head_dim 64 (64 heads of 64 channels, one query head per kv head), 128K context
+        return Workload("x7_d64_64h_128k", 7, 1, 64, 64, 64, 256, 32, (131072,), (0.1, 0.3, 0.6))
+    if n == 8:
+        # extra: a four-class mix with INT8 chunks (FP16, INT8, INT4, INT2), 128K context, 32 heads
+        return Workload("x8_int8_mix_32h_128k", 8, 1, 32, 32, 128, 256, 64, (131072,), (0.05, 0.15, 0.3, 0.5))
+    if n == 9:
+        # extra: the same four-class mix on a grouped-query shape
+        return Workload("x9_int8_mix_gqa_64k_b4", 9, 4, 32, 8, 128, 256, 64, (65536,) * 4, (0.05, 0.15, 0.3, 0.5))
     raise ValueError(f"unknown config {n}")
 
 
