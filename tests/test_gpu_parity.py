@@ -211,18 +211,59 @@ def test_strided_padded_source():
     Case(w, workers=4, strided_pad=8).check_all()
 
 
-@pytest.mark.parametrize("page_size,head_major,rep,head_dim", [(16, True, 1, 128), (64, False, 1, 128), (128, True, 4, 128),
-                                                               (5, True, 1, 128), (256, False, 2, 128), (16, True, 4, 64)])
-def test_paged_source(page_size, head_major, rep, head_dim):
+def test_strided_source_into_a_cache_with_room_to_grow():
+    """Dense [B, Hkv, Tmax, D] source, FP16 runs laid out for longer contexts: class buffers equal the oracle's
+    image with zero blocks behind every FP16 run, and attention is unaffected by the spare blocks."""
+    w = workloads.small("strided_room", 3, 4, 2, [300, 0, 129], 32, 64, mix=(0.3, 0.3, 0.4), seed_offset=19)
+    _announce(w.name)
+    dev = _dev()
+    shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
+    bits = workloads.chunk_bits(w)
+    room = [65, 130, 1]
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), 16, max_seq_lens=[t + r for t, r in zip(w.seq_lens, room)])
+    cache = ck.PackedCache(plan, dev)
+    for t in cache.k + cache.v:
+        t.fill_(0xAB)
+    tmax = max(w.seq_lens)
+    k = np.zeros((w.batch, w.num_kv_heads, tmax, w.head_dim), dtype=np.float16)
+    v = np.zeros_like(k)
+    ks, vs = [], []
+    for b in range(w.batch):
+        kh, vh = zip(*[workloads.kv_head(w, 0, b, h) for h in range(w.num_kv_heads)])
+        ks.append(np.stack(kh)), vs.append(np.stack(vh))
+        k[b, :, :w.seq_lens[b]], v[b, :, :w.seq_lens[b]] = ks[b], vs[b]
+    ck.cocktail_reorder_quantize(cache, torch.from_numpy(k).to(dev), torch.from_numpy(v).to(dev))
+    oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
+    v_quads = int(plan.sizes.v_layout) == 1
+    for c in range(O.NUM_CLASSES):
+        assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k", reserve=room)), f"K class {c}"
+        assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads, reserve=room)), f"V class {c}"
+    q = workloads.query(w, 0)
+    out, lse = ck.cocktail_decode_attention(cache, torch.from_numpy(q).to(dev))
+    ck.cocktail_decode_check(cache)
+    ref, _ = O.decode_attention(q, oc)
+    got = out.cpu().numpy().astype(np.float64)
+    for b in (0, 2):
+        err = np.abs(got[b] - ref[b]).max(axis=1) / np.abs(ref[b]).max(axis=1)
+        assert err.max() <= TOL
+    assert (got[1] == 0).all() and np.isneginf(lse.cpu().numpy()[1]).all()
+
+
+@pytest.mark.parametrize("page_size,head_major,rep,head_dim,room", [(16, True, 1, 128, 0), (64, False, 1, 128, 0), (128, True, 4, 128, 0),
+                                                                    (5, True, 1, 128, 0), (256, False, 2, 128, 0), (16, True, 4, 64, 0),
+                                                                    (16, True, 1, 128, 100), (5, False, 4, 128, 70), (64, True, 2, 64, 1)])
+def test_paged_source(page_size, head_major, rep, head_dim, room):
     """Reorder+quantize straight from a paged KV cache with a shuffled page table: the packed cache must be the
-    one the oracle makes from the gathered K and V, byte for byte."""
+    one the oracle makes from the gathered K and V, byte for byte.  room: the FP16 runs are laid out with room for
+    that many more tokens per sequence (the empty sequence too), which reorder+quantize writes as zero blocks."""
     w = workloads.small(f"paged{page_size}", 3, 2 * rep, 2, [64 * 9 + 21, 0, 700], 32, 32, mix=(0.2, 0.4, 0.4),
                         head_dim=head_dim, seed_offset=600 + page_size)
     _announce(f"{w.name} head_major={head_major} rep={rep}")
     dev = _dev()
     shape = ck.make_shape(w.batch, w.num_q_heads, w.num_kv_heads, w.head_dim, w.chunk_size, w.group_size)
     bits = workloads.chunk_bits(w)
-    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), 8)
+    plan = ck.cocktail_plan(shape, w.seq_lens, np.concatenate(bits), 8,
+                            max_seq_lens=[t + room for t in w.seq_lens] if room else None)
     cache = ck.PackedCache(plan, dev)
     for t in cache.k + cache.v:
         t.fill_(0xAB)
@@ -252,9 +293,10 @@ def test_paged_source(page_size, head_major, rep, head_dim):
     vs = [O.gather_pages(pools[1], table[b], w.seq_lens[b]) for b in range(w.batch)]
     oc = O.reorder_quantize(ks, vs, bits, w.chunk_size, w.group_size)
     v_quads = int(plan.sizes.v_layout) == 1
+    reserve = [room] * w.batch if room else None
     for c in range(O.NUM_CLASSES):
-        assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k")), f"K class {c}"
-        assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads)), f"V class {c}"
+        assert np.array_equal(cache.k[c].cpu().numpy(), O.pack_class_buffer(oc, c, "k", reserve=reserve)), f"K class {c}"
+        assert np.array_equal(cache.v[c].cpu().numpy(), O.pack_class_buffer(oc, c, "v", v_quads=v_quads, reserve=reserve)), f"V class {c}"
     q = workloads.query(w, 0)
     out, _ = ck.cocktail_decode_attention(cache, torch.from_numpy(q).to(dev))
     ck.cocktail_decode_check(cache)
