@@ -291,6 +291,17 @@ int cocktail_decode_attention(const cocktail_shape* shape, const void* q, const 
                               size_t workspace_bytes, void* stream);
 
 /*
+ * Measurement aid: cocktail_decode_attention that also records `event_between` (a hipEvent_t created by the
+ * caller with timing enabled) on `stream` between its two kernels, so that the partial-state kernel (Alg. 1
+ * decode phase, the kernel that streams the cache) and the merge can be timed apart with events on the launch
+ * stream.  The record itself sits between the kernels: time whole calls with cocktail_decode_attention.
+ * Errors: as cocktail_decode_attention; EINVAL if event_between is NULL; EHIP if the record fails.
+ */
+int cocktail_decode_attention_marked(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
+                                     float sm_scale, void* out, float* lse, void* workspace, size_t workspace_bytes,
+                                     void* stream, void* event_between);
+
+/*
  * cocktail_decode_attention for callers that cannot allocate device memory or hand over a workspace: code
  * that runs under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
  * same two kernels and same results, but the partial states go to a workspace built into the library: a

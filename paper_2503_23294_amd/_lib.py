@@ -72,6 +72,8 @@ EXPORTS = {
     "cocktail_reorder_quantize_paged": (C.c_int, [C.POINTER(Shape), C.POINTER(PagedSource), C.POINTER(Cache), C.c_void_p]),
     "cocktail_decode_attention": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "cocktail_decode_attention_marked": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float, C.c_void_p,
+                                                   C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]),
     "cocktail_decode_attention_static": (C.c_int, [C.POINTER(Shape), C.c_void_p, C.POINTER(Cache), C.c_float,
                                                    C.c_void_p, C.c_void_p, C.c_void_p]),
     "cocktail_decode_check": (C.c_int, [C.POINTER(Shape), C.POINTER(Cache), C.c_void_p, C.c_void_p]),

@@ -251,6 +251,19 @@ def cocktail_decode_attention(cache: PackedCache, q: torch.Tensor, sm_scale: flo
     return out, lse
 
 
+def cocktail_decode_attention_marked(cache: PackedCache, q: torch.Tensor, event_between: torch.cuda.Event,
+                                     out: torch.Tensor, lse: torch.Tensor, sm_scale: float = 0.0,
+                                     stream: Optional[torch.cuda.Stream] = None) -> None:
+    """Measurement aid: cocktail_decode_attention that records `event_between` (created with enable_timing=True
+    and recorded once before, so that its handle exists) between the partial-state kernel and the merge."""
+    handle = int(event_between.cuda_event)
+    if not handle:
+        raise ValueError("record event_between once before passing it, torch creates the handle lazily")
+    check(lib().cocktail_decode_attention_marked(C.byref(cache.plan.shape), q.data_ptr(), C.byref(cache.desc), float(sm_scale),
+                                                 out.data_ptr(), lse.data_ptr(), cache.workspace.data_ptr(),
+                                                 cache.workspace.numel(), _stream_ptr(stream), handle))
+
+
 def cocktail_decode_attention_static(cache: PackedCache, q: torch.Tensor, sm_scale: float, out: torch.Tensor,
                                      lse: Optional[torch.Tensor] = None,
                                      stream: Optional[torch.cuda.Stream] = None) -> None:

@@ -180,7 +180,7 @@ int check_plan_matches(const cocktail_shape* shape, const cocktail_cache* cache,
 
 // Validates the arguments and enqueues the two kernels; `workspace` holds at least hd->workspace_bytes.
 int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void* q, const cocktail_cache* cache,
-                   float sm_scale, void* out, float* lse, void* workspace, void* stream) {
+                   float sm_scale, void* out, float* lse, void* workspace, void* stream, void* event_between = nullptr) {
   if (shape->head_dim != 64 && shape->head_dim != 128)
     return fail(COCKTAIL_EUNSUPPORTED, "kernels are built for head_dim 64 and 128, got %d", shape->head_dim);
   if (hd->rep > COCKTAIL_MAX_Q_PER_KV)
@@ -263,6 +263,10 @@ int decode_enqueue(const cocktail_shape* shape, const PlanHeader* hd, const void
                                       : launch_decode_heads<128>(p, shape->group_size, nt, int8, int(grid.x), st));
     if (e != hipSuccess) return fail(COCKTAIL_EHIP, "decode launch failed: %s", hipGetErrorString(e));
   }
+  if (event_between) {   // measurement aid: when the partial-state kernel is done
+    const hipError_t ev = hipEventRecord(static_cast<hipEvent_t>(event_between), st);
+    if (ev != hipSuccess) return fail(COCKTAIL_EHIP, "recording the event between the two kernels failed: %s", hipGetErrorString(ev));
+  }
   if (shape->head_dim == 64)
     hipLaunchKernelGGL(decode_merge_kernel<64>, dim3(shape->batch * shape->num_q_heads), dim3(16 * kMergeSlices), 0, st, p);
   else
@@ -286,6 +290,18 @@ extern "C" int cocktail_decode_attention(const cocktail_shape* shape, const void
     return fail(COCKTAIL_ENOSPACE, "workspace holds %zu bytes, %lld needed", workspace_bytes,
                 (long long)hd->workspace_bytes);
   return decode_enqueue(shape, hd, q, cache, sm_scale, out, lse, workspace, stream);
+}
+
+extern "C" int cocktail_decode_attention_marked(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,
+                                                float sm_scale, void* out, float* lse, void* workspace,
+                                                size_t workspace_bytes, void* stream, void* event_between) {
+  const PlanHeader* hd = nullptr;
+  if (int rc = check_plan_matches(shape, cache, &hd)) return rc;
+  if (!q || !out || !workspace || !event_between) return fail(COCKTAIL_EINVAL, "q, out, workspace and event_between must not be NULL");
+  if (workspace_bytes < static_cast<size_t>(hd->workspace_bytes))
+    return fail(COCKTAIL_ENOSPACE, "workspace holds %zu bytes, %lld needed", workspace_bytes,
+                (long long)hd->workspace_bytes);
+  return decode_enqueue(shape, hd, q, cache, sm_scale, out, lse, workspace, stream, event_between);
 }
 
 extern "C" int cocktail_decode_attention_static(const cocktail_shape* shape, const void* q, const cocktail_cache* cache,

@@ -693,6 +693,33 @@ def test_quantizer_division_shortcuts_are_exact_on_every_operand():
     assert ck.cocktail_selftest_arithmetic(_dev()) == [0, 0, 0, 0]
 
 
+def test_marked_call_equals_the_plain_call_and_records_its_event():
+    """cocktail_decode_attention_marked (a measurement aid) computes what cocktail_decode_attention computes and
+    records the caller's event between the two kernels."""
+    w = workloads.small("marked", 2, 8, 2, [700, 64 * 6], 32, 32, mix=(0.2, 0.4, 0.4), seed_offset=77)
+    _announce(w.name)
+    c = Case(w, workers=16)
+    out = torch.empty_like(c.out_dev)
+    lse = torch.empty_like(c.lse_dev)
+    start, mid, end = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+    mid.record()                                           # creates the handle
+    torch.cuda.synchronize()
+    start.record()
+    ck.cocktail_decode_attention_marked(c.cache, c.q_dev, mid, out, lse)
+    end.record()
+    torch.cuda.synchronize()
+    ck.cocktail_decode_check(c.cache)
+    assert start.elapsed_time(mid) > 0 and mid.elapsed_time(end) > 0
+    got = out.cpu().numpy().astype(np.float64)
+    ref = c.out.astype(np.float64)
+    assert (np.abs(got - ref).max(axis=2) / np.abs(ref).max(axis=2)).max() <= 1e-3     # pool tickets may be drawn in another order
+    from paper_2503_23294_amd import _lib
+    import ctypes as C
+    rc = _lib.lib().cocktail_decode_attention_marked(C.byref(c.shape), c.q_dev.data_ptr(), C.byref(c.cache.desc), 0.0, out.data_ptr(),
+                                                     lse.data_ptr(), c.cache.workspace.data_ptr(), c.cache.workspace.numel(), None, None)
+    assert rc == _lib.EINVAL
+
+
 def test_runs_on_a_side_stream():
     w = workloads.small("stream", 1, 2, 2, [512], 64, 32, seed_offset=4)
     _announce(w.name)
